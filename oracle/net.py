@@ -1,0 +1,161 @@
+"""ResNet-50 (v1.5 bottleneck) training step wired from the oracle's operations.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+Wiring (appendix log of the paper: stem convolution with stride 2, 64 filters
+and no bias, batch normalization, max-pool 112 -> 56, bottleneck blocks;
+He et al. for the rest):
+  stem:   conv 7x7/2 pad 3 -> BN -> ReLU -> max-pool 3x3/2 pad 1
+  block:  conv 1x1 -> BN -> ReLU -> conv 3x3 (stride s, pad 1) -> BN -> ReLU
+          -> conv 1x1 -> BN -> (+ shortcut) -> ReLU
+          shortcut = input, or conv 1x1 (stride s) -> BN in the first block of a stage
+  stages: 3, 4, 6, 3 blocks of width 64, 128, 256, 512 (outputs 4x wider); s = 2
+          in the first block of stages 2-4, on the 3x3 convolution
+  head:   global average pool -> FC -> softmax cross-entropy (label smoothing)
+  update: LARS + momentum on every parameter tensor (Sec. III-A1), weight decay
+          only on convolution / FC weights.
+
+Parameter order (the order of every params / grads list here): stem W, stem
+gamma, stem beta; per block conv1 W, g, b, conv2 W, g, b, conv3 W, g, b and, if
+the block has a projection shortcut, proj W, g, b; then FC W, FC b.
+"""
+import numpy as np
+
+from . import (avgpool_bwd, avgpool_fwd, bn_relu_bwd, bn_relu_fwd, conv_dgrad, conv_fwd,
+               conv_wgrad, fc_bwd, fc_fwd, lars_update, maxpool_bwd, maxpool_fwd, xent_fwd_bwd)
+
+
+def param_table(widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem=64, classes=1000, in_ch=3,
+                expansion=4):
+    """List of (name, shape, kind); kind in conv|gamma|beta|fcw|fcb."""
+    t = []
+
+    def conv(name, k, r, c):
+        t.append((name + ".w", (k, r, r, c), "conv"))
+        t.append((name + ".gamma", (k,), "gamma"))
+        t.append((name + ".beta", (k,), "beta"))
+
+    conv("stem", stem, 7, in_ch)
+    cin = stem
+    for i, (wd, nb) in enumerate(zip(widths, blocks)):
+        for j in range(nb):
+            p = f"s{i}b{j}"
+            conv(p + ".c1", wd, 1, cin)
+            conv(p + ".c2", wd, 3, wd)
+            conv(p + ".c3", wd * expansion, 1, wd)
+            if j == 0:
+                conv(p + ".proj", wd * expansion, 1, cin)
+            cin = wd * expansion
+    t.append(("fc.w", (classes, cin), "fcw"))
+    t.append(("fc.b", (classes,), "fcb"))
+    return t
+
+
+def _conv_bn_fwd(x, w, gamma, beta, stride, pad, mode, eps, residual=None):
+    y = conv_fwd(x, w, stride, pad)
+    z, mean, rstd = bn_relu_fwd(y, gamma, beta, residual, eps, mode)
+    return z, dict(x=x, w=w, y=y, z=z, gamma=gamma, mean=mean, rstd=rstd, stride=stride, pad=pad,
+                   mode=mode)
+
+
+def _conv_bn_bwd(dz, tp, need_dx=True):
+    """Returns dx (or None), dresidual (or None), (dw, dgamma, dbeta)."""
+    dy, dres, dgamma, dbeta = bn_relu_bwd(dz, tp["y"], tp["z"], tp["gamma"], tp["mean"],
+                                          tp["rstd"], tp["mode"])
+    dw = conv_wgrad(tp["x"], dy, tp["w"].shape, tp["stride"], tp["pad"])
+    dx = conv_dgrad(dy, tp["w"], tp["x"].shape, tp["stride"], tp["pad"]) if need_dx else None
+    return dx, dres, (dw, dgamma, dbeta)
+
+
+def bottleneck_fwd(x, p, stride, has_proj, eps=1e-5):
+    """p: list of 9 (or 12 with projection) arrays in parameter order."""
+    z1, t1 = _conv_bn_fwd(x, p[0], p[1], p[2], 1, 0, 1, eps)
+    z2, t2 = _conv_bn_fwd(z1, p[3], p[4], p[5], stride, 1, 1, eps)
+    if has_proj:
+        sc, tp = _conv_bn_fwd(x, p[9], p[10], p[11], stride, 0, 0, eps)
+    else:
+        sc, tp = x, None
+    z3, t3 = _conv_bn_fwd(z2, p[6], p[7], p[8], 1, 0, 2, eps, residual=sc)
+    return z3, (t1, t2, t3, tp)
+
+
+def bottleneck_bwd(dout, tape):
+    t1, t2, t3, tp = tape
+    d2, dsc, g3 = _conv_bn_bwd(dout, t3)
+    d1, _, g2 = _conv_bn_bwd(d2, t2)
+    dx, _, g1 = _conv_bn_bwd(d1, t1)
+    grads = list(g1) + list(g2) + list(g3)
+    if tp is not None:
+        dxp, _, gp = _conv_bn_bwd(dsc, tp)
+        dx = (dx.astype(np.float64) + dxp.astype(np.float64)).astype(dx.dtype)
+        grads += list(gp)
+    else:
+        dx = (dx.astype(np.float64) + dsc.astype(np.float64)).astype(dx.dtype)
+    return dx, grads
+
+
+def forward_backward(images, labels, params, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3),
+                     eps=1e-5, label_smoothing=0.0, grad_scale=1.0, keep=False):
+    """images NHWC, labels int32[N], params in parameter order (the values the
+    forward pass uses).  Returns dict(loss, logits, grads[, acts])."""
+    it = iter(range(len(params)))
+
+    def take(n):
+        return [params[next(it)] for _ in range(n)]
+
+    acts = {}
+    sp = take(3)
+    z0, t0 = _conv_bn_fwd(images, sp[0], sp[1], sp[2], 2, 3, 1, eps)
+    cur = maxpool_fwd(z0, 3, 2, 1)
+    if keep:
+        acts["stem.y"] = t0["y"]; acts["stem.z"] = z0; acts["pool"] = cur
+    tapes = []
+    for i, nb in enumerate(blocks):
+        for j in range(nb):
+            has_proj = j == 0
+            stride = 2 if (j == 0 and i > 0) else 1
+            bp = take(12 if has_proj else 9)
+            cur, tp = bottleneck_fwd(cur, bp, stride, has_proj, eps)
+            tapes.append(tp)
+            if keep:
+                acts[f"s{i}b{j}.out"] = cur
+    fw, fb = take(2)
+    N, H, W, C = cur.shape
+    a = avgpool_fwd(cur)
+    logits = fc_fwd(a, fw, fb)
+    loss, row_loss, dlogits = xent_fwd_bwd(logits, labels, label_smoothing, grad_scale)
+
+    da, dfw, dfb = fc_bwd(a, fw, dlogits)
+    d = avgpool_bwd(da, H, W)
+    block_grads = []
+    for tp in reversed(tapes):
+        d, g = bottleneck_bwd(d, tp)
+        block_grads.append(g)
+    d = maxpool_bwd(z0, d, 3, 2, 1)
+    _, _, g0 = _conv_bn_bwd(d, t0, need_dx=False)
+    grads = list(g0)
+    for g in reversed(block_grads):
+        grads += g
+    grads += [dfw, dfb]
+    out = dict(loss=loss, row_loss=row_loss, logits=logits, dlogits=dlogits, grads=grads)
+    if keep:
+        out["acts"] = acts
+    return out
+
+
+def lars_hyper(table, weight_decay):
+    """Per-tensor weight decay: on convolution / FC weights only."""
+    return [weight_decay if kind in ("conv", "fcw") else 0.0 for (_, _, kind) in table]
+
+
+def train_step(images, labels, master, model, velocity, table, *, eta=0.001, momentum=0.9, lr=1.0,
+               weight_decay=5e-5, lars_eps=0.0, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3),
+               eps=1e-5, label_smoothing=0.0, grad_scale=1.0):
+    """One training step.  `model` are the values the forward/backward use (the
+    master weights themselves, or their half-precision rounding, Sec. IV);
+    LARS updates `master` (single precision) with the resulting gradients."""
+    fb = forward_backward(images, labels, model, widths, blocks, eps, label_smoothing, grad_scale)
+    wds = lars_hyper(table, weight_decay)
+    w_new, v_new, norms = lars_update(master, fb["grads"], velocity, eta, momentum, lr, wds, lars_eps)
+    fb.update(w_new=w_new, v_new=v_new, norms=norms)
+    return fb

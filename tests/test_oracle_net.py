@@ -1,0 +1,186 @@
+"""Pins for the oracle's network wiring (ResNet-50 v1.5) and the whole training step."""
+import numpy as np
+import pytest
+
+import oracle as orc
+import synth
+from oracle import net
+
+SEED = synth.DEFAULT_SEED
+
+
+def test_parameter_table_counts():
+    """161 tensors, 25,557,032 parameters, 53 convolutions (ResNet-50 with a 1000-way head)."""
+    t = net.param_table()
+    assert len(t) == 161
+    assert sum(int(np.prod(s)) for _, s, _ in t) == 25_557_032
+    assert sum(k == "conv" for _, _, k in t) == 53
+    assert sum(int(np.prod(s)) for _, s, k in t if k == "conv") == 23_454_912
+    assert sum(1 for _, s, _ in t if int(np.prod(s)) <= 2048) == 107
+    assert t[0][1] == (64, 7, 7, 3) and t[-2][1] == (1000, 2048)
+
+
+def test_stem_shape_walk():
+    """Appendix log: [3(4),224,224] -> (64,112,112) -> max-pool -> (64,56,56)."""
+    x = np.zeros((1, 224, 224, 3), np.float32); w = np.zeros((64, 7, 7, 3), np.float32)
+    y = orc.conv_fwd(x, w, 2, 3)
+    assert y.shape == (1, 112, 112, 64)
+    assert orc.maxpool_fwd(y, 3, 2, 1).shape == (1, 56, 56, 64)
+
+
+SMALL = dict(widths=(4, 6, 8, 10), blocks=(2, 1, 2, 1))
+
+
+def _small_setup(dtype, N=2, HW=32, classes=7):
+    table = net.param_table(SMALL["widths"], SMALL["blocks"], stem=4, classes=classes, in_ch=3, expansion=2)
+    params = synth.params_from_table(SEED, table, dtype)
+    # non-trivial gamma / beta so that their gradients and the affine step are exercised
+    for i, (name, shape, kind) in enumerate(table):
+        if kind == "gamma":
+            params[i] = (1.0 + 0.3 * synth.normal(SEED, name, shape)).astype(dtype)
+        if kind in ("beta", "fcb"):
+            params[i] = (0.2 * synth.normal(SEED, name, shape)).astype(dtype)
+    images = synth.activation_nhwc(SEED, "img", N, 3, HW, HW, 1.0, dtype)
+    labels = synth.labels(SEED, "lab", N, classes)
+    return table, params, images, labels
+
+
+def _torch_forward(images, labels, params, table, blocks, ls, expansion=2):
+    """The same network written with torch CPU ops (NCHW, autograd): an independent
+    implementation of the wiring and of every operation."""
+    import torch
+    import torch.nn.functional as F
+    P = [torch.tensor(p, dtype=torch.float64, requires_grad=True) for p in params]
+    it = iter(P)
+
+    def cbn(x, stride, pad, relu=True, res=None):
+        w, g, b = next(it), next(it), next(it)
+        y = F.conv2d(x, w.permute(0, 3, 1, 2), None, stride, pad)
+        y = F.batch_norm(y, None, None, g, b, True, 0.1, 1e-5)
+        if res is not None:
+            y = y + res
+        return F.relu(y) if relu else y
+
+    x = torch.tensor(images, dtype=torch.float64).permute(0, 3, 1, 2)
+    cur = F.max_pool2d(cbn(x, 2, 3), 3, 2, 1)
+    for i, nb in enumerate(blocks):
+        for j in range(nb):
+            stride = 2 if (j == 0 and i > 0) else 1
+            inp = cur
+            z1 = cbn(inp, 1, 0)
+            z2 = cbn(z1, stride, 1)
+            # conv3's parameters come before the projection's in parameter order
+            w3, g3, b3 = next(it), next(it), next(it)
+            if j == 0:
+                sc = cbn(inp, stride, 0, relu=False)
+            else:
+                sc = inp
+            y3 = F.batch_norm(F.conv2d(z2, w3.permute(0, 3, 1, 2)), None, None, g3, b3, True, 0.1, 1e-5)
+            cur = F.relu(y3 + sc)
+    a = cur.mean(dim=(2, 3))
+    fw, fb = next(it), next(it)
+    logits = a @ fw.T + fb
+    loss = F.cross_entropy(logits, torch.tensor(labels, dtype=torch.long), label_smoothing=ls)
+    loss.backward()
+    return float(loss.detach()), logits.detach().numpy(), [p.grad.numpy() for p in P]
+
+
+@pytest.mark.parametrize("ls", [0.0, 0.1])
+def test_small_net_matches_torch_autograd(ls):
+    table, params, images, labels = _small_setup(np.float64)
+    out = net.forward_backward(images, labels, params, SMALL["widths"], SMALL["blocks"], label_smoothing=ls)
+    tl, tlogits, tg = _torch_forward(images, labels, params, table, SMALL["blocks"], ls)
+    assert abs(out["loss"] - tl) < 1e-10
+    np.testing.assert_allclose(out["logits"], tlogits, rtol=1e-8, atol=1e-10)
+    for (name, _, _), g, t in zip(table, out["grads"], tg):
+        assert orc.rel_l2(g, t) < 1e-7, name
+
+
+def test_small_net_finite_differences():
+    """Central differences of the full loss in a sample of parameter entries (float64 build)."""
+    table, params, images, labels = _small_setup(np.float64, N=2, HW=16)
+    f = lambda ps: net.forward_backward(images, labels, ps, SMALL["widths"], SMALL["blocks"], label_smoothing=0.1)
+    base = f(params)
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    for ti in [0, 1, 2, 3, 7, 12, 13, 14, 21, len(table) - 2, len(table) - 1]:
+        p = params[ti]
+        for _ in range(2):
+            idx = tuple(rng.integers(0, s) for s in p.shape)
+            old = p[idx]
+            p[idx] = old + h; lp = f(params)["loss"]
+            p[idx] = old - h; lm = f(params)["loss"]
+            p[idx] = old
+            fd = (lp - lm) / (2 * h)
+            an = base["grads"][ti][idx]
+            assert abs(fd - an) < 1e-6 * max(1.0, abs(an)) + 2e-7, (table[ti][0], idx, fd, an)
+
+
+def test_conv_weights_orthogonal_to_their_gradient():
+    """Every convolution feeds a batch-stat BN, so <w, dL/dw> ~ 0 for all 10+ of them."""
+    table, params, images, labels = _small_setup(np.float64, N=3, HW=64)      # m >= 12 everywhere
+    out = net.forward_backward(images, labels, params, SMALL["widths"], SMALL["blocks"], eps=1e-13)
+    for (name, _, kind), p, g in zip(table, params, out["grads"]):
+        if kind == "conv":
+            assert abs(np.sum(p * g)) < 1e-6 * np.linalg.norm(p) * np.linalg.norm(g) + 1e-12, name
+
+
+def test_f32_build_tracks_f64_build_through_the_net():
+    table, params, images, labels = _small_setup(np.float32, N=3, HW=64)
+    o32 = net.forward_backward(images, labels, params, SMALL["widths"], SMALL["blocks"])
+    o64 = net.forward_backward(images.astype(np.float64), labels, [p.astype(np.float64) for p in params],
+                               SMALL["widths"], SMALL["blocks"])
+    assert abs(o32["loss"] - o64["loss"]) < 1e-5
+    for (name, _, _), a, b in zip(table, o32["grads"], o64["grads"]):
+        assert orc.rel_l2(a, b) < 2e-4, name      # ReLU masks may flip on a few near-zero values
+
+
+def test_bottleneck_block_matches_torch():
+    """BASELINE config-1 style block (projection shortcut) at a reduced spatial size."""
+    import torch
+    import torch.nn.functional as F
+    N, H, C, Wd = 2, 8, 8, 4
+    x = synth.activation_nhwc(SEED, "x", N, C, H, H, 1.0, np.float64)
+    shapes = [(Wd, 1, 1, C), (Wd,), (Wd,), (Wd, 3, 3, Wd), (Wd,), (Wd,), (4 * Wd, 1, 1, Wd), (4 * Wd,), (4 * Wd,),
+              (4 * Wd, 1, 1, C), (4 * Wd,), (4 * Wd,)]
+    p = [synth.normal(SEED, f"p{i}", s, 1.0, np.float64) + (1.5 if len(s) == 1 and i % 3 == 1 else 0) for i, s in enumerate(shapes)]
+    T = synth.activation_nhwc(SEED, "T", N, 4 * Wd, H // 2, H // 2, 1.0, np.float64)
+    out, tape = net.bottleneck_fwd(x, p, 2, True)
+    dx, grads = net.bottleneck_bwd(T, tape)
+
+    tp = [torch.tensor(a, requires_grad=True) for a in p]
+    tx = torch.tensor(x.transpose(0, 3, 1, 2).copy(), requires_grad=True)
+    bn = lambda y, g, b: F.batch_norm(y, None, None, g, b, True, 0.1, 1e-5)
+    cw = lambda w: w.permute(0, 3, 1, 2)
+    z1 = F.relu(bn(F.conv2d(tx, cw(tp[0])), tp[1], tp[2]))
+    z2 = F.relu(bn(F.conv2d(z1, cw(tp[3]), None, 2, 1), tp[4], tp[5]))
+    y3 = bn(F.conv2d(z2, cw(tp[6])), tp[7], tp[8])
+    sc = bn(F.conv2d(tx, cw(tp[9]), None, 2, 0), tp[10], tp[11])
+    o = F.relu(y3 + sc)
+    (o * torch.tensor(T.transpose(0, 3, 1, 2).copy())).sum().backward()
+    assert orc.rel_l2(out, o.detach().numpy().transpose(0, 2, 3, 1)) < 1e-12
+    assert orc.rel_l2(dx, tx.grad.numpy().transpose(0, 2, 3, 1)) < 1e-9
+    for i, (g, t) in enumerate(zip(grads, tp)):
+        assert orc.rel_l2(g, t.grad.numpy()) < 1e-9, i
+
+
+def test_train_step_applies_lars_to_master_weights():
+    table, params, images, labels = _small_setup(np.float32)
+    model = [synth.round_bf16(p) for p in params]
+    vel = [np.zeros_like(p) for p in params]
+    out = net.train_step(images, labels, params, model, vel, table, widths=SMALL["widths"], blocks=SMALL["blocks"])
+    wds = net.lars_hyper(table, 5e-5)
+    assert sum(w > 0 for w in wds) == sum(k in ("conv", "fcw") for _, _, k in table)
+    for t in (0, 1, len(table) - 1):
+        w, g = params[t].astype(np.float64), out["grads"][t].astype(np.float64)
+        wn, gn = np.linalg.norm(w), np.linalg.norm(g)
+        local = 0.001 * wn / (gn + wds[t] * wn) if wn > 0 and gn > 0 else 1.0
+        np.testing.assert_allclose(out["w_new"][t], w - local * (g + wds[t] * w), rtol=2e-6, atol=1e-9)
+
+
+def test_round_bf16_helper():
+    a = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.14159265, 1e-40, 65504.0], np.float32)
+    r = synth.round_bf16(a)
+    import torch
+    np.testing.assert_array_equal(r, torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy())
+    assert synth.bf16_bits(r).dtype == np.uint16
