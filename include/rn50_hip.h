@@ -1,0 +1,238 @@
+/*
+ * rn50_hip.h — C ABI of the MI355X (gfx950) library that runs one worker's share
+ * of the large-minibatch ResNet-50 training step: convolution forward /
+ * data-gradient / weight-gradient, fused BatchNorm+ReLU forward / backward,
+ * pooling, the classifier, softmax cross-entropy and the layer-wise LARS +
+ * momentum update of single-precision master weights.
+ *
+ * Conventions (all functions)
+ *  - Every pointer called "device" is GPU memory owned by the caller; the
+ *    library never allocates, frees or synchronizes, and creates no streams.
+ *    All work is enqueued in order on `stream` (a hipStream_t passed as void*;
+ *    NULL = the default stream).  Pointers called "host" are ordinary CPU memory
+ *    read during the call only.
+ *  - Activations are NHWC, convolution weights KRSC (output channel, filter
+ *    row, filter column, input channel), all contiguous; every device base
+ *    pointer must be 16-byte aligned.
+ *  - dtype: RN50_F32 (float) or RN50_BF16 (bfloat16 storage, float arithmetic
+ *    and accumulation).  Per-channel BN vectors, gradients of parameters,
+ *    logits and the loss are always float.
+ *  - Return value: 0 on success, negative on error; on error nothing has been
+ *    launched.  rn50_last_error() returns a thread-local description.
+ *  - Scratch memory: each operation has a *_workspace_bytes() query; pass a
+ *    device buffer of at least that size (16-byte aligned).  Its contents on
+ *    entry are irrelevant and on return unspecified.
+ */
+#ifndef RN50_HIP_H
+#define RN50_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RN50_OK 0
+#define RN50_ERR_INVALID (-1)     /* null pointer, non-positive size, bad enum       */
+#define RN50_ERR_UNSUPPORTED (-2) /* shape / dtype / layout the kernels do not cover */
+#define RN50_ERR_WORKSPACE (-3)   /* workspace smaller than *_workspace_bytes()      */
+#define RN50_ERR_ALIGN (-4)       /* a device pointer is not 16-byte aligned         */
+#define RN50_ERR_HIP (-5)         /* the HIP runtime reported an error at launch     */
+
+#define RN50_F32 0
+#define RN50_BF16 1
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* rn50_last_error(void);
+/* Library version, for the binding's sanity check. */
+int rn50_version(void);
+
+/* ------------------------------------------------------------------ convolution
+ * y[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]
+ * (cross-correlation, zero padding, no bias: the paper's appendix logs
+ * "use_bias: false" for its convolutions), with Ho = (H+2*pad-R)/stride+1.
+ * Supported: Cin % 8 == 0 (bf16) or % 4 == 0 (f32), or the stem case Cin == 3
+ * with R == S == 7, stride 2, pad 3; Cout % 8 == 0. */
+typedef struct {
+  int N, H, W, Cin, Cout, R, S, stride, pad;
+  int dtype; /* RN50_F32 or RN50_BF16: storage type of x, w, y, dy, dx */
+} rn50_conv_desc;
+
+size_t conv_fwd_workspace_bytes(const rn50_conv_desc* d);
+size_t conv_dgrad_workspace_bytes(const rn50_conv_desc* d);
+size_t conv_wgrad_workspace_bytes(const rn50_conv_desc* d);
+
+/* Forward.  x [N,H,W,Cin], w [Cout,R,S,Cin], y [N,Ho,Wo,Cout]: device, dtype. */
+int conv_fwd(const rn50_conv_desc* d, const void* x, const void* w, void* y, void* workspace,
+             size_t workspace_bytes, void* stream);
+/* Data gradient: dx[n,h,w,c] = sum over (k,r,s) with h = p*stride-pad+r,
+ * w = q*stride-pad+s of dy[n,p,q,k] * w[k,r,s,c].  dy [N,Ho,Wo,Cout], dx [N,H,W,Cin]. */
+int conv_dgrad(const rn50_conv_desc* d, const void* dy, const void* w, void* dx, void* workspace,
+               size_t workspace_bytes, void* stream);
+/* Weight gradient: dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n,p*stride-pad+r,q*stride-pad+s,c].
+ * dw is always float [Cout,R,S,Cin] (it feeds the single-precision update). */
+int conv_wgrad(const rn50_conv_desc* d, const void* x, const void* dy, float* dw, void* workspace,
+               size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------- batch norm (+ReLU, +add)
+ * Training-mode batch normalization over the local batch only (the paper keeps
+ * BN statistics per process, Sec. III-A3; appendix: epsilon 1e-5, scale and
+ * centre on, moving-average momentum 0.9), fused with what follows it in a
+ * bottleneck block.  With m = N*H*W and per channel c:
+ *   mu = mean_m x, var = mean_m (x-mu)^2, rstd = 1/sqrt(var+eps), xhat = (x-mu)*rstd
+ *   v = gamma*xhat + beta
+ *   mode 0: y = v          mode 1: y = max(v,0)      mode 2: y = max(v+residual,0)
+ * C % 8 == 0 (bf16) or % 4 == 0 (f32). */
+typedef struct {
+  int N, H, W, C;
+  float eps;
+  int dtype;
+  int mode;
+} rn50_bn_desc;
+
+size_t bn_relu_fwd_workspace_bytes(const rn50_bn_desc* d);
+size_t bn_relu_bwd_workspace_bytes(const rn50_bn_desc* d);
+
+/* x, y, residual (mode 2 only, else NULL): device [m,C] dtype.  gamma, beta,
+ * save_mean, save_rstd: device float[C] (save_* are outputs kept for backward).
+ * running_mean / running_var: device float[C] or NULL; when given they are
+ * updated in place as running = momentum*running + (1-momentum)*batch statistic
+ * (biased variance). */
+int bn_relu_fwd(const rn50_bn_desc* d, const void* x, const float* gamma, const float* beta,
+                const void* residual, void* y, float* save_mean, float* save_rstd,
+                float* running_mean, float* running_var, float momentum, void* workspace,
+                size_t workspace_bytes, void* stream);
+/* Backward of the above.  dz (and optional dz2, summed with it: the two branches
+ * that consume a block's output), x: device [m,C] dtype.  The ReLU mask is
+ * z > 0, taken from z (the forward output) when z != NULL; in mode 1, z may be
+ * NULL and the mask is recomputed from x, gamma, beta (required then).  Mode 2
+ * needs z.   g = (dz+dz2)*mask;  dbeta = sum_m g;  dgamma = sum_m g*xhat;
+ * dx = gamma*rstd*(g - dbeta/m - xhat*dgamma/m);  mode 2: dresidual = g.
+ * dx, dresidual: device [m,C] dtype; dgamma, dbeta: device float[C]. */
+int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const void* x,
+                const void* z, const float* gamma, const float* beta, const float* save_mean,
+                const float* save_rstd, void* dx, void* dresidual, float* dgamma, float* dbeta,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------- pooling
+ * Max pooling, window 3x3, stride 2, pad 1 (the appendix's 112 -> 56 step);
+ * padding never wins; among equal maxima the first in row-major window order
+ * wins.  Backward recomputes the winner from x and adds dy (+ optional dy2) to
+ * it.  x, dx [N,H,W,C]; y, dy, dy2 [N,Ho,Wo,C]; device, dtype; C % 8 == 0. */
+int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x, void* y, void* stream);
+int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x, const void* dy,
+                const void* dy2, void* dx, void* stream);
+/* Global average pool over the HW positions of each image and its adjoint.
+ * x, dx [N,HW,C]; y, dy [N,C]; device, dtype. */
+int avgpool_fwd(int N, int HW, int C, int dtype, const void* x, void* y, void* stream);
+int avgpool_bwd(int N, int HW, int C, int dtype, const void* dy, void* dx, void* stream);
+
+/* ------------------------------------------------------------------ classifier
+ * logits[n,k] = sum_c a[n,c]*W[k,c] + b[k].  a [N,Cin], W [K,Cin]: device dtype;
+ * b, logits: device float.  Backward: da[n,c] = sum_k dlogits[n,k]*W[k,c] (dtype),
+ * dW[k,c] = sum_n dlogits[n,k]*a[n,c], db[k] = sum_n dlogits[n,k] (float). */
+int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const void* W, const float* b,
+           float* logits, void* stream);
+int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const void* W, const float* dlogits,
+           void* da, float* dW, float* db, void* stream);
+
+/* ----------------------------------------------------- softmax cross-entropy
+ * With label smoothing (Sec. III-A2 of the paper).  Per row n: p = softmax(logits[n,:])
+ * (maximum subtracted first), q_k = (1-ls)*[k==label]+ls/K, row_loss[n] = -sum_k q_k log p_k,
+ * loss = mean_n row_loss, dlogits[n,k] = grad_scale*(p_k-q_k)/N.
+ * logits, dlogits: device float [N,K]; labels: device int32[N] in [0,K);
+ * loss_out: device float[1]; row_loss_out: device float[N] (required: the mean is
+ * taken over it in a fixed order).  A label outside [0,K) matches no class.  K <= 65536. */
+int xent_fwd_bwd(int N, int K, const float* logits, const int32_t* labels, float label_smoothing,
+                 float grad_scale, float* loss_out, float* row_loss_out, float* dlogits,
+                 void* stream);
+
+/* ------------------------------------------------------------------------ LARS
+ * Layer-wise adaptive rate scaling with momentum over a table of parameter
+ * tensors ("layers", Sec. III-A1), the norms of all tensors computed by one
+ * batched launch (Sec. III-B2), on single-precision master weights (Sec. IV):
+ *   wn = ||w||_2, gn = ||g||_2
+ *   local = eta*wn/(gn + weight_decay*wn + eps)  if apply_trust && wn>0 && gn>0, else 1
+ *   v <- momentum*v + lr*local*(g + weight_decay*w);   w <- w - v
+ *   w_lowp <- bf16(w) when w_lowp != NULL (the model copy of mixed precision). */
+typedef struct {
+  float* w;       /* device float[n], updated in place                       */
+  const void* g;  /* device gradient[n]: float, or bf16 when grad_dtype is BF16 */
+  float* v;       /* device float[n] momentum buffer, updated in place       */
+  void* w_lowp;   /* device bf16[n] or NULL                                   */
+  int64_t n;
+  float weight_decay;
+  int apply_trust;
+} rn50_lars_tensor;
+
+typedef struct {
+  int num_tensors;
+  float eta, momentum, lr, eps;
+  int grad_dtype;
+} rn50_lars_desc;
+
+size_t lars_update_workspace_bytes(const rn50_lars_desc* d, const rn50_lars_tensor* table_host);
+/* table_host: host array[num_tensors]; table_dev: a device copy of the same
+ * array (made by the caller).  norms_out: device float[num_tensors*2] receiving
+ * (||w||, ||g||) per tensor, or NULL. */
+int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
+                const rn50_lars_tensor* table_dev, float* norms_out, void* workspace,
+                size_t workspace_bytes, void* stream);
+
+/* ----------------------------------------------------------------- whole step
+ * One training step of ResNet-50 v1.5 on the local batch: forward, softmax
+ * cross-entropy, backward, LARS update of every parameter tensor (the gradient
+ * exchange between workers, Sec. III-C, would sit between backward and LARS and
+ * is not part of this library).
+ *
+ * Parameter order (161 tensors for the full network): stem W, gamma, beta; per
+ * bottleneck block conv1 W, gamma, beta, conv2 ..., conv3 ..., and, in the first
+ * block of a stage, projection W, gamma, beta; then FC W, FC b. */
+typedef struct {
+  int N;          /* local batch                                    */
+  int image_hw;   /* input height = width (224)                      */
+  int classes;    /* 1000                                            */
+  int dtype;      /* RN50_BF16: mixed precision; RN50_F32: all float */
+  int widths[4];  /* bottleneck widths per stage: 64,128,256,512     */
+  int blocks[4];  /* blocks per stage: 3,4,6,3                       */
+  int stem;       /* stem filters: 64                                */
+  int expansion;  /* block output = expansion*width: 4               */
+  float bn_eps;   /* 1e-5 */
+  float label_smoothing, grad_scale;
+  float eta, momentum, weight_decay, lars_eps; /* LARS; weight decay on conv/FC weights only */
+} rn50_step_config;
+
+typedef struct rn50_plan rn50_plan; /* host-side object; holds no device memory */
+
+int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_out);
+void resnet_plan_destroy(rn50_plan* plan);
+int resnet_plan_num_tensors(const rn50_plan* plan);
+/* Shape of parameter tensor i: dims_out[4] = {K,R,S,C} for convolution weights,
+ * {K,C,0,0} for the FC weight, {C,0,0,0} for vectors.  Returns the element count. */
+int64_t resnet_plan_tensor_shape(const rn50_plan* plan, int i, int dims_out[4]);
+/* Element offset of tensor i inside each parameter arena (multiple of 64). */
+int64_t resnet_plan_tensor_offset(const rn50_plan* plan, int i);
+/* Total elements of one parameter arena, and the device workspace the step needs. */
+int64_t resnet_plan_arena_elems(const rn50_plan* plan);
+size_t resnet_plan_workspace_bytes(const rn50_plan* plan);
+
+/* Arenas (device, each resnet_plan_arena_elems long, tensors at their offsets):
+ *   master  float  : master weights, updated in place by LARS
+ *   velocity float : momentum buffers, updated in place
+ *   grads   float  : gradients of this step (output)
+ *   model   dtype  : the weights the forward/backward passes read; in BF16 mode the
+ *                    bf16 copy, refreshed from master by the LARS update; in F32
+ *                    mode pass the master arena itself.
+ * images: device [N,hw,hw,3] dtype (NHWC); labels: device int32[N].
+ * loss_out: device float[1]; logits_out: device float[N,classes] or NULL.
+ * lr: the learning rate of this step (schedules live with the caller).
+ * If update == 0 the step stops after backward (gradients only). */
+int resnet_step(rn50_plan* plan, const void* images, const int32_t* labels, float* master,
+                float* velocity, float* grads, void* model, float lr, int update, float* loss_out,
+                float* logits_out, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RN50_HIP_H */

@@ -1,0 +1,118 @@
+// Shared host/device helpers of the gfx950 library (error reporting, bf16
+// conversion, 16-byte vector access, wave/block reductions).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/rn50_hip.h"
+
+namespace rn50 {
+
+// ---------------------------------------------------------------- host: errors
+int fail(int code, const char* fmt, ...);
+void clear_error();
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define RN50_REQUIRE(cond, code, ...) \
+  do {                                \
+    if (!(cond)) return ::rn50::fail((code), __VA_ARGS__); \
+  } while (0)
+
+// Call after a launch sequence: turns a launch error into RN50_ERR_HIP.
+inline int launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(RN50_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return RN50_OK;
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// -------------------------------------------------------------- device: types
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// 16 bytes of storage, viewed either as 8 bf16 or as 4 floats.
+union alignas(16) Vec16 {
+  uint4 u;
+  float f[4];
+  uint16_t h[8];
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) {
+  return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+// Round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+// Element traits: VEC elements per 16-byte vector.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int VEC = 4;
+  static __device__ __forceinline__ void unpack(const Vec16& v, float* out) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = v.f[i];
+  }
+  static __device__ __forceinline__ void pack(const float* in, Vec16& v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v.f[i] = in[i];
+  }
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float x) { *p = x; }
+};
+template <> struct Elem<uint16_t> {  // bf16 storage
+  static constexpr int VEC = 8;
+  static __device__ __forceinline__ void unpack(const Vec16& v, float* out) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = bf16_bits_to_float(v.h[i]);
+  }
+  static __device__ __forceinline__ void pack(const float* in, Vec16& v) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v.h[i] = float_to_bf16_bits(in[i]);
+  }
+  static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
+  static __device__ __forceinline__ void store(uint16_t* p, float x) { *p = float_to_bf16_bits(x); }
+};
+
+template <typename T>
+__device__ __forceinline__ Vec16 load16(const T* p) {
+  Vec16 v;
+  v.u = *reinterpret_cast<const uint4*>(p);
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ void store16(T* p, const Vec16& v) {
+  *reinterpret_cast<uint4*>(p) = v.u;
+}
+
+// ------------------------------------------------------- device: reductions
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+// Sum over a 256-thread block; result valid in every thread.  `lds` holds >= 4 floats.
+__device__ __forceinline__ float block256_sum(float v, float* lds) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) lds[wave] = v;
+  __syncthreads();
+  return (lds[0] + lds[1]) + (lds[2] + lds[3]);
+}
+
+}  // namespace rn50

@@ -1,0 +1,432 @@
+// Pooling, classifier and loss kernels: max-pool 3x3/2 (appendix log of the
+// paper: 112 -> 56 after the stem), global average pool, the fully connected
+// classifier, and softmax cross-entropy with label smoothing (Sec. III-A2).
+// All are bandwidth- or latency-bound and small next to the convolutions.
+#include "common.h"
+
+namespace rn50 {
+
+// ------------------------------------------------------------------ max pool
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ x,
+                                                          T* __restrict__ y, int N, int H, int W,
+                                                          int C, int P, int Q) {
+  constexpr int V = Elem<T>::VEC;
+  const int cv = C / V;
+  const int64_t total = static_cast<int64_t>(N) * P * Q * cv;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = static_cast<int>(i % cv);
+  int64_t t = i / cv;
+  const int q = static_cast<int>(t % Q); t /= Q;
+  const int p = static_cast<int>(t % P);
+  const int n = static_cast<int>(t / P);
+  float best[V];
+  bool have = false;
+  for (int r = 0; r < 3; ++r) {
+    const int ih = p * 2 - 1 + r;
+    if (ih < 0 || ih >= H) continue;
+    for (int s = 0; s < 3; ++s) {
+      const int iw = q * 2 - 1 + s;
+      if (iw < 0 || iw >= W) continue;
+      float f[V];
+      Elem<T>::unpack(load16(x + ((static_cast<int64_t>(n) * H + ih) * W + iw) * C + c * V), f);
+      if (!have) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) best[j] = f[j];
+        have = true;
+      } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) best[j] = f[j] > best[j] ? f[j] : best[j];
+      }
+    }
+  }
+  Vec16 o;
+  Elem<T>::pack(best, o);
+  store16(y + i * V, o);
+}
+
+// One thread per input pixel vector.  The pixel receives dy of window (p,q) iff
+// it is that window's first maximum in row-major order: strictly greater than
+// every earlier tap and not less than every later one.
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ x,
+                                                          const T* __restrict__ dy,
+                                                          const T* __restrict__ dy2,
+                                                          T* __restrict__ dx, int N, int H, int W,
+                                                          int C, int P, int Q) {
+  constexpr int V = Elem<T>::VEC;
+  const int cv = C / V;
+  const int64_t total = static_cast<int64_t>(N) * H * W * cv;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = static_cast<int>(i % cv);
+  int64_t t = i / cv;
+  const int w = static_cast<int>(t % W); t /= W;
+  const int h = static_cast<int>(t % H);
+  const int n = static_cast<int>(t / H);
+  float mine[V], acc[V];
+  Elem<T>::unpack(load16(x + i * V), mine);
+#pragma unroll
+  for (int j = 0; j < V; ++j) acc[j] = 0.f;
+  // windows containing (h,w): p*2-1 <= h <= p*2+1
+  const int p_lo = max((h - 1 + 1) / 2, 0), p_hi = min((h + 1) / 2, P - 1);
+  const int q_lo = max((w - 1 + 1) / 2, 0), q_hi = min((w + 1) / 2, Q - 1);
+  for (int p = p_lo; p <= p_hi; ++p)
+    for (int q = q_lo; q <= q_hi; ++q) {
+      const int my_r = h - (p * 2 - 1), my_s = w - (q * 2 - 1);
+      const int my_pos = my_r * 3 + my_s;
+      bool win[V];
+#pragma unroll
+      for (int j = 0; j < V; ++j) win[j] = true;
+      for (int r = 0; r < 3; ++r) {
+        const int ih = p * 2 - 1 + r;
+        if (ih < 0 || ih >= H) continue;
+        for (int s = 0; s < 3; ++s) {
+          const int iw = q * 2 - 1 + s;
+          if (iw < 0 || iw >= W) continue;
+          const int pos = r * 3 + s;
+          if (pos == my_pos) continue;
+          float f[V];
+          Elem<T>::unpack(load16(x + ((static_cast<int64_t>(n) * H + ih) * W + iw) * C + c * V), f);
+          if (pos < my_pos) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) win[j] = win[j] && (mine[j] > f[j]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) win[j] = win[j] && (mine[j] >= f[j]);
+          }
+        }
+      }
+      const int64_t o = ((static_cast<int64_t>(n) * P + p) * Q + q) * C + c * V;
+      float g[V];
+      Elem<T>::unpack(load16(dy + o), g);
+      if (dy2) {
+        float g2[V];
+        Elem<T>::unpack(load16(dy2 + o), g2);
+#pragma unroll
+        for (int j = 0; j < V; ++j) g[j] += g2[j];
+      }
+#pragma unroll
+      for (int j = 0; j < V; ++j) acc[j] += win[j] ? g[j] : 0.f;
+    }
+  Vec16 o;
+  Elem<T>::pack(acc, o);
+  store16(dx + i * V, o);
+}
+
+// -------------------------------------------------------------- average pool
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const T* __restrict__ x,
+                                                          T* __restrict__ y, int N, int HW, int C) {
+  constexpr int V = Elem<T>::VEC;
+  const int cv = C / V;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= N * cv) return;
+  const int n = i / cv, c = i % cv;
+  float acc[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) acc[j] = 0.f;
+  const T* p = x + static_cast<int64_t>(n) * HW * C + c * V;
+  for (int r = 0; r < HW; ++r) {
+    float f[V];
+    Elem<T>::unpack(load16(p + static_cast<int64_t>(r) * C), f);
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] += f[j];
+  }
+  const float inv = 1.0f / static_cast<float>(HW);
+#pragma unroll
+  for (int j = 0; j < V; ++j) acc[j] *= inv;
+  Vec16 o;
+  Elem<T>::pack(acc, o);
+  store16(y + static_cast<int64_t>(i) * V, o);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const T* __restrict__ dy,
+                                                          T* __restrict__ dx, int N, int HW,
+                                                          int C) {
+  constexpr int V = Elem<T>::VEC;
+  const int cv = C / V;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= static_cast<int64_t>(N) * HW * cv) return;
+  const int c = static_cast<int>(i % cv);
+  const int n = static_cast<int>(i / (static_cast<int64_t>(HW) * cv));
+  float f[V];
+  Elem<T>::unpack(load16(dy + (static_cast<int64_t>(n) * cv + c) * V), f);
+  const float inv = 1.0f / static_cast<float>(HW);
+#pragma unroll
+  for (int j = 0; j < V; ++j) f[j] *= inv;
+  Vec16 o;
+  Elem<T>::pack(f, o);
+  store16(dx + i * V, o);
+}
+
+// ---------------------------------------------------- small strided GEMM (FC)
+// C[i,j] = sum_k A(i,k)*B(k,j) (+ bias[j]); A(i,k) = a[i*as_i + k*as_k], same for B.
+// 64x64 tile per workgroup, 16-deep LDS stages, 4x4 outputs per thread, float
+// accumulation.  The classifier is ~0.05% of the step's arithmetic.
+template <typename TA, typename TB, typename TC>
+__global__ __launch_bounds__(256) void small_gemm_kernel(const TA* __restrict__ a, int64_t as_i,
+                                                         int64_t as_k, const TB* __restrict__ b,
+                                                         int64_t bs_k, int64_t bs_j,
+                                                         const float* __restrict__ bias,
+                                                         TC* __restrict__ c, int M, int Nn, int K) {
+  __shared__ float As[16][65];
+  __shared__ float Bs[16][65];
+  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  float acc[4][4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[u][v] = 0.f;
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int idx = threadIdx.x + e * 256;  // 0..1023
+      {
+        // A tile: choose the faster-varying index to follow the smaller stride
+        const int kk = as_k == 1 ? (idx & 15) : (idx >> 6);
+        const int ii = as_k == 1 ? (idx >> 4) : (idx & 63);
+        const int gi = i0 + ii, gk = k0 + kk;
+        As[kk][ii] = (gi < M && gk < K) ? Elem<TA>::load(a + gi * as_i + gk * as_k) : 0.f;
+      }
+      {
+        const int kk = bs_k == 1 ? (idx & 15) : (idx >> 6);
+        const int jj = bs_k == 1 ? (idx >> 4) : (idx & 63);
+        const int gj = j0 + jj, gk = k0 + kk;
+        Bs[kk][jj] = (gj < Nn && gk < K) ? Elem<TB>::load(b + gk * bs_k + gj * bs_j) : 0.f;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) av[u] = As[kk][ty * 4 + u];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) bv[v] = Bs[kk][tx * 4 + v];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[u][v] = fmaf(av[u], bv[v], acc[u][v]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int gi = i0 + ty * 4 + u, gj = j0 + tx * 4 + v;
+      if (gi < M && gj < Nn)
+        Elem<TC>::store(c + static_cast<int64_t>(gi) * Nn + gj, acc[u][v] + (bias ? bias[gj] : 0.f));
+    }
+}
+
+// db[k] = sum_n dlogits[n,k]
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ dl, float* __restrict__ db,
+                                                     int N, int K) {
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  if (k >= K) return;
+  float s = 0.f;
+  for (int n = 0; n < N; ++n) s += dl[static_cast<int64_t>(n) * K + k];
+  db[k] = s;
+}
+
+template <typename TA, typename TB, typename TC>
+static void small_gemm(const TA* a, int64_t as_i, int64_t as_k, const TB* b, int64_t bs_k,
+                       int64_t bs_j, const float* bias, TC* c, int M, int Nn, int K, hipStream_t s) {
+  hipLaunchKernelGGL((small_gemm_kernel<TA, TB, TC>), dim3(ceil_div(Nn, 64), ceil_div(M, 64)),
+                     dim3(256), 0, s, a, as_i, as_k, b, bs_k, bs_j, bias, c, M, Nn, K);
+}
+
+// ------------------------------------------------------ softmax cross-entropy
+// One workgroup per row.
+__global__ __launch_bounds__(256) void xent_rows_kernel(const float* __restrict__ logits,
+                                                        const int32_t* __restrict__ labels, int N,
+                                                        int K, float ls, float grad_scale,
+                                                        float* __restrict__ row_loss,
+                                                        float* __restrict__ dlogits) {
+  __shared__ float red[8];
+  const int n = blockIdx.x;
+  const float* l = logits + static_cast<int64_t>(n) * K;
+  float mx = -INFINITY;
+  for (int k = threadIdx.x; k < K; k += 256) mx = fmaxf(mx, l[k]);
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float se = 0.f, sl = 0.f;  // sum exp(l-mx), sum (l-mx)
+  for (int k = threadIdx.x; k < K; k += 256) {
+    const float d = l[k] - mx;
+    se += expf(d);
+    sl += d;
+  }
+  se = block256_sum(se, red);
+  sl = block256_sum(sl, red + 4);
+  const float lse = logf(se);  // log-sum-exp relative to mx
+  const int label = labels[n];
+  const float qoff = ls / static_cast<float>(K), qon = 1.0f - ls;
+  const float coef = grad_scale / static_cast<float>(N);
+  for (int k = threadIdx.x; k < K; k += 256) {
+    const float logp = l[k] - mx - lse;
+    const float q = qoff + (k == label ? qon : 0.f);
+    dlogits[static_cast<int64_t>(n) * K + k] = coef * (expf(logp) - q);
+  }
+  if (threadIdx.x == 0) {
+    // -sum_k q_k logp_k = -(ls/K) * sum_k logp_k - (1-ls) * logp_label
+    const float sum_logp = sl - static_cast<float>(K) * lse;
+    float rl = -qoff * sum_logp;
+    if (label >= 0 && label < K) rl -= qon * (l[label] - mx - lse);
+    row_loss[n] = rl;
+  }
+}
+
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ v, int n,
+                                                   float* __restrict__ out) {
+  __shared__ float red[4];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += v[i];
+  s = block256_sum(s, red);
+  if (threadIdx.x == 0) out[0] = s / static_cast<float>(n);
+}
+
+static int check_dtype(int dtype, const char* who) {
+  RN50_REQUIRE(dtype == RN50_F32 || dtype == RN50_BF16, RN50_ERR_INVALID, "%s: dtype %d", who, dtype);
+  return RN50_OK;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+#define DISPATCH_T(dtype, ...)             \
+  do {                                     \
+    if ((dtype) == RN50_BF16) {            \
+      typedef uint16_t T;                  \
+      __VA_ARGS__;                         \
+    } else {                               \
+      typedef float T;                     \
+      __VA_ARGS__;                         \
+    }                                      \
+  } while (0)
+
+extern "C" int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x, void* y,
+                           void* stream) {
+  clear_error();
+  if (int rc = check_dtype(dtype, "maxpool_fwd")) return rc;
+  RN50_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, RN50_ERR_INVALID, "maxpool_fwd: non-positive size");
+  RN50_REQUIRE(x && y, RN50_ERR_INVALID, "maxpool_fwd: null pointer");
+  RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "maxpool_fwd: C=%d", C);
+  RN50_REQUIRE(aligned16(x) && aligned16(y), RN50_ERR_ALIGN, "maxpool_fwd: pointer not 16-byte aligned");
+  const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DISPATCH_T(dtype, {
+    const int64_t total = static_cast<int64_t>(N) * P * Q * (C / Elem<T>::VEC);
+    hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+                       static_cast<const T*>(x), static_cast<T*>(y), N, H, W, C, P, Q);
+  });
+  return launch_status("maxpool_fwd");
+}
+
+extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x, const void* dy,
+                           const void* dy2, void* dx, void* stream) {
+  clear_error();
+  if (int rc = check_dtype(dtype, "maxpool_bwd")) return rc;
+  RN50_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, RN50_ERR_INVALID, "maxpool_bwd: non-positive size");
+  RN50_REQUIRE(x && dy && dx, RN50_ERR_INVALID, "maxpool_bwd: null pointer");
+  RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "maxpool_bwd: C=%d", C);
+  RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2) && aligned16(dx), RN50_ERR_ALIGN,
+               "maxpool_bwd: pointer not 16-byte aligned");
+  const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DISPATCH_T(dtype, {
+    const int64_t total = static_cast<int64_t>(N) * H * W * (C / Elem<T>::VEC);
+    hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+                       static_cast<const T*>(x), static_cast<const T*>(dy),
+                       static_cast<const T*>(dy2), static_cast<T*>(dx), N, H, W, C, P, Q);
+  });
+  return launch_status("maxpool_bwd");
+}
+
+extern "C" int avgpool_fwd(int N, int HW, int C, int dtype, const void* x, void* y, void* stream) {
+  clear_error();
+  if (int rc = check_dtype(dtype, "avgpool_fwd")) return rc;
+  RN50_REQUIRE(N > 0 && HW > 0 && C > 0, RN50_ERR_INVALID, "avgpool_fwd: non-positive size");
+  RN50_REQUIRE(x && y, RN50_ERR_INVALID, "avgpool_fwd: null pointer");
+  RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "avgpool_fwd: C=%d", C);
+  RN50_REQUIRE(aligned16(x) && aligned16(y), RN50_ERR_ALIGN, "avgpool_fwd: pointer not 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DISPATCH_T(dtype, {
+    const int total = N * (C / Elem<T>::VEC);
+    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+                       static_cast<const T*>(x), static_cast<T*>(y), N, HW, C);
+  });
+  return launch_status("avgpool_fwd");
+}
+
+extern "C" int avgpool_bwd(int N, int HW, int C, int dtype, const void* dy, void* dx, void* stream) {
+  clear_error();
+  if (int rc = check_dtype(dtype, "avgpool_bwd")) return rc;
+  RN50_REQUIRE(N > 0 && HW > 0 && C > 0, RN50_ERR_INVALID, "avgpool_bwd: non-positive size");
+  RN50_REQUIRE(dy && dx, RN50_ERR_INVALID, "avgpool_bwd: null pointer");
+  RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "avgpool_bwd: C=%d", C);
+  RN50_REQUIRE(aligned16(dy) && aligned16(dx), RN50_ERR_ALIGN, "avgpool_bwd: pointer not 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DISPATCH_T(dtype, {
+    const int64_t total = static_cast<int64_t>(N) * HW * (C / Elem<T>::VEC);
+    hipLaunchKernelGGL(avgpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+                       static_cast<const T*>(dy), static_cast<T*>(dx), N, HW, C);
+  });
+  return launch_status("avgpool_bwd");
+}
+
+extern "C" int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const void* W,
+                      const float* b, float* logits, void* stream) {
+  clear_error();
+  if (int rc = check_dtype(dtype, "fc_fwd")) return rc;
+  RN50_REQUIRE(N > 0 && Cin > 0 && K > 0, RN50_ERR_INVALID, "fc_fwd: non-positive size");
+  RN50_REQUIRE(a && W && b && logits, RN50_ERR_INVALID, "fc_fwd: null pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DISPATCH_T(dtype, {
+    small_gemm<T, T, float>(static_cast<const T*>(a), Cin, 1, static_cast<const T*>(W), 1, Cin, b,
+                            logits, N, K, Cin, s);
+  });
+  return launch_status("fc_fwd");
+}
+
+extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const void* W,
+                      const float* dlogits, void* da, float* dW, float* db, void* stream) {
+  clear_error();
+  if (int rc = check_dtype(dtype, "fc_bwd")) return rc;
+  RN50_REQUIRE(N > 0 && Cin > 0 && K > 0, RN50_ERR_INVALID, "fc_bwd: non-positive size");
+  RN50_REQUIRE(a && W && dlogits && da && dW && db, RN50_ERR_INVALID, "fc_bwd: null pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DISPATCH_T(dtype, {
+    // da[n,c] = sum_k dl[n,k] * W[k,c]
+    small_gemm<float, T, T>(dlogits, K, 1, static_cast<const T*>(W), Cin, 1, nullptr,
+                            static_cast<T*>(da), N, Cin, K, s);
+    // dW[k,c] = sum_n dl[n,k] * a[n,c]
+    small_gemm<float, T, float>(dlogits, 1, K, static_cast<const T*>(a), Cin, 1, nullptr, dW, K,
+                                Cin, N, s);
+  });
+  hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(K, 256)), dim3(256), 0, s, dlogits, db, N, K);
+  return launch_status("fc_bwd");
+}
+
+extern "C" int xent_fwd_bwd(int N, int K, const float* logits, const int32_t* labels,
+                            float label_smoothing, float grad_scale, float* loss_out,
+                            float* row_loss_out, float* dlogits, void* stream) {
+  clear_error();
+  RN50_REQUIRE(N > 0 && K > 0 && K <= 65536, RN50_ERR_INVALID, "xent_fwd_bwd: N=%d K=%d", N, K);
+  RN50_REQUIRE(logits && labels && loss_out && row_loss_out && dlogits, RN50_ERR_INVALID,
+               "xent_fwd_bwd: null pointer");
+  RN50_REQUIRE(label_smoothing >= 0.f && label_smoothing <= 1.f, RN50_ERR_INVALID,
+               "xent_fwd_bwd: label_smoothing %g", label_smoothing);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(xent_rows_kernel, dim3(N), dim3(256), 0, s, logits, labels, N, K,
+                     label_smoothing, grad_scale, row_loss_out, dlogits);
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, s, row_loss_out, N, loss_out);
+  return launch_status("xent_fwd_bwd");
+}

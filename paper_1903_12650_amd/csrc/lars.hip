@@ -1,0 +1,213 @@
+// Multi-tensor LARS + momentum update (Sec. III-A1 of the paper) with the
+// batched norm computation of Sec. III-B2: the squared norms of every tensor's
+// weights and gradients are produced by ONE launch whose grid covers all
+// tensors in fixed-size chunks, so the 107 tiny tensors of ResNet-50 do not
+// each cost a launch that cannot fill the GPU.  A second launch over the same
+// chunks finishes the per-tensor sums (fixed order, so results are bitwise
+// reproducible), forms the local learning rate and updates w and v in place.
+//
+// HBM traffic per parameter: 8 B (norm pass: w, g) + 20 B (update: w, g, v read,
+// w, v written) + 2 B for the bf16 model copy.  The second read of w and g can
+// be served by the 256 MB last-level cache when the model fits.
+#include "common.h"
+
+namespace rn50 {
+
+constexpr int kLarsChunk = 8192;      // elements per workgroup
+constexpr int kLarsMaxTensors = 480;  // per launch (chunk table travels as a kernel argument)
+
+struct LarsArgs {
+  const rn50_lars_tensor* table;  // device, already offset to this launch's first tensor
+  int num;
+  int grad_bf16;
+  float eta, momentum, lr, eps;
+  float* partial;    // [total_chunks][2]
+  float* norms_out;  // [num][2] or null, offset like table
+  int chunk_prefix[kLarsMaxTensors + 1];
+};
+
+__device__ __forceinline__ int find_tensor(const LarsArgs& a, int chunk) {
+  int lo = 0, hi = a.num;  // invariant: prefix[lo] <= chunk < prefix[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.chunk_prefix[mid] <= chunk) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <bool GBF16>
+__device__ __forceinline__ void load_g4(const void* g, int64_t i, float* out) {
+  if (GBF16) {
+    const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(g) + i);
+    out[0] = __uint_as_float(r.x << 16);
+    out[1] = __uint_as_float(r.x & 0xffff0000u);
+    out[2] = __uint_as_float(r.y << 16);
+    out[3] = __uint_as_float(r.y & 0xffff0000u);
+  } else {
+    const float4 r = *reinterpret_cast<const float4*>(static_cast<const float*>(g) + i);
+    out[0] = r.x; out[1] = r.y; out[2] = r.z; out[3] = r.w;
+  }
+}
+template <bool GBF16>
+__device__ __forceinline__ float load_g1(const void* g, int64_t i) {
+  if (GBF16) return bf16_bits_to_float(static_cast<const uint16_t*>(g)[i]);
+  return static_cast<const float*>(g)[i];
+}
+
+template <bool GBF16>
+__global__ __launch_bounds__(256) void lars_norms_kernel(const LarsArgs a) {
+  __shared__ float red[8];
+  const int chunk = blockIdx.x;
+  const int t = find_tensor(a, chunk);
+  const rn50_lars_tensor T = a.table[t];
+  const int64_t base = static_cast<int64_t>(chunk - a.chunk_prefix[t]) * kLarsChunk;
+  const int64_t end = min(base + static_cast<int64_t>(kLarsChunk), T.n);
+  const int64_t vend = base + ((end - base) & ~static_cast<int64_t>(3));
+  float sw = 0.f, sg = 0.f;
+  for (int64_t i = base + threadIdx.x * 4; i < vend; i += 1024) {
+    const float4 w4 = *reinterpret_cast<const float4*>(T.w + i);
+    float g4[4];
+    load_g4<GBF16>(T.g, i, g4);
+    sw += (w4.x * w4.x + w4.y * w4.y) + (w4.z * w4.z + w4.w * w4.w);
+    sg += (g4[0] * g4[0] + g4[1] * g4[1]) + (g4[2] * g4[2] + g4[3] * g4[3]);
+  }
+  for (int64_t i = vend + threadIdx.x; i < end; i += 256) {
+    const float w = T.w[i], g = load_g1<GBF16>(T.g, i);
+    sw += w * w;
+    sg += g * g;
+  }
+  sw = block256_sum(sw, red);
+  sg = block256_sum(sg, red + 4);
+  if (threadIdx.x == 0) {
+    a.partial[2 * chunk] = sw;
+    a.partial[2 * chunk + 1] = sg;
+  }
+}
+
+template <bool GBF16>
+__global__ __launch_bounds__(256) void lars_apply_kernel(const LarsArgs a) {
+  __shared__ float red[8];
+  const int chunk = blockIdx.x;
+  const int t = find_tensor(a, chunk);
+  const rn50_lars_tensor T = a.table[t];
+  const int c0 = a.chunk_prefix[t], c1 = a.chunk_prefix[t + 1];
+  // Finish the two sums of this tensor: same order in every block of the tensor.
+  float sw = 0.f, sg = 0.f;
+  for (int c = c0 + threadIdx.x; c < c1; c += 256) {
+    sw += a.partial[2 * c];
+    sg += a.partial[2 * c + 1];
+  }
+  sw = block256_sum(sw, red);
+  sg = block256_sum(sg, red + 4);
+  const float wn = sqrtf(sw), gn = sqrtf(sg);
+  float local = 1.0f;
+  if (T.apply_trust && wn > 0.f && gn > 0.f) local = a.eta * wn / (gn + T.weight_decay * wn + a.eps);
+  const float step = a.lr * local, wd = T.weight_decay, mu = a.momentum;
+  if (chunk == c0 && threadIdx.x == 0 && a.norms_out) {
+    a.norms_out[2 * t] = wn;
+    a.norms_out[2 * t + 1] = gn;
+  }
+  const int64_t base = static_cast<int64_t>(chunk - c0) * kLarsChunk;
+  const int64_t end = min(base + static_cast<int64_t>(kLarsChunk), T.n);
+  const int64_t vend = base + ((end - base) & ~static_cast<int64_t>(3));
+  uint16_t* lowp = static_cast<uint16_t*>(T.w_lowp);
+  for (int64_t i = base + threadIdx.x * 4; i < vend; i += 1024) {
+    float4 w4 = *reinterpret_cast<const float4*>(T.w + i);
+    float4 v4 = *reinterpret_cast<const float4*>(T.v + i);
+    float g4[4];
+    load_g4<GBF16>(T.g, i, g4);
+    v4.x = mu * v4.x + step * (g4[0] + wd * w4.x);
+    v4.y = mu * v4.y + step * (g4[1] + wd * w4.y);
+    v4.z = mu * v4.z + step * (g4[2] + wd * w4.z);
+    v4.w = mu * v4.w + step * (g4[3] + wd * w4.w);
+    w4.x -= v4.x; w4.y -= v4.y; w4.z -= v4.z; w4.w -= v4.w;
+    *reinterpret_cast<float4*>(T.v + i) = v4;
+    *reinterpret_cast<float4*>(T.w + i) = w4;
+    if (lowp) {
+      uint2 p;
+      p.x = float_to_bf16_bits(w4.x) | (static_cast<uint32_t>(float_to_bf16_bits(w4.y)) << 16);
+      p.y = float_to_bf16_bits(w4.z) | (static_cast<uint32_t>(float_to_bf16_bits(w4.w)) << 16);
+      *reinterpret_cast<uint2*>(lowp + i) = p;
+    }
+  }
+  for (int64_t i = vend + threadIdx.x; i < end; i += 256) {
+    const float w = T.w[i], g = load_g1<GBF16>(T.g, i);
+    const float v = mu * T.v[i] + step * (g + wd * w);
+    const float wnew = w - v;
+    T.v[i] = v;
+    T.w[i] = wnew;
+    if (lowp) lowp[i] = float_to_bf16_bits(wnew);
+  }
+}
+
+static int64_t total_chunks(const rn50_lars_desc* d, const rn50_lars_tensor* tab) {
+  int64_t c = 0;
+  for (int t = 0; t < d->num_tensors; ++t) c += ceil_div(tab[t].n, kLarsChunk);
+  return c;
+}
+
+static int check_table(const rn50_lars_desc* d, const rn50_lars_tensor* tab) {
+  RN50_REQUIRE(d && tab, RN50_ERR_INVALID, "lars_update: null descriptor or table");
+  RN50_REQUIRE(d->num_tensors > 0, RN50_ERR_INVALID, "lars_update: num_tensors = %d", d->num_tensors);
+  RN50_REQUIRE(d->grad_dtype == RN50_F32 || d->grad_dtype == RN50_BF16, RN50_ERR_INVALID,
+               "lars_update: grad_dtype = %d", d->grad_dtype);
+  for (int t = 0; t < d->num_tensors; ++t) {
+    RN50_REQUIRE(tab[t].n > 0, RN50_ERR_INVALID, "lars_update: tensor %d has n = %lld", t,
+                 (long long)tab[t].n);
+    RN50_REQUIRE(tab[t].w && tab[t].g && tab[t].v, RN50_ERR_INVALID,
+                 "lars_update: tensor %d has a null pointer", t);
+    RN50_REQUIRE(aligned16(tab[t].w) && aligned16(tab[t].g) && aligned16(tab[t].v) &&
+                     aligned16(tab[t].w_lowp),
+                 RN50_ERR_ALIGN, "lars_update: tensor %d is not 16-byte aligned", t);
+  }
+  return RN50_OK;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+extern "C" size_t lars_update_workspace_bytes(const rn50_lars_desc* d,
+                                              const rn50_lars_tensor* table_host) {
+  if (!d || !table_host || d->num_tensors <= 0) return 0;
+  return align_up(static_cast<size_t>(total_chunks(d, table_host)) * 2 * sizeof(float), 256);
+}
+
+extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
+                           const rn50_lars_tensor* table_dev, float* norms_out, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_table(d, table_host)) return rc;
+  RN50_REQUIRE(table_dev && workspace, RN50_ERR_INVALID, "lars_update: null device table or workspace");
+  RN50_REQUIRE(aligned16(table_dev) && aligned16(workspace), RN50_ERR_ALIGN,
+               "lars_update: table_dev / workspace not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= lars_update_workspace_bytes(d, table_host), RN50_ERR_WORKSPACE,
+               "lars_update: workspace %zu < %zu bytes", workspace_bytes,
+               lars_update_workspace_bytes(d, table_host));
+  RN50_REQUIRE(total_chunks(d, table_host) < (1ll << 30), RN50_ERR_UNSUPPORTED,
+               "lars_update: too many elements");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* partial = static_cast<float*>(workspace);
+  for (int t0 = 0; t0 < d->num_tensors; t0 += kLarsMaxTensors) {
+    LarsArgs a;
+    a.num = d->num_tensors - t0 < kLarsMaxTensors ? d->num_tensors - t0 : kLarsMaxTensors;
+    a.table = table_dev + t0;
+    a.grad_bf16 = d->grad_dtype == RN50_BF16;
+    a.eta = d->eta; a.momentum = d->momentum; a.lr = d->lr; a.eps = d->eps;
+    a.partial = partial;
+    a.norms_out = norms_out ? norms_out + 2 * t0 : nullptr;
+    a.chunk_prefix[0] = 0;
+    for (int t = 0; t < a.num; ++t)
+      a.chunk_prefix[t + 1] = a.chunk_prefix[t] + static_cast<int>(ceil_div(table_host[t0 + t].n, kLarsChunk));
+    const int grid = a.chunk_prefix[a.num];
+    if (a.grad_bf16) {
+      hipLaunchKernelGGL(lars_norms_kernel<true>, dim3(grid), dim3(256), 0, s, a);
+      hipLaunchKernelGGL(lars_apply_kernel<true>, dim3(grid), dim3(256), 0, s, a);
+    } else {
+      hipLaunchKernelGGL(lars_norms_kernel<false>, dim3(grid), dim3(256), 0, s, a);
+      hipLaunchKernelGGL(lars_apply_kernel<false>, dim3(grid), dim3(256), 0, s, a);
+    }
+    partial += 2 * static_cast<size_t>(grid);
+  }
+  return launch_status("lars_update");
+}
