@@ -1,0 +1,794 @@
+// Convolution forward, data gradient and weight gradient as implicit GEMMs on
+// the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16 for bf16 storage,
+// v_mfma_f32_32x32x2_f32 for float storage; float accumulation in both).
+//
+// Forward and data gradient share one kernel, igemm_kernel:
+//     C[m][n] = sum_k A[m][k] * B[n][k]
+// where row m is an output pixel, A is gathered on the fly from the NHWC
+// activation tensor (k = tap*Cg + channel, 128 contiguous bytes per tap and row,
+// zero outside the image), and B is the weight matrix with K contiguous
+// (the KRSC weights as they are for the forward pass; for the data gradient a
+// [Cin][R][S][Cout] transposition written by a small kernel first).
+// 256 threads = 4 waves; global -> registers -> LDS double buffering (one
+// barrier per 128-byte K chunk); each wave owns 32x32 MFMA tiles fed by 16-byte
+// LDS reads; the MFMA is issued with the weight fragment as its first operand
+// so that every lane ends up with 4 consecutive output channels of one pixel,
+// which the epilogue packs, stages through LDS and stores as full rows.
+//
+// The weight gradient, wgrad_kernel, is the GEMM whose reduction runs over the
+// pixels: dw[ko][tap][c] = sum_m dy[m][ko] * A[m][tap*Cg + c].  Both operands
+// have the reduction index as their slow (row) index in memory, so tiles are
+// copied to LDS untransposed and the bf16 fragments are fetched with the
+// gfx950 transposing LDS read (ds_read_b64_tr_b16); the reduction is split over
+// workgroups and finished by a fixed-order sum (bitwise reproducible).
+#include <mutex>
+
+#include "common.h"
+
+namespace rn50 {
+
+// ----------------------------------------------------------- small utilities
+struct FastDiv {  // exact unsigned division by a runtime constant (Granlund-Montgomery)
+  uint32_t mul, sh1, sh2;
+};
+static FastDiv make_fastdiv(uint32_t d) {
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  FastDiv f;
+  f.mul = static_cast<uint32_t>(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
+  const uint32_t t = __umulhi(f.mul, n);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+template <typename T> struct Mma;
+template <> struct Mma<uint16_t> {  // bf16: one 32x32x16 MFMA per 16-byte fragment pair
+  static __device__ __forceinline__ void run(const Vec16& a, const Vec16& b, f32x16& acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a),
+                                                  *reinterpret_cast<const bf16x8*>(&b), acc, 0, 0, 0);
+  }
+};
+template <> struct Mma<float> {  // float: four 32x32x2 MFMAs (k pairs {j, 4+j} of the 8 in flight)
+  static __device__ __forceinline__ void run(const Vec16& a, const Vec16& b, f32x16& acc) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.f[j], b.f[j], acc, 0, 0, 0);
+  }
+};
+
+__device__ __forceinline__ Vec16 zero16() {
+  Vec16 v;
+  v.u = make_uint4(0, 0, 0, 0);
+  return v;
+}
+
+// ------------------------------------------------- forward / dgrad implicit GEMM
+struct IgemmArgs {
+  const void* act;  // gathered activation tensor [N][H][W] pixels of PS elements
+  const void* wgt;  // B: [Ncols][Ktot]
+  void* out;        // C: [M][Ncols]
+  int M, Ncols, Ktot;
+  int H, W;         // spatial size of the gathered tensor
+  int P, Q;         // spatial size of the output pixel grid (M = N*P*Q)
+  int PS;           // pixel stride of the gathered tensor, in elements
+  int Cg;           // channels per tap
+  int R, S, stride, pad;
+  int mode;         // 0: ih = p*stride - pad + r;  1: ih = (p + pad - r)/stride when divisible
+  int cpt;          // 128-byte chunks per tap
+  int ntn;          // number of column tiles
+};
+
+constexpr int kPitch = 144;  // LDS row pitch of a 128-byte K chunk (conflict-free 16-byte reads)
+
+template <typename T, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
+  constexpr int V = 16 / sizeof(T);
+  constexpr int BK = 128 / sizeof(T);
+  constexpr int RA = BM / 32, RB = BN / 32;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int STAGE = (BM + BN) * kPitch;
+  constexpr int CP = BN * sizeof(T) + 16;  // epilogue pitch
+  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+  static_assert(BM * CP <= 2 * STAGE, "epilogue tile must fit in the pipeline buffers");
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x, piece = tid & 7, lrow = tid >> 3;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave % WM, wn = wave / WM;
+  const int nt = blockIdx.x % a.ntn, mt = blockIdx.x / a.ntn;
+  const int m0 = mt * BM, n0 = nt * BN;
+  const T* act = static_cast<const T*>(a.act);
+  const T* wgt = static_cast<const T*>(a.wgt);
+
+  // per-thread rows of the A tile: decode the output pixel once
+  int a_h0[RA], a_w0[RA], a_base[RA];
+  bool a_ok[RA];
+#pragma unroll
+  for (int i = 0; i < RA; ++i) {
+    const int m = m0 + lrow + 32 * i;
+    a_ok[i] = m < a.M;
+    const int mm = a_ok[i] ? m : 0;
+    const int q = mm % a.Q, t = mm / a.Q;
+    const int p = t % a.P, n = t / a.P;
+    a_base[i] = n * a.H * a.W;
+    if (a.mode == 0) {
+      a_h0[i] = p * a.stride - a.pad;
+      a_w0[i] = q * a.stride - a.pad;
+    } else {
+      a_h0[i] = p + a.pad;
+      a_w0[i] = q + a.pad;
+    }
+  }
+  int b_off[RB];
+  bool b_ok[RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    const int n = n0 + lrow + 32 * i;
+    b_ok[i] = n < a.Ncols;
+    b_off[i] = (b_ok[i] ? n : 0) * a.Ktot;
+  }
+
+  Vec16 ra[RA], rb[RB];
+  auto load_chunk = [&](int kc) {
+    const int tap = kc / a.cpt;
+    const int c = (kc - tap * a.cpt) * BK + piece * V;
+    const bool cval = c < a.Cg;
+    const int r = tap / a.S, s = tap - r * a.S;
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+      int ih, iw;
+      bool ok = a_ok[i] && cval;
+      if (a.mode == 0) {
+        ih = a_h0[i] + r;
+        iw = a_w0[i] + s;
+      } else {
+        const int th = a_h0[i] - r, tw = a_w0[i] - s;
+        const int msk = a.stride - 1;  // stride is 1 or 2
+        ok = ok && th >= 0 && tw >= 0 && ((th | tw) & msk) == 0;
+        ih = th >> msk;
+        iw = tw >> msk;
+      }
+      ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
+           static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
+      ra[i] = ok ? load16(act + (static_cast<int64_t>(a_base[i] + ih * a.W + iw) * a.PS + c)) : zero16();
+    }
+    const int kb = tap * a.Cg + c;
+#pragma unroll
+    for (int i = 0; i < RB; ++i) rb[i] = (b_ok[i] && cval) ? load16(wgt + (static_cast<int64_t>(b_off[i]) + kb)) : zero16();
+  };
+  auto store_chunk = [&](int stage) {
+    unsigned char* sa = smem + stage * STAGE;
+    unsigned char* sb = sa + BM * kPitch;
+#pragma unroll
+    for (int i = 0; i < RA; ++i) *reinterpret_cast<uint4*>(sa + (lrow + 32 * i) * kPitch + piece * 16) = ra[i].u;
+#pragma unroll
+    for (int i = 0; i < RB; ++i) *reinterpret_cast<uint4*>(sb + (lrow + 32 * i) * kPitch + piece * 16) = rb[i].u;
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nchunks = a.R * a.S * a.cpt;
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  const int frag_off = (lane & 31) * kPitch + (lane >> 5) * 16;
+  for (int kc = 0; kc < nchunks; ++kc) {
+    const bool more = kc + 1 < nchunks;
+    if (more) load_chunk(kc + 1);
+    const unsigned char* sa = smem + (kc & 1) * STAGE + wm * (BM / WM) * kPitch + frag_off;
+    const unsigned char* sb = smem + (kc & 1) * STAGE + BM * kPitch + wn * (BN / WN) * kPitch + frag_off;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      Vec16 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i].u = *reinterpret_cast<const uint4*>(sa + i * 32 * kPitch + kk * 32);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j].u = *reinterpret_cast<const uint4*>(sb + j * 32 * kPitch + kk * 32);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) Mma<T>::run(fb[j], fa[i], acc[i][j]);  // D'[n][m]
+    }
+    if (more) store_chunk((kc + 1) & 1);
+    __syncthreads();
+  }
+
+  // Epilogue.  acc[i][j][v]: output channel n = j*32 + (v/4)*8 + (lane/32)*4 + v%4, pixel m = i*32 + lane%32.
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int row = wm * (BM / WM) + i * 32 + (lane & 31);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = wn * (BN / WN) + j * 32 + g * 8 + (lane >> 5) * 4;
+        unsigned char* dst = smem + row * CP + col * sizeof(T);
+        if (sizeof(T) == 2) {
+          uint2 p;
+          p.x = float_to_bf16_bits(acc[i][j][g * 4 + 0]) | (static_cast<uint32_t>(float_to_bf16_bits(acc[i][j][g * 4 + 1])) << 16);
+          p.y = float_to_bf16_bits(acc[i][j][g * 4 + 2]) | (static_cast<uint32_t>(float_to_bf16_bits(acc[i][j][g * 4 + 3])) << 16);
+          *reinterpret_cast<uint2*>(dst) = p;
+        } else {
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+        }
+      }
+    }
+  __syncthreads();
+  constexpr int PPR = BN * sizeof(T) / 16;  // 16-byte pieces per output row
+  constexpr int RPP = 256 / PPR;            // rows per pass
+  T* out = static_cast<T*>(a.out);
+  const int op = tid % PPR, orow = tid / PPR;
+#pragma unroll
+  for (int pass = 0; pass < BM / RPP; ++pass) {
+    const int row = orow + pass * RPP;
+    const int m = m0 + row, n = n0 + op * V;
+    if (m < a.M && n < a.Ncols)
+      *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) =
+          *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+  }
+}
+
+// ------------------------------------------------------------ weight gradient
+struct WgradArgs {
+  const void* x;   // gathered activation tensor (as in IgemmArgs, mode 0)
+  const void* dy;  // [M][Cout]
+  float* out;      // dw [Cout][Ktot], or split partials
+  int M, Cout, Ktot;
+  int H, W, P, Q, PS, Cg, R, S, stride, pad;
+  int ctiles;          // column tiles per tap
+  int rows_per_split;  // multiple of the K chunk
+  int64_t split_stride;
+  FastDiv divQ, divP;
+};
+
+template <typename T> struct WgradCfg;
+template <> struct WgradCfg<uint16_t> { static constexpr int BKM = 64; };
+template <> struct WgradCfg<float> { static constexpr int BKM = 32; };
+
+// Fragment of a [k][col] LDS tile for the MFMA operand "32 columns x 16 (8 for float) k".
+template <typename T>
+__device__ __forceinline__ Vec16 load_frag_kmajor(const unsigned char* tile, int pitch, int col0, int k0, int lane);
+template <>
+__device__ __forceinline__ Vec16 load_frag_kmajor<uint16_t>(const unsigned char* tile, int pitch, int col0, int k0, int lane) {
+  // ds_read_b64_tr_b16: within 16 lanes, lane t supplies the address of row t/4, columns 4*(t%4)..+3 and
+  // receives column t of rows 0..3.  Two reads give 8 k values of column lane%32.
+  const int g = lane >> 4, t = lane & 15;
+  const int krow = k0 + 8 * (g >> 1) + (t >> 2);
+  const int col = col0 + 16 * (g & 1) + 4 * (t & 3);
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const unsigned char* p0 = tile + krow * pitch + col * 2;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * pitch));
+  Vec16 v;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    v.h[j] = static_cast<uint16_t>(lo[j]);
+    v.h[4 + j] = static_cast<uint16_t>(hi[j]);
+  }
+  return v;
+}
+template <>
+__device__ __forceinline__ Vec16 load_frag_kmajor<float>(const unsigned char* tile, int pitch, int col0, int k0, int lane) {
+  Vec16 v;
+  const unsigned char* p = tile + (k0 + (lane >> 5) * 4) * pitch + (col0 + (lane & 31)) * 4;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v.f[j] = *reinterpret_cast<const float*>(p + j * pitch);
+  return v;
+}
+
+template <typename T, int BMO, int BC>
+__global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
+  constexpr int V = 16 / sizeof(T);
+  constexpr int BKM = WgradCfg<T>::BKM;
+  constexpr int KSTEP = sizeof(T) == 2 ? 16 : 8;
+  constexpr int PA = BMO * sizeof(T) + 64, PB = BC * sizeof(T) + 64;  // LDS pitches
+  constexpr int PPRA = BMO / V, PPRB = BC / V;                        // 16-byte pieces per row
+  constexpr int NA = BKM * PPRA / 256, NB = BKM * PPRB / 256;         // pieces per thread
+  constexpr int STAGE = BKM * (PA + PB);
+  constexpr int TM = BMO / 64, TN = BC / 64;  // 2x2 waves
+  static_assert(NA >= 1 && NB >= 1, "tile too small");
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int tap = blockIdx.x / a.ctiles, c0 = (blockIdx.x - tap * a.ctiles) * BC;
+  const int r = tap / a.S, s = tap - r * a.S;
+  const int ko0 = blockIdx.y * BMO;
+  const int row_begin = blockIdx.z * a.rows_per_split;
+  const int row_end = min(row_begin + a.rows_per_split, a.M);
+  const T* x = static_cast<const T*>(a.x);
+  const T* dy = static_cast<const T*>(a.dy);
+
+  const int pa = tid % PPRA, rowa = tid / PPRA;
+  const int pb = tid % PPRB, rowb = tid / PPRB;
+  const bool a_col_ok = ko0 + pa * V < a.Cout;
+  const bool b_col_ok = c0 + pb * V < a.Cg;
+
+  Vec16 ra[NA], rb[NB];
+  auto load_chunk = [&](int m_base) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      const int m = m_base + rowa + i * (256 / PPRA);
+      ra[i] = (a_col_ok && m < row_end) ? load16(dy + (static_cast<int64_t>(m) * a.Cout + ko0 + pa * V)) : zero16();
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int m = m_base + rowb + i * (256 / PPRB);
+      bool ok = b_col_ok && m < row_end;
+      const uint32_t mm = ok ? static_cast<uint32_t>(m) : 0u;
+      const uint32_t t = fdiv(mm, a.divQ);
+      const int q = static_cast<int>(mm - t * a.Q);
+      const uint32_t n = fdiv(t, a.divP);
+      const int p = static_cast<int>(t - n * a.P);
+      const int ih = p * a.stride - a.pad + r, iw = q * a.stride - a.pad + s;
+      ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
+           static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
+      rb[i] = ok ? load16(x + (static_cast<int64_t>((static_cast<int>(n) * a.H + ih) * a.W + iw) * a.PS + c0 + pb * V)) : zero16();
+    }
+  };
+  auto store_chunk = [&](int stage) {
+    unsigned char* sa = smem + stage * STAGE;
+    unsigned char* sb = sa + BKM * PA;
+#pragma unroll
+    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(sa + (rowa + i * (256 / PPRA)) * PA + pa * 16) = ra[i].u;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(sb + (rowb + i * (256 / PPRB)) * PB + pb * 16) = rb[i].u;
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nchunks = (row_end - row_begin + BKM - 1) / BKM;
+  if (nchunks > 0) {
+    load_chunk(row_begin);
+    store_chunk(0);
+  }
+  __syncthreads();
+  for (int kc = 0; kc < nchunks; ++kc) {
+    const bool more = kc + 1 < nchunks;
+    if (more) load_chunk(row_begin + (kc + 1) * BKM);
+    const unsigned char* sa = smem + (kc & 1) * STAGE;
+    const unsigned char* sb = sa + BKM * PA;
+#pragma unroll
+    for (int kk = 0; kk < BKM / KSTEP; ++kk) {
+      Vec16 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = load_frag_kmajor<T>(sa, PA, wm * (BMO / 2) + i * 32, kk * KSTEP, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = load_frag_kmajor<T>(sb, PB, wn * (BC / 2) + j * 32, kk * KSTEP, lane);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) Mma<T>::run(fa[i], fb[j], acc[i][j]);  // D[ko][c]
+    }
+    if (more) store_chunk((kc + 1) & 1);
+    __syncthreads();
+  }
+
+  // acc[i][j][v]: ko = i*32 + (v/4)*8 + (lane/32)*4 + v%4, c = j*32 + lane%32
+  float* out = a.out + static_cast<int64_t>(blockIdx.z) * a.split_stride;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int c = c0 + wn * (BC / 2) + j * 32 + (lane & 31);
+      if (c >= a.Cg) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ko = ko0 + wm * (BMO / 2) + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (ko < a.Cout) out[static_cast<int64_t>(ko) * a.Ktot + tap * a.Cg + c] = acc[i][j][v];
+      }
+    }
+}
+
+// dw[i] = sum_s partial[s][i], s ascending
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                            int64_t n, float* __restrict__ out) {
+  const int64_t i = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  if (i + 4 <= n) {
+    float4 s = *reinterpret_cast<const float4*>(partial + i);
+    for (int k = 1; k < splits; ++k) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + k * n + i);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    *reinterpret_cast<float4*>(out + i) = s;
+  } else {
+    for (int64_t j = i; j < n; ++j) {
+      float s = partial[j];
+      for (int k = 1; k < splits; ++k) s += partial[k * n + j];
+      out[j] = s;
+    }
+  }
+}
+
+// ------------------------------------------------------- layout helper kernels
+// wT[c][t][k] = w[k][t][c]  (t = r*S+s): the B matrix of the data gradient.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kc_kernel(const T* __restrict__ w, T* __restrict__ wT,
+                                                           int K, int taps, int C) {
+  __shared__ T tile[32][33];
+  const int t = blockIdx.z, c0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8) {
+    const int k = k0 + i, c = c0 + tx;
+    if (k < K && c < C) tile[i][tx] = w[(static_cast<int64_t>(k) * taps + t) * C + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, k = k0 + tx;
+    if (k < K && c < C) wT[(static_cast<int64_t>(c) * taps + t) * K + k] = tile[tx][i];
+  }
+}
+
+// Stem input: x [N][H][W][3] -> xp [N][H+6][Wp][4], zero border (3 pixels each side, Wp - W - 3 on the
+// right) and zero 4th channel, so that a 7-tap filter row is 8 pixels = 32 contiguous elements.
+template <typename T>
+__global__ __launch_bounds__(256) void stem_pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp,
+                                                             int N, int H, int W, int Hp, int Wp) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= static_cast<int64_t>(N) * Hp * Wp) return;
+  const int wq = static_cast<int>(i % Wp);
+  const int64_t t = i / Wp;
+  const int hq = static_cast<int>(t % Hp), n = static_cast<int>(t / Hp);
+  const int h = hq - 3, w = wq - 3;
+  T v[4] = {0, 0, 0, 0};
+  if (h >= 0 && h < H && w >= 0 && w < W) {
+    const T* s = x + ((static_cast<int64_t>(n) * H + h) * W + w) * 3;
+    v[0] = s[0]; v[1] = s[1]; v[2] = s[2];
+  }
+  T* d = xp + i * 4;
+  d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+}
+// Stem weights: w [K][7][7][3] -> wp [K][7][8][4] with zeros in tap column 7 and channel 3.
+template <typename T>
+__global__ __launch_bounds__(256) void stem_pad_weight_kernel(const T* __restrict__ w, T* __restrict__ wp, int K) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K * 7 * 32) return;
+  const int c = i & 3, s = (i >> 2) & 7, r = (i >> 5) % 7, k = i / 224;
+  wp[i] = (c < 3 && s < 7) ? w[((k * 7 + r) * 7 + s) * 3 + c] : static_cast<T>(0);
+}
+// dw [K][7][7][3] <- dwp [K][7][8][4]
+__global__ __launch_bounds__(256) void stem_unpad_dw_kernel(const float* __restrict__ dwp, float* __restrict__ dw, int K) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K * 147) return;
+  const int c = i % 3, s = (i / 3) % 7, r = (i / 21) % 7, k = i / 147;
+  dw[i] = dwp[((k * 7 + r) * 8 + s) * 4 + c];
+}
+
+// ------------------------------------------------------------------ host side
+template <typename K>
+static void allow_big_lds(K kernel, int bytes) {
+  if (bytes > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+static void launch_igemm_cfg(IgemmArgs a, hipStream_t s) {
+  constexpr int lds = 2 * (BM + BN) * kPitch;
+  static std::once_flag once;
+  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN>, lds); });
+  a.ntn = static_cast<int>(ceil_div(a.Ncols, BN));
+  const int64_t grid = ceil_div(a.M, BM) * a.ntn;
+  hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a);
+}
+
+// Tile choice: the widest tile that still gives every CU a couple of workgroups.
+template <typename T>
+static void launch_igemm(const IgemmArgs& a, hipStream_t s) {
+  const int64_t target = 512;
+  auto blocks = [&](int bm, int bn) { return ceil_div(a.M, bm) * ceil_div(a.Ncols, bn); };
+  if (a.Ncols > 64 && blocks(128, 128) >= target) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, s);
+  if (blocks(128, 64) >= target) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, s);
+  if (a.Ncols > 64 && blocks(64, 128) >= target / 2) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, s);
+  return launch_igemm_cfg<T, 64, 64, 2, 2>(a, s);
+}
+
+struct WgradPlan {
+  int bmo, bc, ctiles, splits, rows_per_split;
+};
+static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype) {
+  WgradPlan p;
+  const int bkm = dtype == RN50_BF16 ? 64 : 32;
+  p.bmo = Cout > 64 ? 128 : 64;
+  p.bc = Cg > 64 ? 128 : 64;
+  p.ctiles = static_cast<int>(ceil_div(Cg, p.bc));
+  const int64_t tiles = static_cast<int64_t>(taps) * p.ctiles * ceil_div(Cout, p.bmo);
+  int64_t splits = ceil_div(1024, tiles);
+  const int64_t max_splits = ceil_div(M, 4 * bkm);
+  if (splits > max_splits) splits = max_splits;
+  if (splits < 1) splits = 1;
+  int64_t rps = ceil_div(ceil_div(M, splits), bkm) * bkm;
+  p.rows_per_split = static_cast<int>(rps);
+  p.splits = static_cast<int>(ceil_div(M, rps));
+  return p;
+}
+
+template <typename T, int BMO, int BC>
+static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
+  constexpr int BKM = WgradCfg<T>::BKM;
+  constexpr int lds = 2 * BKM * ((BMO + BC) * static_cast<int>(sizeof(T)) + 128);
+  static std::once_flag once;
+  std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC>, lds); });
+  const dim3 grid(a.R * a.S * a.ctiles, static_cast<unsigned>(ceil_div(a.Cout, BMO)), splits);
+  hipLaunchKernelGGL((wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, a);
+}
+
+template <typename T>
+static void launch_wgrad(WgradArgs a, const WgradPlan& p, float* dw, float* partial, hipStream_t s) {
+  a.ctiles = p.ctiles;
+  a.rows_per_split = p.rows_per_split;
+  a.split_stride = static_cast<int64_t>(a.Cout) * a.Ktot;
+  a.out = p.splits > 1 ? partial : dw;
+  a.divQ = make_fastdiv(a.Q);
+  a.divP = make_fastdiv(a.P);
+  if (p.bmo == 128 && p.bc == 128) launch_wgrad_cfg<T, 128, 128>(a, p.splits, s);
+  else if (p.bmo == 128) launch_wgrad_cfg<T, 128, 64>(a, p.splits, s);
+  else if (p.bc == 128) launch_wgrad_cfg<T, 64, 128>(a, p.splits, s);
+  else launch_wgrad_cfg<T, 64, 64>(a, p.splits, s);
+  if (p.splits > 1) {
+    const int64_t n = a.split_stride;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 256))), dim3(256), 0, s,
+                       partial, p.splits, n, dw);
+  }
+}
+
+static int out_dim(int in, int pad, int k, int stride) { return (in + 2 * pad - k) / stride + 1; }
+static bool is_stem(const rn50_conv_desc* d) {
+  return d->Cin == 3 && d->R == 7 && d->S == 7 && d->stride == 2 && d->pad == 3;
+}
+static int esize(int dtype) { return dtype == RN50_BF16 ? 2 : 4; }
+
+static int check_conv(const rn50_conv_desc* d, const char* who) {
+  RN50_REQUIRE(d, RN50_ERR_INVALID, "%s: null descriptor", who);
+  RN50_REQUIRE(d->N > 0 && d->H > 0 && d->W > 0 && d->Cin > 0 && d->Cout > 0 && d->R > 0 && d->S > 0 &&
+                   d->stride > 0 && d->pad >= 0,
+               RN50_ERR_INVALID, "%s: non-positive size", who);
+  RN50_REQUIRE(d->dtype == RN50_F32 || d->dtype == RN50_BF16, RN50_ERR_INVALID, "%s: dtype %d", who, d->dtype);
+  const int V = 16 / esize(d->dtype);
+  RN50_REQUIRE(d->H + 2 * d->pad >= d->R && d->W + 2 * d->pad >= d->S, RN50_ERR_INVALID, "%s: filter larger than padded input", who);
+  RN50_REQUIRE(d->Cout % V == 0, RN50_ERR_UNSUPPORTED, "%s: Cout=%d is not a multiple of %d", who, d->Cout, V);
+  RN50_REQUIRE(d->Cin % V == 0 || is_stem(d), RN50_ERR_UNSUPPORTED,
+               "%s: Cin=%d is neither a multiple of %d nor the 7x7/2 pad-3 stem", who, d->Cin, V);
+  RN50_REQUIRE(d->pad < d->R && d->pad < d->S, RN50_ERR_UNSUPPORTED, "%s: pad >= filter size", who);
+  const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
+  const int64_t lim = (1ll << 31) - 1;
+  RN50_REQUIRE(static_cast<int64_t>(d->N) * (d->H + 6) * (d->W + 16) * (d->Cin < 4 ? 4 : d->Cin) < lim &&
+                   static_cast<int64_t>(d->N) * P * Q * d->Cout < lim &&
+                   static_cast<int64_t>(d->Cout) * d->R * d->S * (d->Cin < 4 ? 32 : d->Cin) < lim,
+               RN50_ERR_UNSUPPORTED, "%s: tensor has 2^31 or more elements", who);
+  return RN50_OK;
+}
+
+// Geometry of the padded stem: 7 "taps" (filter rows) of 32 elements on pixels of 4 channels.
+struct StemGeom {
+  int Hp, Wp;
+  size_t xp_bytes, wp_bytes;
+};
+static StemGeom stem_geom(const rn50_conv_desc* d) {
+  StemGeom g;
+  g.Hp = d->H + 6;
+  g.Wp = (d->W + 6 + 2 + 3) / 4 * 4;  // room for the 8th (zero-weight) tap, row pitch a multiple of 16 bytes
+  g.xp_bytes = align_up(static_cast<size_t>(d->N) * g.Hp * g.Wp * 4 * esize(d->dtype), 256);
+  g.wp_bytes = align_up(static_cast<size_t>(d->Cout) * 224 * esize(d->dtype), 256);
+  return g;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+// Internal entry points shared with the whole-step driver (declared in step_internal.h).
+namespace rn50 {
+
+void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_t s) {
+  const StemGeom g = stem_geom(d);
+  const int64_t n = static_cast<int64_t>(d->N) * g.Hp * g.Wp;
+  if (d->dtype == RN50_BF16)
+    hipLaunchKernelGGL(stem_pad_input_kernel<uint16_t>, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s,
+                       static_cast<const uint16_t*>(x), static_cast<uint16_t*>(xp), d->N, d->H, d->W, g.Hp, g.Wp);
+  else
+    hipLaunchKernelGGL(stem_pad_input_kernel<float>, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s,
+                       static_cast<const float*>(x), static_cast<float*>(xp), d->N, d->H, d->W, g.Hp, g.Wp);
+}
+
+size_t stem_padded_input_bytes(const rn50_conv_desc* d) { return stem_geom(d).xp_bytes; }
+size_t stem_padded_weight_bytes(const rn50_conv_desc* d) { return stem_geom(d).wp_bytes; }
+
+static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const void* wp, void* y) {
+  const StemGeom g = stem_geom(d);
+  IgemmArgs a{};
+  a.act = xp; a.wgt = wp; a.out = y;
+  a.P = out_dim(d->H, 3, 7, 2); a.Q = out_dim(d->W, 3, 7, 2);
+  a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = 224;
+  a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.Cg = 32; a.R = 7; a.S = 1; a.stride = 2; a.pad = 0; a.mode = 0;
+  a.cpt = 1;
+  return a;
+}
+
+// Forward of the stem from an already padded input; wp is scratch for the padded weights.
+void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, hipStream_t s) {
+  const int nw = d->Cout * 224;
+  if (d->dtype == RN50_BF16) {
+    hipLaunchKernelGGL(stem_pad_weight_kernel<uint16_t>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
+                       static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wp), d->Cout);
+    launch_igemm<uint16_t>(stem_igemm_args(d, xp, wp, y), s);
+  } else {
+    hipLaunchKernelGGL(stem_pad_weight_kernel<float>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
+                       static_cast<const float*>(w), static_cast<float*>(wp), d->Cout);
+    launch_igemm<float>(stem_igemm_args(d, xp, wp, y), s);
+  }
+}
+
+static WgradArgs wgrad_args(const rn50_conv_desc* d, const void* x, const void* dy) {
+  WgradArgs a{};
+  a.x = x; a.dy = dy;
+  a.P = out_dim(d->H, d->pad, d->R, d->stride); a.Q = out_dim(d->W, d->pad, d->S, d->stride);
+  a.M = d->N * a.P * a.Q; a.Cout = d->Cout; a.Ktot = d->R * d->S * d->Cin;
+  a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
+  return a;
+}
+static WgradArgs stem_wgrad_args(const rn50_conv_desc* d, const void* xp, const void* dy) {
+  const StemGeom g = stem_geom(d);
+  WgradArgs a{};
+  a.x = xp; a.dy = dy;
+  a.P = out_dim(d->H, 3, 7, 2); a.Q = out_dim(d->W, 3, 7, 2);
+  a.M = d->N * a.P * a.Q; a.Cout = d->Cout; a.Ktot = 224;
+  a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.Cg = 32; a.R = 7; a.S = 1; a.stride = 2; a.pad = 0;
+  return a;
+}
+
+size_t wgrad_partial_bytes(const rn50_conv_desc* d) {
+  const bool stem = is_stem(d);
+  const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
+  const int M = d->N * P * Q;
+  const WgradPlan p = stem ? plan_wgrad(M, d->Cout, 32, 7, d->dtype) : plan_wgrad(M, d->Cout, d->Cin, d->R * d->S, d->dtype);
+  const size_t dw_elems = static_cast<size_t>(d->Cout) * (stem ? 224 : d->R * d->S * d->Cin);
+  size_t b = p.splits > 1 ? align_up(dw_elems * p.splits * sizeof(float), 256) : 0;
+  if (stem) b += align_up(dw_elems * sizeof(float), 256);  // padded dw
+  return b;
+}
+
+// Weight gradient; for the stem x must be the padded input.  scratch: wgrad_partial_bytes(d).
+void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s) {
+  const bool stem = is_stem(d);
+  WgradArgs a = stem ? stem_wgrad_args(d, x_or_xp, dy) : wgrad_args(d, x_or_xp, dy);
+  const WgradPlan p = plan_wgrad(a.M, a.Cout, a.Cg, a.R * a.S, d->dtype);
+  float* partial = static_cast<float*>(scratch);
+  float* target = dw;
+  if (stem) {
+    target = partial;
+    partial += align_up(static_cast<size_t>(d->Cout) * 224 * sizeof(float), 256) / sizeof(float);
+  }
+  if (d->dtype == RN50_BF16) launch_wgrad<uint16_t>(a, p, target, partial, s);
+  else launch_wgrad<float>(a, p, target, partial, s);
+  if (stem)
+    hipLaunchKernelGGL(stem_unpad_dw_kernel, dim3(ceil_div(d->Cout * 147, 256)), dim3(256), 0, s, target, dw, d->Cout);
+}
+
+void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hipStream_t s) {
+  IgemmArgs a{};
+  a.act = x; a.wgt = w; a.out = y;
+  a.P = out_dim(d->H, d->pad, d->R, d->stride); a.Q = out_dim(d->W, d->pad, d->S, d->stride);
+  a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = d->R * d->S * d->Cin;
+  a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
+  a.mode = 0;
+  a.cpt = static_cast<int>(ceil_div(d->Cin * esize(d->dtype), 128));
+  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, s); else launch_igemm<float>(a, s);
+}
+
+size_t dgrad_wt_bytes(const rn50_conv_desc* d) {
+  return align_up(static_cast<size_t>(d->Cout) * d->R * d->S * d->Cin * esize(d->dtype), 256);
+}
+void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, hipStream_t s) {
+  const dim3 grid(ceil_div(d->Cin, 32), ceil_div(d->Cout, 32), d->R * d->S);
+  if (d->dtype == RN50_BF16)
+    hipLaunchKernelGGL(transpose_kc_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(w),
+                       static_cast<uint16_t*>(wT), d->Cout, d->R * d->S, d->Cin);
+  else
+    hipLaunchKernelGGL(transpose_kc_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(w),
+                       static_cast<float*>(wT), d->Cout, d->R * d->S, d->Cin);
+}
+// Data gradient from already transposed weights wT [Cin][R][S][Cout].
+void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, hipStream_t s) {
+  IgemmArgs a{};
+  a.act = dy; a.wgt = wT; a.out = dx;
+  a.P = d->H; a.Q = d->W;
+  a.H = out_dim(d->H, d->pad, d->R, d->stride); a.W = out_dim(d->W, d->pad, d->S, d->stride);
+  a.M = d->N * d->H * d->W; a.Ncols = d->Cin; a.Ktot = d->R * d->S * d->Cout;
+  a.PS = d->Cout; a.Cg = d->Cout; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
+  a.mode = 1;
+  a.cpt = static_cast<int>(ceil_div(d->Cout * esize(d->dtype), 128));
+  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, s); else launch_igemm<float>(a, s);
+}
+
+}  // namespace rn50
+
+extern "C" size_t conv_fwd_workspace_bytes(const rn50_conv_desc* d) {
+  if (!d || check_conv(d, "conv_fwd_workspace_bytes")) return 0;
+  if (!is_stem(d)) return 0;
+  const StemGeom g = stem_geom(d);
+  return g.xp_bytes + g.wp_bytes;
+}
+extern "C" size_t conv_dgrad_workspace_bytes(const rn50_conv_desc* d) {
+  if (!d || check_conv(d, "conv_dgrad_workspace_bytes")) return 0;
+  return dgrad_wt_bytes(d);
+}
+extern "C" size_t conv_wgrad_workspace_bytes(const rn50_conv_desc* d) {
+  if (!d || check_conv(d, "conv_wgrad_workspace_bytes")) return 0;
+  return wgrad_partial_bytes(d) + (is_stem(d) ? stem_geom(d).xp_bytes : 0);
+}
+
+extern "C" int conv_fwd(const rn50_conv_desc* d, const void* x, const void* w, void* y, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_fwd")) return rc;
+  RN50_REQUIRE(x && w && y, RN50_ERR_INVALID, "conv_fwd: null pointer");
+  RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(workspace), RN50_ERR_ALIGN,
+               "conv_fwd: pointer not 16-byte aligned");
+  const size_t need = conv_fwd_workspace_bytes(d);
+  RN50_REQUIRE(workspace_bytes >= need && (need == 0 || workspace), RN50_ERR_WORKSPACE,
+               "conv_fwd: workspace %zu < %zu bytes", workspace_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (is_stem(d)) {
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    stem_pad_input(d, x, ws, s);
+    stem_fwd_padded(d, ws, w, ws + stem_geom(d).xp_bytes, y, s);
+  } else {
+    fwd_run(d, x, w, y, s);
+  }
+  return launch_status("conv_fwd");
+}
+
+extern "C" int conv_dgrad(const rn50_conv_desc* d, const void* dy, const void* w, void* dx, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_dgrad")) return rc;
+  RN50_REQUIRE(!is_stem(d) && d->Cin % (16 / esize(d->dtype)) == 0, RN50_ERR_UNSUPPORTED,
+               "conv_dgrad: the 3-channel stem has no data gradient here (the network input needs none)");
+  RN50_REQUIRE(d->stride == 1 || d->stride == 2, RN50_ERR_UNSUPPORTED, "conv_dgrad: stride %d", d->stride);
+  RN50_REQUIRE(dy && w && dx && workspace, RN50_ERR_INVALID, "conv_dgrad: null pointer");
+  RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(workspace), RN50_ERR_ALIGN,
+               "conv_dgrad: pointer not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= dgrad_wt_bytes(d), RN50_ERR_WORKSPACE, "conv_dgrad: workspace %zu < %zu bytes",
+               workspace_bytes, dgrad_wt_bytes(d));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  dgrad_transpose_weights(d, w, workspace, s);
+  dgrad_run(d, dy, workspace, dx, s);
+  return launch_status("conv_dgrad");
+}
+
+extern "C" int conv_wgrad(const rn50_conv_desc* d, const void* x, const void* dy, float* dw, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_wgrad")) return rc;
+  RN50_REQUIRE(x && dy && dw, RN50_ERR_INVALID, "conv_wgrad: null pointer");
+  RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dw) && aligned16(workspace), RN50_ERR_ALIGN,
+               "conv_wgrad: pointer not 16-byte aligned");
+  const size_t need = conv_wgrad_workspace_bytes(d);
+  RN50_REQUIRE(workspace_bytes >= need && (need == 0 || workspace), RN50_ERR_WORKSPACE,
+               "conv_wgrad: workspace %zu < %zu bytes", workspace_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  if (is_stem(d)) {
+    stem_pad_input(d, x, ws, s);
+    wgrad_run(d, ws, dy, dw, ws + stem_geom(d).xp_bytes, s);
+  } else {
+    wgrad_run(d, x, dy, dw, ws, s);
+  }
+  return launch_status("conv_wgrad");
+}
