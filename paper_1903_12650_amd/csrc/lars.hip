@@ -10,6 +10,7 @@
 // w, v written) + 2 B for the bf16 model copy.  The second read of w and g can
 // be served by the 256 MB last-level cache when the model fits.
 #include "common.h"
+#include "step_internal.h"
 
 namespace rn50 {
 
@@ -24,9 +25,42 @@ struct LarsArgs {
   float* partial;    // [total_chunks][2]
   float* norms_out;  // [num][2] or null, offset like table
   int chunk_prefix[kLarsMaxTensors + 1];
+  __device__ __forceinline__ rn50_lars_tensor tensor(int t) const { return table[t]; }
 };
 
-__device__ __forceinline__ int find_tensor(const LarsArgs& a, int chunk) {
+// The same launch for tensors that live at known offsets of four arenas (the whole-step
+// driver): the table travels entirely in the kernel arguments.
+constexpr int kLarsArenaMaxTensors = 192;
+struct LarsArenaArgs {
+  float* master;
+  const void* grads;
+  float* velocity;
+  uint16_t* lowp;  // or null
+  int num;
+  int grad_bf16;
+  float eta, momentum, lr, eps, weight_decay;
+  float* partial;
+  float* norms_out;
+  uint32_t offset[kLarsArenaMaxTensors];  // elements
+  uint32_t count[kLarsArenaMaxTensors];
+  uint32_t decay_mask[kLarsArenaMaxTensors / 32];
+  int chunk_prefix[kLarsArenaMaxTensors + 1];
+  __device__ __forceinline__ rn50_lars_tensor tensor(int t) const {
+    rn50_lars_tensor T;
+    T.w = master + offset[t];
+    T.g = grad_bf16 ? static_cast<const void*>(static_cast<const uint16_t*>(grads) + offset[t])
+                    : static_cast<const void*>(static_cast<const float*>(grads) + offset[t]);
+    T.v = velocity + offset[t];
+    T.w_lowp = lowp ? lowp + offset[t] : nullptr;
+    T.n = count[t];
+    T.weight_decay = ((decay_mask[t >> 5] >> (t & 31)) & 1u) ? weight_decay : 0.f;
+    T.apply_trust = 1;
+    return T;
+  }
+};
+
+template <typename Args>
+__device__ __forceinline__ int find_tensor(const Args& a, int chunk) {
   int lo = 0, hi = a.num;  // invariant: prefix[lo] <= chunk < prefix[hi]
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
@@ -54,12 +88,12 @@ __device__ __forceinline__ float load_g1(const void* g, int64_t i) {
   return static_cast<const float*>(g)[i];
 }
 
-template <bool GBF16>
-__global__ __launch_bounds__(256) void lars_norms_kernel(const LarsArgs a) {
+template <bool GBF16, typename Args>
+__global__ __launch_bounds__(256) void lars_norms_kernel(const Args a) {
   __shared__ float red[8];
   const int chunk = blockIdx.x;
   const int t = find_tensor(a, chunk);
-  const rn50_lars_tensor T = a.table[t];
+  const rn50_lars_tensor T = a.tensor(t);
   const int64_t base = static_cast<int64_t>(chunk - a.chunk_prefix[t]) * kLarsChunk;
   const int64_t end = min(base + static_cast<int64_t>(kLarsChunk), T.n);
   const int64_t vend = base + ((end - base) & ~static_cast<int64_t>(3));
@@ -84,12 +118,12 @@ __global__ __launch_bounds__(256) void lars_norms_kernel(const LarsArgs a) {
   }
 }
 
-template <bool GBF16>
-__global__ __launch_bounds__(256) void lars_apply_kernel(const LarsArgs a) {
+template <bool GBF16, typename Args>
+__global__ __launch_bounds__(256) void lars_apply_kernel(const Args a) {
   __shared__ float red[8];
   const int chunk = blockIdx.x;
   const int t = find_tensor(a, chunk);
-  const rn50_lars_tensor T = a.table[t];
+  const rn50_lars_tensor T = a.tensor(t);
   const int c0 = a.chunk_prefix[t], c1 = a.chunk_prefix[t + 1];
   // Finish the two sums of this tensor: same order in every block of the tensor.
   float sw = 0.f, sg = 0.f;
@@ -163,6 +197,37 @@ static int check_table(const rn50_lars_desc* d, const rn50_lars_tensor* tab) {
   return RN50_OK;
 }
 
+// Arena form used by the whole-step driver.  partial: lars_arena_partial_bytes().
+size_t lars_arena_partial_bytes(const LarsArenaSpec& sp) {
+  int64_t chunks = 0;
+  for (int t = 0; t < sp.num; ++t) chunks += ceil_div(sp.count[t], kLarsChunk);
+  return align_up(static_cast<size_t>(chunks) * 2 * sizeof(float), 256);
+}
+
+void lars_arena_run(const LarsArenaSpec& sp, float* master, const float* grads, float* velocity, void* lowp,
+                    float eta, float momentum, float lr, float eps, float weight_decay, float* partial,
+                    hipStream_t s) {
+  for (int t0 = 0; t0 < sp.num; t0 += kLarsArenaMaxTensors) {
+    LarsArenaArgs a{};
+    a.num = sp.num - t0 < kLarsArenaMaxTensors ? sp.num - t0 : kLarsArenaMaxTensors;
+    a.master = master; a.grads = grads; a.velocity = velocity; a.lowp = static_cast<uint16_t*>(lowp);
+    a.grad_bf16 = 0;
+    a.eta = eta; a.momentum = momentum; a.lr = lr; a.eps = eps; a.weight_decay = weight_decay;
+    a.partial = partial; a.norms_out = nullptr;
+    a.chunk_prefix[0] = 0;
+    for (int t = 0; t < a.num; ++t) {
+      a.offset[t] = static_cast<uint32_t>(sp.offset[t0 + t]);
+      a.count[t] = static_cast<uint32_t>(sp.count[t0 + t]);
+      if (sp.decay[t0 + t]) a.decay_mask[t >> 5] |= 1u << (t & 31);
+      a.chunk_prefix[t + 1] = a.chunk_prefix[t] + static_cast<int>(ceil_div(sp.count[t0 + t], kLarsChunk));
+    }
+    const int grid = a.chunk_prefix[a.num];
+    hipLaunchKernelGGL((lars_norms_kernel<false, LarsArenaArgs>), dim3(grid), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((lars_apply_kernel<false, LarsArenaArgs>), dim3(grid), dim3(256), 0, s, a);
+    partial += 2 * static_cast<size_t>(grid);
+  }
+}
+
 }  // namespace rn50
 
 using namespace rn50;
@@ -201,11 +266,11 @@ extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* tabl
       a.chunk_prefix[t + 1] = a.chunk_prefix[t] + static_cast<int>(ceil_div(table_host[t0 + t].n, kLarsChunk));
     const int grid = a.chunk_prefix[a.num];
     if (a.grad_bf16) {
-      hipLaunchKernelGGL(lars_norms_kernel<true>, dim3(grid), dim3(256), 0, s, a);
-      hipLaunchKernelGGL(lars_apply_kernel<true>, dim3(grid), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((lars_norms_kernel<true, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((lars_apply_kernel<true, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
     } else {
-      hipLaunchKernelGGL(lars_norms_kernel<false>, dim3(grid), dim3(256), 0, s, a);
-      hipLaunchKernelGGL(lars_apply_kernel<false>, dim3(grid), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((lars_norms_kernel<false, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((lars_apply_kernel<false, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
     }
     partial += 2 * static_cast<size_t>(grid);
   }

@@ -1,0 +1,307 @@
+// resnet_step: the launch sequence of one ResNet-50 v1.5 training step on the
+// local batch (forward, softmax cross-entropy, backward, LARS), all on one
+// stream, using a caller-provided workspace.  Wiring follows the paper's
+// appendix log (stem convolution stride 2 / 64 filters / no bias -> BN -> ReLU
+// -> max-pool 112 -> 56, bottleneck blocks) and He et al.; the gradient exchange
+// between workers (Sec. III-C) would sit between backward and the LARS call.
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+#include "step_internal.h"
+
+namespace rn50 {
+
+struct Unit {  // convolution + BN (+ReLU / +add+ReLU)
+  rn50_conv_desc conv;
+  rn50_bn_desc bn;
+  int iw, ig, ib;        // parameter tensor indices: weight, gamma, beta
+  size_t y, z;           // workspace offsets of the conv output and the BN output
+  size_t mean, rstd;     // workspace offsets (float[C])
+  int P, Q;
+};
+
+struct Block {
+  int u1, u2, u3, up;  // unit indices; up = -1 without projection
+};
+
+struct Tensor {
+  int dims[4];
+  int64_t count, offset;
+  bool decay;
+};
+
+}  // namespace rn50
+
+struct rn50_plan {
+  rn50_step_config cfg;
+  std::vector<rn50::Tensor> tensors;
+  std::vector<rn50::Unit> units;
+  std::vector<rn50::Block> blocks;
+  int64_t arena_elems = 0;
+  int es = 2;  // element size of the activation dtype
+  int fc_in = 0, final_hw = 0;
+  // workspace layout (byte offsets)
+  size_t ws_bytes = 0;
+  size_t xp = 0, wp = 0, pool = 0, avg = 0, logits = 0, dlogits = 0, row_loss = 0, davg = 0;
+  size_t g[5] = {0, 0, 0, 0, 0};
+  size_t wT = 0, wgrad_scratch = 0, bn_scratch = 0, lars_scratch = 0;
+  size_t bn_scratch_bytes = 0;
+  rn50::LarsArenaSpec lars;
+};
+
+using namespace rn50;
+
+namespace {
+
+int add_tensor(rn50_plan* p, int d0, int d1, int d2, int d3, bool decay) {
+  Tensor t;
+  t.dims[0] = d0; t.dims[1] = d1; t.dims[2] = d2; t.dims[3] = d3;
+  t.count = 1;
+  for (int i = 0; i < 4; ++i)
+    if (t.dims[i] > 0) t.count *= t.dims[i];
+  t.offset = p->arena_elems;
+  t.decay = decay;
+  p->arena_elems += (t.count + 63) / 64 * 64;
+  p->tensors.push_back(t);
+  return static_cast<int>(p->tensors.size()) - 1;
+}
+
+int add_unit(rn50_plan* p, int N, int H, int W, int Cin, int Cout, int R, int stride, int pad, int mode) {
+  Unit u{};
+  u.conv = rn50_conv_desc{N, H, W, Cin, Cout, R, R, stride, pad, p->cfg.dtype};
+  u.P = (H + 2 * pad - R) / stride + 1;
+  u.Q = (W + 2 * pad - R) / stride + 1;
+  u.bn = rn50_bn_desc{N, u.P, u.Q, Cout, p->cfg.bn_eps, p->cfg.dtype, mode};
+  u.iw = add_tensor(p, Cout, R, R, Cin, true);
+  u.ig = add_tensor(p, Cout, 0, 0, 0, false);
+  u.ib = add_tensor(p, Cout, 0, 0, 0, false);
+  p->units.push_back(u);
+  return static_cast<int>(p->units.size()) - 1;
+}
+
+size_t bump(size_t* top, size_t bytes) {
+  const size_t at = *top;
+  *top += align_up(bytes, 256);
+  return at;
+}
+
+}  // namespace
+
+extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_out) {
+  clear_error();
+  RN50_REQUIRE(cfg && plan_out, RN50_ERR_INVALID, "resnet_plan_create: null pointer");
+  RN50_REQUIRE(cfg->N > 0 && cfg->image_hw >= 32 && cfg->classes > 0 && cfg->stem > 0 && cfg->expansion > 0,
+               RN50_ERR_INVALID, "resnet_plan_create: bad sizes");
+  RN50_REQUIRE(cfg->dtype == RN50_F32 || cfg->dtype == RN50_BF16, RN50_ERR_INVALID, "resnet_plan_create: dtype");
+  const int V = cfg->dtype == RN50_BF16 ? 8 : 4;
+  RN50_REQUIRE(cfg->stem % V == 0, RN50_ERR_UNSUPPORTED, "resnet_plan_create: stem width %% %d", V);
+  for (int i = 0; i < 4; ++i)
+    RN50_REQUIRE(cfg->widths[i] > 0 && cfg->widths[i] % V == 0 && cfg->blocks[i] > 0, RN50_ERR_UNSUPPORTED,
+                 "resnet_plan_create: stage %d width/blocks", i);
+  rn50_plan* p = new rn50_plan();
+  p->cfg = *cfg;
+  p->es = cfg->dtype == RN50_BF16 ? 2 : 4;
+  const int N = cfg->N;
+  int H = cfg->image_hw;
+  const int stem = add_unit(p, N, H, H, 3, cfg->stem, 7, 2, 3, 1);
+  (void)stem;
+  H = p->units[0].P;          // 112
+  const int Hpool = (H - 1) / 2 + 1;  // 56
+  H = Hpool;
+  int cin = cfg->stem;
+  for (int st = 0; st < 4; ++st)
+    for (int b = 0; b < cfg->blocks[st]; ++b) {
+      const int wd = cfg->widths[st], cout = wd * cfg->expansion;
+      const int stride = (b == 0 && st > 0) ? 2 : 1;
+      Block blk;
+      blk.u1 = add_unit(p, N, H, H, cin, wd, 1, 1, 0, 1);
+      blk.u2 = add_unit(p, N, H, H, wd, wd, 3, stride, 1, 1);
+      const int Ho = p->units[blk.u2].P;
+      blk.u3 = add_unit(p, N, Ho, Ho, wd, cout, 1, 1, 0, 2);
+      blk.up = b == 0 ? add_unit(p, N, H, H, cin, cout, 1, stride, 0, 0) : -1;
+      p->blocks.push_back(blk);
+      H = Ho;
+      cin = cout;
+    }
+  p->fc_in = cin;
+  p->final_hw = H;
+  add_tensor(p, cfg->classes, cin, 0, 0, true);
+  add_tensor(p, cfg->classes, 0, 0, 0, false);
+  RN50_REQUIRE(p->arena_elems < (1ll << 31), RN50_ERR_UNSUPPORTED, "resnet_plan_create: too many parameters");
+
+  // ---- workspace layout
+  size_t top = 0;
+  const size_t es = p->es;
+  const Unit& u0 = p->units[0];
+  p->xp = bump(&top, stem_padded_input_bytes(&u0.conv));
+  p->wp = bump(&top, stem_padded_weight_bytes(&u0.conv));
+  size_t max_act = 0, max_wT = 0, max_wg = 0, max_bn = 0;
+  for (Unit& u : p->units) {
+    const size_t out_elems = static_cast<size_t>(N) * u.P * u.Q * u.conv.Cout;
+    const size_t in_elems = static_cast<size_t>(N) * u.conv.H * u.conv.W * u.conv.Cin;
+    u.y = bump(&top, out_elems * es);
+    u.z = bump(&top, out_elems * es);
+    u.mean = bump(&top, u.conv.Cout * sizeof(float));
+    u.rstd = bump(&top, u.conv.Cout * sizeof(float));
+    if (out_elems > max_act) max_act = out_elems;
+    if (in_elems > max_act && u.conv.Cin != 3) max_act = in_elems;
+    if (u.conv.Cin != 3 && dgrad_wt_bytes(&u.conv) > max_wT) max_wT = dgrad_wt_bytes(&u.conv);
+    if (wgrad_partial_bytes(&u.conv) > max_wg) max_wg = wgrad_partial_bytes(&u.conv);
+    if (bn_relu_fwd_workspace_bytes(&u.bn) > max_bn) max_bn = bn_relu_fwd_workspace_bytes(&u.bn);
+  }
+  p->pool = bump(&top, static_cast<size_t>(N) * Hpool * Hpool * cfg->stem * es);
+  p->avg = bump(&top, static_cast<size_t>(N) * cin * es);
+  p->davg = bump(&top, static_cast<size_t>(N) * cin * es);
+  p->logits = bump(&top, static_cast<size_t>(N) * cfg->classes * sizeof(float));
+  p->dlogits = bump(&top, static_cast<size_t>(N) * cfg->classes * sizeof(float));
+  p->row_loss = bump(&top, static_cast<size_t>(N) * sizeof(float));
+  for (int i = 0; i < 5; ++i) p->g[i] = bump(&top, max_act * es);
+  p->wT = bump(&top, max_wT);
+  p->wgrad_scratch = bump(&top, max_wg);
+  p->bn_scratch = bump(&top, max_bn);
+  p->bn_scratch_bytes = max_bn;
+  p->lars.num = static_cast<int>(p->tensors.size());
+  for (const Tensor& t : p->tensors) {
+    p->lars.offset.push_back(t.offset);
+    p->lars.count.push_back(t.count);
+    p->lars.decay.push_back(t.decay ? 1 : 0);
+  }
+  p->lars_scratch = bump(&top, lars_arena_partial_bytes(p->lars));
+  p->ws_bytes = top;
+  *plan_out = p;
+  return RN50_OK;
+}
+
+extern "C" void resnet_plan_destroy(rn50_plan* plan) { delete plan; }
+extern "C" int resnet_plan_num_tensors(const rn50_plan* plan) {
+  return plan ? static_cast<int>(plan->tensors.size()) : 0;
+}
+extern "C" int64_t resnet_plan_tensor_shape(const rn50_plan* plan, int i, int dims_out[4]) {
+  if (!plan || i < 0 || i >= static_cast<int>(plan->tensors.size())) return 0;
+  if (dims_out) memcpy(dims_out, plan->tensors[i].dims, sizeof(int) * 4);
+  return plan->tensors[i].count;
+}
+extern "C" int64_t resnet_plan_tensor_offset(const rn50_plan* plan, int i) {
+  if (!plan || i < 0 || i >= static_cast<int>(plan->tensors.size())) return -1;
+  return plan->tensors[i].offset;
+}
+extern "C" int64_t resnet_plan_arena_elems(const rn50_plan* plan) { return plan ? plan->arena_elems : 0; }
+extern "C" size_t resnet_plan_workspace_bytes(const rn50_plan* plan) { return plan ? plan->ws_bytes : 0; }
+
+#define STEP_TRY(expr)           \
+  do {                           \
+    const int rc_ = (expr);      \
+    if (rc_ != RN50_OK) return rc_; \
+  } while (0)
+
+extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* labels, float* master,
+                           float* velocity, float* grads, void* model, float lr, int update, float* loss_out,
+                           float* logits_out, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  RN50_REQUIRE(plan && images && labels && grads && model && loss_out && workspace, RN50_ERR_INVALID,
+               "resnet_step: null pointer");
+  RN50_REQUIRE(!update || (master && velocity), RN50_ERR_INVALID, "resnet_step: update needs master and velocity");
+  RN50_REQUIRE(aligned16(images) && aligned16(master) && aligned16(velocity) && aligned16(grads) &&
+                   aligned16(model) && aligned16(workspace) && aligned16(logits_out),
+               RN50_ERR_ALIGN, "resnet_step: pointer not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= plan->ws_bytes, RN50_ERR_WORKSPACE, "resnet_step: workspace %zu < %zu bytes",
+               workspace_bytes, plan->ws_bytes);
+  const rn50_step_config& cfg = plan->cfg;
+  RN50_REQUIRE(cfg.dtype == RN50_BF16 || model == static_cast<void*>(master) || !update, RN50_ERR_INVALID,
+               "resnet_step: in F32 mode the model arena must be the master arena");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const size_t es = plan->es;
+  const int dt = cfg.dtype;
+  auto W = [&](int ti) -> const void* { return static_cast<const unsigned char*>(model) + plan->tensors[ti].offset * es; };
+  auto MP = [&](int ti) -> const float* {  // per-channel vectors are read in float from the master arena
+    return (master ? master : static_cast<const float*>(model)) + plan->tensors[ti].offset;
+  };
+  auto G = [&](int ti) -> float* { return grads + plan->tensors[ti].offset; };
+  auto F = [&](size_t off) -> float* { return reinterpret_cast<float*>(ws + off); };
+  void* bn_ws = ws + plan->bn_scratch;
+  const size_t bn_ws_bytes = plan->bn_scratch_bytes;
+  RN50_REQUIRE(cfg.dtype == RN50_F32 || master, RN50_ERR_INVALID,
+               "resnet_step: BF16 mode reads BN gamma/beta and the FC bias from the float master arena");
+
+  // --------------------------------------------------------------- forward
+  Unit& u0 = plan->units[0];
+  stem_pad_input(&u0.conv, images, ws + plan->xp, s);
+  stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, s);
+  STEP_TRY(bn_relu_fwd(&u0.bn, ws + u0.y, MP(u0.ig), MP(u0.ib), nullptr, ws + u0.z, F(u0.mean), F(u0.rstd),
+                       nullptr, nullptr, 0.f, bn_ws, bn_ws_bytes, s));
+  STEP_TRY(maxpool_fwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool, s));
+  const unsigned char* cur = ws + plan->pool;
+  auto conv_bn = [&](Unit& u, const void* in, const void* residual) -> int {
+    fwd_run(&u.conv, in, W(u.iw), ws + u.y, s);
+    return bn_relu_fwd(&u.bn, ws + u.y, MP(u.ig), MP(u.ib), residual, ws + u.z, F(u.mean), F(u.rstd), nullptr,
+                       nullptr, 0.f, bn_ws, bn_ws_bytes, s);
+  };
+  for (const Block& b : plan->blocks) {
+    Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
+    STEP_TRY(conv_bn(u1, cur, nullptr));
+    STEP_TRY(conv_bn(u2, ws + u1.z, nullptr));
+    const void* shortcut = cur;
+    if (b.up >= 0) {
+      Unit& up = plan->units[b.up];
+      STEP_TRY(conv_bn(up, cur, nullptr));
+      shortcut = ws + up.z;
+    }
+    STEP_TRY(conv_bn(u3, ws + u2.z, shortcut));
+    cur = ws + u3.z;
+  }
+  const int HW = plan->final_hw * plan->final_hw;
+  const int fcw = static_cast<int>(plan->tensors.size()) - 2, fcb = fcw + 1;
+  float* logits = logits_out ? logits_out : F(plan->logits);
+  STEP_TRY(avgpool_fwd(cfg.N, HW, plan->fc_in, dt, cur, ws + plan->avg, s));
+  STEP_TRY(fc_fwd(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, W(fcw), MP(fcb), logits, s));
+  STEP_TRY(xent_fwd_bwd(cfg.N, cfg.classes, logits, labels, cfg.label_smoothing, cfg.grad_scale, loss_out,
+                        F(plan->row_loss), F(plan->dlogits), s));
+
+  // -------------------------------------------------------------- backward
+  STEP_TRY(fc_bwd(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, W(fcw), F(plan->dlogits), ws + plan->davg,
+                  G(fcw), G(fcb), s));
+  unsigned char* g[5];
+  for (int i = 0; i < 5; ++i) g[i] = ws + plan->g[i];
+  // g[0], g[1]: the two summands of the gradient w.r.t. the current block output (g[1] may be unused)
+  STEP_TRY(avgpool_bwd(cfg.N, HW, plan->fc_in, dt, ws + plan->davg, g[0], s));
+  bool have2 = false;
+  // BN backward + wgrad + dgrad of one unit.  dz (+dz2) -> dy in `dy`; dgrad into `dx` (skipped if null).
+  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dy, void* dres,
+                      void* dx) -> int {
+    const void* z = u.bn.mode == 2 ? static_cast<const void*>(ws + u.z) : nullptr;  // mode 1 recomputes the mask
+    STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, z, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
+                         G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
+    wgrad_run(&u.conv, in, dy, G(u.iw), ws + plan->wgrad_scratch, s);
+    if (dx) {
+      dgrad_transpose_weights(&u.conv, W(u.iw), ws + plan->wT, s);
+      dgrad_run(&u.conv, dy, ws + plan->wT, dx, s);
+    }
+    return RN50_OK;
+  };
+  for (int bi = static_cast<int>(plan->blocks.size()) - 1; bi >= 0; --bi) {
+    const Block& b = plan->blocks[bi];
+    Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
+    const void* block_in = bi == 0 ? static_cast<const void*>(ws + plan->pool)
+                                   : static_cast<const void*>(ws + plan->units[plan->blocks[bi - 1].u3].z);
+    STEP_TRY(unit_bwd(u3, ws + u2.z, g[0], have2 ? g[1] : nullptr, g[2], g[3], g[4]));
+    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, g[2], nullptr, g[4]));
+    STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, g[2], nullptr, g[0]));
+    if (b.up >= 0) {
+      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, g[2], nullptr, g[1]));
+    } else {
+      unsigned char* t = g[1]; g[1] = g[3]; g[3] = t;
+    }
+    have2 = true;
+  }
+  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, g[0], g[1], g[2], s));
+  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, g[4], nullptr, nullptr));
+
+  // ------------------------------------------------------------------ LARS
+  if (update)
+    lars_arena_run(plan->lars, master, grads, velocity, cfg.dtype == RN50_BF16 ? model : nullptr, cfg.eta,
+                   cfg.momentum, lr, cfg.lars_eps, cfg.weight_decay, F(plan->lars_scratch), s);
+  return launch_status("resnet_step");
+}

@@ -1,0 +1,36 @@
+// Entry points of the kernel files that the whole-step driver calls directly
+// (below the argument checking of the C ABI), so that padded / transposed
+// operands and scratch buffers are shared across the passes of one step.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "../../include/rn50_hip.h"
+
+namespace rn50 {
+
+// conv.hip
+size_t stem_padded_input_bytes(const rn50_conv_desc* d);
+size_t stem_padded_weight_bytes(const rn50_conv_desc* d);
+void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_t s);
+void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, hipStream_t s);
+void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hipStream_t s);
+size_t dgrad_wt_bytes(const rn50_conv_desc* d);
+void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, hipStream_t s);
+void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, hipStream_t s);
+size_t wgrad_partial_bytes(const rn50_conv_desc* d);
+void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s);
+
+// lars.hip
+struct LarsArenaSpec {
+  int num = 0;
+  std::vector<int64_t> offset, count;
+  std::vector<char> decay;
+};
+size_t lars_arena_partial_bytes(const LarsArenaSpec& sp);
+void lars_arena_run(const LarsArenaSpec& sp, float* master, const float* grads, float* velocity, void* lowp,
+                    float eta, float momentum, float lr, float eps, float weight_decay, float* partial,
+                    hipStream_t s);
+
+}  // namespace rn50

@@ -1,0 +1,152 @@
+"""The ResNet-50 training step driven operation by operation through the C ABI, with every
+operation checked against the oracle ON THE GPU PATH'S OWN INPUTS (teacher forcing).
+
+Why: a randomly initialised BN-ResNet fed white-noise images is a chaotic map -- rounding
+activations to bf16 after every layer (which any bf16-storage implementation must do) moves
+the oracle's own logits by ~10% and its last block outputs by ~50% (measured by rounding the
+oracle's activations; see the design notes).  An end-to-end comparison of the bf16 step with
+the unrounded oracle therefore cannot meet a per-tensor 2e-2 bar for reasons that have nothing
+to do with kernel correctness.  Instead (i) every launch of the step is compared with the
+oracle's operation applied to the very same inputs, at the bf16 bar, and (ii) resnet_step is
+required to be BITWISE equal to this chain, and (iii) the float mode of resnet_step (same code,
+other template argument) is compared end to end with the oracle at the float bar.
+"""
+import numpy as np
+import torch
+
+import oracle as orc
+import synth
+from gpu_util import host
+
+
+def _h(t):
+    return host(t)
+
+
+class Chain:
+    def __init__(self, rn, tol, check=True):
+        self.rn, self.tol, self.check = rn, tol, check
+        self.worst = {}
+
+    def cmp(self, name, got, want, tol=None):
+        if not self.check:
+            return
+        e = orc.rel_l2(_h(got), want)
+        self.worst[name] = e
+        t = self.tol if tol is None else tol
+        assert e <= t, f"{name}: rel-L2 {e:.3e} > {t:.1e}"
+
+    # forward of conv + BN
+    def cbn(self, name, x, w, gamma, beta, stride, pad, mode, res=None):
+        rn = self.rn
+        y = rn.conv_fwd(x, w, stride, pad)
+        if self.check:
+            self.cmp(name + ".conv", y, orc.conv_fwd(_h(x), _h(w), stride, pad))
+        z, mean, rstd = rn.bn_relu_fwd(y, gamma, beta, res, 1e-5, mode)
+        if self.check:
+            zo, mo, ro = orc.bn_relu_fwd(_h(y), _h(gamma), _h(beta), _h(res) if res is not None else None, 1e-5, mode)
+            self.cmp(name + ".bn", z, zo)
+            self.cmp(name + ".rstd", rstd, ro, 1e-4)
+        return dict(name=name, x=x, w=w, gamma=gamma, beta=beta, y=y, z=z, mean=mean, rstd=rstd, stride=stride,
+                    pad=pad, mode=mode)
+
+    # backward of conv + BN; returns dx (or None), dres, (dw, dgamma, dbeta)
+    def cbn_bwd(self, t, dz, dz2=None, need_dx=True):
+        rn = self.rn
+        z = t["z"] if t["mode"] == 2 else None                      # mode 1: mask recomputed, as the step does
+        dy, dres, dg, db = rn.bn_relu_bwd(dz, t["y"], z, t["gamma"], t["mean"], t["rstd"], t["mode"],
+                                          beta=t["beta"], dz2=dz2)
+        if self.check:
+            dzs = _h(dz) + (_h(dz2) if dz2 is not None else 0)
+            dyo, dro, dgo, dbo = orc.bn_relu_bwd(dzs.astype(np.float32), _h(t["y"]), _h(t["z"]), _h(t["gamma"]),
+                                                 _h(t["mean"]), _h(t["rstd"]), t["mode"])
+            n = t["name"]
+            self.cmp(n + ".bn_bwd.dx", dy, dyo); self.cmp(n + ".dgamma", dg, dgo); self.cmp(n + ".dbeta", db, dbo)
+            if dres is not None:
+                self.cmp(n + ".bn_bwd.dres", dres, dro)
+        dw = rn.conv_wgrad(t["x"], dy, t["w"].shape, t["stride"], t["pad"])
+        if self.check:
+            self.cmp(t["name"] + ".dw", dw, orc.conv_wgrad(_h(t["x"]), _h(dy), tuple(t["w"].shape), t["stride"], t["pad"]))
+        dx = None
+        if need_dx:
+            dx = rn.conv_dgrad(dy, t["w"], t["x"].shape, t["stride"], t["pad"])
+            if self.check:
+                self.cmp(t["name"] + ".dx", dx, orc.conv_dgrad(_h(dy), _h(t["w"]), tuple(t["x"].shape), t["stride"], t["pad"]))
+        return dx, dres, [dw, dg, db]
+
+
+def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
+    """model[i]: device tensors the convolutions / FC read (storage dtype); vecs[i]: float device
+    tensors of the same parameter list (gamma, beta, bias are read from these).
+    Returns loss, logits, grads (parameter order), Chain."""
+    ch = Chain(rn, tol, check)
+    it = iter(range(len(model)))
+
+    def take():
+        i = next(it); j = next(it); k = next(it)
+        return model[i], vecs[j], vecs[k]
+
+    w, g, b = take()
+    t0 = ch.cbn("stem", images, w, g, b, 2, 3, 1)
+    pool = rn.maxpool_fwd(t0["z"])
+    if check:
+        assert np.array_equal(_h(pool), orc.maxpool_fwd(_h(t0["z"])))
+    cur = pool
+    tapes = []
+    for i, nb in enumerate(blocks):
+        for j in range(nb):
+            stride = 2 if (j == 0 and i > 0) else 1
+            p = f"s{i}b{j}"
+            w1, g1, b1 = take(); w2, g2, b2 = take(); w3, g3, b3 = take()
+            t1 = ch.cbn(p + ".c1", cur, w1, g1, b1, 1, 0, 1)
+            t2 = ch.cbn(p + ".c2", t1["z"], w2, g2, b2, stride, 1, 1)
+            tp = None
+            sc = cur
+            if j == 0:
+                wp, gp, bp = take()
+                tp = ch.cbn(p + ".proj", cur, wp, gp, bp, stride, 0, 0)
+                sc = tp["z"]
+            t3 = ch.cbn(p + ".c3", t2["z"], w3, g3, b3, 1, 0, 2, res=sc)
+            tapes.append((t1, t2, t3, tp))
+            cur = t3["z"]
+    fi = next(it); bi = next(it)
+    fw, fb = model[fi], vecs[bi]
+    N, H, W, C = cur.shape
+    a = rn.avgpool_fwd(cur)
+    logits = rn.fc_fwd(a, fw, fb)
+    loss, row, dl = rn.xent_fwd_bwd(logits, labels, ls, 1.0)
+    if check:
+        ch.cmp("avgpool", a, orc.avgpool_fwd(_h(cur)))
+        ch.cmp("fc", logits, orc.fc_fwd(_h(a), _h(fw), _h(fb)), 1e-4)
+        lo, ro, dlo = orc.xent_fwd_bwd(_h(logits), _h(labels), ls, 1.0)
+        assert abs(float(loss.item()) - lo) <= 1e-5 * abs(lo)
+        ch.cmp("dlogits", dl, dlo, 1e-4)
+    da, dfw, dfb = rn.fc_bwd(a, fw, dl)
+    d = rn.avgpool_bwd(da, H, W)
+    if check:
+        dao, dfwo, dfbo = orc.fc_bwd(_h(a), _h(fw), _h(dl))
+        ch.cmp("fc.da", da, dao); ch.cmp("fc.dW", dfw, dfwo, 1e-4); ch.cmp("fc.db", dfb, dfbo, 1e-4)
+        ch.cmp("avgpool_bwd", d, orc.avgpool_bwd(_h(da), H, W))
+    d2 = None
+    block_grads = []
+    for (t1, t2, t3, tp) in reversed(tapes):
+        dz2_, dres, g3 = ch.cbn_bwd(t3, d, d2)
+        dz1_, _, g2 = ch.cbn_bwd(t2, dz2_)
+        dxa, _, g1 = ch.cbn_bwd(t1, dz1_)
+        gl = g1 + g2 + g3
+        if tp is not None:
+            dxb, _, gp = ch.cbn_bwd(tp, dres)
+            gl = gl + gp
+            d, d2 = dxa, dxb
+        else:
+            d, d2 = dxa, dres
+        block_grads.append(gl)
+    dpool = rn.maxpool_bwd(t0["z"], d, d2)
+    if check:
+        ch.cmp("maxpool_bwd", dpool, orc.maxpool_bwd(_h(t0["z"]), (_h(d) + _h(d2)).astype(np.float32)), max(tol, 4e-3))
+    _, _, g0 = ch.cbn_bwd(t0, dpool, need_dx=False)
+    grads = list(g0)
+    for gl in reversed(block_grads):
+        grads += gl
+    grads += [dfw, dfb]
+    return loss, logits, grads, ch
