@@ -1,0 +1,131 @@
+"""Benchmark: ResNet-50 v1.5 training step (forward, backward, LARS) on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 40] [--dtype bf16|f32]
+
+Prints ONE JSON line: images/s for whole training steps at batch 40 (one worker's share of the
+paper's 81,920-image minibatch), with inputs, parameters and workspace resident in HBM before
+the timed region, plus
+  "roofline":     achieved vs peak for the step's dominant kernel, from HIP events recorded by the
+                  library around every launch of that kernel inside the timed steps, and
+  "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload.
+Synthetic data: N(0,1) images of ImageNet's shape, uniform labels, He-normal weights.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--batch", type=int, default=40)
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--roofline-kernel", default=None, help="kernel tag to time (default: the dominant one)")
+    return ap.parse_args()
+
+
+def build_state(rn, N, dtype):
+    import numpy as np
+    import torch
+    import synth
+    bf = dtype == "bf16"
+    plan = rn.ResnetPlan(N, rn.BF16 if bf else rn.F32)
+    table = [("t%d" % i, s, "conv" if len(s) == 4 else ("fcw" if len(s) == 2 else ("gamma" if i % 3 == 1 else "beta")))
+             for i, s in enumerate(plan.shapes)]
+    table[-1] = (table[-1][0], table[-1][1], "fcb")
+    params = synth.params_from_table(synth.DEFAULT_SEED, table)
+    M = torch.zeros(plan.arena_elems, dtype=torch.float32)
+    for off, p in zip(plan.offsets, params):
+        M[off:off + p.size] = torch.from_numpy(p.ravel())
+    M = M.cuda()
+    S = dict(plan=plan, M=M, V=torch.zeros_like(M), G=torch.zeros_like(M),
+             Mod=M.to(torch.bfloat16) if bf else M,
+             ws=torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda"),
+             loss=torch.zeros(1, device="cuda"))
+    img = synth.activation_nhwc(synth.DEFAULT_SEED, "img", N, 3, 224, 224)
+    S["images"] = torch.from_numpy(img).cuda().to(torch.bfloat16 if bf else torch.float32)
+    S["labels"] = torch.from_numpy(synth.labels(synth.DEFAULT_SEED, "lab", N, 1000)).cuda()
+    return S
+
+
+def cpu_baseline(batch_sample=2):
+    """The oracle's training step (forward, backward, LARS) on a bounded sample: `batch_sample`
+    images of the same 224x224 workload, all host cores OpenMP gives it."""
+    import numpy as np
+    import oracle  # noqa: F401
+    import synth
+    from oracle import net
+    table = net.param_table()
+    master = synth.params_from_table(synth.DEFAULT_SEED, table)
+    model = [synth.round_bf16(p) for p in master]
+    vel = [np.zeros_like(p) for p in master]
+    img = synth.round_bf16(synth.activation_nhwc(synth.DEFAULT_SEED, "img", batch_sample, 3, 224, 224))
+    lab = synth.labels(synth.DEFAULT_SEED, "lab", batch_sample, 1000)
+    t0 = time.perf_counter()
+    net.train_step(img, lab, master, model, vel, table)
+    dt = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp:
+        cores = min(cores, int(omp))
+    return {"value": batch_sample / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"one full training step (fwd+bwd+LARS) of ResNet-50 on {batch_sample} of the 40 images, "
+                      f"{dt:.1f} s wall"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the batch-40 share of one worker); "
+              "--gpus %d is not supported, no multi-GPU figure is produced" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_1903_12650_amd as rn
+    from paper_1903_12650_amd import roofline as rl
+
+    S = build_state(rn, args.batch, args.dtype)
+    plan = S["plan"]
+
+    def step():
+        rn.resnet_step(plan, S["images"], S["labels"], S["M"], S["V"], S["G"], S["Mod"], 1.0, S["ws"], update=True,
+                       loss_out=S["loss"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    tag = None
+    if not args.no_roofline:
+        tag = args.roofline_kernel or rl.DOMINANT_KERNEL
+        rn.profile_begin(tag, args.steps * 256)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+    out = {"metric": "ResNet-50 train images/sec on 1 MI355X, batch 40 bf16", "value": args.batch / (ms * 1e-3),
+           "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype,
+           "data": "synthetic",
+           "config": {"workload": f"full ResNet-50 v1.5 training step (fwd+bwd+LARS), batch {args.batch}, 224x224, "
+                                  f"1000 classes, {args.dtype} activations with fp32 master weights",
+                      "global_batch": args.batch, "loss": float(S["loss"].item())}}
+    if tag is not None:
+        durations_ms = rn.profile_end()
+        out["roofline"] = rl.roofline(tag, plan, durations_ms, args.steps)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -11,7 +11,7 @@ import torch
 
 __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd",
            "bn_relu_bwd", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "fc_fwd", "fc_bwd",
-           "xent_fwd_bwd", "lars_update", "LarsTable", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
+           "xent_fwd_bwd", "lars_update", "LarsTable", "profile_begin", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw"]
 
@@ -333,3 +333,19 @@ def resnet_step(plan, images, labels, master, velocity, grads, model, lr, worksp
                            _ptr(model), ctypes.c_float(lr), int(bool(update)), _ptr(loss_out), _ptr(logits_out),
                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
     return loss_out
+
+
+# ------------------------------------------------------------ launch timing
+def profile_begin(kernel_tag, max_records):
+    _check(raw.rn50_profile_begin(kernel_tag.encode(), int(max_records)))
+    profile_begin._cap = int(max_records)
+
+
+def profile_end():
+    """Elapsed milliseconds of every recorded launch of the tagged kernel, in launch order."""
+    cap = getattr(profile_begin, "_cap", 0)
+    buf = (ctypes.c_float * max(cap, 1))()
+    n = raw.rn50_profile_end(buf, cap)
+    if n < 0:
+        _check(n)
+    return [float(buf[i]) for i in range(min(n, cap))]

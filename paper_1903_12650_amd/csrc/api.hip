@@ -1,0 +1,71 @@
+// Error text and version of the C ABI.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+namespace rn50 {
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_err[0] = 0; }
+
+// ------------------------------------------------------------- launch timing
+static bool g_prof_on = false;
+static char g_prof_tag[64] = "";
+static size_t g_prof_max = 0, g_prof_used = 0;
+static std::vector<hipEvent_t> g_prof_events;  // start/stop pairs, grown on demand, reused
+
+ScopedKernelTimer::ScopedKernelTimer(const char* tag, hipStream_t s) : stream_(s), slot_(-1) {
+  if (!g_prof_on || g_prof_used >= g_prof_max || strcmp(tag, g_prof_tag) != 0) return;
+  slot_ = static_cast<long>(g_prof_used++);
+  while (g_prof_events.size() < 2 * g_prof_used) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) { slot_ = -1; --g_prof_used; return; }
+    g_prof_events.push_back(e);
+  }
+  (void)hipEventRecord(g_prof_events[2 * slot_], stream_);
+}
+ScopedKernelTimer::~ScopedKernelTimer() {
+  if (slot_ >= 0) (void)hipEventRecord(g_prof_events[2 * slot_ + 1], stream_);
+}
+}  // namespace rn50
+
+extern "C" int rn50_profile_begin(const char* kernel_tag, int max_records) {
+  rn50::clear_error();
+  if (!kernel_tag || max_records <= 0 || strlen(kernel_tag) >= sizeof(rn50::g_prof_tag))
+    return rn50::fail(RN50_ERR_INVALID, "rn50_profile_begin: bad tag or max_records");
+  strcpy(rn50::g_prof_tag, kernel_tag);
+  rn50::g_prof_max = static_cast<size_t>(max_records);
+  rn50::g_prof_used = 0;
+  rn50::g_prof_on = true;
+  return RN50_OK;
+}
+extern "C" int rn50_profile_end(float* ms_out, int capacity) {
+  using namespace rn50;
+  g_prof_on = false;
+  const size_t n = g_prof_used;
+  if (n == 0) return 0;
+  if (hipEventSynchronize(g_prof_events[2 * n - 1]) != hipSuccess)
+    return fail(RN50_ERR_HIP, "rn50_profile_end: event synchronize failed");
+  size_t w = 0;
+  for (size_t i = 0; i < n && ms_out && w < static_cast<size_t>(capacity); ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]) != hipSuccess) ms = -1.f;
+    ms_out[w++] = ms;
+  }
+  g_prof_used = 0;
+  return static_cast<int>(n);
+}
+
+extern "C" const char* rn50_last_error(void) { return rn50::g_err; }
+extern "C" int rn50_version(void) { return 1; }

@@ -373,15 +373,17 @@ static void launch_fwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                        float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
                        float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
-  hipLaunchKernelGGL(bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
-                     static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial);
+  RN50_TIMED("bn_stats", s,
+             hipLaunchKernelGGL(bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
+                                static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial));
   hipLaunchKernelGGL(bn_finalize_kernel<T>, dim3(ceil_div(d->C, 4)), dim3(256), 0, s,
                      static_cast<const T*>(x), partial, g.nblk, m, d->C, d->eps, save_mean,
                      save_rstd, rm, rv, momentum);
-  hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
-                     static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
-                     static_cast<const T*>(residual), static_cast<T*>(y), m, d->C, g.tx_log2,
-                     g.rpb, d->mode);
+  RN50_TIMED("bn_apply", s,
+             hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
+                                static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
+                                static_cast<const T*>(residual), static_cast<T*>(y), m, d->C,
+                                g.tx_log2, g.rpb, d->mode));
 }
 
 template <typename T>
@@ -390,17 +392,19 @@ static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                        const float* beta, const float* mean, const float* rstd, void* dx,
                        void* dres, float* dgamma, float* dbeta, float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
-  hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
-                     static_cast<const T*>(dz), static_cast<const T*>(dz2),
-                     static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta, mean, rstd,
-                     m, d->C, g.tx_log2, g.rpb, d->mode, partial);
+  RN50_TIMED("bn_bwd_reduce", s,
+             hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
+                                static_cast<const T*>(dz), static_cast<const T*>(dz2),
+                                static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
+                                mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial));
   hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(d->C, 4)), dim3(256), 0, s, partial,
                      g.nblk, d->C, dgamma, dbeta);
-  hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
-                     static_cast<const T*>(dz), static_cast<const T*>(dz2),
-                     static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta, mean, rstd,
-                     dgamma, dbeta, static_cast<T*>(dx), static_cast<T*>(dres), m, d->C,
-                     g.tx_log2, g.rpb, d->mode);
+  RN50_TIMED("bn_bwd_apply", s,
+             hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
+                                static_cast<const T*>(dz), static_cast<const T*>(dz2),
+                                static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
+                                mean, rstd, dgamma, dbeta, static_cast<T*>(dx),
+                                static_cast<T*>(dres), m, d->C, g.tx_log2, g.rpb, d->mode));
 }
 
 }  // namespace rn50

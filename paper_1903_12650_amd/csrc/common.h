@@ -27,6 +27,22 @@ inline int launch_status(const char* what) {
   return RN50_OK;
 }
 
+// Records an event pair around the launches issued during its lifetime when launch
+// timing is enabled for `tag` (see rn50_profile_begin); otherwise does nothing.
+class ScopedKernelTimer {
+ public:
+  ScopedKernelTimer(const char* tag, hipStream_t s);
+  ~ScopedKernelTimer();
+ private:
+  hipStream_t stream_;
+  long slot_;
+};
+#define RN50_TIMED(tag, stream, launch)              \
+  do {                                               \
+    ::rn50::ScopedKernelTimer timer_((tag), (stream)); \
+    launch;                                          \
+  } while (0)
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 

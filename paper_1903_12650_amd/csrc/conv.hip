@@ -478,24 +478,24 @@ static void allow_big_lds(K kernel, int bytes) {
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
-static void launch_igemm_cfg(IgemmArgs a, hipStream_t s) {
+static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   constexpr int lds = 2 * (BM + BN) * kPitch;
   static std::once_flag once;
   std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN>, lds); });
   a.ntn = static_cast<int>(ceil_div(a.Ncols, BN));
   const int64_t grid = ceil_div(a.M, BM) * a.ntn;
-  hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a);
+  RN50_TIMED(tag, s, hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a));
 }
 
 // Tile choice: the widest tile that still gives every CU a couple of workgroups.
 template <typename T>
-static void launch_igemm(const IgemmArgs& a, hipStream_t s) {
+static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
   const int64_t target = 512;
   auto blocks = [&](int bm, int bn) { return ceil_div(a.M, bm) * ceil_div(a.Ncols, bn); };
-  if (a.Ncols > 64 && blocks(128, 128) >= target) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, s);
-  if (blocks(128, 64) >= target) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, s);
-  if (a.Ncols > 64 && blocks(64, 128) >= target / 2) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, s);
-  return launch_igemm_cfg<T, 64, 64, 2, 2>(a, s);
+  if (a.Ncols > 64 && blocks(128, 128) >= target) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
+  if (blocks(128, 64) >= target) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
+  if (a.Ncols > 64 && blocks(64, 128) >= target / 2) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
+  return launch_igemm_cfg<T, 64, 64, 2, 2>(a, tag, s);
 }
 
 struct WgradPlan {
@@ -525,7 +525,7 @@ static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   static std::once_flag once;
   std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC>, lds); });
   const dim3 grid(a.R * a.S * a.ctiles, static_cast<unsigned>(ceil_div(a.Cout, BMO)), splits);
-  hipLaunchKernelGGL((wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, a);
+  RN50_TIMED("conv_wgrad", s, hipLaunchKernelGGL((wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, a));
 }
 
 template <typename T>
@@ -626,11 +626,11 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
   if (d->dtype == RN50_BF16) {
     hipLaunchKernelGGL(stem_pad_weight_kernel<uint16_t>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
                        static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wp), d->Cout);
-    launch_igemm<uint16_t>(stem_igemm_args(d, xp, wp, y), s);
+    launch_igemm<uint16_t>(stem_igemm_args(d, xp, wp, y), "conv_fwd", s);
   } else {
     hipLaunchKernelGGL(stem_pad_weight_kernel<float>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
                        static_cast<const float*>(w), static_cast<float*>(wp), d->Cout);
-    launch_igemm<float>(stem_igemm_args(d, xp, wp, y), s);
+    launch_igemm<float>(stem_igemm_args(d, xp, wp, y), "conv_fwd", s);
   }
 }
 
@@ -688,7 +688,7 @@ void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hip
   a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
   a.mode = 0;
   a.cpt = static_cast<int>(ceil_div(d->Cin * esize(d->dtype), 128));
-  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, s); else launch_igemm<float>(a, s);
+  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, "conv_fwd", s); else launch_igemm<float>(a, "conv_fwd", s);
 }
 
 size_t dgrad_wt_bytes(const rn50_conv_desc* d) {
@@ -713,7 +713,7 @@ void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx
   a.PS = d->Cout; a.Cg = d->Cout; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
   a.mode = 1;
   a.cpt = static_cast<int>(ceil_div(d->Cout * esize(d->dtype), 128));
-  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, s); else launch_igemm<float>(a, s);
+  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, "conv_dgrad", s); else launch_igemm<float>(a, "conv_dgrad", s);
 }
 
 }  // namespace rn50

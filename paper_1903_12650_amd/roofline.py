@@ -1,0 +1,145 @@
+"""Algorithmic cost model of the step's kernels (what the method itself must move or multiply,
+independent of how the kernels are written) and the roofline record bench.py prints.
+
+Per unit of work (elements are activation elements of the BN's tensor, bf16 = 2 bytes):
+  conv_fwd / conv_dgrad  2*M*N*K flop;  bytes = es*(|in| + |out| + |w|), a 1x1 stride-2 conv only
+                         needs (and is only charged) every other row and column of its input
+  conv_wgrad             2*M*N*K flop;  bytes = es*(|x| + |dy|) + 4*|dw|
+  bn_stats               es bytes/element (read x)
+  bn_apply               2*es bytes/element (read x, write y) + es for the residual read (mode 2)
+  bn_bwd_reduce          2*es bytes/element (read dz, x)
+  bn_bwd_apply           3*es bytes/element (read dz, x, write dx) + es for dresidual (mode 2)
+  lars_norms             8 bytes/parameter (read w, g)
+  lars_apply             20 bytes/parameter (read w, g, v; write w, v) + 2 for the bf16 copy
+Peaks (MI355X, published): HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s; fp32 MFMA 157.3 TFLOP/s.
+"""
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+DOMINANT_KERNEL = "bn_bwd_apply"
+
+
+def layers(plan):
+    """Conv+BN units of the plan in parameter order: dict(N,H,W,Cin,Cout,R,stride,P,mode)."""
+    cfg = plan.cfg
+    N = cfg.N
+    out = []
+    H = cfg.image_hw
+    P = (H + 6 - 7) // 2 + 1
+    out.append(dict(N=N, H=H, Cin=3, Cout=cfg.stem, R=7, stride=2, P=P, mode=1))
+    H = (P - 1) // 2 + 1
+    cin = cfg.stem
+    for st in range(4):
+        for b in range(cfg.blocks[st]):
+            wd = cfg.widths[st]
+            cout = wd * cfg.expansion
+            stride = 2 if (b == 0 and st > 0) else 1
+            Ho = (H + 2 - 3) // stride + 1
+            out.append(dict(N=N, H=H, Cin=cin, Cout=wd, R=1, stride=1, P=H, mode=1))
+            out.append(dict(N=N, H=H, Cin=wd, Cout=wd, R=3, stride=stride, P=Ho, mode=1))
+            out.append(dict(N=N, H=Ho, Cin=wd, Cout=cout, R=1, stride=1, P=Ho, mode=2))
+            if b == 0:
+                out.append(dict(N=N, H=H, Cin=cin, Cout=cout, R=1, stride=stride, P=Ho, mode=0))
+            H, cin = Ho, cout
+    return out
+
+
+def per_launch_cost(tag, plan):
+    """List of (flops, bytes) per launch of `tag` within one step, in launch order."""
+    es = 2 if plan.dtype == 1 else 4
+    L = layers(plan)
+    res = []
+
+    def conv_cost(l, wgrad=False):
+        m = l["N"] * l["P"] * l["P"]
+        k = l["R"] * l["R"] * l["Cin"]
+        flops = 2.0 * m * l["Cout"] * k
+        x = l["N"] * l["H"] * l["H"] * l["Cin"]
+        if l["R"] == 1 and l["stride"] == 2:
+            x /= 4
+        y = m * l["Cout"]
+        w = l["Cout"] * k
+        by = es * (x + y) + (4 * w if wgrad else es * w)
+        return flops, by
+
+    def elems(l):
+        return l["N"] * l["P"] * l["P"] * l["Cout"]
+
+    if tag == "conv_fwd":
+        return _fwd_order(L, [conv_cost(l) for l in L])
+    if tag == "conv_dgrad":
+        return [conv_cost(l) for l in _bwd_order(L) if l["Cin"] != 3]
+    if tag == "conv_wgrad":
+        return [conv_cost(l, True) for l in _bwd_order(L)]
+    per_elem = {"bn_stats": (es, 0), "bn_apply": (2 * es, es), "bn_bwd_reduce": (2 * es, 0),
+                "bn_bwd_apply": (3 * es, es)}
+    if tag in per_elem:
+        base, extra = per_elem[tag]
+        seq = _fwd_order(L, L) if tag in ("bn_stats", "bn_apply") else _bwd_order(L)
+        return [(0.0, elems(l) * (base + (extra if l["mode"] == 2 else 0))) for l in seq]
+    n_params = sum(plan.sizes)
+    if tag == "lars_norms":
+        return [(0.0, 8.0 * n_params)]
+    if tag == "lars_apply":
+        return [(0.0, (20.0 + (2.0 if plan.dtype == 1 else 0.0)) * n_params)]
+    raise KeyError(tag)
+
+
+def _blocks(L):
+    """Group layer records: [stem], then per block [c1, c2, c3, (proj)]."""
+    out, i = [[L[0]]], 1
+    while i < len(L):
+        n = 4 if (i + 3 < len(L) and L[i + 3]["mode"] == 0) else 3
+        out.append(L[i:i + n])
+        i += n
+    return out
+
+
+def _fwd_order(L, vals):
+    """The step launches c1, c2, proj, c3 per block."""
+    idx = {id(l): v for l, v in zip(L, vals)}
+    seq = []
+    for b in _blocks(L):
+        order = b if len(b) < 4 else [b[0], b[1], b[3], b[2]]
+        seq += [idx[id(l)] for l in order]
+    return seq
+
+
+def _bwd_order(L):
+    """Backward launches, per block from the last: c3, c2, c1, proj; the stem last."""
+    seq = []
+    bl = _blocks(L)
+    for b in reversed(bl[1:]):
+        seq += [b[2], b[1], b[0]] + ([b[3]] if len(b) == 4 else [])
+    seq += bl[0]
+    return seq
+
+
+def roofline(tag, plan, durations_ms, steps):
+    """Roofline record for the kernel `tag` from per-launch event durations of `steps` steps."""
+    cost = per_launch_cost(tag, plan)
+    n = len(cost)
+    rec = {"kernel": tag, "launches_per_step": n}
+    if not durations_ms or len(durations_ms) % n != 0:
+        rec.update(bound=None, achieved=None, note=f"{len(durations_ms or [])} event records, expected a multiple of {n}")
+        return rec
+    total_ms = sum(durations_ms)
+    reps = len(durations_ms) // n
+    flops = sum(c[0] for c in cost) * reps
+    nbytes = sum(c[1] for c in cost) * reps
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if plan.dtype == 1 else MFMA_F32_PEAK_TFLOPS
+    t_flop = flops / (mfma_peak * 1e12)
+    t_byte = nbytes / (HBM_PEAK_GBS * 1e9)
+    rec["avg_launch_us"] = total_ms * 1e3 / len(durations_ms)
+    rec["time_per_step_ms"] = total_ms / reps
+    if t_flop > t_byte:
+        a = flops / (total_ms * 1e-3) / 1e12
+        rec.update(bound="mfma", achieved=a, peak=mfma_peak, unit="TFLOP/s", frac=a / mfma_peak)
+    else:
+        a = nbytes / (total_ms * 1e-3) / 1e9
+        rec.update(bound="hbm", achieved=a, peak=HBM_PEAK_GBS, unit="GB/s", frac=a / HBM_PEAK_GBS)
+    rec["algorithmic_bytes_per_launch"] = nbytes / len(durations_ms)
+    rec["algorithmic_flops_per_launch"] = flops / len(durations_ms)
+    rec["traffic"] = None
+    return rec

@@ -1,0 +1,77 @@
+"""The C-ABI library builds, loads, and exports every symbol that include/rn50_hip.h declares
+(no compute calls: this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "rn50_hip.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", src)
+    return sorted({n for n in names if n not in ("defined",) and not n.startswith("__")})
+
+
+def test_library_exports_every_declared_symbol():
+    lib_path = os.path.join(ROOT, "paper_1903_12650_amd", "librn50_hip.so")
+    if not os.path.exists(lib_path):
+        from paper_1903_12650_amd import build
+        build.build()
+    lib = ctypes.CDLL(lib_path)
+    names = _declared()
+    assert len(names) >= 30, names
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in rn50_hip.h but not exported"
+    for must in ("resnet_step", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd", "bn_relu_bwd", "xent_fwd_bwd",
+                 "lars_update"):
+        assert must in names
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    import paper_1903_12650_amd as rn
+    raw = rn.raw
+    assert raw.rn50_version() >= 1
+    # null descriptor / pointers are rejected before anything touches the device
+    assert raw.conv_fwd(None, None, None, None, None, ctypes.c_size_t(0), None) == -1
+    assert b"null" in raw.rn50_last_error()
+    d = rn.ConvDesc(1, 8, 8, 12, 8, 3, 3, 1, 1, rn.BF16)
+    one = ctypes.c_void_p(16)
+    assert raw.conv_fwd(ctypes.byref(d), one, one, one, None, ctypes.c_size_t(0), None) == -2     # Cin % 8
+    d = rn.ConvDesc(1, 8, 8, 16, 8, 3, 3, 1, 1, rn.BF16)
+    assert raw.conv_fwd(ctypes.byref(d), ctypes.c_void_p(8), one, one, None, ctypes.c_size_t(0), None) == -4
+    assert raw.conv_dgrad(ctypes.byref(d), one, one, one, one, ctypes.c_size_t(16), None) == -3
+    assert rn.conv_dgrad_workspace_bytes(d) >= 8 * 9 * 16 * 2
+    b = rn.BnDesc(2, 4, 4, 16, 1e-5, rn.BF16, 2)
+    assert raw.bn_relu_fwd(ctypes.byref(b), one, one, one, None, one, one, one, None, None, ctypes.c_float(0.9), one,
+                           ctypes.c_size_t(1 << 20), None) == -1                                # mode 2 without residual
+    assert raw.xent_fwd_bwd(0, 10, one, one, ctypes.c_float(0), ctypes.c_float(1), one, one, one, None) == -1
+
+
+def test_plan_matches_the_oracles_parameter_table():
+    import paper_1903_12650_amd as rn
+    from oracle import net
+    plan = rn.ResnetPlan(40, rn.BF16)
+    table = net.param_table()
+    assert plan.num_tensors == 161 and sum(plan.sizes) == 25_557_032
+    for (name, shape, _), ps in zip(table, plan.shapes):
+        assert tuple(shape) == tuple(ps), name
+    assert all(o % 64 == 0 for o in plan.offsets)
+    assert plan.workspace_bytes > 0 and plan.arena_elems >= sum(plan.sizes)
+
+
+def test_roofline_cost_model_totals():
+    """Algorithmic totals per step at batch 40 match the hand-derived figures: ~8.17 GFLOP/image of
+    forward convolution, 444.6 M BN elements."""
+    import paper_1903_12650_amd as rn
+    from paper_1903_12650_amd import roofline as rl
+    plan = rn.ResnetPlan(40, rn.BF16)
+    fwd = rl.per_launch_cost("conv_fwd", plan)
+    assert len(fwd) == 53 and len(rl.per_launch_cost("conv_dgrad", plan)) == 52
+    gflop_per_image = sum(f for f, _ in fwd) / 40 / 1e9
+    assert abs(gflop_per_image - 8.17) < 0.05, gflop_per_image
+    stats = rl.per_launch_cost("bn_stats", plan)
+    assert abs(sum(b for _, b in stats) / 2 / 1e6 - 444.6) < 0.5
+    assert rl.per_launch_cost("lars_apply", plan)[0][1] == 22 * 25_557_032
