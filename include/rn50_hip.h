@@ -49,10 +49,10 @@ const char* rn50_last_error(void);
 int rn50_version(void);
 
 /* Measurement aid (not part of the method): while enabled, the library records a
- * HIP event pair on the launch stream around every launch whose kernel tag equals
- * `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply",
- * "bn_bwd_reduce", "bn_bwd_apply", "lars_norms", "lars_apply", ...), up to
- * max_records launches.  rn50_profile_end waits for the last recorded event, writes
+ * HIP event pair on the launch stream around every launch whose kernel tag begins
+ * with `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad" (which also covers
+ * "conv_wgrad_reduce"), "bn_stats", "bn_apply", "bn_bwd_reduce", "bn_bwd_apply",
+ * "lars_norms", "lars_apply", ...), up to max_records launches.  rn50_profile_end waits for the last recorded event, writes
  * the elapsed milliseconds of each recorded launch in launch order to ms_out (host,
  * capacity floats), disables recording and returns the number of records.  Events
  * are the only resource created; both calls are host-side and not thread-safe. */

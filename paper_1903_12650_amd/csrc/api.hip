@@ -26,7 +26,7 @@ static size_t g_prof_max = 0, g_prof_used = 0;
 static std::vector<hipEvent_t> g_prof_events;  // start/stop pairs, grown on demand, reused
 
 ScopedKernelTimer::ScopedKernelTimer(const char* tag, hipStream_t s) : stream_(s), slot_(-1) {
-  if (!g_prof_on || g_prof_used >= g_prof_max || strcmp(tag, g_prof_tag) != 0) return;
+  if (!g_prof_on || g_prof_used >= g_prof_max || strncmp(tag, g_prof_tag, strlen(g_prof_tag)) != 0) return;
   slot_ = static_cast<long>(g_prof_used++);
   while (g_prof_events.size() < 2 * g_prof_used) {
     hipEvent_t e;

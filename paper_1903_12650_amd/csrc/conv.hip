@@ -21,6 +21,8 @@
 // copied to LDS untransposed and the bf16 fragments are fetched with the
 // gfx950 transposing LDS read (ds_read_b64_tr_b16); the reduction is split over
 // workgroups and finished by a fixed-order sum (bitwise reproducible).
+#include <stdlib.h>
+
 #include <mutex>
 
 #include "common.h"
@@ -59,6 +61,21 @@ template <> struct Mma<float> {  // float: four 32x32x2 MFMAs (k pairs {j, 4+j} 
   }
 };
 
+// Workgroups are dealt to the 8 XCDs round-robin; renumber them so that consecutive logical ids
+// (which share rows of the activation tile) run on the same XCD and meet in its L2.
+__device__ __forceinline__ int xcd_remap(int id, int n) {
+  const int xcd = id & 7, idx = id >> 3;
+  const int q = n >> 3, rem = n & 7;
+  return xcd < rem ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
+}
+
+// v if keep, else zeros (component-wise masks: a select between two aggregates would be turned into a
+// select of their addresses and force both into scratch memory).
+__device__ __forceinline__ uint4 keep_or_zero(uint4 v, bool keep) {
+  const uint32_t m = keep ? 0xffffffffu : 0u;
+  return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+}
+
 __device__ __forceinline__ Vec16 zero16() {
   Vec16 v;
   v.u = make_uint4(0, 0, 0, 0);
@@ -70,20 +87,35 @@ struct IgemmArgs {
   const void* act;  // gathered activation tensor [N][H][W] pixels of PS elements
   const void* wgt;  // B: [Ncols][Ktot]
   void* out;        // C: [M][Ncols]
+  uint32_t act_bytes, wgt_bytes;
   int M, Ncols, Ktot;
   int H, W;         // spatial size of the gathered tensor
   int P, Q;         // spatial size of the output pixel grid (M = N*P*Q)
   int PS;           // pixel stride of the gathered tensor, in elements
   int Cg;           // channels per tap
   int R, S, stride, pad;
-  int mode;         // 0: ih = p*stride - pad + r;  1: ih = (p + pad - r)/stride when divisible
   int cpt;          // 128-byte chunks per tap
   int ntn;          // number of column tiles
+  int mode;         // host side only: selects the MODE template argument
 };
 
 constexpr int kPitch = 144;  // LDS row pitch of a 128-byte K chunk (conflict-free 16-byte reads)
+constexpr uint32_t kOob = 0x80000000u;  // buffer offset beyond every tensor: the load returns zeros
 
-template <typename T, int BM, int BN, int WM, int WN>
+// Raw buffer descriptor over a tensor: loads whose offset is >= bytes return 0, which is how padding,
+// tile tails and ragged channel counts are zero-filled without any per-element masking.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t voffset, uint32_t soffset) {
+  typedef int v4i __attribute__((ext_vector_type(4)));
+  const v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, static_cast<int>(voffset), static_cast<int>(soffset), 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// MODE 0: forward gather  ih = p*stride - pad + r.
+// MODE 1: data-gradient gather  ih = (p + pad - r)/stride when divisible (stride 1 or 2).
+template <typename T, int BM, int BN, int WM, int WN, int MODE>
 __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   constexpr int V = 16 / sizeof(T);
   constexpr int BK = 128 / sizeof(T);
@@ -98,74 +130,85 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   const int tid = threadIdx.x, piece = tid & 7, lrow = tid >> 3;
   const int wave = tid >> 6, lane = tid & 63;
   const int wm = wave % WM, wn = wave / WM;
-  const int nt = blockIdx.x % a.ntn, mt = blockIdx.x / a.ntn;
+  const int bid = xcd_remap(blockIdx.x, gridDim.x);
+  const int nt = bid % a.ntn, mt = bid / a.ntn;
   const int m0 = mt * BM, n0 = nt * BN;
-  const T* act = static_cast<const T*>(a.act);
-  const T* wgt = static_cast<const T*>(a.wgt);
+  const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a.act, a.act_bytes), rsB = make_rsrc(a.wgt, a.wgt_bytes);
 
   // per-thread rows of the A tile: decode the output pixel once
   int a_h0[RA], a_w0[RA], a_base[RA];
-  bool a_ok[RA];
 #pragma unroll
   for (int i = 0; i < RA; ++i) {
     const int m = m0 + lrow + 32 * i;
-    a_ok[i] = m < a.M;
-    const int mm = a_ok[i] ? m : 0;
+    const bool ok = m < a.M;
+    const int mm = ok ? m : 0;
     const int q = mm % a.Q, t = mm / a.Q;
     const int p = t % a.P, n = t / a.P;
     a_base[i] = n * a.H * a.W;
-    if (a.mode == 0) {
-      a_h0[i] = p * a.stride - a.pad;
-      a_w0[i] = q * a.stride - a.pad;
-    } else {
-      a_h0[i] = p + a.pad;
-      a_w0[i] = q + a.pad;
-    }
+    // a row beyond M gets coordinates that fail every bounds check below
+    a_h0[i] = ok ? (MODE == 0 ? p * a.stride - a.pad : p + a.pad) : -(1 << 20);
+    a_w0[i] = MODE == 0 ? q * a.stride - a.pad : q + a.pad;
   }
-  int b_off[RB];
-  bool b_ok[RB];
+  uint32_t b_row[RB];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
     const int n = n0 + lrow + 32 * i;
-    b_ok[i] = n < a.Ncols;
-    b_off[i] = (b_ok[i] ? n : 0) * a.Ktot;
+    b_row[i] = n < a.Ncols ? static_cast<uint32_t>(n * a.Ktot + piece * V) * sizeof(T) : kOob;
   }
 
-  Vec16 ra[RA], rb[RB];
-  auto load_chunk = [&](int kc) {
-    const int tap = kc / a.cpt;
-    const int c = (kc - tap * a.cpt) * BK + piece * V;
-    const bool cval = c < a.Cg;
-    const int r = tap / a.S, s = tap - r * a.S;
+  // Load cursor: tap (r,s), chunk cc within the tap.  Per tap, the byte offset of every row's pixel (or
+  // kOob); within a tap successive chunks only differ by a scalar offset.
+  int cur_r = 0, cur_s = 0, cur_cc = 0;
+  uint32_t a_off[RA], b_tap = 0;
+  const bool ragged = (a.Cg % BK) != 0;
+  auto tap_setup = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
       int ih, iw;
-      bool ok = a_ok[i] && cval;
-      if (a.mode == 0) {
-        ih = a_h0[i] + r;
-        iw = a_w0[i] + s;
+      bool ok = true;
+      if (MODE == 0) {
+        ih = a_h0[i] + cur_r;
+        iw = a_w0[i] + cur_s;
       } else {
-        const int th = a_h0[i] - r, tw = a_w0[i] - s;
+        const int th = a_h0[i] - cur_r, tw = a_w0[i] - cur_s;
         const int msk = a.stride - 1;  // stride is 1 or 2
-        ok = ok && th >= 0 && tw >= 0 && ((th | tw) & msk) == 0;
+        ok = th >= 0 && tw >= 0 && ((th | tw) & msk) == 0;
         ih = th >> msk;
         iw = tw >> msk;
       }
       ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
            static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
-      ra[i] = ok ? load16(act + (static_cast<int64_t>(a_base[i] + ih * a.W + iw) * a.PS + c)) : zero16();
+      a_off[i] = ok ? static_cast<uint32_t>((a_base[i] + ih * a.W + iw) * a.PS + piece * V) * sizeof(T) : kOob;
     }
-    const int kb = tap * a.Cg + c;
-#pragma unroll
-    for (int i = 0; i < RB; ++i) rb[i] = (b_ok[i] && cval) ? load16(wgt + (static_cast<int64_t>(b_off[i]) + kb)) : zero16();
   };
-  auto store_chunk = [&](int stage) {
+  struct Staged {
+    uint4 a[RA], b[RB];
+  };
+  auto load_chunk = [&](Staged& st) __attribute__((always_inline)) {
+    const uint32_t so = static_cast<uint32_t>(cur_cc) * 128u;
+    const bool cval = !ragged || (cur_cc * BK + piece * V < a.Cg);
+#pragma unroll
+    for (int i = 0; i < RA; ++i) st.a[i] = buffer_load16(rsA, cval ? a_off[i] : kOob, so);
+#pragma unroll
+    for (int i = 0; i < RB; ++i) st.b[i] = buffer_load16(rsB, cval ? b_row[i] : kOob, b_tap + so);
+    // advance the cursor
+    if (++cur_cc == a.cpt) {
+      cur_cc = 0;
+      b_tap += static_cast<uint32_t>(a.Cg) * sizeof(T);
+      if (++cur_s == a.S) {
+        cur_s = 0;
+        ++cur_r;
+      }
+      tap_setup();
+    }
+  };
+  auto store_chunk = [&](int stage, const Staged& st) __attribute__((always_inline)) {
     unsigned char* sa = smem + stage * STAGE;
     unsigned char* sb = sa + BM * kPitch;
 #pragma unroll
-    for (int i = 0; i < RA; ++i) *reinterpret_cast<uint4*>(sa + (lrow + 32 * i) * kPitch + piece * 16) = ra[i].u;
+    for (int i = 0; i < RA; ++i) *reinterpret_cast<uint4*>(sa + (lrow + 32 * i) * kPitch + piece * 16) = st.a[i];
 #pragma unroll
-    for (int i = 0; i < RB; ++i) *reinterpret_cast<uint4*>(sb + (lrow + 32 * i) * kPitch + piece * 16) = rb[i].u;
+    for (int i = 0; i < RB; ++i) *reinterpret_cast<uint4*>(sb + (lrow + 32 * i) * kPitch + piece * 16) = st.b[i];
   };
 
   f32x16 acc[TM][TN];
@@ -177,15 +220,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nchunks = a.R * a.S * a.cpt;
-  load_chunk(0);
-  store_chunk(0);
-  __syncthreads();
   const int frag_off = (lane & 31) * kPitch + (lane >> 5) * 16;
-  for (int kc = 0; kc < nchunks; ++kc) {
-    const bool more = kc + 1 < nchunks;
-    if (more) load_chunk(kc + 1);
-    const unsigned char* sa = smem + (kc & 1) * STAGE + wm * (BM / WM) * kPitch + frag_off;
-    const unsigned char* sb = smem + (kc & 1) * STAGE + BM * kPitch + wn * (BN / WN) * kPitch + frag_off;
+  auto compute = [&](int stage) __attribute__((always_inline)) {
+    const unsigned char* sa = smem + stage * STAGE + wm * (BM / WM) * kPitch + frag_off;
+    const unsigned char* sb = smem + stage * STAGE + BM * kPitch + wn * (BN / WN) * kPitch + frag_off;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       Vec16 fa[TM], fb[TN];
@@ -198,8 +236,26 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) Mma<T>::run(fb[j], fa[i], acc[i][j]);  // D'[n][m]
     }
-    if (more) store_chunk((kc + 1) & 1);
+  };
+  // Two register sets: the loads of chunk k+2 are issued before chunk k is multiplied, so every global
+  // load has a full chunk of MFMA work (plus the other resident workgroups) to land.
+  Staged st0, st1;
+  tap_setup();
+  load_chunk(st0);
+  if (nchunks > 1) load_chunk(st1);
+  store_chunk(0, st0);
+  __syncthreads();
+  for (int kc = 0; kc < nchunks; kc += 2) {
+    if (kc + 2 < nchunks) load_chunk(st0);
+    compute(0);
+    if (kc + 1 < nchunks) store_chunk(1, st1);
     __syncthreads();
+    if (kc + 1 < nchunks) {
+      if (kc + 3 < nchunks) load_chunk(st1);
+      compute(1);
+      if (kc + 2 < nchunks) store_chunk(0, st0);
+      __syncthreads();
+    }
   }
 
   // Epilogue.  acc[i][j][v]: output channel n = j*32 + (v/4)*8 + (lane/32)*4 + v%4, pixel m = i*32 + lane%32.
@@ -239,13 +295,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 
 // ------------------------------------------------------------ weight gradient
 struct WgradArgs {
-  const void* x;   // gathered activation tensor (as in IgemmArgs, mode 0)
+  const void* x;   // gathered activation tensor (as in IgemmArgs, forward gather)
   const void* dy;  // [M][Cout]
   float* out;      // dw [Cout][Ktot], or split partials
+  uint32_t x_bytes, dy_bytes;
   int M, Cout, Ktot;
   int H, W, P, Q, PS, Cg, R, S, stride, pad;
   int ctiles;          // column tiles per tap
   int rows_per_split;  // multiple of the K chunk
+  int linear;          // 1x1, stride 1, pad 0: gathered row m is pixel m
   int64_t split_stride;
   FastDiv divQ, divP;
 };
@@ -306,43 +364,63 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   const int ko0 = blockIdx.y * BMO;
   const int row_begin = blockIdx.z * a.rows_per_split;
   const int row_end = min(row_begin + a.rows_per_split, a.M);
-  const T* x = static_cast<const T*>(a.x);
-  const T* dy = static_cast<const T*>(a.dy);
+  const __amdgpu_buffer_rsrc_t rsX = make_rsrc(a.x, a.x_bytes), rsD = make_rsrc(a.dy, a.dy_bytes);
 
   const int pa = tid % PPRA, rowa = tid / PPRA;
   const int pb = tid % PPRB, rowb = tid / PPRB;
   const bool a_col_ok = ko0 + pa * V < a.Cout;
   const bool b_col_ok = c0 + pb * V < a.Cg;
+  // byte offsets of this thread's first rows at m = row_begin; later chunks add a scalar offset
+  uint32_t a_off[NA], b_off[NB];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+    a_off[i] = a_col_ok ? static_cast<uint32_t>((row_begin + rowa + i * (256 / PPRA)) * a.Cout + ko0 + pa * V) * sizeof(T) : kOob;
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+    b_off[i] = b_col_ok ? static_cast<uint32_t>((row_begin + rowb + i * (256 / PPRB)) * a.PS + c0 + pb * V) * sizeof(T) : kOob;
 
-  Vec16 ra[NA], rb[NB];
-  auto load_chunk = [&](int m_base) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-      const int m = m_base + rowa + i * (256 / PPRA);
-      ra[i] = (a_col_ok && m < row_end) ? load16(dy + (static_cast<int64_t>(m) * a.Cout + ko0 + pa * V)) : zero16();
-    }
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int m = m_base + rowb + i * (256 / PPRB);
-      bool ok = b_col_ok && m < row_end;
-      const uint32_t mm = ok ? static_cast<uint32_t>(m) : 0u;
-      const uint32_t t = fdiv(mm, a.divQ);
-      const int q = static_cast<int>(mm - t * a.Q);
-      const uint32_t n = fdiv(t, a.divP);
-      const int p = static_cast<int>(t - n * a.P);
-      const int ih = p * a.stride - a.pad + r, iw = q * a.stride - a.pad + s;
-      ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
-           static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
-      rb[i] = ok ? load16(x + (static_cast<int64_t>((static_cast<int>(n) * a.H + ih) * a.W + iw) * a.PS + c0 + pb * V)) : zero16();
-    }
+  struct Staged {  // two register sets, unconditional zero-filling buffer loads (see igemm_kernel)
+    uint4 a[NA], b[NB];
   };
-  auto store_chunk = [&](int stage) {
+  int cur = 0;  // chunk index of the load cursor
+  auto load_chunk = [&](Staged& st) __attribute__((always_inline)) {
+    const int m_base = row_begin + cur * BKM;
+    const int left = row_end - m_base;  // rows of this chunk that belong to the split
+    const uint32_t soA = static_cast<uint32_t>(cur) * static_cast<uint32_t>(BKM * a.Cout) * sizeof(T);
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      st.a[i] = buffer_load16(rsD, (rowa + i * (256 / PPRA) < left) ? a_off[i] : kOob, soA);
+    if (a.linear) {
+      const uint32_t soB = static_cast<uint32_t>(cur) * static_cast<uint32_t>(BKM * a.PS) * sizeof(T);
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+        st.b[i] = buffer_load16(rsX, (rowb + i * (256 / PPRB) < left) ? b_off[i] : kOob, soB);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int lr = rowb + i * (256 / PPRB);
+        bool ok = b_col_ok && lr < left;
+        const uint32_t mm = ok ? static_cast<uint32_t>(m_base + lr) : 0u;
+        const uint32_t t = fdiv(mm, a.divQ);
+        const int q = static_cast<int>(mm - t * a.Q);
+        const uint32_t n = fdiv(t, a.divP);
+        const int p = static_cast<int>(t - n * a.P);
+        const int ih = p * a.stride - a.pad + r, iw = q * a.stride - a.pad + s;
+        ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
+             static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
+        const uint32_t off = static_cast<uint32_t>(((static_cast<int>(n) * a.H + ih) * a.W + iw) * a.PS + c0 + pb * V) * sizeof(T);
+        st.b[i] = buffer_load16(rsX, ok ? off : kOob, 0);
+      }
+    }
+    ++cur;
+  };
+  auto store_chunk = [&](int stage, const Staged& st) __attribute__((always_inline)) {
     unsigned char* sa = smem + stage * STAGE;
     unsigned char* sb = sa + BKM * PA;
 #pragma unroll
-    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(sa + (rowa + i * (256 / PPRA)) * PA + pa * 16) = ra[i].u;
+    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(sa + (rowa + i * (256 / PPRA)) * PA + pa * 16) = st.a[i];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(sb + (rowb + i * (256 / PPRB)) * PB + pb * 16) = rb[i].u;
+    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(sb + (rowb + i * (256 / PPRB)) * PB + pb * 16) = st.b[i];
   };
 
   f32x16 acc[TM][TN];
@@ -354,15 +432,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nchunks = (row_end - row_begin + BKM - 1) / BKM;
-  if (nchunks > 0) {
-    load_chunk(row_begin);
-    store_chunk(0);
-  }
-  __syncthreads();
-  for (int kc = 0; kc < nchunks; ++kc) {
-    const bool more = kc + 1 < nchunks;
-    if (more) load_chunk(row_begin + (kc + 1) * BKM);
-    const unsigned char* sa = smem + (kc & 1) * STAGE;
+  auto compute = [&](int stage) __attribute__((always_inline)) {
+    const unsigned char* sa = smem + stage * STAGE;
     const unsigned char* sb = sa + BKM * PA;
 #pragma unroll
     for (int kk = 0; kk < BKM / KSTEP; ++kk) {
@@ -376,8 +447,25 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) Mma<T>::run(fa[i], fb[j], acc[i][j]);  // D[ko][c]
     }
-    if (more) store_chunk((kc + 1) & 1);
+  };
+  Staged st0, st1;
+  if (nchunks > 0) {
+    load_chunk(st0);
+    if (nchunks > 1) load_chunk(st1);
+    store_chunk(0, st0);
+  }
+  __syncthreads();
+  for (int kc = 0; kc < nchunks; kc += 2) {
+    if (kc + 2 < nchunks) load_chunk(st0);
+    compute(0);
+    if (kc + 1 < nchunks) store_chunk(1, st1);
     __syncthreads();
+    if (kc + 1 < nchunks) {
+      if (kc + 3 < nchunks) load_chunk(st1);
+      compute(1);
+      if (kc + 2 < nchunks) store_chunk(0, st0);
+      __syncthreads();
+    }
   }
 
   // acc[i][j][v]: ko = i*32 + (v/4)*8 + (lane/32)*4 + v%4, c = j*32 + lane%32
@@ -396,23 +484,40 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     }
 }
 
-// dw[i] = sum_s partial[s][i], s ascending
+// dw[i] = sum_s partial[s][i].  A workgroup owns 64 float4 outputs; its four waves each sum every
+// fourth split (ascending) and the four sums are added in wave order: a fixed order.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits,
                                                             int64_t n, float* __restrict__ out) {
-  const int64_t i = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
-  if (i >= n) return;
+  __shared__ float4 red[4][64];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int64_t i = (static_cast<int64_t>(blockIdx.x) * 64 + lane) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (i + 4 <= n) {
-    float4 s = *reinterpret_cast<const float4*>(partial + i);
-    for (int k = 1; k < splits; ++k) {
+#pragma unroll 4
+    for (int k = grp; k < splits; k += 4) {
       const float4 v = *reinterpret_cast<const float4*>(partial + k * n + i);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
-    *reinterpret_cast<float4*>(out + i) = s;
-  } else {
-    for (int64_t j = i; j < n; ++j) {
-      float s = partial[j];
-      for (int k = 1; k < splits; ++k) s += partial[k * n + j];
-      out[j] = s;
+  } else if (i < n) {
+    for (int k = grp; k < splits; k += 4) {
+      const float* p = partial + k * n + i;
+      s.x += p[0];
+      if (i + 1 < n) s.y += p[1];
+      if (i + 2 < n) s.z += p[2];
+    }
+  }
+  red[grp][lane] = s;
+  __syncthreads();
+  if (grp == 0 && i < n) {
+    const float4 a = red[0][lane], b = red[1][lane], c = red[2][lane], d = red[3][lane];
+    const float4 r = make_float4((a.x + b.x) + (c.x + d.x), (a.y + b.y) + (c.y + d.y), (a.z + b.z) + (c.z + d.z),
+                                 (a.w + b.w) + (c.w + d.w));
+    if (i + 4 <= n) {
+      *reinterpret_cast<float4*>(out + i) = r;
+    } else {
+      out[i] = r.x;
+      if (i + 1 < n) out[i + 1] = r.y;
+      if (i + 2 < n) out[i + 2] = r.z;
     }
   }
 }
@@ -477,19 +582,30 @@ static void allow_big_lds(K kernel, int bytes) {
   if (bytes > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
-static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
+template <typename T, int BM, int BN, int WM, int WN, int MODE>
+static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid, hipStream_t s) {
   constexpr int lds = 2 * (BM + BN) * kPitch;
   static std::once_flag once;
-  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN>, lds); });
+  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE>, lds); });
+  RN50_TIMED(tag, s, hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, MODE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a));
+}
+template <typename T, int BM, int BN, int WM, int WN>
+static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   a.ntn = static_cast<int>(ceil_div(a.Ncols, BN));
   const int64_t grid = ceil_div(a.M, BM) * a.ntn;
-  RN50_TIMED(tag, s, hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a));
+  if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0>(a, tag, grid, s);
+  else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
 }
 
 // Tile choice: the widest tile that still gives every CU a couple of workgroups.
 template <typename T>
 static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
+  int fbm = 0, fbn = 0;  // tuning aid: RN50_IGEMM_TILE=bm,bn forces a tile shape
+  if (const char* e = getenv("RN50_IGEMM_TILE")) sscanf(e, "%d,%d", &fbm, &fbn);
+  if (fbm == 128 && fbn == 128) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
+  if (fbm == 128 && fbn == 64) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
+  if (fbm == 64 && fbn == 128) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
+  if (fbm == 64 && fbn == 64) return launch_igemm_cfg<T, 64, 64, 2, 2>(a, tag, s);
   const int64_t target = 512;
   auto blocks = [&](int bm, int bn) { return ceil_div(a.M, bm) * ceil_div(a.Ncols, bn); };
   if (a.Ncols > 64 && blocks(128, 128) >= target) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
@@ -501,21 +617,47 @@ static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
 struct WgradPlan {
   int bmo, bc, ctiles, splits, rows_per_split;
 };
+// Tile shape and number of reduction splits: the candidate with the smallest estimated time,
+//   waves * chunks_per_workgroup * t_chunk  +  cost of writing and re-reading the split partials,
+// where a "wave" is one round of workgroups over the chip (two resident per CU).
 static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype) {
-  WgradPlan p;
   const int bkm = dtype == RN50_BF16 ? 64 : 32;
-  p.bmo = Cout > 64 ? 128 : 64;
-  p.bc = Cg > 64 ? 128 : 64;
-  p.ctiles = static_cast<int>(ceil_div(Cg, p.bc));
-  const int64_t tiles = static_cast<int64_t>(taps) * p.ctiles * ceil_div(Cout, p.bmo);
-  int64_t splits = ceil_div(1024, tiles);
-  const int64_t max_splits = ceil_div(M, 4 * bkm);
-  if (splits > max_splits) splits = max_splits;
-  if (splits < 1) splits = 1;
-  int64_t rps = ceil_div(ceil_div(M, splits), bkm) * bkm;
-  p.rows_per_split = static_cast<int>(rps);
-  p.splits = static_cast<int>(ceil_div(M, rps));
-  return p;
+  const double dw_bytes = 4.0 * Cout * taps * Cg;
+  const int cand[4][2] = {{128, 128}, {128, 64}, {64, 128}, {64, 64}};
+  WgradPlan best{};
+  double best_t = 1e30;
+  if (const char* e = getenv("RN50_WGRAD_PLAN")) {  // tuning aid: bmo,bc,splits
+    int bmo = 0, bc = 0, sp = 0;
+    if (sscanf(e, "%d,%d,%d", &bmo, &bc, &sp) == 3 && (bmo == 64 || bmo == 128) && (bc == 64 || bc == 128) && sp >= 1) {
+      const int64_t rps = ceil_div(ceil_div(M, sp), bkm) * bkm;
+      best.bmo = bmo; best.bc = bc; best.ctiles = static_cast<int>(ceil_div(Cg, bc));
+      best.splits = static_cast<int>(ceil_div(M, rps));
+      best.rows_per_split = static_cast<int>(rps);
+      return best;
+    }
+  }
+  for (int ci = 0; ci < 4; ++ci) {
+    const int bmo = cand[ci][0], bc = cand[ci][1];
+    if ((bmo == 128 && Cout <= 64) || (bc == 128 && Cg <= 64)) continue;
+    const int ctiles = static_cast<int>(ceil_div(Cg, bc));
+    const int64_t tiles = static_cast<int64_t>(taps) * ctiles * ceil_div(Cout, bmo);
+    const double t_chunk = (bmo == 128 ? 1.0 : 0.6) * (bc == 128 ? 1.0 : 0.6) * 0.45e-6;
+    const int64_t max_splits = ceil_div(M, 2 * bkm);
+    for (int64_t splits = 1; splits <= max_splits && splits <= 1024; splits = splits < 8 ? splits + 1 : splits * 2) {
+      const int64_t rps = ceil_div(ceil_div(M, splits), bkm) * bkm;
+      const int64_t real_splits = ceil_div(M, rps);
+      const double waves = static_cast<double>(ceil_div(tiles * real_splits, 512));
+      double t = waves * static_cast<double>(rps / bkm) * t_chunk + 2e-6;
+      if (real_splits > 1) t += (2.0 * real_splits + 1.0) * dw_bytes / 3.0e12 + 4e-6;
+      if (t < best_t) {
+        best_t = t;
+        best.bmo = bmo; best.bc = bc; best.ctiles = ctiles;
+        best.splits = static_cast<int>(real_splits);
+        best.rows_per_split = static_cast<int>(rps);
+      }
+    }
+  }
+  return best;
 }
 
 template <typename T, int BMO, int BC>
@@ -542,8 +684,9 @@ static void launch_wgrad(WgradArgs a, const WgradPlan& p, float* dw, float* part
   else launch_wgrad_cfg<T, 64, 64>(a, p.splits, s);
   if (p.splits > 1) {
     const int64_t n = a.split_stride;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 256))), dim3(256), 0, s,
-                       partial, p.splits, n, dw);
+    RN50_TIMED("conv_wgrad_reduce", s,
+               hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 64))),
+                                  dim3(256), 0, s, partial, p.splits, n, dw));
   }
 }
 
@@ -566,11 +709,11 @@ static int check_conv(const rn50_conv_desc* d, const char* who) {
                "%s: Cin=%d is neither a multiple of %d nor the 7x7/2 pad-3 stem", who, d->Cin, V);
   RN50_REQUIRE(d->pad < d->R && d->pad < d->S, RN50_ERR_UNSUPPORTED, "%s: pad >= filter size", who);
   const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
-  const int64_t lim = (1ll << 31) - 1;
+  const int64_t lim = ((1ll << 31) - 1) / esize(d->dtype);  // byte offsets are 31-bit
   RN50_REQUIRE(static_cast<int64_t>(d->N) * (d->H + 6) * (d->W + 16) * (d->Cin < 4 ? 4 : d->Cin) < lim &&
                    static_cast<int64_t>(d->N) * P * Q * d->Cout < lim &&
                    static_cast<int64_t>(d->Cout) * d->R * d->S * (d->Cin < 4 ? 32 : d->Cin) < lim,
-               RN50_ERR_UNSUPPORTED, "%s: tensor has 2^31 or more elements", who);
+               RN50_ERR_UNSUPPORTED, "%s: a tensor is 2 GiB or larger", who);
   return RN50_OK;
 }
 
@@ -617,6 +760,8 @@ static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const 
   a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = 224;
   a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.Cg = 32; a.R = 7; a.S = 1; a.stride = 2; a.pad = 0; a.mode = 0;
   a.cpt = 1;
+  a.act_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * g.Hp * g.Wp * 4 * esize(d->dtype));
+  a.wgt_bytes = static_cast<uint32_t>(static_cast<size_t>(d->Cout) * 224 * esize(d->dtype));
   return a;
 }
 
@@ -640,6 +785,9 @@ static WgradArgs wgrad_args(const rn50_conv_desc* d, const void* x, const void* 
   a.P = out_dim(d->H, d->pad, d->R, d->stride); a.Q = out_dim(d->W, d->pad, d->S, d->stride);
   a.M = d->N * a.P * a.Q; a.Cout = d->Cout; a.Ktot = d->R * d->S * d->Cin;
   a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
+  a.x_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * d->H * d->W * d->Cin * esize(d->dtype));
+  a.dy_bytes = static_cast<uint32_t>(static_cast<size_t>(a.M) * d->Cout * esize(d->dtype));
+  a.linear = d->R == 1 && d->S == 1 && d->stride == 1 && d->pad == 0;
   return a;
 }
 static WgradArgs stem_wgrad_args(const rn50_conv_desc* d, const void* xp, const void* dy) {
@@ -649,6 +797,9 @@ static WgradArgs stem_wgrad_args(const rn50_conv_desc* d, const void* xp, const 
   a.P = out_dim(d->H, 3, 7, 2); a.Q = out_dim(d->W, 3, 7, 2);
   a.M = d->N * a.P * a.Q; a.Cout = d->Cout; a.Ktot = 224;
   a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.Cg = 32; a.R = 7; a.S = 1; a.stride = 2; a.pad = 0;
+  a.x_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * g.Hp * g.Wp * 4 * esize(d->dtype));
+  a.dy_bytes = static_cast<uint32_t>(static_cast<size_t>(a.M) * d->Cout * esize(d->dtype));
+  a.linear = 0;
   return a;
 }
 
@@ -687,6 +838,8 @@ void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hip
   a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = d->R * d->S * d->Cin;
   a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
   a.mode = 0;
+  a.act_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * d->H * d->W * d->Cin * esize(d->dtype));
+  a.wgt_bytes = static_cast<uint32_t>(static_cast<size_t>(d->Cout) * a.Ktot * esize(d->dtype));
   a.cpt = static_cast<int>(ceil_div(d->Cin * esize(d->dtype), 128));
   if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, "conv_fwd", s); else launch_igemm<float>(a, "conv_fwd", s);
 }
@@ -712,6 +865,8 @@ void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx
   a.M = d->N * d->H * d->W; a.Ncols = d->Cin; a.Ktot = d->R * d->S * d->Cout;
   a.PS = d->Cout; a.Cg = d->Cout; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
   a.mode = 1;
+  a.act_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * a.H * a.W * d->Cout * esize(d->dtype));
+  a.wgt_bytes = static_cast<uint32_t>(static_cast<size_t>(d->Cin) * a.Ktot * esize(d->dtype));
   a.cpt = static_cast<int>(ceil_div(d->Cout * esize(d->dtype), 128));
   if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, "conv_dgrad", s); else launch_igemm<float>(a, "conv_dgrad", s);
 }
