@@ -129,11 +129,15 @@ int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const vo
 /* --------------------------------------------------------------------- pooling
  * Max pooling, window 3x3, stride 2, pad 1 (the appendix's 112 -> 56 step);
  * padding never wins; among equal maxima the first in row-major window order
- * wins.  Backward recomputes the winner from x and adds dy (+ optional dy2) to
- * it.  x, dx [N,H,W,C]; y, dy, dy2 [N,Ho,Wo,C]; device, dtype; C % 8 == 0. */
-int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x, void* y, void* stream);
-int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x, const void* dy,
-                const void* dy2, void* dx, void* stream);
+ * wins.  Forward optionally records the winner's window position r*3+s per output
+ * element in argmax (device uint8 [N,Ho,Wo,C], or NULL).  Backward adds dy (+ optional
+ * dy2) to the winner, taken from argmax when given, else recomputed from x (then x is
+ * required).  x, dx [N,H,W,C]; y, dy, dy2 [N,Ho,Wo,C]; device, dtype; C % 8 == 0
+ * (bf16) or % 4 (f32). */
+int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x, void* y, uint8_t* argmax,
+                void* stream);
+int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x, const uint8_t* argmax,
+                const void* dy, const void* dy2, void* dx, void* stream);
 /* Global average pool over the HW positions of each image and its adjoint.
  * x, dx [N,HW,C]; y, dy [N,C]; device, dtype. */
 int avgpool_fwd(int N, int HW, int C, int dtype, const void* x, void* y, void* stream);
@@ -141,12 +145,14 @@ int avgpool_bwd(int N, int HW, int C, int dtype, const void* dy, void* dx, void*
 
 /* ------------------------------------------------------------------ classifier
  * logits[n,k] = sum_c a[n,c]*W[k,c] + b[k].  a [N,Cin], W [K,Cin]: device dtype;
- * b, logits: device float.  Backward: da[n,c] = sum_k dlogits[n,k]*W[k,c] (dtype),
+ * b, logits: device float; Cin a multiple of the 16-byte vector.  Backward:
+ * da[n,c] = sum_k dlogits[n,k]*W[k,c] (dtype; dlogits is rounded to dtype for this product),
  * dW[k,c] = sum_n dlogits[n,k]*a[n,c], db[k] = sum_n dlogits[n,k] (float). */
 int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const void* W, const float* b,
            float* logits, void* stream);
+size_t fc_bwd_workspace_bytes(int N, int Cin, int K, int dtype);
 int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const void* W, const float* dlogits,
-           void* da, float* dW, float* db, void* stream);
+           void* da, float* dW, float* db, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ----------------------------------------------------- softmax cross-entropy
  * With label smoothing (Sec. III-A2 of the paper).  Per row n: p = softmax(logits[n,:])

@@ -202,17 +202,19 @@ def bn_relu_bwd(dz, x, z, gamma, mean, rstd, mode=1, beta=None, dz2=None, eps=1e
 
 
 # -------------------------------------------------------------------- pooling
-def maxpool_fwd(x):
+def maxpool_fwd(x, return_argmax=False):
     N, H, W, C = x.shape
     y = torch.empty((N, (H - 1) // 2 + 1, (W - 1) // 2 + 1, C), dtype=x.dtype, device=x.device)
-    _check(raw.maxpool_fwd(N, H, W, C, _dt(x), _ptr(x), _ptr(y), _stream()))
-    return y
+    am = torch.empty(y.shape, dtype=torch.uint8, device=x.device) if return_argmax else None
+    _check(raw.maxpool_fwd(N, H, W, C, _dt(x), _ptr(x), _ptr(y), _ptr(am), _stream()))
+    return (y, am) if return_argmax else y
 
 
-def maxpool_bwd(x, dy, dy2=None):
+def maxpool_bwd(x, dy, dy2=None, argmax=None):
+    """Winner from `argmax` (as returned by maxpool_fwd) when given, else recomputed from x."""
     N, H, W, C = x.shape
     dx = torch.empty_like(x)
-    _check(raw.maxpool_bwd(N, H, W, C, _dt(x), _ptr(x), _ptr(dy), _ptr(dy2), _ptr(dx), _stream()))
+    _check(raw.maxpool_bwd(N, H, W, C, _dt(x), _ptr(x), _ptr(argmax), _ptr(dy), _ptr(dy2), _ptr(dx), _stream()))
     return dx
 
 
@@ -245,7 +247,10 @@ def fc_bwd(a, W, dlogits):
     da = torch.empty_like(a)
     dW = torch.empty((K, Cin), dtype=torch.float32, device=a.device)
     db = torch.empty(K, dtype=torch.float32, device=a.device)
-    _check(raw.fc_bwd(N, Cin, K, _dt(a), _ptr(a), _ptr(W), _ptr(dlogits), _ptr(da), _ptr(dW), _ptr(db), _stream()))
+    raw.fc_bwd_workspace_bytes.restype = ctypes.c_size_t
+    ws = _ws(raw.fc_bwd_workspace_bytes(N, Cin, K, _dt(a)), a.device)
+    _check(raw.fc_bwd(N, Cin, K, _dt(a), _ptr(a), _ptr(W), _ptr(dlogits), _ptr(da), _ptr(dW), _ptr(db), _ptr(ws),
+                      ctypes.c_size_t(ws.numel()), _stream()))
     return da, dW, db
 
 

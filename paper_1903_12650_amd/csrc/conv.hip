@@ -26,6 +26,7 @@
 #include <mutex>
 
 #include "common.h"
+#include "step_internal.h"
 
 namespace rn50 {
 
@@ -541,6 +542,46 @@ __global__ __launch_bounds__(256) void transpose_kc_kernel(const T* __restrict__
   }
 }
 
+// The same transposition for a whole list of weight tensors in one launch (the step's backward pass
+// needs every convolution's [Cin][R][S][Cout] form once per step).
+constexpr int kTransposeBatchMax = 64;
+struct TransposeBatchArgs {
+  const void* src;  // arena of [K][taps][C] tensors
+  void* dst;        // arena of [C][taps][K] tensors, same offsets
+  int num;
+  int tile_prefix[kTransposeBatchMax + 1];
+  uint32_t offset[kTransposeBatchMax];  // elements
+  int K[kTransposeBatchMax], taps[kTransposeBatchMax], C[kTransposeBatchMax];
+};
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_batch_kernel(const TransposeBatchArgs a) {
+  __shared__ T tile[32][33];
+  int lo = 0, hi = a.num;
+  const int b = blockIdx.x;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.tile_prefix[mid] <= b) lo = mid; else hi = mid;
+  }
+  const int K = a.K[lo], taps = a.taps[lo], C = a.C[lo];
+  const T* w = static_cast<const T*>(a.src) + a.offset[lo];
+  T* wT = static_cast<T*>(a.dst) + a.offset[lo];
+  int rem = b - a.tile_prefix[lo];
+  const int ct = (C + 31) / 32, kt = (K + 31) / 32;
+  const int c0 = (rem % ct) * 32; rem /= ct;
+  const int k0 = (rem % kt) * 32;
+  const int t = rem / kt;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8) {
+    const int k = k0 + i, c = c0 + tx;
+    if (k < K && c < C) tile[i][tx] = w[(static_cast<int64_t>(k) * taps + t) * C + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, k = k0 + tx;
+    if (k < K && c < C) wT[(static_cast<int64_t>(c) * taps + t) * K + k] = tile[tx][i];
+  }
+}
+
 // Stem input: x [N][H][W][3] -> xp [N][H+6][Wp][4], zero border (3 pixels each side, Wp - W - 3 on the
 // right) and zero 4th channel, so that a 7-tap filter row is 8 pixels = 32 contiguous elements.
 template <typename T>
@@ -856,6 +897,25 @@ void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, h
     hipLaunchKernelGGL(transpose_kc_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(w),
                        static_cast<float*>(wT), d->Cout, d->R * d->S, d->Cin);
 }
+void transpose_batch_run(const std::vector<TransposeEntry>& list, int dtype, const void* src_arena, void* dst_arena,
+                         hipStream_t s) {
+  for (size_t i0 = 0; i0 < list.size(); i0 += kTransposeBatchMax) {
+    TransposeBatchArgs a{};
+    a.src = src_arena; a.dst = dst_arena;
+    a.num = static_cast<int>(list.size() - i0 < kTransposeBatchMax ? list.size() - i0 : kTransposeBatchMax);
+    a.tile_prefix[0] = 0;
+    for (int i = 0; i < a.num; ++i) {
+      const TransposeEntry& e = list[i0 + i];
+      a.offset[i] = static_cast<uint32_t>(e.offset);
+      a.K[i] = e.K; a.taps[i] = e.taps; a.C[i] = e.C;
+      a.tile_prefix[i + 1] = a.tile_prefix[i] + static_cast<int>(ceil_div(e.K, 32) * ceil_div(e.C, 32) * e.taps);
+    }
+    const int grid = a.tile_prefix[a.num];
+    if (dtype == RN50_BF16) hipLaunchKernelGGL(transpose_batch_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(transpose_batch_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+  }
+}
+
 // Data gradient from already transposed weights wT [Cin][R][S][Cout].
 void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, hipStream_t s) {
   IgemmArgs a{};

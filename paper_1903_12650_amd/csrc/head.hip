@@ -3,14 +3,16 @@
 // classifier, and softmax cross-entropy with label smoothing (Sec. III-A2).
 // All are bandwidth- or latency-bound and small next to the convolutions.
 #include "common.h"
+#include "step_internal.h"
 
 namespace rn50 {
 
 // ------------------------------------------------------------------ max pool
 template <typename T>
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ x,
-                                                          T* __restrict__ y, int N, int H, int W,
-                                                          int C, int P, int Q) {
+                                                          T* __restrict__ y,
+                                                          uint8_t* __restrict__ argmax, int N,
+                                                          int H, int W, int C, int P, int Q) {
   constexpr int V = Elem<T>::VEC;
   const int cv = C / V;
   const int64_t total = static_cast<int64_t>(N) * P * Q * cv;
@@ -22,6 +24,7 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ 
   const int p = static_cast<int>(t % P);
   const int n = static_cast<int>(t / P);
   float best[V];
+  int at[V];  // window position r*3+s of the first maximum
   bool have = false;
   for (int r = 0; r < 3; ++r) {
     const int ih = p * 2 - 1 + r;
@@ -33,17 +36,80 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ 
       Elem<T>::unpack(load16(x + ((static_cast<int64_t>(n) * H + ih) * W + iw) * C + c * V), f);
       if (!have) {
 #pragma unroll
-        for (int j = 0; j < V; ++j) best[j] = f[j];
+        for (int j = 0; j < V; ++j) {
+          best[j] = f[j];
+          at[j] = r * 3 + s;
+        }
         have = true;
       } else {
 #pragma unroll
-        for (int j = 0; j < V; ++j) best[j] = f[j] > best[j] ? f[j] : best[j];
+        for (int j = 0; j < V; ++j)
+          if (f[j] > best[j]) {
+            best[j] = f[j];
+            at[j] = r * 3 + s;
+          }
       }
     }
   }
   Vec16 o;
   Elem<T>::pack(best, o);
   store16(y + i * V, o);
+  if (argmax) {
+    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      if (j < 4) w0 |= static_cast<uint32_t>(at[j]) << (8 * j);
+      else w1 |= static_cast<uint32_t>(at[j]) << (8 * (j - 4));
+    }
+    if (V == 8) *reinterpret_cast<uint2*>(argmax + i * V) = make_uint2(w0, w1);
+    else *reinterpret_cast<uint32_t*>(argmax + i * V) = w0;
+  }
+}
+
+// Backward from the stored window positions: one thread per input pixel vector; it collects dy of the
+// (at most four) windows that contain it and whose recorded maximum is this pixel.
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const uint8_t* __restrict__ argmax,
+                                                              const T* __restrict__ dy,
+                                                              const T* __restrict__ dy2,
+                                                              T* __restrict__ dx, int N, int H, int W,
+                                                              int C, int P, int Q) {
+  constexpr int V = Elem<T>::VEC;
+  const int cv = C / V;
+  const int64_t total = static_cast<int64_t>(N) * H * W * cv;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = static_cast<int>(i % cv);
+  int64_t t = i / cv;
+  const int w = static_cast<int>(t % W); t /= W;
+  const int h = static_cast<int>(t % H);
+  const int n = static_cast<int>(t / H);
+  float acc[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) acc[j] = 0.f;
+  const int p_lo = h / 2, p_hi = min((h + 1) / 2, P - 1);
+  const int q_lo = w / 2, q_hi = min((w + 1) / 2, Q - 1);
+  for (int p = p_lo; p <= p_hi; ++p)
+    for (int q = q_lo; q <= q_hi; ++q) {
+      const int my_pos = (h - (p * 2 - 1)) * 3 + (w - (q * 2 - 1));
+      const int64_t o = ((static_cast<int64_t>(n) * P + p) * Q + q) * C + c * V;
+      uint8_t idx[V];
+      if (V == 8) *reinterpret_cast<uint2*>(idx) = *reinterpret_cast<const uint2*>(argmax + o);
+      else *reinterpret_cast<uint32_t*>(idx) = *reinterpret_cast<const uint32_t*>(argmax + o);
+      float g[V];
+      Elem<T>::unpack(load16(dy + o), g);
+      if (dy2) {
+        float g2[V];
+        Elem<T>::unpack(load16(dy2 + o), g2);
+#pragma unroll
+        for (int j = 0; j < V; ++j) g[j] += g2[j];
+      }
+#pragma unroll
+      for (int j = 0; j < V; ++j) acc[j] += idx[j] == my_pos ? g[j] : 0.f;
+    }
+  Vec16 ov;
+  Elem<T>::pack(acc, ov);
+  store16(dx + i * V, ov);
 }
 
 // One thread per input pixel vector.  The pixel receives dy of window (p,q) iff
@@ -224,6 +290,61 @@ __global__ __launch_bounds__(256) void small_gemm_kernel(const TA* __restrict__ 
     }
 }
 
+// logits[n][k] = sum_c a[n][c]*W[k][c] + b[k]: one wave per class k.  The wave streams its weight row
+// once per block of 8 batch rows (the activations, N*Cin elements, stay in cache), accumulates in
+// float and finishes each dot product with a wave reduction.
+template <typename T>
+__global__ __launch_bounds__(256) void fc_fwd_kernel(const T* __restrict__ a, const T* __restrict__ W,
+                                                     const float* __restrict__ b,
+                                                     float* __restrict__ logits, int N, int Cin, int K) {
+  constexpr int V = Elem<T>::VEC;
+  const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (k >= K) return;
+  const int lane = threadIdx.x & 63;
+  const T* wrow = W + static_cast<int64_t>(k) * Cin;
+  const float bias = b[k];
+  for (int n0 = 0; n0 < N; n0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = 0.f;
+    for (int c = lane * V; c < Cin; c += 64 * V) {
+      float wv[V];
+      if (c + V <= Cin) {
+        Elem<T>::unpack(load16(wrow + c), wv);
+      } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) wv[j] = c + j < Cin ? Elem<T>::load(wrow + c + j) : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (n0 + u < N) {
+          const T* arow = a + static_cast<int64_t>(n0 + u) * Cin + c;
+          float av[V];
+          if (c + V <= Cin) {
+            Elem<T>::unpack(load16(arow), av);
+          } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) av[j] = c + j < Cin ? Elem<T>::load(arow + j) : 0.f;
+          }
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[u] = fmaf(av[j], wv[j], acc[u]);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float sum = wave_sum(acc[u]);
+      if (lane == 0 && n0 + u < N) logits[static_cast<int64_t>(n0 + u) * K + k] = sum + bias;
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void cast_from_float_kernel(const float* __restrict__ in, T* __restrict__ out, int64_t n) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) Elem<T>::store(out + i, in[i]);
+}
+
 // db[k] = sum_n dlogits[n,k]
 __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ dl, float* __restrict__ db,
                                                      int N, int K) {
@@ -313,7 +434,7 @@ using namespace rn50;
   } while (0)
 
 extern "C" int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x, void* y,
-                           void* stream) {
+                           uint8_t* argmax, void* stream) {
   clear_error();
   if (int rc = check_dtype(dtype, "maxpool_fwd")) return rc;
   RN50_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, RN50_ERR_INVALID, "maxpool_fwd: non-positive size");
@@ -325,27 +446,33 @@ extern "C" int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x,
   DISPATCH_T(dtype, {
     const int64_t total = static_cast<int64_t>(N) * P * Q * (C / Elem<T>::VEC);
     hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
-                       static_cast<const T*>(x), static_cast<T*>(y), N, H, W, C, P, Q);
+                       static_cast<const T*>(x), static_cast<T*>(y), argmax, N, H, W, C, P, Q);
   });
   return launch_status("maxpool_fwd");
 }
 
-extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x, const void* dy,
-                           const void* dy2, void* dx, void* stream) {
+extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x,
+                           const uint8_t* argmax, const void* dy, const void* dy2, void* dx,
+                           void* stream) {
   clear_error();
   if (int rc = check_dtype(dtype, "maxpool_bwd")) return rc;
   RN50_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, RN50_ERR_INVALID, "maxpool_bwd: non-positive size");
-  RN50_REQUIRE(x && dy && dx, RN50_ERR_INVALID, "maxpool_bwd: null pointer");
+  RN50_REQUIRE((x || argmax) && dy && dx, RN50_ERR_INVALID, "maxpool_bwd: null pointer");
   RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "maxpool_bwd: C=%d", C);
-  RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2) && aligned16(dx), RN50_ERR_ALIGN,
-               "maxpool_bwd: pointer not 16-byte aligned");
+  RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2) && aligned16(dx) && aligned16(argmax),
+               RN50_ERR_ALIGN, "maxpool_bwd: pointer not 16-byte aligned");
   const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int64_t total = static_cast<int64_t>(N) * H * W * (C / Elem<T>::VEC);
-    hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
-                       static_cast<const T*>(x), static_cast<const T*>(dy),
-                       static_cast<const T*>(dy2), static_cast<T*>(dx), N, H, W, C, P, Q);
+    if (argmax)
+      hipLaunchKernelGGL(maxpool_bwd_idx_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s, argmax,
+                         static_cast<const T*>(dy), static_cast<const T*>(dy2), static_cast<T*>(dx), N,
+                         H, W, C, P, Q);
+    else
+      hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+                         static_cast<const T*>(x), static_cast<const T*>(dy),
+                         static_cast<const T*>(dy2), static_cast<T*>(dx), N, H, W, C, P, Q);
   });
   return launch_status("maxpool_bwd");
 }
@@ -388,26 +515,69 @@ extern "C" int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const voi
   if (int rc = check_dtype(dtype, "fc_fwd")) return rc;
   RN50_REQUIRE(N > 0 && Cin > 0 && K > 0, RN50_ERR_INVALID, "fc_fwd: non-positive size");
   RN50_REQUIRE(a && W && b && logits, RN50_ERR_INVALID, "fc_fwd: null pointer");
+  RN50_REQUIRE(Cin % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "fc_fwd: Cin=%d", Cin);
+  RN50_REQUIRE(aligned16(a) && aligned16(W), RN50_ERR_ALIGN, "fc_fwd: pointer not 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
-    small_gemm<T, T, float>(static_cast<const T*>(a), Cin, 1, static_cast<const T*>(W), 1, Cin, b,
-                            logits, N, K, Cin, s);
+    hipLaunchKernelGGL(fc_fwd_kernel<T>, dim3(ceil_div(K, 4)), dim3(256), 0, s, static_cast<const T*>(a),
+                       static_cast<const T*>(W), b, logits, N, Cin, K);
   });
   return launch_status("fc_fwd");
 }
 
+// The data gradient runs on the matrix cores when the shapes allow it (Cin and K multiples of the
+// 16-byte vector): da = dl x W as a 1x1 "convolution" over N pixels with K input channels, reading
+// dl in the storage type and W transposed to [Cin][K].
+static bool fc_mfma_ok(int Cin, int K, int dtype) {
+  const int V = dtype == RN50_BF16 ? 8 : 4;
+  return Cin % V == 0 && K % V == 0;
+}
+static rn50_conv_desc fc_dgrad_desc(int N, int Cin, int K, int dtype) {
+  return rn50_conv_desc{N, 1, 1, K, Cin, 1, 1, 1, 0, dtype};  // "input channels" K -> "output channels" Cin
+}
+
+extern "C" size_t fc_bwd_workspace_bytes(int N, int Cin, int K, int dtype) {
+  if (N <= 0 || Cin <= 0 || K <= 0 || !fc_mfma_ok(Cin, K, dtype)) return 0;
+  const size_t es = dtype == RN50_BF16 ? 2 : 4;
+  return align_up(static_cast<size_t>(N) * K * es, 256) + align_up(static_cast<size_t>(K) * Cin * es, 256);
+}
+
 extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const void* W,
-                      const float* dlogits, void* da, float* dW, float* db, void* stream) {
+                      const float* dlogits, void* da, float* dW, float* db, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   clear_error();
   if (int rc = check_dtype(dtype, "fc_bwd")) return rc;
   RN50_REQUIRE(N > 0 && Cin > 0 && K > 0, RN50_ERR_INVALID, "fc_bwd: non-positive size");
   RN50_REQUIRE(a && W && dlogits && da && dW && db, RN50_ERR_INVALID, "fc_bwd: null pointer");
+  const size_t need = fc_bwd_workspace_bytes(N, Cin, K, dtype);
+  RN50_REQUIRE(workspace_bytes >= need && (need == 0 || workspace), RN50_ERR_WORKSPACE,
+               "fc_bwd: workspace %zu < %zu bytes", workspace_bytes, need);
+  RN50_REQUIRE(aligned16(a) && aligned16(W) && aligned16(da) && aligned16(dlogits) && aligned16(workspace),
+               RN50_ERR_ALIGN, "fc_bwd: pointer not 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (fc_mfma_ok(Cin, K, dtype)) {
+    const size_t es = dtype == RN50_BF16 ? 2 : 4;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const void* dl_t = dlogits;
+    if (dtype == RN50_BF16) {
+      const int64_t n = static_cast<int64_t>(N) * K;
+      hipLaunchKernelGGL(cast_from_float_kernel<uint16_t>, dim3(ceil_div(n, 256)), dim3(256), 0, s, dlogits,
+                         reinterpret_cast<uint16_t*>(ws), n);
+      dl_t = ws;
+    }
+    void* wT = ws + align_up(static_cast<size_t>(N) * K * es, 256);
+    const rn50_conv_desc wdesc{1, 1, 1, Cin, K, 1, 1, 1, 0, dtype};  // W [K][Cin] -> wT [Cin][K]
+    dgrad_transpose_weights(&wdesc, W, wT, s);
+    const rn50_conv_desc d = fc_dgrad_desc(N, Cin, K, dtype);
+    fwd_run(&d, dl_t, wT, da, s);
+  } else {
+    DISPATCH_T(dtype, {
+      small_gemm<float, T, T>(dlogits, K, 1, static_cast<const T*>(W), Cin, 1, nullptr,
+                              static_cast<T*>(da), N, Cin, K, s);
+    });
+  }
   DISPATCH_T(dtype, {
-    // da[n,c] = sum_k dl[n,k] * W[k,c]
-    small_gemm<float, T, T>(dlogits, K, 1, static_cast<const T*>(W), Cin, 1, nullptr,
-                            static_cast<T*>(da), N, Cin, K, s);
-    // dW[k,c] = sum_n dl[n,k] * a[n,c]
+    // dW[k,c] = sum_n dl[n,k] * a[n,c] (float dl: the parameter gradient keeps float accuracy)
     small_gemm<float, T, float>(dlogits, 1, K, static_cast<const T*>(a), Cin, 1, nullptr, dW, K,
                                 Cin, N, s);
   });

@@ -46,8 +46,9 @@ struct rn50_plan {
   size_t ws_bytes = 0;
   size_t xp = 0, wp = 0, pool = 0, avg = 0, logits = 0, dlogits = 0, row_loss = 0, davg = 0;
   size_t g[5] = {0, 0, 0, 0, 0};
-  size_t wT = 0, wgrad_scratch = 0, bn_scratch = 0, lars_scratch = 0;
-  size_t bn_scratch_bytes = 0;
+  size_t wT = 0, wgrad_scratch = 0, bn_scratch = 0, lars_scratch = 0, pool_argmax = 0, fc_scratch = 0;
+  size_t bn_scratch_bytes = 0, fc_scratch_bytes = 0;
+  std::vector<rn50::TransposeEntry> transposes;
   rn50::LarsArenaSpec lars;
 };
 
@@ -158,7 +159,14 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->dlogits = bump(&top, static_cast<size_t>(N) * cfg->classes * sizeof(float));
   p->row_loss = bump(&top, static_cast<size_t>(N) * sizeof(float));
   for (int i = 0; i < 5; ++i) p->g[i] = bump(&top, max_act * es);
-  p->wT = bump(&top, max_wT);
+  (void)max_wT;
+  p->wT = bump(&top, static_cast<size_t>(p->arena_elems) * es);  // transposed copy of every conv weight
+  for (const Unit& u : p->units)
+    if (u.conv.Cin != 3)
+      p->transposes.push_back(TransposeEntry{p->tensors[u.iw].offset, u.conv.Cout, u.conv.R * u.conv.S, u.conv.Cin});
+  p->pool_argmax = bump(&top, static_cast<size_t>(N) * Hpool * Hpool * cfg->stem);
+  p->fc_scratch_bytes = fc_bwd_workspace_bytes(N, cin, cfg->classes, cfg->dtype);
+  p->fc_scratch = bump(&top, p->fc_scratch_bytes);
   p->wgrad_scratch = bump(&top, max_wg);
   p->bn_scratch = bump(&top, max_bn);
   p->bn_scratch_bytes = max_bn;
@@ -232,7 +240,7 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, s);
   STEP_TRY(bn_relu_fwd(&u0.bn, ws + u0.y, MP(u0.ig), MP(u0.ib), nullptr, ws + u0.z, F(u0.mean), F(u0.rstd),
                        nullptr, nullptr, 0.f, bn_ws, bn_ws_bytes, s));
-  STEP_TRY(maxpool_fwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool, s));
+  STEP_TRY(maxpool_fwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool, ws + plan->pool_argmax, s));
   const unsigned char* cur = ws + plan->pool;
   auto conv_bn = [&](Unit& u, const void* in, const void* residual) -> int {
     fwd_run(&u.conv, in, W(u.iw), ws + u.y, s);
@@ -262,7 +270,9 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
 
   // -------------------------------------------------------------- backward
   STEP_TRY(fc_bwd(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, W(fcw), F(plan->dlogits), ws + plan->davg,
-                  G(fcw), G(fcb), s));
+                  G(fcw), G(fcb), ws + plan->fc_scratch, plan->fc_scratch_bytes, s));
+  // every convolution's weights in [Cin][R][S][Cout] form for the data gradients: one launch
+  transpose_batch_run(plan->transposes, dt, model, ws + plan->wT, s);
   unsigned char* g[5];
   for (int i = 0; i < 5; ++i) g[i] = ws + plan->g[i];
   // g[0], g[1]: the two summands of the gradient w.r.t. the current block output (g[1] may be unused)
@@ -275,10 +285,7 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, z, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
                          G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
     wgrad_run(&u.conv, in, dy, G(u.iw), ws + plan->wgrad_scratch, s);
-    if (dx) {
-      dgrad_transpose_weights(&u.conv, W(u.iw), ws + plan->wT, s);
-      dgrad_run(&u.conv, dy, ws + plan->wT, dx, s);
-    }
+    if (dx) dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, s);
     return RN50_OK;
   };
   for (int bi = static_cast<int>(plan->blocks.size()) - 1; bi >= 0; --bi) {
@@ -296,7 +303,7 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     }
     have2 = true;
   }
-  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, g[0], g[1], g[2], s));
+  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, g[0], g[1], g[2], s));
   STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, g[4], nullptr, nullptr));
 
   // ------------------------------------------------------------------ LARS

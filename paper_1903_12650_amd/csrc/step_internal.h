@@ -19,6 +19,12 @@ void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hip
 size_t dgrad_wt_bytes(const rn50_conv_desc* d);
 void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, hipStream_t s);
 void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, hipStream_t s);
+struct TransposeEntry {
+  int64_t offset;  // element offset of the tensor in both arenas
+  int K, taps, C;
+};
+void transpose_batch_run(const std::vector<TransposeEntry>& list, int dtype, const void* src_arena, void* dst_arena,
+                         hipStream_t s);
 size_t wgrad_partial_bytes(const rn50_conv_desc* d);
 void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s);
 

@@ -88,7 +88,7 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
 
     w, g, b = take()
     t0 = ch.cbn("stem", images, w, g, b, 2, 3, 1)
-    pool = rn.maxpool_fwd(t0["z"])
+    pool, pool_argmax = rn.maxpool_fwd(t0["z"], return_argmax=True)
     if check:
         assert np.array_equal(_h(pool), orc.maxpool_fwd(_h(t0["z"])))
     cur = pool
@@ -141,7 +141,7 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
         else:
             d, d2 = dxa, dres
         block_grads.append(gl)
-    dpool = rn.maxpool_bwd(t0["z"], d, d2)
+    dpool = rn.maxpool_bwd(t0["z"], d, d2, argmax=pool_argmax)
     if check:
         ch.cmp("maxpool_bwd", dpool, orc.maxpool_bwd(_h(t0["z"]), (_h(d) + _h(d2)).astype(np.float32)), max(tol, 4e-3))
     _, _, g0 = ch.cbn_bwd(t0, dpool, need_dx=False)

@@ -103,6 +103,16 @@ def test_maxpool(rn, mode_name, shape):
     assert_close(dx, orc.maxpool_bwd(x, dy), 1e-6 if not bf else 4e-3, "dx")
     dx2 = rn.maxpool_bwd(dev(x, bf), dev(dy, bf), dev(dy2, bf))
     assert_close(dx2, orc.maxpool_bwd(x, dy + dy2), 1e-6 if not bf else 4e-3, "dx(dy+dy2)")
+    # the recorded-winner path: same winners as the oracle's index, same gradients bit for bit
+    y2, am = rn.maxpool_fwd(dev(x, bf), return_argmax=True)
+    _, idx_o = orc.maxpool_fwd(x, return_index=True)
+    P, Q = y_o.shape[1:3]
+    pp, qq = np.meshgrid(np.arange(P), np.arange(Q), indexing="ij")
+    am_h = host(am).astype(np.int64)
+    ih = (2 * pp - 1)[None, :, :, None] + am_h // 3
+    iw = (2 * qq - 1)[None, :, :, None] + am_h % 3
+    assert np.array_equal(ih * W + iw, idx_o) and torch.equal(y2, y)
+    assert torch.equal(rn.maxpool_bwd(dev(x, bf), dev(dy, bf), dev(dy2, bf), argmax=am), dx2)
 
 
 @pytest.mark.parametrize("mode_name", ["f32", "bf16"])
