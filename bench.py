@@ -57,7 +57,7 @@ def build_state(rn, N, dtype):
     return S
 
 
-def cpu_baseline(batch_sample=2):
+def cpu_baseline(batch_sample=40):
     """The oracle's training step (forward, backward, LARS) on a bounded sample: `batch_sample`
     images of the same 224x224 workload, all host cores OpenMP gives it."""
     import numpy as np
