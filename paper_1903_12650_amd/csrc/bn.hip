@@ -21,6 +21,8 @@
 
 namespace rn50 {
 
+constexpr int kBnRows = 4;  // rows a thread loads before it touches any of them (memory-level parallelism)
+
 struct BnGeom {
   int V;        // elements per 16-byte vector
   int cvecs;    // C / V
@@ -38,9 +40,14 @@ static BnGeom bn_geom(int64_t m, int C, int dtype) {
   while ((1 << g.tx_log2) < g.cvecs && g.tx_log2 < 5) ++g.tx_log2;
   const int TX = 1 << g.tx_log2, TY = 256 / TX;
   g.gy = static_cast<int>(ceil_div(g.cvecs, TX));
-  int64_t rpb = ceil_div(m, 1024);
-  if (rpb < TY * 8) rpb = TY * 8;
-  rpb = ceil_div(rpb, TY) * TY;
+  // rows per thread: aim at ~1024 workgroups in all, but at least 64 rows per workgroup so that the
+  // per-workgroup partial sums stay a few percent of the tensor; a multiple of the 4 rows whose loads
+  // are issued together
+  const int64_t nblk_target = 1024 / g.gy > 0 ? 1024 / g.gy : 1;
+  int64_t rpt = ceil_div(m, static_cast<int64_t>(TY) * nblk_target);
+  if (rpt * TY < 64) rpt = ceil_div(64, TY);
+  rpt = ceil_div(rpt, kBnRows) * kBnRows;
+  const int64_t rpb = rpt * TY;
   g.rpb = static_cast<int>(rpb);
   g.nblk = static_cast<int>(ceil_div(m, rpb));
   return g;
@@ -94,15 +101,22 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
     const int64_t r1 = min(r0 + rpb, m);
     const T* p = x + static_cast<int64_t>(col) * V;
-#pragma unroll 4
-    for (int64_t r = r0 + trow; r < r1; r += TY) {
-      float f[V];
-      Elem<T>::unpack(load16(p + r * C), f);
+    for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
+      Vec16 v[kBnRows];
 #pragma unroll
-      for (int j = 0; j < V; ++j) {
-        const float d = f[j] - K[j];
-        acc[j] += d;
-        acc[V + j] = fmaf(d, d, acc[V + j]);
+      for (int u = 0; u < kBnRows; ++u) v[u] = load16(p + min(r + u * TY, r1 - 1) * C);
+#pragma unroll
+      for (int u = 0; u < kBnRows; ++u) {
+        if (r + u * TY < r1) {
+          float f[V];
+          Elem<T>::unpack(v[u], f);
+#pragma unroll
+          for (int j = 0; j < V; ++j) {
+            const float d = f[j] - K[j];
+            acc[j] += d;
+            acc[V + j] = fmaf(d, d, acc[V + j]);
+          }
+        }
       }
     }
   }
@@ -118,39 +132,74 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   }
 }
 
-// One wave per channel: sums the nblk partials in double (fixed order).
+// Sums of the nblk partials of cpb = 1 << cpb_log2 channels per workgroup: thread (c, part) adds every
+// (256/cpb)-th partial row, the parts are then added in order; all in double, a fixed order.  Few
+// channels per workgroup (narrow layers) keeps enough workgroups busy; many (wide layers) keeps the
+// reads of a partial row contiguous.  Result for channel c in the first cpb threads.
+__device__ __forceinline__ bool finalize_sums(const float* __restrict__ partial, int nblk, int C, int cpb_log2,
+                                              double* s1_out, double* s2_out, int* c_out) {
+  __shared__ double red[2][256];
+  const int cpb = 1 << cpb_log2, parts = 256 >> cpb_log2;
+  const int cl = threadIdx.x & (cpb - 1), part = threadIdx.x >> cpb_log2;
+  const int c = blockIdx.x * cpb + cl;
+  double s1 = 0.0, s2 = 0.0;
+  if (c < C) {
+    // batches of 8 rows whose 16 loads are issued before the (ordered) additions
+    int b = part;
+    for (; b + 7 * parts < nblk; b += 8 * parts) {
+      float v1[8], v2[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        v1[u] = partial[(static_cast<int64_t>(b + u * parts) * 2) * C + c];
+        v2[u] = partial[(static_cast<int64_t>(b + u * parts) * 2 + 1) * C + c];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        s1 += static_cast<double>(v1[u]);
+        s2 += static_cast<double>(v2[u]);
+      }
+    }
+    for (; b < nblk; b += parts) {
+      s1 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2) * C + c]);
+      s2 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2 + 1) * C + c]);
+    }
+  }
+  red[0][threadIdx.x] = s1;
+  red[1][threadIdx.x] = s2;
+  __syncthreads();
+  *c_out = c;
+  if (part != 0 || c >= C) return false;
+  s1 = 0.0; s2 = 0.0;
+  for (int k = 0; k < parts; ++k) {
+    s1 += red[0][k * cpb + cl];
+    s2 += red[1][k * cpb + cl];
+  }
+  *s1_out = s1;
+  *s2_out = s2;
+  return true;
+}
+static int finalize_cpb_log2(int C) { return C >= 1024 ? 3 : 2; }
+
 template <typename T>
 __global__ __launch_bounds__(256) void bn_finalize_kernel(const T* __restrict__ x,
                                                           const float* __restrict__ partial,
-                                                          int nblk, int64_t m, int C, float eps,
-                                                          float* __restrict__ mean_out,
+                                                          int nblk, int64_t m, int C, int cpb_log2,
+                                                          float eps, float* __restrict__ mean_out,
                                                           float* __restrict__ rstd_out,
                                                           float* running_mean, float* running_var,
                                                           float momentum) {
-  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (c >= C) return;
-  const int lane = threadIdx.x & 63;
-  double s1 = 0.0, s2 = 0.0;
-  for (int b = lane; b < nblk; b += 64) {
-    s1 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2) * C + c]);
-    s2 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2 + 1) * C + c]);
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    s1 += __shfl_xor(s1, off, 64);
-    s2 += __shfl_xor(s2, off, 64);
-  }
-  if (lane == 0) {
-    const double K = static_cast<double>(Elem<T>::load(x + c));
-    const double d = s1 / static_cast<double>(m);
-    double var = s2 / static_cast<double>(m) - d * d;
-    if (var < 0.0) var = 0.0;
-    const double mean = K + d;
-    mean_out[c] = static_cast<float>(mean);
-    rstd_out[c] = static_cast<float>(1.0 / sqrt(var + static_cast<double>(eps)));
-    if (running_mean) running_mean[c] = momentum * running_mean[c] + (1.f - momentum) * static_cast<float>(mean);
-    if (running_var) running_var[c] = momentum * running_var[c] + (1.f - momentum) * static_cast<float>(var);
-  }
+  double s1, s2;
+  int c;
+  if (!finalize_sums(partial, nblk, C, cpb_log2, &s1, &s2, &c)) return;
+  const double K = static_cast<double>(Elem<T>::load(x + c));
+  const double d = s1 / static_cast<double>(m);
+  double var = s2 / static_cast<double>(m) - d * d;
+  if (var < 0.0) var = 0.0;
+  const double mean = K + d;
+  mean_out[c] = static_cast<float>(mean);
+  rstd_out[c] = static_cast<float>(1.0 / sqrt(var + static_cast<double>(eps)));
+  if (running_mean) running_mean[c] = momentum * running_mean[c] + (1.f - momentum) * static_cast<float>(mean);
+  if (running_var) running_var[c] = momentum * running_var[c] + (1.f - momentum) * static_cast<float>(var);
 }
 
 template <typename T>
@@ -176,47 +225,86 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
   }
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
   const int64_t r1 = min(r0 + rpb, m);
-#pragma unroll 4
-  for (int64_t r = r0 + trow; r < r1; r += TY) {
-    const int64_t off = r * C + static_cast<int64_t>(col) * V;
-    float f[V];
-    Elem<T>::unpack(load16(x + off), f);
-    if (mode == 2) {
-      float rr[V];
-      Elem<T>::unpack(load16(residual + off), rr);
+  for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
+    int64_t off[kBnRows];
+    Vec16 vx[kBnRows], vr[kBnRows];
 #pragma unroll
-      for (int j = 0; j < V; ++j) f[j] = fmaxf(bn_affine(f[j], scale[j], bias[j]) + rr[j], 0.f);
-    } else if (mode == 1) {
-#pragma unroll
-      for (int j = 0; j < V; ++j) f[j] = fmaxf(bn_affine(f[j], scale[j], bias[j]), 0.f);
-    } else {
-#pragma unroll
-      for (int j = 0; j < V; ++j) f[j] = bn_affine(f[j], scale[j], bias[j]);
+    for (int u = 0; u < kBnRows; ++u) {
+      off[u] = min(r + u * TY, r1 - 1) * C + static_cast<int64_t>(col) * V;
+      vx[u] = load16(x + off[u]);
     }
-    Vec16 o;
-    Elem<T>::pack(f, o);
-    store16(y + off, o);
+    if (mode == 2) {
+#pragma unroll
+      for (int u = 0; u < kBnRows; ++u) vr[u] = load16(residual + off[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kBnRows; ++u) {
+      if (r + u * TY < r1) {
+        float f[V];
+        Elem<T>::unpack(vx[u], f);
+        if (mode == 2) {
+          float rr[V];
+          Elem<T>::unpack(vr[u], rr);
+#pragma unroll
+          for (int j = 0; j < V; ++j) f[j] = fmaxf(bn_affine(f[j], scale[j], bias[j]) + rr[j], 0.f);
+        } else if (mode == 1) {
+#pragma unroll
+          for (int j = 0; j < V; ++j) f[j] = fmaxf(bn_affine(f[j], scale[j], bias[j]), 0.f);
+        } else {
+#pragma unroll
+          for (int j = 0; j < V; ++j) f[j] = bn_affine(f[j], scale[j], bias[j]);
+        }
+        Vec16 o;
+        Elem<T>::pack(f, o);
+        store16(y + off[u], o);
+      }
+    }
   }
 }
 
 // ------------------------------------------------------------------ backward
+// The operands of kBnRows rows, loaded before any is used.
+struct BwdRows {
+  Vec16 x[kBnRows], dz[kBnRows], dz2[kBnRows], z[kBnRows];
+  int64_t off[kBnRows];
+};
+template <typename T>
+__device__ __forceinline__ void load_bwd_rows(BwdRows& b, const T* dz, const T* dz2, const T* x, const T* z,
+                                              int64_t r, int64_t r1, int TY, int C, int col) {
+  constexpr int V = Elem<T>::VEC;
+#pragma unroll
+  for (int u = 0; u < kBnRows; ++u) {
+    b.off[u] = min(r + u * TY, r1 - 1) * C + static_cast<int64_t>(col) * V;
+    b.x[u] = load16(x + b.off[u]);
+    b.dz[u] = load16(dz + b.off[u]);
+  }
+  if (dz2) {
+#pragma unroll
+    for (int u = 0; u < kBnRows; ++u) b.dz2[u] = load16(dz2 + b.off[u]);
+  }
+  if (z) {
+#pragma unroll
+    for (int u = 0; u < kBnRows; ++u) b.z[u] = load16(z + b.off[u]);
+  }
+}
+
 // g = (dz + dz2) * mask for one 16-byte vector.
 template <typename T>
-__device__ __forceinline__ void masked_grad(const T* dz, const T* dz2, const T* z, int64_t off,
-                                            const float* xf, const float* scale, const float* bias,
+__device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2, const Vec16& vz, bool has_dz2,
+                                            bool has_z, const float* xf, const float* scale, const float* bias,
                                             int mode, float* g) {
   constexpr int V = Elem<T>::VEC;
-  Elem<T>::unpack(load16(dz + off), g);
-  if (dz2) {
+  Elem<T>::unpack(vdz, g);
+  if (has_dz2) {
     float g2[V];
-    Elem<T>::unpack(load16(dz2 + off), g2);
+    Elem<T>::unpack(vdz2, g2);
 #pragma unroll
     for (int j = 0; j < V; ++j) g[j] += g2[j];
   }
   if (mode >= 1) {
-    if (z) {
+    if (has_z) {
       float zf[V];
-      Elem<T>::unpack(load16(z + off), zf);
+      Elem<T>::unpack(vz, zf);
 #pragma unroll
       for (int j = 0; j < V; ++j) g[j] = zf[j] > 0.f ? g[j] : 0.f;
     } else {
@@ -253,16 +341,21 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     }
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
     const int64_t r1 = min(r0 + rpb, m);
-#pragma unroll 2
-    for (int64_t r = r0 + trow; r < r1; r += TY) {
-      const int64_t off = r * C + static_cast<int64_t>(col) * V;
-      float xf[V], g[V];
-      Elem<T>::unpack(load16(x + off), xf);
-      masked_grad<T>(dz, dz2, z, off, xf, scale, bias, mode, g);
+    for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
+      BwdRows b;
+      load_bwd_rows<T>(b, dz, dz2, x, z, r, r1, TY, C, col);
 #pragma unroll
-      for (int j = 0; j < V; ++j) {
-        acc[j] += g[j];
-        acc[V + j] = fmaf(g[j], fmaf(xf[j], rs[j], nmr[j]), acc[V + j]);
+      for (int u = 0; u < kBnRows; ++u) {
+        if (r + u * TY < r1) {
+          float xf[V], g[V];
+          Elem<T>::unpack(b.x[u], xf);
+          masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], dz2 != nullptr, z != nullptr, xf, scale, bias, mode, g);
+#pragma unroll
+          for (int j = 0; j < V; ++j) {
+            acc[j] += g[j];
+            acc[V + j] = fmaf(g[j], fmaf(xf[j], rs[j], nmr[j]), acc[V + j]);
+          }
+        }
       }
     }
   }
@@ -279,26 +372,14 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 }
 
 __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partial,
-                                                              int nblk, int C,
+                                                              int nblk, int C, int cpb_log2,
                                                               float* __restrict__ dgamma,
                                                               float* __restrict__ dbeta) {
-  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (c >= C) return;
-  const int lane = threadIdx.x & 63;
-  double s1 = 0.0, s2 = 0.0;
-  for (int b = lane; b < nblk; b += 64) {
-    s1 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2) * C + c]);
-    s2 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2 + 1) * C + c]);
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    s1 += __shfl_xor(s1, off, 64);
-    s2 += __shfl_xor(s2, off, 64);
-  }
-  if (lane == 0) {
-    dbeta[c] = static_cast<float>(s1);
-    dgamma[c] = static_cast<float>(s2);
-  }
+  double s1, s2;
+  int c;
+  if (!finalize_sums(partial, nblk, C, cpb_log2, &s1, &s2, &c)) return;
+  dbeta[c] = static_cast<float>(s1);
+  dgamma[c] = static_cast<float>(s2);
 }
 
 template <typename T>
@@ -327,24 +408,29 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
   }
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
   const int64_t r1 = min(r0 + rpb, m);
-#pragma unroll 2
-  for (int64_t r = r0 + trow; r < r1; r += TY) {
-    const int64_t off = r * C + static_cast<int64_t>(col) * V;
-    float xf[V], g[V], o[V];
-    Elem<T>::unpack(load16(x + off), xf);
-    masked_grad<T>(dz, dz2, z, off, xf, scale, bias, mode, g);
+  for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
+    BwdRows b;
+    load_bwd_rows<T>(b, dz, dz2, x, z, r, r1, TY, C, col);
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-      const float xh = fmaf(xf[j], rs[j], nmr[j]);
-      o[j] = scale[j] * (g[j] - mg[j] - xh * mgx[j]);
-    }
-    Vec16 ov;
-    Elem<T>::pack(o, ov);
-    store16(dx + off, ov);
-    if (mode == 2) {
-      Vec16 gv;
-      Elem<T>::pack(g, gv);
-      store16(dres + off, gv);
+    for (int u = 0; u < kBnRows; ++u) {
+      if (r + u * TY < r1) {
+        float xf[V], g[V], o[V];
+        Elem<T>::unpack(b.x[u], xf);
+        masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], dz2 != nullptr, z != nullptr, xf, scale, bias, mode, g);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+          const float xh = fmaf(xf[j], rs[j], nmr[j]);
+          o[j] = scale[j] * (g[j] - mg[j] - xh * mgx[j]);
+        }
+        Vec16 ov;
+        Elem<T>::pack(o, ov);
+        store16(dx + b.off[u], ov);
+        if (mode == 2) {
+          Vec16 gv;
+          Elem<T>::pack(g, gv);
+          store16(dres + b.off[u], gv);
+        }
+      }
     }
   }
 }
@@ -376,9 +462,11 @@ static void launch_fwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
   RN50_TIMED("bn_stats", s,
              hipLaunchKernelGGL(bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
                                 static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial));
-  hipLaunchKernelGGL(bn_finalize_kernel<T>, dim3(ceil_div(d->C, 4)), dim3(256), 0, s,
-                     static_cast<const T*>(x), partial, g.nblk, m, d->C, d->eps, save_mean,
-                     save_rstd, rm, rv, momentum);
+  RN50_TIMED("bn_finalize", s,
+             hipLaunchKernelGGL(bn_finalize_kernel<T>, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
+                                dim3(256), 0, s, static_cast<const T*>(x), partial, g.nblk, m, d->C,
+                                finalize_cpb_log2(d->C), d->eps,
+                                save_mean, save_rstd, rm, rv, momentum));
   RN50_TIMED("bn_apply", s,
              hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
                                 static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
@@ -397,8 +485,10 @@ static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                                 static_cast<const T*>(dz), static_cast<const T*>(dz2),
                                 static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
                                 mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial));
-  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(d->C, 4)), dim3(256), 0, s, partial,
-                     g.nblk, d->C, dgamma, dbeta);
+  RN50_TIMED("bn_bwd_finalize", s,
+             hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
+                                dim3(256), 0, s, partial, g.nblk, d->C, finalize_cpb_log2(d->C), dgamma,
+                                dbeta));
   RN50_TIMED("bn_bwd_apply", s,
              hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
                                 static_cast<const T*>(dz), static_cast<const T*>(dz2),
