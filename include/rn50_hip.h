@@ -126,6 +126,37 @@ int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const vo
                 const float* save_rstd, void* dx, void* dresidual, float* dgamma, float* dbeta,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------- convolution + batch norm with fused sums
+ * The same operations, with the per-channel sums of the batch norm taken in the
+ * output stage of the convolution that produces the tensor they range over
+ * (one row of partial sums per output tile), so that no separate pass re-reads
+ * that tensor.  Forward: conv_fwd_bn_sums produces y and `sums`, then
+ * bn_relu_fwd_from_sums(d, producer, y, sums, ...) gives what bn_relu_fwd(d, y, ...)
+ * gives.  Backward, for a mode-1 BN layer (ReLU, no residual) whose output z feeds
+ * exactly one convolution `producer`: conv_dgrad_bn_sums computes dz = that
+ * convolution's data gradient and the sums over g = dz*[z>0] and g*xhat of the BN
+ * layer (bn_x: the BN layer's input, [N,H,W,Cin] of the convolution; gamma, beta,
+ * save_mean, save_rstd: the layer's, device float[Cin]); bn_relu_bwd_from_sums then
+ * gives what bn_relu_bwd(d, dz, NULL, x, NULL, ...) gives.  The sums are formed
+ * from the rounded values that are stored, in a fixed order.
+ * sums: device float, conv_bn_sums_bytes(d) bytes (16-byte aligned), layout private
+ * to the pair of calls; `producer` must be the descriptor the sums were made with. */
+size_t conv_bn_sums_bytes(const rn50_conv_desc* d);
+int conv_fwd_bn_sums(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* sums,
+                     size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream);
+int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* x,
+                          const float* sums, const float* gamma, const float* beta,
+                          const void* residual, void* y, float* save_mean, float* save_rstd,
+                          float* running_mean, float* running_var, float momentum, void* stream);
+int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
+                       const void* bn_x, const float* gamma, const float* beta,
+                       const float* save_mean, const float* save_rstd, float* sums,
+                       size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream);
+int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* dz,
+                          const void* x, const float* gamma, const float* beta,
+                          const float* save_mean, const float* save_rstd, const float* sums,
+                          void* dx, float* dgamma, float* dbeta, void* stream);
+
 /* --------------------------------------------------------------------- pooling
  * Max pooling, window 3x3, stride 2, pad 1 (the appendix's 112 -> 56 step);
  * padding never wins; among equal maxima the first in row-major window order

@@ -13,7 +13,8 @@ __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "co
            "bn_relu_bwd", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "fc_fwd", "fc_bwd",
            "xent_fwd_bwd", "lars_update", "LarsTable", "profile_begin", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
-           "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw"]
+           "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
+           "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums"]
 
 F32, BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -65,7 +66,7 @@ class StepConfig(ctypes.Structure):
 raw.rn50_last_error.restype = ctypes.c_char_p
 for _n in ("conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "lars_update_workspace_bytes",
-           "resnet_plan_workspace_bytes"):
+           "resnet_plan_workspace_bytes", "conv_bn_sums_bytes"):
     if hasattr(raw, _n):
         getattr(raw, _n).restype = ctypes.c_size_t
 for _n in ("resnet_plan_tensor_shape", "resnet_plan_tensor_offset", "resnet_plan_arena_elems"):
@@ -199,6 +200,70 @@ def bn_relu_bwd(dz, x, z, gamma, mean, rstd, mode=1, beta=None, dz2=None, eps=1e
                            _ptr(mean), _ptr(rstd), _ptr(dx), _ptr(dres), _ptr(dgamma), _ptr(dbeta),
                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
     return dx, dres, dgamma, dbeta
+
+
+# ------------------------------------- convolution + batch norm with fused sums
+def conv_bn_sums_bytes(desc):
+    return raw.conv_bn_sums_bytes(ctypes.byref(desc))
+
+
+def conv_fwd_bn_sums(x, w, stride, pad, y=None, workspace=None, sums=None):
+    """Returns y and the handle (producer descriptor, sums buffer) bn_relu_fwd_from_sums takes."""
+    d = _conv_desc(x.shape, w.shape, stride, pad, _dt(x))
+    P = (d.H + 2 * pad - d.R) // stride + 1
+    Q = (d.W + 2 * pad - d.S) // stride + 1
+    if y is None:
+        y = torch.empty((d.N, P, Q, d.Cout), dtype=x.dtype, device=x.device)
+    if workspace is None:
+        workspace = _ws(conv_fwd_workspace_bytes(d), x.device)
+    if sums is None:
+        sums = _ws(conv_bn_sums_bytes(d), x.device)
+    _check(raw.conv_fwd_bn_sums(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _ptr(sums), ctypes.c_size_t(sums.numel()),
+                                _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    return y, (d, sums)
+
+
+def bn_relu_fwd_from_sums(x, handle, gamma, beta, residual=None, eps=1e-5, mode=1, running_mean=None,
+                          running_var=None, momentum=0.9):
+    """Returns y, save_mean, save_rstd."""
+    producer, sums = handle
+    d = _bn_desc(x, eps, mode)
+    y = torch.empty_like(x)
+    mean = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    rstd = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    _check(raw.bn_relu_fwd_from_sums(ctypes.byref(d), ctypes.byref(producer), _ptr(x), _ptr(sums), _ptr(gamma),
+                                     _ptr(beta), _ptr(residual), _ptr(y), _ptr(mean), _ptr(rstd), _ptr(running_mean),
+                                     _ptr(running_var), ctypes.c_float(momentum), _stream()))
+    return y, mean, rstd
+
+
+def conv_dgrad_bn_sums(dy, w, x_shape, stride, pad, bn_x, gamma, beta, mean, rstd, dx=None, workspace=None,
+                       sums=None):
+    """Returns dx and the handle bn_relu_bwd_from_sums takes."""
+    d = _conv_desc(x_shape, w.shape, stride, pad, _dt(dy))
+    if dx is None:
+        dx = torch.empty(tuple(x_shape), dtype=dy.dtype, device=dy.device)
+    if workspace is None:
+        workspace = _ws(conv_dgrad_workspace_bytes(d), dy.device)
+    if sums is None:
+        sums = _ws(conv_bn_sums_bytes(d), dy.device)
+    _check(raw.conv_dgrad_bn_sums(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(bn_x), _ptr(gamma), _ptr(beta),
+                                  _ptr(mean), _ptr(rstd), _ptr(sums), ctypes.c_size_t(sums.numel()), _ptr(workspace),
+                                  ctypes.c_size_t(workspace.numel()), _stream()))
+    return dx, (d, sums)
+
+
+def bn_relu_bwd_from_sums(dz, x, handle, gamma, beta, mean, rstd, eps=1e-5):
+    """Returns dx, dgamma, dbeta (BN + ReLU, no residual)."""
+    producer, sums = handle
+    d = _bn_desc(x, eps, 1)
+    dx = torch.empty_like(x)
+    dgamma = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    dbeta = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    _check(raw.bn_relu_bwd_from_sums(ctypes.byref(d), ctypes.byref(producer), _ptr(dz), _ptr(x), _ptr(gamma),
+                                     _ptr(beta), _ptr(mean), _ptr(rstd), _ptr(sums), _ptr(dx), _ptr(dgamma),
+                                     _ptr(dbeta), _stream()))
+    return dx, dgamma, dbeta
 
 
 # -------------------------------------------------------------------- pooling

@@ -18,6 +18,7 @@
 // within a few standard deviations of the mean; partial sums of all workgroups
 // then combine by plain addition (done in double).
 #include "common.h"
+#include "step_internal.h"
 
 namespace rn50 {
 
@@ -53,12 +54,6 @@ static BnGeom bn_geom(int64_t m, int C, int dtype) {
   return g;
 }
 
-// The affine step, written once so that forward and backward take the ReLU
-// decision from bit-identical arithmetic.
-__device__ __forceinline__ float bn_affine(float x, float scale, float bias) {
-  return fmaf(x, scale, bias);
-}
-
 // Tree-combine NV floats per thread over the TY rows of the workgroup; the
 // result lands in the threads of row 0.
 template <int NV>
@@ -92,11 +87,10 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   const int tcol = threadIdx.x & (TX - 1), trow = threadIdx.x >> tx_log2;
   const int col = blockIdx.y * TX + tcol;
   const bool active = col < C / V;
-  float acc[2 * V];
+  float acc[2 * V], K[V];
 #pragma unroll
   for (int j = 0; j < 2 * V; ++j) acc[j] = 0.f;
   if (active) {
-    float K[V];
     Elem<T>::unpack(load16(x + static_cast<int64_t>(col) * V), K);
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
     const int64_t r1 = min(r0 + rpb, m);
@@ -122,12 +116,12 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   }
   combine_rows<2 * V>(acc, lds, tx_log2);
   if (active && trow == 0) {
-    float* o1 = partial + (static_cast<int64_t>(blockIdx.x) * 2) * C + col * V;
-    float* o2 = o1 + C;
+    float* o0 = partial + (static_cast<int64_t>(blockIdx.x) * 3) * C + col * V;
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-      o1[j] = acc[j];
-      o2[j] = acc[V + j];
+      o0[j] = K[j];
+      o0[C + j] = acc[j];
+      o0[2 * C + j] = acc[V + j];
     }
   }
 }
@@ -180,18 +174,75 @@ __device__ __forceinline__ bool finalize_sums(const float* __restrict__ partial,
 }
 static int finalize_cpb_log2(int C) { return C >= 1024 ? 3 : 2; }
 
-template <typename T>
-__global__ __launch_bounds__(256) void bn_finalize_kernel(const T* __restrict__ x,
-                                                          const float* __restrict__ partial,
-                                                          int nblk, int64_t m, int C, int cpb_log2,
-                                                          float eps, float* __restrict__ mean_out,
+// The forward statistics come as rows [shift, S1, S2] over `rpp` consecutive rows of x each (the last row
+// of partials may cover fewer), every row with a shift of its own: S1 = sum(x - shift), S2 = sum((x -
+// shift)^2).  They are moved to the first row's shift K0 exactly, in double,
+//   sum(x - K0) = S1 + n e,  sum((x - K0)^2) = S2 + 2 e S1 + n e^2,  e = shift - K0,
+// and added as in finalize_sums.
+__device__ __forceinline__ bool finalize_stats(const float* __restrict__ partial, int nrows, int rpp, int64_t m,
+                                               int C, int cpb_log2, double* s1_out, double* s2_out,
+                                               double* k0_out, int* c_out) {
+  __shared__ double red[2][256];
+  const int cpb = 1 << cpb_log2, parts = 256 >> cpb_log2;
+  const int cl = threadIdx.x & (cpb - 1), part = threadIdx.x >> cpb_log2;
+  const int c = blockIdx.x * cpb + cl;
+  double s1 = 0.0, s2 = 0.0, k0 = 0.0;
+  if (c < C) {
+    k0 = static_cast<double>(partial[c]);
+    constexpr int U = 4;
+    int b = part;
+    for (; b + (U - 1) * parts < nrows; b += U * parts) {
+      float vk[U], v1[U], v2[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float* p = partial + (static_cast<int64_t>(b + u * parts) * 3) * C + c;
+        vk[u] = p[0];
+        v1[u] = p[C];
+        v2[u] = p[2 * C];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t left = m - static_cast<int64_t>(b + u * parts) * rpp;
+        const double n = static_cast<double>(left < rpp ? left : rpp);
+        const double e = static_cast<double>(vk[u]) - k0, a1 = static_cast<double>(v1[u]);
+        s1 += a1 + n * e;
+        s2 += static_cast<double>(v2[u]) + e * (2.0 * a1 + n * e);
+      }
+    }
+    for (; b < nrows; b += parts) {
+      const float* p = partial + (static_cast<int64_t>(b) * 3) * C + c;
+      const int64_t left = m - static_cast<int64_t>(b) * rpp;
+      const double n = static_cast<double>(left < rpp ? left : rpp);
+      const double e = static_cast<double>(p[0]) - k0, a1 = static_cast<double>(p[C]);
+      s1 += a1 + n * e;
+      s2 += static_cast<double>(p[2 * C]) + e * (2.0 * a1 + n * e);
+    }
+  }
+  red[0][threadIdx.x] = s1;
+  red[1][threadIdx.x] = s2;
+  __syncthreads();
+  *c_out = c;
+  if (part != 0 || c >= C) return false;
+  s1 = 0.0; s2 = 0.0;
+  for (int k = 0; k < parts; ++k) {
+    s1 += red[0][k * cpb + cl];
+    s2 += red[1][k * cpb + cl];
+  }
+  *s1_out = s1;
+  *s2_out = s2;
+  *k0_out = k0;
+  return true;
+}
+
+__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partial, int nrows, int rpp,
+                                                          int64_t m, int C, int cpb_log2, float eps,
+                                                          float* __restrict__ mean_out,
                                                           float* __restrict__ rstd_out,
                                                           float* running_mean, float* running_var,
                                                           float momentum) {
-  double s1, s2;
+  double s1, s2, K;
   int c;
-  if (!finalize_sums(partial, nblk, C, cpb_log2, &s1, &s2, &c)) return;
-  const double K = static_cast<double>(Elem<T>::load(x + c));
+  if (!finalize_stats(partial, nrows, rpp, m, C, cpb_log2, &s1, &s2, &K, &c)) return;
   const double d = s1 / static_cast<double>(m);
   double var = s2 / static_cast<double>(m) - d * d;
   if (var < 0.0) var = 0.0;
@@ -220,8 +271,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     const int c = col * V + j;
-    scale[j] = gamma[c] * rstd[c];
-    bias[j] = beta[c] - mean[c] * scale[j];
+    bn_coeffs(gamma[c], beta[c], mean[c], rstd[c], &scale[j], &bias[j]);
   }
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
   const int64_t r1 = min(r0 + rpb, m);
@@ -336,8 +386,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
       const int c = col * V + j;
       rs[j] = rstd[c];
       nmr[j] = -mean[c] * rs[j];
-      scale[j] = gamma[c] * rs[j];
-      bias[j] = (beta ? beta[c] : 0.f) - mean[c] * scale[j];
+      bn_coeffs(gamma[c], beta ? beta[c] : 0.f, mean[c], rs[j], &scale[j], &bias[j]);
     }
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
     const int64_t r1 = min(r0 + rpb, m);
@@ -401,8 +450,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     const int c = col * V + j;
     rs[j] = rstd[c];
     nmr[j] = -mean[c] * rs[j];
-    scale[j] = gamma[c] * rs[j];
-    bias[j] = (beta ? beta[c] : 0.f) - mean[c] * scale[j];
+    bn_coeffs(gamma[c], beta ? beta[c] : 0.f, mean[c], rs[j], &scale[j], &bias[j]);
     mg[j] = dbeta[c] * inv_m;
     mgx[j] = dgamma[c] * inv_m;
   }
@@ -450,7 +498,25 @@ static int check_desc(const rn50_bn_desc* d, const char* who) {
 static size_t bn_ws_bytes(const rn50_bn_desc* d) {
   const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
   const BnGeom g = bn_geom(m, d->C, d->dtype);
-  return align_up(static_cast<size_t>(g.nblk) * 2 * d->C * sizeof(float), 256);
+  return align_up(static_cast<size_t>(g.nblk) * 3 * d->C * sizeof(float), 256);
+}
+
+// finalize + apply from partial statistics rows (see finalize_stats)
+template <typename T>
+static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* x,
+                            const float* gamma, const float* beta, const void* residual, void* y,
+                            float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
+                            const float* partial, int nrows, int rpp, hipStream_t s) {
+  RN50_TIMED("bn_finalize", s,
+             hipLaunchKernelGGL(bn_finalize_kernel, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
+                                dim3(256), 0, s, partial, nrows, rpp, m, d->C,
+                                finalize_cpb_log2(d->C), d->eps,
+                                save_mean, save_rstd, rm, rv, momentum));
+  RN50_TIMED("bn_apply", s,
+             hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
+                                static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
+                                static_cast<const T*>(residual), static_cast<T*>(y), m, d->C,
+                                g.tx_log2, g.rpb, d->mode));
 }
 
 template <typename T>
@@ -462,16 +528,27 @@ static void launch_fwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
   RN50_TIMED("bn_stats", s,
              hipLaunchKernelGGL(bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
                                 static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial));
-  RN50_TIMED("bn_finalize", s,
-             hipLaunchKernelGGL(bn_finalize_kernel<T>, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
-                                dim3(256), 0, s, static_cast<const T*>(x), partial, g.nblk, m, d->C,
-                                finalize_cpb_log2(d->C), d->eps,
-                                save_mean, save_rstd, rm, rv, momentum));
-  RN50_TIMED("bn_apply", s,
-             hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
-                                static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
-                                static_cast<const T*>(residual), static_cast<T*>(y), m, d->C,
-                                g.tx_log2, g.rpb, d->mode));
+  launch_fwd_tail<T>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
+                     g.nblk, g.rpb, s);
+}
+
+// finalize + apply from partial sums rows [sum g, sum g*xhat]
+template <typename T>
+static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* dz,
+                            const void* dz2, const void* x, const void* z, const float* gamma,
+                            const float* beta, const float* mean, const float* rstd, void* dx,
+                            void* dres, float* dgamma, float* dbeta, const float* partial, int nrows,
+                            hipStream_t s) {
+  RN50_TIMED("bn_bwd_finalize", s,
+             hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
+                                dim3(256), 0, s, partial, nrows, d->C, finalize_cpb_log2(d->C), dgamma,
+                                dbeta));
+  RN50_TIMED("bn_bwd_apply", s,
+             hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
+                                static_cast<const T*>(dz), static_cast<const T*>(dz2),
+                                static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
+                                mean, rstd, dgamma, dbeta, static_cast<T*>(dx),
+                                static_cast<T*>(dres), m, d->C, g.tx_log2, g.rpb, d->mode));
 }
 
 template <typename T>
@@ -485,16 +562,34 @@ static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                                 static_cast<const T*>(dz), static_cast<const T*>(dz2),
                                 static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
                                 mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial));
-  RN50_TIMED("bn_bwd_finalize", s,
-             hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
-                                dim3(256), 0, s, partial, g.nblk, d->C, finalize_cpb_log2(d->C), dgamma,
-                                dbeta));
-  RN50_TIMED("bn_bwd_apply", s,
-             hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
-                                static_cast<const T*>(dz), static_cast<const T*>(dz2),
-                                static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
-                                mean, rstd, dgamma, dbeta, static_cast<T*>(dx),
-                                static_cast<T*>(dres), m, d->C, g.tx_log2, g.rpb, d->mode));
+  launch_bwd_tail<T>(d, g, m, dz, dz2, x, z, gamma, beta, mean, rstd, dx, dres, dgamma, dbeta, partial, g.nblk, s);
+}
+
+// Entry points for the whole-step driver and the fused C-ABI calls: the sums come from the output stage
+// of the convolution that produced x (forward) or dz (backward).
+void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* partial, int nrows, int rpp,
+                          const float* gamma, const float* beta, const void* residual, void* y, float* save_mean,
+                          float* save_rstd, float* rm, float* rv, float momentum, hipStream_t s) {
+  const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
+  const BnGeom g = bn_geom(m, d->C, d->dtype);
+  if (d->dtype == RN50_BF16)
+    launch_fwd_tail<uint16_t>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
+                              nrows, rpp, s);
+  else
+    launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
+                           nrows, rpp, s);
+}
+void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const float* gamma,
+                          const float* beta, const float* mean, const float* rstd, const float* partial, int nrows,
+                          void* dx, float* dgamma, float* dbeta, hipStream_t s) {
+  const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
+  const BnGeom g = bn_geom(m, d->C, d->dtype);
+  if (d->dtype == RN50_BF16)
+    launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
+                              partial, nrows, s);
+  else
+    launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
+                           partial, nrows, s);
 }
 
 }  // namespace rn50
@@ -564,4 +659,53 @@ extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz
     launch_bwd<float>(d, g, m, dz, dz2, x, z, gamma, beta, save_mean, save_rstd, dx, dresidual,
                       dgamma, dbeta, static_cast<float*>(workspace), s);
   return launch_status("bn_relu_bwd");
+}
+
+// ---- batch norm from sums fused into the producing convolution (conv_fwd_bn_sums / conv_dgrad_bn_sums)
+extern "C" int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* x,
+                                     const float* sums, const float* gamma, const float* beta,
+                                     const void* residual, void* y, float* save_mean, float* save_rstd,
+                                     float* running_mean, float* running_var, float momentum, void* stream) {
+  clear_error();
+  if (int rc = check_desc(d, "bn_relu_fwd_from_sums")) return rc;
+  RN50_REQUIRE(producer && conv_bn_sums_bytes(producer) > 0, RN50_ERR_INVALID,
+               "bn_relu_fwd_from_sums: bad producer descriptor");
+  RN50_REQUIRE(x && sums && gamma && beta && y && save_mean && save_rstd, RN50_ERR_INVALID,
+               "bn_relu_fwd_from_sums: null pointer");
+  RN50_REQUIRE((d->mode == 2) == (residual != nullptr), RN50_ERR_INVALID,
+               "bn_relu_fwd_from_sums: residual must be given exactly in mode 2");
+  RN50_REQUIRE(aligned16(x) && aligned16(y) && aligned16(residual) && aligned16(sums) && aligned16(gamma) &&
+                   aligned16(beta) && aligned16(save_mean) && aligned16(save_rstd),
+               RN50_ERR_ALIGN, "bn_relu_fwd_from_sums: pointer not 16-byte aligned");
+  const int P = (producer->H + 2 * producer->pad - producer->R) / producer->stride + 1;
+  const int Q = (producer->W + 2 * producer->pad - producer->S) / producer->stride + 1;
+  RN50_REQUIRE(producer->N == d->N && P == d->H && Q == d->W && producer->Cout == d->C &&
+                   producer->dtype == d->dtype,
+               RN50_ERR_INVALID, "bn_relu_fwd_from_sums: the producer's output is not this layer's input");
+  const PartialRows pr = fwd_partial_rows(producer);
+  bn_fwd_from_partials(d, x, sums, pr.num, pr.rows, gamma, beta, residual, y, save_mean, save_rstd, running_mean,
+                       running_var, momentum, static_cast<hipStream_t>(stream));
+  return launch_status("bn_relu_fwd_from_sums");
+}
+
+extern "C" int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* dz,
+                                     const void* x, const float* gamma, const float* beta,
+                                     const float* save_mean, const float* save_rstd, const float* sums,
+                                     void* dx, float* dgamma, float* dbeta, void* stream) {
+  clear_error();
+  if (int rc = check_desc(d, "bn_relu_bwd_from_sums")) return rc;
+  RN50_REQUIRE(d->mode == 1, RN50_ERR_UNSUPPORTED, "bn_relu_bwd_from_sums: mode %d (only BN+ReLU)", d->mode);
+  RN50_REQUIRE(producer && conv_bn_sums_bytes(producer) > 0, RN50_ERR_INVALID,
+               "bn_relu_bwd_from_sums: bad producer descriptor");
+  RN50_REQUIRE(dz && x && gamma && beta && save_mean && save_rstd && sums && dx && dgamma && dbeta,
+               RN50_ERR_INVALID, "bn_relu_bwd_from_sums: null pointer");
+  RN50_REQUIRE(aligned16(dz) && aligned16(x) && aligned16(dx) && aligned16(sums), RN50_ERR_ALIGN,
+               "bn_relu_bwd_from_sums: pointer not 16-byte aligned");
+  RN50_REQUIRE(producer->N == d->N && producer->H == d->H && producer->W == d->W && producer->Cin == d->C &&
+                   producer->dtype == d->dtype,
+               RN50_ERR_INVALID, "bn_relu_bwd_from_sums: the producer's input is not this layer's output");
+  const PartialRows pr = dgrad_partial_rows(producer);
+  bn_bwd_from_partials(d, dz, x, gamma, beta, save_mean, save_rstd, sums, pr.num, dx, dgamma, dbeta,
+                       static_cast<hipStream_t>(stream));
+  return launch_status("bn_relu_bwd_from_sums");
 }

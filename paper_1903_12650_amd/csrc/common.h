@@ -110,6 +110,17 @@ __device__ __forceinline__ void store16(T* p, const Vec16& v) {
   *reinterpret_cast<uint4*>(p) = v.u;
 }
 
+// ------------------------------------------------- device: batch-norm affine
+// The affine step y = x*scale + bias and its coefficients, written once so that every kernel that takes
+// a ReLU decision from it (forward, backward, the sums fused into the convolutions) uses bit-identical
+// arithmetic.
+__device__ __forceinline__ float bn_affine(float x, float scale, float bias) { return fmaf(x, scale, bias); }
+__device__ __forceinline__ void bn_coeffs(float gamma, float beta, float mean, float rstd, float* scale,
+                                          float* bias) {
+  *scale = gamma * rstd;
+  *bias = fmaf(-mean, *scale, beta);
+}
+
 // ------------------------------------------------------- device: reductions
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -98,6 +98,14 @@ struct IgemmArgs {
   int cpt;          // 128-byte chunks per tap
   int ntn;          // number of column tiles
   int mode;         // host side only: selects the MODE template argument
+  // Optional batch-norm sums over the rows of each output tile, taken from the rounded values that are
+  // stored (null: none).  Forward: partial[mt][3][Ncols] = shift (the tile's first row), sum(y - shift),
+  // sum((y - shift)^2).  Data gradient: partial[mt][2][Ncols] = sum(g), sum(g * xhat) with g the output
+  // gradient masked by the ReLU of the BN layer whose conv output is bn_x [M][Ncols], xhat its
+  // normalized input.
+  float* partial;
+  const void* bn_x;
+  const float *bn_gamma, *bn_beta, *bn_mean, *bn_rstd;
 };
 
 constexpr int kPitch = 144;  // LDS row pitch of a 128-byte K chunk (conflict-free 16-byte reads)
@@ -282,15 +290,117 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   __syncthreads();
   constexpr int PPR = BN * sizeof(T) / 16;  // 16-byte pieces per output row
   constexpr int RPP = 256 / PPR;            // rows per pass
+  constexpr int NPASS = BM / RPP;
   T* out = static_cast<T*>(a.out);
   const int op = tid % PPR, orow = tid / PPR;
+  const int n = n0 + op * V;
+  if (a.partial == nullptr) {
 #pragma unroll
-  for (int pass = 0; pass < BM / RPP; ++pass) {
-    const int row = orow + pass * RPP;
-    const int m = m0 + row, n = n0 + op * V;
-    if (m < a.M && n < a.Ncols)
-      *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) =
-          *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int row = orow + pass * RPP;
+      const int m = m0 + row;
+      if (m < a.M && n < a.Ncols)
+        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) =
+            *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+    }
+    return;
+  }
+
+  // Output stage with batch-norm sums: every thread owns V channels and NPASS rows of the tile.
+  __shared__ float red[4][2][BN];
+  const bool col_ok = n < a.Ncols;
+  float s1[V], s2[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) s1[j] = s2[j] = 0.f;
+  if (MODE == 0) {
+    float shift[V];
+    Vec16 k0;
+    k0.u = *reinterpret_cast<const uint4*>(smem + op * 16);  // row m0 of the tile always exists
+    Elem<T>::unpack(k0, shift);
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int row = orow + pass * RPP;
+      const int m = m0 + row;
+      if (m < a.M && col_ok) {
+        Vec16 v;
+        v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) = v.u;
+        float f[V];
+        Elem<T>::unpack(v, f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+          const float d = f[j] - shift[j];
+          s1[j] += d;
+          s2[j] = fmaf(d, d, s2[j]);
+        }
+      }
+    }
+  } else {
+    const T* bx = static_cast<const T*>(a.bn_x);
+    const int nc = col_ok ? n : 0;
+    Vec16 xv[NPASS];
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int m = min(m0 + orow + pass * RPP, a.M - 1);
+      xv[pass] = load16(bx + (static_cast<int64_t>(m) * a.Ncols + nc));
+    }
+    float scale[V], bias[V], rs[V], nmr[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      rs[j] = a.bn_rstd[nc + j];
+      nmr[j] = -a.bn_mean[nc + j] * rs[j];
+      bn_coeffs(a.bn_gamma[nc + j], a.bn_beta[nc + j], a.bn_mean[nc + j], rs[j], &scale[j], &bias[j]);
+    }
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int row = orow + pass * RPP;
+      const int m = m0 + row;
+      if (m < a.M && col_ok) {
+        Vec16 v;
+        v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) = v.u;
+        float g[V], xf[V];
+        Elem<T>::unpack(v, g);
+        Elem<T>::unpack(xv[pass], xf);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+          const float gm = bn_affine(xf[j], scale[j], bias[j]) > 0.f ? g[j] : 0.f;
+          s1[j] += gm;
+          s2[j] = fmaf(gm, fmaf(xf[j], rs[j], nmr[j]), s2[j]);
+        }
+      }
+    }
+  }
+  // rows of one wave (lanes with equal op), then the four waves in order
+#pragma unroll
+  for (int off = PPR; off < 64; off <<= 1) {
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      s1[j] += __shfl_xor(s1[j], off, 64);
+      s2[j] += __shfl_xor(s2[j], off, 64);
+    }
+  }
+  if (lane < PPR) {
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      red[wave][0][op * V + j] = s1[j];
+      red[wave][1][op * V + j] = s2[j];
+    }
+  }
+  __syncthreads();
+  if (tid < BN && n0 + tid < a.Ncols) {
+    const float t1 = ((red[0][0][tid] + red[1][0][tid]) + red[2][0][tid]) + red[3][0][tid];
+    const float t2 = ((red[0][1][tid] + red[1][1][tid]) + red[2][1][tid]) + red[3][1][tid];
+    if (MODE == 0) {
+      float* o = a.partial + static_cast<int64_t>(mt) * 3 * a.Ncols + n0 + tid;
+      o[0] = Elem<T>::load(reinterpret_cast<const T*>(smem) + tid);
+      o[a.Ncols] = t1;
+      o[2 * a.Ncols] = t2;
+    } else {
+      float* o = a.partial + static_cast<int64_t>(mt) * 2 * a.Ncols + n0 + tid;
+      o[0] = t1;
+      o[a.Ncols] = t2;
+    }
   }
 }
 
@@ -303,6 +413,7 @@ struct WgradArgs {
   int M, Cout, Ktot;
   int H, W, P, Q, PS, Cg, R, S, stride, pad;
   int ctiles;          // column tiles per tap
+  int tiles_per_split; // taps * ctiles * output-channel tiles
   int rows_per_split;  // multiple of the K chunk
   int linear;          // 1x1, stride 1, pad 0: gathered row m is pixel m
   int64_t split_stride;
@@ -360,10 +471,16 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave & 1, wn = wave >> 1;
-  const int tap = blockIdx.x / a.ctiles, c0 = (blockIdx.x - tap * a.ctiles) * BC;
+  // Logical id = (split, output-channel tile, tap, column tile), the last fastest.  All tiles of one
+  // split read the same rows of x and dy, so the renumbering keeps them on one XCD and in its L2.
+  const int lid = xcd_remap(blockIdx.x, gridDim.x);
+  const int split = lid / a.tiles_per_split, tile = lid - split * a.tiles_per_split;
+  const int tiles_x = a.R * a.S * a.ctiles;
+  const int ko_tile = tile / tiles_x, tx = tile - ko_tile * tiles_x;
+  const int tap = tx / a.ctiles, c0 = (tx - tap * a.ctiles) * BC;
   const int r = tap / a.S, s = tap - r * a.S;
-  const int ko0 = blockIdx.y * BMO;
-  const int row_begin = blockIdx.z * a.rows_per_split;
+  const int ko0 = ko_tile * BMO;
+  const int row_begin = split * a.rows_per_split;
   const int row_end = min(row_begin + a.rows_per_split, a.M);
   const __amdgpu_buffer_rsrc_t rsX = make_rsrc(a.x, a.x_bytes), rsD = make_rsrc(a.dy, a.dy_bytes);
 
@@ -470,7 +587,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   }
 
   // acc[i][j][v]: ko = i*32 + (v/4)*8 + (lane/32)*4 + v%4, c = j*32 + lane%32
-  float* out = a.out + static_cast<int64_t>(blockIdx.z) * a.split_stride;
+  float* out = a.out + static_cast<int64_t>(split) * a.split_stride;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -639,19 +756,26 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
 }
 
 // Tile choice: the widest tile that still gives every CU a couple of workgroups.
-template <typename T>
-static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
+struct TileShape {
+  int bm, bn;
+};
+static TileShape igemm_tile(int64_t M, int Ncols) {
   int fbm = 0, fbn = 0;  // tuning aid: RN50_IGEMM_TILE=bm,bn forces a tile shape
   if (const char* e = getenv("RN50_IGEMM_TILE")) sscanf(e, "%d,%d", &fbm, &fbn);
-  if (fbm == 128 && fbn == 128) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
-  if (fbm == 128 && fbn == 64) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
-  if (fbm == 64 && fbn == 128) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
-  if (fbm == 64 && fbn == 64) return launch_igemm_cfg<T, 64, 64, 2, 2>(a, tag, s);
+  if ((fbm == 128 || fbm == 64) && (fbn == 128 || fbn == 64)) return TileShape{fbm, fbn};
   const int64_t target = 512;
-  auto blocks = [&](int bm, int bn) { return ceil_div(a.M, bm) * ceil_div(a.Ncols, bn); };
-  if (a.Ncols > 64 && blocks(128, 128) >= target) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
-  if (blocks(128, 64) >= target) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
-  if (a.Ncols > 64 && blocks(64, 128) >= target / 2) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
+  auto blocks = [&](int bm, int bn) { return ceil_div(M, bm) * ceil_div(Ncols, bn); };
+  if (Ncols > 64 && blocks(128, 128) >= target) return TileShape{128, 128};
+  if (blocks(128, 64) >= target) return TileShape{128, 64};
+  if (Ncols > 64 && blocks(64, 128) >= target / 2) return TileShape{64, 128};
+  return TileShape{64, 64};
+}
+template <typename T>
+static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
+  const TileShape t = igemm_tile(a.M, a.Ncols);
+  if (t.bm == 128 && t.bn == 128) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
+  if (t.bm == 128) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
+  if (t.bn == 128) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
   return launch_igemm_cfg<T, 64, 64, 2, 2>(a, tag, s);
 }
 
@@ -707,8 +831,10 @@ static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   constexpr int lds = 2 * BKM * ((BMO + BC) * static_cast<int>(sizeof(T)) + 128);
   static std::once_flag once;
   std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC>, lds); });
-  const dim3 grid(a.R * a.S * a.ctiles, static_cast<unsigned>(ceil_div(a.Cout, BMO)), splits);
-  RN50_TIMED("conv_wgrad", s, hipLaunchKernelGGL((wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, a));
+  WgradArgs b = a;
+  b.tiles_per_split = a.R * a.S * a.ctiles * static_cast<int>(ceil_div(a.Cout, BMO));
+  const dim3 grid(static_cast<unsigned>(b.tiles_per_split) * splits);
+  RN50_TIMED("conv_wgrad", s, hipLaunchKernelGGL((wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, b));
 }
 
 template <typename T>
@@ -793,6 +919,18 @@ void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_
 size_t stem_padded_input_bytes(const rn50_conv_desc* d) { return stem_geom(d).xp_bytes; }
 size_t stem_padded_weight_bytes(const rn50_conv_desc* d) { return stem_geom(d).wp_bytes; }
 
+static PartialRows tile_rows(int64_t M, int Ncols) {
+  const int bm = igemm_tile(M, Ncols).bm;
+  return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
+}
+PartialRows fwd_partial_rows(const rn50_conv_desc* d) {
+  const int64_t M = static_cast<int64_t>(d->N) * out_dim(d->H, d->pad, d->R, d->stride) * out_dim(d->W, d->pad, d->S, d->stride);
+  return tile_rows(M, d->Cout);
+}
+PartialRows dgrad_partial_rows(const rn50_conv_desc* d) {
+  return tile_rows(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin);
+}
+
 static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const void* wp, void* y) {
   const StemGeom g = stem_geom(d);
   IgemmArgs a{};
@@ -807,16 +945,19 @@ static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const 
 }
 
 // Forward of the stem from an already padded input; wp is scratch for the padded weights.
-void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, hipStream_t s) {
+void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
+                     hipStream_t s) {
   const int nw = d->Cout * 224;
+  IgemmArgs a = stem_igemm_args(d, xp, wp, y);
+  a.partial = bn_partial;
   if (d->dtype == RN50_BF16) {
     hipLaunchKernelGGL(stem_pad_weight_kernel<uint16_t>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
                        static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wp), d->Cout);
-    launch_igemm<uint16_t>(stem_igemm_args(d, xp, wp, y), "conv_fwd", s);
+    launch_igemm<uint16_t>(a, "conv_fwd", s);
   } else {
     hipLaunchKernelGGL(stem_pad_weight_kernel<float>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
                        static_cast<const float*>(w), static_cast<float*>(wp), d->Cout);
-    launch_igemm<float>(stem_igemm_args(d, xp, wp, y), "conv_fwd", s);
+    launch_igemm<float>(a, "conv_fwd", s);
   }
 }
 
@@ -872,9 +1013,9 @@ void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, flo
     hipLaunchKernelGGL(stem_unpad_dw_kernel, dim3(ceil_div(d->Cout * 147, 256)), dim3(256), 0, s, target, dw, d->Cout);
 }
 
-void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hipStream_t s) {
+void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s) {
   IgemmArgs a{};
-  a.act = x; a.wgt = w; a.out = y;
+  a.act = x; a.wgt = w; a.out = y; a.partial = bn_partial;
   a.P = out_dim(d->H, d->pad, d->R, d->stride); a.Q = out_dim(d->W, d->pad, d->S, d->stride);
   a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = d->R * d->S * d->Cin;
   a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
@@ -917,9 +1058,13 @@ void transpose_batch_run(const std::vector<TransposeEntry>& list, int dtype, con
 }
 
 // Data gradient from already transposed weights wT [Cin][R][S][Cout].
-void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, hipStream_t s) {
+void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, const BnBwdSums* bn, hipStream_t s) {
   IgemmArgs a{};
   a.act = dy; a.wgt = wT; a.out = dx;
+  if (bn) {
+    a.partial = bn->partial; a.bn_x = bn->x;
+    a.bn_gamma = bn->gamma; a.bn_beta = bn->beta; a.bn_mean = bn->mean; a.bn_rstd = bn->rstd;
+  }
   a.P = d->H; a.Q = d->W;
   a.H = out_dim(d->H, d->pad, d->R, d->stride); a.W = out_dim(d->W, d->pad, d->S, d->stride);
   a.M = d->N * d->H * d->W; a.Ncols = d->Cin; a.Ktot = d->R * d->S * d->Cout;
@@ -962,9 +1107,9 @@ extern "C" int conv_fwd(const rn50_conv_desc* d, const void* x, const void* w, v
   if (is_stem(d)) {
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     stem_pad_input(d, x, ws, s);
-    stem_fwd_padded(d, ws, w, ws + stem_geom(d).xp_bytes, y, s);
+    stem_fwd_padded(d, ws, w, ws + stem_geom(d).xp_bytes, y, nullptr, s);
   } else {
-    fwd_run(d, x, w, y, s);
+    fwd_run(d, x, w, y, nullptr, s);
   }
   return launch_status("conv_fwd");
 }
@@ -983,7 +1128,7 @@ extern "C" int conv_dgrad(const rn50_conv_desc* d, const void* dy, const void* w
                workspace_bytes, dgrad_wt_bytes(d));
   hipStream_t s = static_cast<hipStream_t>(stream);
   dgrad_transpose_weights(d, w, workspace, s);
-  dgrad_run(d, dy, workspace, dx, s);
+  dgrad_run(d, dy, workspace, dx, nullptr, s);
   return launch_status("conv_dgrad");
 }
 
@@ -1006,4 +1151,62 @@ extern "C" int conv_wgrad(const rn50_conv_desc* d, const void* x, const void* dy
     wgrad_run(d, x, dy, dw, ws, s);
   }
   return launch_status("conv_wgrad");
+}
+
+// ---- fused batch-norm sums (the BN side is in bn.hip)
+extern "C" size_t conv_bn_sums_bytes(const rn50_conv_desc* d) {
+  if (!d || check_conv(d, "conv_bn_sums_bytes")) return 0;
+  // one row per output tile of at least 64 pixels; three planes forward, two backward
+  const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
+  const size_t fwd = static_cast<size_t>(ceil_div(static_cast<int64_t>(d->N) * P * Q, 64)) * 3 * d->Cout;
+  const size_t bwd = static_cast<size_t>(ceil_div(static_cast<int64_t>(d->N) * d->H * d->W, 64)) * 2 * d->Cin;
+  return align_up((fwd > bwd ? fwd : bwd) * sizeof(float), 256);
+}
+
+extern "C" int conv_fwd_bn_sums(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* sums,
+                                size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_fwd_bn_sums")) return rc;
+  RN50_REQUIRE(x && w && y && sums, RN50_ERR_INVALID, "conv_fwd_bn_sums: null pointer");
+  RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(workspace) && aligned16(sums),
+               RN50_ERR_ALIGN, "conv_fwd_bn_sums: pointer not 16-byte aligned");
+  const size_t need = conv_fwd_workspace_bytes(d);
+  RN50_REQUIRE(workspace_bytes >= need && (need == 0 || workspace), RN50_ERR_WORKSPACE,
+               "conv_fwd_bn_sums: workspace %zu < %zu bytes", workspace_bytes, need);
+  RN50_REQUIRE(sums_bytes >= conv_bn_sums_bytes(d), RN50_ERR_WORKSPACE, "conv_fwd_bn_sums: sums %zu < %zu bytes",
+               sums_bytes, conv_bn_sums_bytes(d));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (is_stem(d)) {
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    stem_pad_input(d, x, ws, s);
+    stem_fwd_padded(d, ws, w, ws + stem_geom(d).xp_bytes, y, sums, s);
+  } else {
+    fwd_run(d, x, w, y, sums, s);
+  }
+  return launch_status("conv_fwd_bn_sums");
+}
+
+extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
+                                  const void* bn_x, const float* gamma, const float* beta,
+                                  const float* save_mean, const float* save_rstd, float* sums,
+                                  size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_dgrad_bn_sums")) return rc;
+  RN50_REQUIRE(!is_stem(d) && d->Cin % (16 / esize(d->dtype)) == 0, RN50_ERR_UNSUPPORTED,
+               "conv_dgrad_bn_sums: the 3-channel stem has no data gradient here");
+  RN50_REQUIRE(d->stride == 1 || d->stride == 2, RN50_ERR_UNSUPPORTED, "conv_dgrad_bn_sums: stride %d", d->stride);
+  RN50_REQUIRE(dy && w && dx && workspace && bn_x && gamma && beta && save_mean && save_rstd && sums,
+               RN50_ERR_INVALID, "conv_dgrad_bn_sums: null pointer");
+  RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(workspace) && aligned16(bn_x) &&
+                   aligned16(sums),
+               RN50_ERR_ALIGN, "conv_dgrad_bn_sums: pointer not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= dgrad_wt_bytes(d), RN50_ERR_WORKSPACE,
+               "conv_dgrad_bn_sums: workspace %zu < %zu bytes", workspace_bytes, dgrad_wt_bytes(d));
+  RN50_REQUIRE(sums_bytes >= conv_bn_sums_bytes(d), RN50_ERR_WORKSPACE, "conv_dgrad_bn_sums: sums %zu < %zu bytes",
+               sums_bytes, conv_bn_sums_bytes(d));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  dgrad_transpose_weights(d, w, workspace, s);
+  const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums};
+  dgrad_run(d, dy, workspace, dx, &bn, s);
+  return launch_status("conv_dgrad_bn_sums");
 }

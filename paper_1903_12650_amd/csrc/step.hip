@@ -6,6 +6,7 @@
 // between workers (Sec. III-C) would sit between backward and the LARS call.
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "common.h"
@@ -151,6 +152,11 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
     if (u.conv.Cin != 3 && dgrad_wt_bytes(&u.conv) > max_wT) max_wT = dgrad_wt_bytes(&u.conv);
     if (wgrad_partial_bytes(&u.conv) > max_wg) max_wg = wgrad_partial_bytes(&u.conv);
     if (bn_relu_fwd_workspace_bytes(&u.bn) > max_bn) max_bn = bn_relu_fwd_workspace_bytes(&u.bn);
+    // sums fused into the convolutions: one row per output tile, at most ceil(M/64) rows of 3 planes
+    const size_t fwd_rows = ceil_div(static_cast<int64_t>(N) * u.P * u.Q, 64);
+    const size_t dgrad_rows = ceil_div(static_cast<int64_t>(N) * u.conv.H * u.conv.W, 64);
+    max_bn = std::max(max_bn, align_up(fwd_rows * 3 * u.conv.Cout * sizeof(float), 256));
+    if (u.conv.Cin != 3) max_bn = std::max(max_bn, align_up(dgrad_rows * 2 * u.conv.Cin * sizeof(float), 256));
   }
   p->pool = bump(&top, static_cast<size_t>(N) * Hpool * Hpool * cfg->stem * es);
   p->avg = bump(&top, static_cast<size_t>(N) * cin * es);
@@ -237,15 +243,21 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   // --------------------------------------------------------------- forward
   Unit& u0 = plan->units[0];
   stem_pad_input(&u0.conv, images, ws + plan->xp, s);
-  stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, s);
-  STEP_TRY(bn_relu_fwd(&u0.bn, ws + u0.y, MP(u0.ig), MP(u0.ib), nullptr, ws + u0.z, F(u0.mean), F(u0.rstd),
-                       nullptr, nullptr, 0.f, bn_ws, bn_ws_bytes, s));
+  // Every convolution leaves the sums its batch norm needs, one row per output tile, in bn_ws.
+  float* sums = static_cast<float*>(bn_ws);
+  auto bn_after_conv = [&](Unit& u, const void* residual) {
+    const PartialRows pr = fwd_partial_rows(&u.conv);
+    bn_fwd_from_partials(&u.bn, ws + u.y, sums, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z, F(u.mean),
+                         F(u.rstd), nullptr, nullptr, 0.f, s);
+  };
+  stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, sums, s);
+  bn_after_conv(u0, nullptr);
   STEP_TRY(maxpool_fwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool, ws + plan->pool_argmax, s));
   const unsigned char* cur = ws + plan->pool;
   auto conv_bn = [&](Unit& u, const void* in, const void* residual) -> int {
-    fwd_run(&u.conv, in, W(u.iw), ws + u.y, s);
-    return bn_relu_fwd(&u.bn, ws + u.y, MP(u.ig), MP(u.ib), residual, ws + u.z, F(u.mean), F(u.rstd), nullptr,
-                       nullptr, 0.f, bn_ws, bn_ws_bytes, s);
+    fwd_run(&u.conv, in, W(u.iw), ws + u.y, sums, s);
+    bn_after_conv(u, residual);
+    return RN50_OK;
   };
   for (const Block& b : plan->blocks) {
     Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
@@ -278,14 +290,30 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   // g[0], g[1]: the two summands of the gradient w.r.t. the current block output (g[1] may be unused)
   STEP_TRY(avgpool_bwd(cfg.N, HW, plan->fc_in, dt, ws + plan->davg, g[0], s));
   bool have2 = false;
+  int dgrad_sums_rows = 0;
   // BN backward + wgrad + dgrad of one unit.  dz (+dz2) -> dy in `dy`; dgrad into `dx` (skipped if null).
-  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dy, void* dres,
-                      void* dx) -> int {
-    const void* z = u.bn.mode == 2 ? static_cast<const void*>(ws + u.z) : nullptr;  // mode 1 recomputes the mask
-    STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, z, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
-                         G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
+  // `sums_ready`: the data gradient that produced dz already left this BN layer's sums in bn_ws.
+  // `below`: the unit whose BN output is this unit's only input use (dx is its complete dz): the data
+  // gradient then leaves that layer's sums in bn_ws.
+  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dy, void* dres, void* dx,
+                      bool sums_ready, Unit* below) -> int {
+    if (sums_ready) {
+      bn_bwd_from_partials(&u.bn, dz, ws + u.y, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), sums,
+                           dgrad_sums_rows, dy, G(u.ig), G(u.ib), s);
+    } else {
+      const void* z = u.bn.mode == 2 ? static_cast<const void*>(ws + u.z) : nullptr;  // mode 1 recomputes the mask
+      STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, z, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
+                           G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
+    }
     wgrad_run(&u.conv, in, dy, G(u.iw), ws + plan->wgrad_scratch, s);
-    if (dx) dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, s);
+    if (dx) {
+      BnBwdSums fuse{};
+      if (below) {
+        fuse = BnBwdSums{ws + below->y, MP(below->ig), MP(below->ib), F(below->mean), F(below->rstd), sums};
+        dgrad_sums_rows = dgrad_partial_rows(&u.conv).num;
+      }
+      dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, below ? &fuse : nullptr, s);
+    }
     return RN50_OK;
   };
   for (int bi = static_cast<int>(plan->blocks.size()) - 1; bi >= 0; --bi) {
@@ -293,18 +321,18 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
     const void* block_in = bi == 0 ? static_cast<const void*>(ws + plan->pool)
                                    : static_cast<const void*>(ws + plan->units[plan->blocks[bi - 1].u3].z);
-    STEP_TRY(unit_bwd(u3, ws + u2.z, g[0], have2 ? g[1] : nullptr, g[2], g[3], g[4]));
-    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, g[2], nullptr, g[4]));
-    STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, g[2], nullptr, g[0]));
+    STEP_TRY(unit_bwd(u3, ws + u2.z, g[0], have2 ? g[1] : nullptr, g[2], g[3], g[4], false, &u2));
+    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, g[2], nullptr, g[4], true, &u1));
+    STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, g[2], nullptr, g[0], true, nullptr));
     if (b.up >= 0) {
-      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, g[2], nullptr, g[1]));
+      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, g[2], nullptr, g[1], false, nullptr));
     } else {
       unsigned char* t = g[1]; g[1] = g[3]; g[3] = t;
     }
     have2 = true;
   }
   STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, g[0], g[1], g[2], s));
-  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, g[4], nullptr, nullptr));
+  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, g[4], nullptr, nullptr, false, nullptr));
 
   // ------------------------------------------------------------------ LARS
   if (update)

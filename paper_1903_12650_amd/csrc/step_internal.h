@@ -14,11 +14,27 @@ namespace rn50 {
 size_t stem_padded_input_bytes(const rn50_conv_desc* d);
 size_t stem_padded_weight_bytes(const rn50_conv_desc* d);
 void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_t s);
-void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, hipStream_t s);
-void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, hipStream_t s);
+// Batch-norm sums fused into a convolution's output stage come as one row of partial sums per output
+// tile: `num` rows over `rows` consecutive output pixels each (the last row may cover fewer).
+struct PartialRows {
+  int rows, num;
+};
+PartialRows fwd_partial_rows(const rn50_conv_desc* d);    // tiles of the forward convolution's output
+PartialRows dgrad_partial_rows(const rn50_conv_desc* d);  // tiles of the data gradient
+// bn_partial (null: none): float[num][3][Cout] = shift, sum(y - shift), sum((y - shift)^2) per tile.
+void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
+                     hipStream_t s);
+void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s);
+// The BN layer (with ReLU, no residual) whose output gradient a data gradient produces: x is that
+// layer's input [N*H*W][Cin]; partial receives float[num][2][Cin] = sum(g), sum(g * xhat) per tile.
+struct BnBwdSums {
+  const void* x;
+  const float *gamma, *beta, *mean, *rstd;
+  float* partial;
+};
 size_t dgrad_wt_bytes(const rn50_conv_desc* d);
 void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, hipStream_t s);
-void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, hipStream_t s);
+void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx, const BnBwdSums* bn, hipStream_t s);
 struct TransposeEntry {
   int64_t offset;  // element offset of the tensor in both arenas
   int K, taps, C;
@@ -27,6 +43,14 @@ void transpose_batch_run(const std::vector<TransposeEntry>& list, int dtype, con
                          hipStream_t s);
 size_t wgrad_partial_bytes(const rn50_conv_desc* d);
 void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s);
+
+// bn.hip: the part of the forward / backward pass that follows the sums
+void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* partial, int nrows, int rpp,
+                          const float* gamma, const float* beta, const void* residual, void* y, float* save_mean,
+                          float* save_rstd, float* rm, float* rv, float momentum, hipStream_t s);
+void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const float* gamma,
+                          const float* beta, const float* mean, const float* rstd, const float* partial, int nrows,
+                          void* dx, float* dgamma, float* dbeta, hipStream_t s);
 
 // lars.hip
 struct LarsArenaSpec {

@@ -39,10 +39,11 @@ class Chain:
     # forward of conv + BN
     def cbn(self, name, x, w, gamma, beta, stride, pad, mode, res=None):
         rn = self.rn
-        y = rn.conv_fwd(x, w, stride, pad)
+        # as in resnet_step: the convolution's output stage leaves the BN sums
+        y, sums = rn.conv_fwd_bn_sums(x, w, stride, pad)
         if self.check:
             self.cmp(name + ".conv", y, orc.conv_fwd(_h(x), _h(w), stride, pad))
-        z, mean, rstd = rn.bn_relu_fwd(y, gamma, beta, res, 1e-5, mode)
+        z, mean, rstd = rn.bn_relu_fwd_from_sums(y, sums, gamma, beta, res, 1e-5, mode)
         if self.check:
             zo, mo, ro = orc.bn_relu_fwd(_h(y), _h(gamma), _h(beta), _h(res) if res is not None else None, 1e-5, mode)
             self.cmp(name + ".bn", z, zo)
@@ -50,12 +51,19 @@ class Chain:
         return dict(name=name, x=x, w=w, gamma=gamma, beta=beta, y=y, z=z, mean=mean, rstd=rstd, stride=stride,
                     pad=pad, mode=mode)
 
-    # backward of conv + BN; returns dx (or None), dres, (dw, dgamma, dbeta)
-    def cbn_bwd(self, t, dz, dz2=None, need_dx=True):
+    # backward of conv + BN; returns dx (or None), dres, (dw, dgamma, dbeta), sums handle for `below`.
+    # sums: handle left by the data gradient that produced dz (then dz2 is None and the mode is 1);
+    # below: tape of the unit whose BN output is this unit's input and has no other use.
+    def cbn_bwd(self, t, dz, dz2=None, need_dx=True, sums=None, below=None):
         rn = self.rn
         z = t["z"] if t["mode"] == 2 else None                      # mode 1: mask recomputed, as the step does
-        dy, dres, dg, db = rn.bn_relu_bwd(dz, t["y"], z, t["gamma"], t["mean"], t["rstd"], t["mode"],
-                                          beta=t["beta"], dz2=dz2)
+        if sums is not None:
+            assert dz2 is None and t["mode"] == 1
+            dy, dg, db = rn.bn_relu_bwd_from_sums(dz, t["y"], sums, t["gamma"], t["beta"], t["mean"], t["rstd"])
+            dres = None
+        else:
+            dy, dres, dg, db = rn.bn_relu_bwd(dz, t["y"], z, t["gamma"], t["mean"], t["rstd"], t["mode"],
+                                              beta=t["beta"], dz2=dz2)
         if self.check:
             dzs = _h(dz) + (_h(dz2) if dz2 is not None else 0)
             dyo, dro, dgo, dbo = orc.bn_relu_bwd(dzs.astype(np.float32), _h(t["y"]), _h(t["z"]), _h(t["gamma"]),
@@ -68,11 +76,16 @@ class Chain:
         if self.check:
             self.cmp(t["name"] + ".dw", dw, orc.conv_wgrad(_h(t["x"]), _h(dy), tuple(t["w"].shape), t["stride"], t["pad"]))
         dx = None
+        out_sums = None
         if need_dx:
-            dx = rn.conv_dgrad(dy, t["w"], t["x"].shape, t["stride"], t["pad"])
+            if below is not None:
+                dx, out_sums = rn.conv_dgrad_bn_sums(dy, t["w"], t["x"].shape, t["stride"], t["pad"], below["y"],
+                                                     below["gamma"], below["beta"], below["mean"], below["rstd"])
+            else:
+                dx = rn.conv_dgrad(dy, t["w"], t["x"].shape, t["stride"], t["pad"])
             if self.check:
                 self.cmp(t["name"] + ".dx", dx, orc.conv_dgrad(_h(dy), _h(t["w"]), tuple(t["x"].shape), t["stride"], t["pad"]))
-        return dx, dres, [dw, dg, db]
+        return dx, dres, [dw, dg, db], out_sums
 
 
 def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
@@ -130,12 +143,12 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
     d2 = None
     block_grads = []
     for (t1, t2, t3, tp) in reversed(tapes):
-        dz2_, dres, g3 = ch.cbn_bwd(t3, d, d2)
-        dz1_, _, g2 = ch.cbn_bwd(t2, dz2_)
-        dxa, _, g1 = ch.cbn_bwd(t1, dz1_)
+        dz2_, dres, g3, s2 = ch.cbn_bwd(t3, d, d2, below=t2)
+        dz1_, _, g2, s1 = ch.cbn_bwd(t2, dz2_, sums=s2, below=t1)
+        dxa, _, g1, _ = ch.cbn_bwd(t1, dz1_, sums=s1)
         gl = g1 + g2 + g3
         if tp is not None:
-            dxb, _, gp = ch.cbn_bwd(tp, dres)
+            dxb, _, gp, _ = ch.cbn_bwd(tp, dres)
             gl = gl + gp
             d, d2 = dxa, dxb
         else:
@@ -144,7 +157,7 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
     dpool = rn.maxpool_bwd(t0["z"], d, d2, argmax=pool_argmax)
     if check:
         ch.cmp("maxpool_bwd", dpool, orc.maxpool_bwd(_h(t0["z"]), (_h(d) + _h(d2)).astype(np.float32)), max(tol, 4e-3))
-    _, _, g0 = ch.cbn_bwd(t0, dpool, need_dx=False)
+    _, _, g0, _ = ch.cbn_bwd(t0, dpool, need_dx=False)
     grads = list(g0)
     for gl in reversed(block_grads):
         grads += gl

@@ -1,0 +1,155 @@
+"""GPU parity of the convolution + batch-norm pairs whose per-channel sums are taken in the
+convolution's output stage (conv_fwd_bn_sums -> bn_relu_fwd_from_sums, conv_dgrad_bn_sums ->
+bn_relu_bwd_from_sums), against the oracle's separate operations, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import synth
+from gpu_util import TOL, assert_close, dev, host, inputs
+
+pytestmark = pytest.mark.gpu
+SEED = synth.DEFAULT_SEED
+
+
+@pytest.fixture(scope="module")
+def rn():
+    import paper_1903_12650_amd as rn
+    return rn
+
+
+# (N, H, W, Cin, Cout, R, stride, pad): several row tiles with a ragged last one, ragged channel tiles,
+# both strides, the stem, and a single-tile case
+FUSED_SHAPES = [(2, 14, 14, 64, 64, 1, 1, 0), (3, 13, 9, 24, 40, 3, 1, 1), (2, 28, 28, 32, 136, 3, 2, 1),
+                (5, 28, 28, 128, 128, 1, 1, 0), (2, 30, 30, 64, 256, 1, 2, 0), (1, 5, 5, 8, 8, 3, 1, 1),
+                (2, 64, 64, 3, 64, 7, 2, 3), (40, 7, 7, 256, 64, 1, 1, 0)]
+
+
+def _vec(tag, C, scale, shift):
+    return (shift + scale * synth.normal(SEED, tag, (C,))).astype(np.float32)
+
+
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+def test_conv_fwd_bn_sums(rn, mode_name, shape):
+    bf = mode_name == "bf16"
+    tol = TOL[mode_name]
+    N, H, W, C, K, R, stride, pad = shape
+    x = synth.activation_nhwc(SEED, "x", N, C, H, W)
+    w = synth.conv_weight_krsc(SEED, "w", K, C, R, R)
+    x, w = inputs(mode_name, x, w)
+    gamma, beta = _vec("g", K, 0.3, 1.0), _vec("b", K, 0.2, 0.0)
+    xd, wd = dev(x, bf), dev(w, bf)
+    y, sums = rn.conv_fwd_bn_sums(xd, wd, stride, pad)
+    assert torch.equal(y, rn.conv_fwd(xd, wd, stride, pad)), "the sums must not change the convolution"
+    assert_close(y, orc.conv_fwd(x, w, stride, pad), tol, "y")
+    yh = host(y)
+    res = inputs(mode_name, synth.normal(SEED, "r", yh.shape))[0]
+    for mode in (0, 1, 2):
+        r = res if mode == 2 else None
+        z, mean, rstd = rn.bn_relu_fwd_from_sums(y, sums, dev(gamma), dev(beta), dev(r, bf) if r is not None else None,
+                                                 1e-5, mode)
+        z_o, mean_o, rstd_o = orc.bn_relu_fwd(yh, gamma, beta, r, 1e-5, mode)   # on the GPU path's own y
+        if yh.size // K > 1:
+            assert_close(z, z_o, tol, f"z mode {mode}")
+            assert_close(mean, mean_o, 1e-5, "mean")
+            assert_close(rstd, rstd_o, 1e-4, "rstd")
+        # and the separate-pass kernels agree to rounding of the float sums
+        z_u, mean_u, rstd_u = rn.bn_relu_fwd(y, dev(gamma), dev(beta), dev(r, bf) if r is not None else None, 1e-5, mode)
+        assert_close(mean, host(mean_u), 1e-5, "mean vs separate pass")
+        assert_close(rstd, host(rstd_u), 1e-5, "rstd vs separate pass")
+
+
+def test_conv_fwd_bn_sums_large_mean_and_running_stats(rn):
+    # all-positive operands: every output channel's mean is many standard deviations from zero and the
+    # tiles' shifts differ, so the change of shift in the final sum is exercised
+    N, H, W, C, K = 4, 20, 20, 64, 72
+    x = np.abs(synth.activation_nhwc(SEED, "x", N, C, H, W)) + 3.0
+    w = np.abs(synth.conv_weight_krsc(SEED, "w", K, C, 3, 3)) + 0.05
+    g, b = np.ones(K, np.float32), np.zeros(K, np.float32)
+    y, sums = rn.conv_fwd_bn_sums(dev(x), dev(w), 1, 1)
+    yh = host(y)
+    rm0 = synth.normal(SEED, "rm", (K,)); rv0 = np.abs(synth.normal(SEED, "rv", (K,))) + 1
+    rm, rv = dev(rm0), dev(rv0)
+    z, mean, rstd = rn.bn_relu_fwd_from_sums(y, sums, dev(g), dev(b), None, 1e-5, 0, running_mean=rm, running_var=rv,
+                                             momentum=0.9)
+    z_o, mean_o, rstd_o = orc.bn_relu_fwd(yh, g, b, None, 1e-5, 0)
+    rm_o, rv_o = orc.bn_running_update(yh, rm0, rv0, 0.9)
+    assert float(np.min(np.abs(mean_o) * rstd_o)) > 3.0, "the case must have |mean| >> std"
+    assert_close(mean, mean_o, 1e-6, "mean")
+    assert_close(rstd, rstd_o, 1e-4, "rstd")
+    assert_close(z, z_o, 1e-3, "z")
+    assert_close(rm, rm_o, 1e-6, "running_mean")
+    assert_close(rv, rv_o, 1e-4, "running_var")
+
+
+DGRAD_SHAPES = [s for s in FUSED_SHAPES if s[3] != 3]
+
+
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", DGRAD_SHAPES)
+def test_conv_dgrad_bn_sums(rn, mode_name, shape):
+    bf = mode_name == "bf16"
+    tol = TOL[mode_name]
+    N, H, W, C, K, R, stride, pad = shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    # the BN layer below the convolution: input bx [N,H,W,C], output z feeds the convolution
+    bx = synth.activation_nhwc(SEED, "bx", N, C, H, W) * 1.3 + 0.2
+    dy = synth.activation_nhwc(SEED, "dy", N, K, P, Q)
+    w = synth.conv_weight_krsc(SEED, "w", K, C, R, R)
+    bx, dy, w = inputs(mode_name, bx, dy, w)
+    gamma, beta = _vec("g", C, 0.3, 1.0), _vec("b", C, 0.2, 0.0)
+    z_o, mean_o, rstd_o = orc.bn_relu_fwd(bx, gamma, beta, None, 1e-5, 1)
+    z_o = inputs(mode_name, z_o)[0]
+    dyd, wd, bxd = dev(dy, bf), dev(w, bf), dev(bx, bf)
+    gd, bd, md, rd = dev(gamma), dev(beta), dev(mean_o), dev(rstd_o)
+    dz, sums = rn.conv_dgrad_bn_sums(dyd, wd, (N, H, W, C), stride, pad, bxd, gd, bd, md, rd)
+    assert torch.equal(dz, rn.conv_dgrad(dyd, wd, (N, H, W, C), stride, pad)), "the sums must not change the gradient"
+    assert_close(dz, orc.conv_dgrad(dy, w, (N, H, W, C), stride, pad), tol, "dz")
+    dx, dg, db = rn.bn_relu_bwd_from_sums(dz, bxd, sums, gd, bd, md, rd)
+    dx_o, _, dg_o, db_o = orc.bn_relu_bwd(host(dz).astype(np.float32), bx, z_o, gamma, mean_o, rstd_o, 1)
+    if N * H * W > 1:
+        t2 = max(tol, 2e-3)   # the mask is recomputed from x: it may differ where z rounds to zero
+        assert_close(dx, dx_o, t2, "dx")
+        assert_close(dg, dg_o, t2, "dgamma")
+        assert_close(db, db_o, t2, "dbeta")
+    # the separate-pass kernels (same mask rule) agree to rounding of the float sums
+    dx_u, _, dg_u, db_u = rn.bn_relu_bwd(dz, bxd, None, gd, md, rd, 1, beta=bd)
+    assert_close(dg, host(dg_u), 1e-5, "dgamma vs separate pass")
+    assert_close(db, host(db_u), 1e-5, "dbeta vs separate pass")
+    assert_close(dx, host(dx_u), max(1e-5, tol / 4), "dx vs separate pass")
+
+
+def test_fused_sums_reproducible_and_independent_of_buffer_contents(rn):
+    N, H, W, C, K = 6, 28, 28, 64, 128
+    x = dev(synth.activation_nhwc(SEED, "x", N, C, H, W), True)
+    w = dev(synth.conv_weight_krsc(SEED, "w", K, C, 3, 3), True)
+    g, b = dev(_vec("g", K, 0.3, 1.0)), dev(_vec("b", K, 0.2, 0.0))
+    d = rn.ConvDesc(N, H, W, C, K, 3, 3, 1, 1, rn.BF16)
+    outs = []
+    for fill in (0, 0xFF):
+        sums = torch.full((rn.conv_bn_sums_bytes(d),), fill, dtype=torch.uint8, device="cuda")
+        y, h = rn.conv_fwd_bn_sums(x, w, 1, 1, sums=sums)
+        outs.append(rn.bn_relu_fwd_from_sums(y, h, g, b, None, 1e-5, 1))
+    for a, c in zip(*outs):
+        assert torch.equal(a, c)
+
+
+def test_fused_abi_errors(rn):
+    N, H, W, C, K = 2, 8, 8, 16, 16
+    x = dev(synth.activation_nhwc(SEED, "x", N, C, H, W), True)
+    w = dev(synth.conv_weight_krsc(SEED, "w", K, C, 1, 1), True)
+    g, b = dev(np.ones(K, np.float32)), dev(np.zeros(K, np.float32))
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv_fwd_bn_sums(x, w, 1, 0, sums=small)
+    assert e.value.code == -3                                   # RN50_ERR_WORKSPACE
+    y, h = rn.conv_fwd_bn_sums(x, w, 1, 0)
+    other = (rn.ConvDesc(N, H, W, C, 2 * K, 1, 1, 1, 0, rn.BF16), h[1])
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.bn_relu_fwd_from_sums(y, other, g, b)
+    assert e.value.code == -1                                   # RN50_ERR_INVALID: not this layer's producer
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.bn_relu_fwd_from_sums(y, h, g, b, None, 1e-5, 2)     # mode 2 without residual
+    assert e.value.code == -1
