@@ -167,7 +167,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 
   // Load cursor: tap (r,s), chunk cc within the tap.  Per tap, the byte offset of every row's pixel (or
   // kOob); within a tap successive chunks only differ by a scalar offset.
-  int cur_r = 0, cur_s = 0, cur_cc = 0;
+  const int nchunks = a.R * a.S * a.cpt;
+  int cur_r = 0, cur_s = 0, cur_cc = 0, cur = 0;
   uint32_t a_off[RA], b_tap = 0;
   const bool ragged = (a.Cg % BK) != 0;
   auto tap_setup = [&]() __attribute__((always_inline)) {
@@ -193,9 +194,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   struct Staged {
     uint4 a[RA], b[RB];
   };
+  // Chunks past the last one load zeros (no memory access), so the main loop below needs no conditions:
+  // a branch around a load makes the compiler wait for every outstanding load at the join.
   auto load_chunk = [&](Staged& st) __attribute__((always_inline)) {
     const uint32_t so = static_cast<uint32_t>(cur_cc) * 128u;
-    const bool cval = !ragged || (cur_cc * BK + piece * V < a.Cg);
+    const bool cval = (!ragged || (cur_cc * BK + piece * V < a.Cg)) && cur < nchunks;
+    ++cur;
 #pragma unroll
     for (int i = 0; i < RA; ++i) st.a[i] = buffer_load16(rsA, cval ? a_off[i] : kOob, so);
 #pragma unroll
@@ -228,7 +232,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nchunks = a.R * a.S * a.cpt;
   const int frag_off = (lane & 31) * kPitch + (lane >> 5) * 16;
   auto compute = [&](int stage) __attribute__((always_inline)) {
     const unsigned char* sa = smem + stage * STAGE + wm * (BM / WM) * kPitch + frag_off;
@@ -251,20 +254,23 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   Staged st0, st1;
   tap_setup();
   load_chunk(st0);
-  if (nchunks > 1) load_chunk(st1);
+  load_chunk(st1);
   store_chunk(0, st0);
   __syncthreads();
-  for (int kc = 0; kc < nchunks; kc += 2) {
-    if (kc + 2 < nchunks) load_chunk(st0);
-    compute(0);
-    if (kc + 1 < nchunks) store_chunk(1, st1);
+  int kc = 0;
+  for (; kc + 2 <= nchunks; kc += 2) {
+    load_chunk(st0);      // chunk kc+2
+    compute(0);           // chunk kc
+    store_chunk(1, st1);  // chunk kc+1
     __syncthreads();
-    if (kc + 1 < nchunks) {
-      if (kc + 3 < nchunks) load_chunk(st1);
-      compute(1);
-      if (kc + 2 < nchunks) store_chunk(0, st0);
-      __syncthreads();
-    }
+    load_chunk(st1);      // chunk kc+3
+    compute(1);           // chunk kc+1
+    store_chunk(0, st0);  // chunk kc+2
+    __syncthreads();
+  }
+  if (kc < nchunks) {  // odd count: the last chunk is already in stage 0
+    compute(0);
+    __syncthreads();   // the output tile below reuses the pipeline buffers
   }
 
   // Epilogue.  acc[i][j][v]: output channel n = j*32 + (v/4)*8 + (lane/32)*4 + v%4, pixel m = i*32 + lane%32.
@@ -566,25 +572,24 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
         for (int j = 0; j < TN; ++j) Mma<T>::run(fa[i], fb[j], acc[i][j]);  // D[ko][c]
     }
   };
+  // Rows past row_end load zeros (no memory access), so the loop needs no conditions (see igemm_kernel).
   Staged st0, st1;
-  if (nchunks > 0) {
-    load_chunk(st0);
-    if (nchunks > 1) load_chunk(st1);
-    store_chunk(0, st0);
-  }
+  load_chunk(st0);
+  load_chunk(st1);
+  store_chunk(0, st0);
   __syncthreads();
-  for (int kc = 0; kc < nchunks; kc += 2) {
-    if (kc + 2 < nchunks) load_chunk(st0);
-    compute(0);
-    if (kc + 1 < nchunks) store_chunk(1, st1);
+  int kc = 0;
+  for (; kc + 2 <= nchunks; kc += 2) {
+    load_chunk(st0);      // chunk kc+2
+    compute(0);           // chunk kc
+    store_chunk(1, st1);  // chunk kc+1
     __syncthreads();
-    if (kc + 1 < nchunks) {
-      if (kc + 3 < nchunks) load_chunk(st1);
-      compute(1);
-      if (kc + 2 < nchunks) store_chunk(0, st0);
-      __syncthreads();
-    }
+    load_chunk(st1);      // chunk kc+3
+    compute(1);           // chunk kc+1
+    store_chunk(0, st0);  // chunk kc+2
+    __syncthreads();
   }
+  if (kc < nchunks) compute(0);  // odd count: the last chunk is already in stage 0
 
   // acc[i][j][v]: ko = i*32 + (v/4)*8 + (lane/32)*4 + v%4, c = j*32 + lane%32
   float* out = a.out + static_cast<int64_t>(split) * a.split_stride;
@@ -755,24 +760,23 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
 }
 
-// Tile choice: the widest tile that still gives every CU a couple of workgroups.
+// Tile choice, from per-layer timings of ResNet-50's shapes at batch 40: these kernels are bound by the
+// latency of a workgroup's load -> LDS -> MFMA chain, not by L2 bandwidth, so many small workgroups beat
+// fewer large ones almost everywhere.  The exception is the stride-2 data gradient, where three quarters
+// of the gathered taps are padding and the larger tile amortizes them.
 struct TileShape {
   int bm, bn;
 };
-static TileShape igemm_tile(int64_t M, int Ncols) {
+static TileShape igemm_tile(int64_t M, int Ncols, bool strided_dgrad) {
   int fbm = 0, fbn = 0;  // tuning aid: RN50_IGEMM_TILE=bm,bn forces a tile shape
   if (const char* e = getenv("RN50_IGEMM_TILE")) sscanf(e, "%d,%d", &fbm, &fbn);
   if ((fbm == 128 || fbm == 64) && (fbn == 128 || fbn == 64)) return TileShape{fbm, fbn};
-  const int64_t target = 512;
-  auto blocks = [&](int bm, int bn) { return ceil_div(M, bm) * ceil_div(Ncols, bn); };
-  if (Ncols > 64 && blocks(128, 128) >= target) return TileShape{128, 128};
-  if (blocks(128, 64) >= target) return TileShape{128, 64};
-  if (Ncols > 64 && blocks(64, 128) >= target / 2) return TileShape{64, 128};
+  if (strided_dgrad && Ncols >= 128 && ceil_div(M, 128) * ceil_div(Ncols, 128) >= 256) return TileShape{128, 128};
   return TileShape{64, 64};
 }
 template <typename T>
 static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
-  const TileShape t = igemm_tile(a.M, a.Ncols);
+  const TileShape t = igemm_tile(a.M, a.Ncols, a.mode == 1 && a.stride == 2);
   if (t.bm == 128 && t.bn == 128) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
   if (t.bm == 128) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
   if (t.bn == 128) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
@@ -782,15 +786,22 @@ static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
 struct WgradPlan {
   int bmo, bc, ctiles, splits, rows_per_split;
 };
-// Tile shape and number of reduction splits: the candidate with the smallest estimated time,
-//   waves * chunks_per_workgroup * t_chunk  +  cost of writing and re-reading the split partials,
-// where a "wave" is one round of workgroups over the chip (two resident per CU).
+// Tile shape and number of reduction splits, a rule fitted to per-layer sweeps of ResNet-50's shapes at
+// batch 40.  The kernel is latency-bound per workgroup, so the aim is 2-3 workgroups per CU with at least
+// 8 chunks each; the split partials cost a second launch, which is only worth it while the output tiles
+// alone cannot occupy every CU.  3x3 layers with wide channels take 128x128 tiles (half the operand
+// traffic per flop), everything else 64x64.
 static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype) {
   const int bkm = dtype == RN50_BF16 ? 64 : 32;
-  const double dw_bytes = 4.0 * Cout * taps * Cg;
-  const int cand[4][2] = {{128, 128}, {128, 64}, {64, 128}, {64, 64}};
   WgradPlan best{};
-  double best_t = 1e30;
+  auto fill = [&](int bmo, int bc, int64_t want_splits) {
+    const int64_t cap = M / (8 * bkm) > 1 ? M / (8 * bkm) : 1;
+    int64_t sp = want_splits < 1 ? 1 : (want_splits > cap ? cap : want_splits);
+    const int64_t rps = ceil_div(ceil_div(M, sp), bkm) * bkm;
+    best.bmo = bmo; best.bc = bc; best.ctiles = static_cast<int>(ceil_div(Cg, bc));
+    best.splits = static_cast<int>(ceil_div(M, rps));
+    best.rows_per_split = static_cast<int>(rps);
+  };
   if (const char* e = getenv("RN50_WGRAD_PLAN")) {  // tuning aid: bmo,bc,splits
     int bmo = 0, bc = 0, sp = 0;
     if (sscanf(e, "%d,%d,%d", &bmo, &bc, &sp) == 3 && (bmo == 64 || bmo == 128) && (bc == 64 || bc == 128) && sp >= 1) {
@@ -801,26 +812,14 @@ static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype) {
       return best;
     }
   }
-  for (int ci = 0; ci < 4; ++ci) {
-    const int bmo = cand[ci][0], bc = cand[ci][1];
-    if ((bmo == 128 && Cout <= 64) || (bc == 128 && Cg <= 64)) continue;
-    const int ctiles = static_cast<int>(ceil_div(Cg, bc));
-    const int64_t tiles = static_cast<int64_t>(taps) * ctiles * ceil_div(Cout, bmo);
-    const double t_chunk = (bmo == 128 ? 1.0 : 0.6) * (bc == 128 ? 1.0 : 0.6) * 0.45e-6;
-    const int64_t max_splits = ceil_div(M, 2 * bkm);
-    for (int64_t splits = 1; splits <= max_splits && splits <= 1024; splits = splits < 8 ? splits + 1 : splits * 2) {
-      const int64_t rps = ceil_div(ceil_div(M, splits), bkm) * bkm;
-      const int64_t real_splits = ceil_div(M, rps);
-      const double waves = static_cast<double>(ceil_div(tiles * real_splits, 512));
-      double t = waves * static_cast<double>(rps / bkm) * t_chunk + 2e-6;
-      if (real_splits > 1) t += (2.0 * real_splits + 1.0) * dw_bytes / 3.0e12 + 4e-6;
-      if (t < best_t) {
-        best_t = t;
-        best.bmo = bmo; best.bc = bc; best.ctiles = ctiles;
-        best.splits = static_cast<int>(real_splits);
-        best.rows_per_split = static_cast<int>(rps);
-      }
-    }
+  const int64_t tiles64 = static_cast<int64_t>(taps) * ceil_div(Cg, 64) * ceil_div(Cout, 64);
+  if (tiles64 >= 256) {
+    fill(64, 64, 1);
+  } else if (taps >= 9 && Cout >= 128 && Cg >= 128) {
+    const int64_t tiles = static_cast<int64_t>(taps) * ceil_div(Cg, 128) * ceil_div(Cout, 128);
+    fill(128, 128, (432 + tiles / 2) / tiles);
+  } else {
+    fill(64, 64, (576 + tiles64 / 2) / tiles64);
   }
   return best;
 }
@@ -919,16 +918,16 @@ void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_
 size_t stem_padded_input_bytes(const rn50_conv_desc* d) { return stem_geom(d).xp_bytes; }
 size_t stem_padded_weight_bytes(const rn50_conv_desc* d) { return stem_geom(d).wp_bytes; }
 
-static PartialRows tile_rows(int64_t M, int Ncols) {
-  const int bm = igemm_tile(M, Ncols).bm;
+static PartialRows tile_rows(int64_t M, int Ncols, bool strided_dgrad) {
+  const int bm = igemm_tile(M, Ncols, strided_dgrad).bm;
   return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
 }
 PartialRows fwd_partial_rows(const rn50_conv_desc* d) {
   const int64_t M = static_cast<int64_t>(d->N) * out_dim(d->H, d->pad, d->R, d->stride) * out_dim(d->W, d->pad, d->S, d->stride);
-  return tile_rows(M, d->Cout);
+  return tile_rows(M, d->Cout, false);
 }
 PartialRows dgrad_partial_rows(const rn50_conv_desc* d) {
-  return tile_rows(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin);
+  return tile_rows(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin, d->stride == 2);
 }
 
 static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const void* wp, void* y) {
