@@ -116,137 +116,99 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   }
   combine_rows<2 * V>(acc, lds, tx_log2);
   if (active && trow == 0) {
-    float* o0 = partial + (static_cast<int64_t>(blockIdx.x) * 3) * C + col * V;
+    // partial[plane][c][row]: the rows of one channel are contiguous for the finalize pass
+    const int64_t nrows = gridDim.x;
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-      o0[j] = K[j];
-      o0[C + j] = acc[j];
-      o0[2 * C + j] = acc[V + j];
+      float* o = partial + static_cast<int64_t>(col * V + j) * nrows + blockIdx.x;
+      o[0] = K[j];
+      o[C * nrows] = acc[j];
+      o[2 * C * nrows] = acc[V + j];
     }
   }
 }
 
-// Sums of the nblk partials of cpb = 1 << cpb_log2 channels per workgroup: thread (c, part) adds every
-// (256/cpb)-th partial row, the parts are then added in order; all in double, a fixed order.  Few
-// channels per workgroup (narrow layers) keeps enough workgroups busy; many (wide layers) keeps the
-// reads of a partial row contiguous.  Result for channel c in the first cpb threads.
-__device__ __forceinline__ bool finalize_sums(const float* __restrict__ partial, int nblk, int C, int cpb_log2,
-                                              double* s1_out, double* s2_out, int* c_out) {
-  __shared__ double red[2][256];
-  const int cpb = 1 << cpb_log2, parts = 256 >> cpb_log2;
-  const int cl = threadIdx.x & (cpb - 1), part = threadIdx.x >> cpb_log2;
-  const int c = blockIdx.x * cpb + cl;
-  double s1 = 0.0, s2 = 0.0;
-  if (c < C) {
-    // batches of 8 rows whose 16 loads are issued before the (ordered) additions
-    int b = part;
-    for (; b + 7 * parts < nblk; b += 8 * parts) {
-      float v1[8], v2[8];
+// Finalize passes.  The partial sums lie as partial[plane][c][row], `nrows` rows per channel, so one wave
+// reads the rows of one channel with contiguous 256-byte loads.  A workgroup serves 4/wpc channels with
+// wpc (1 or 4) waves each; lane l of wave w adds rows (w*64 + l) + 64*wpc*i, i = 0, 1, ... in order, then
+// the lanes are combined by a fixed butterfly and the waves in order: all in double, a fixed order.
+__device__ __forceinline__ double wave_sum_double(double v) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        v1[u] = partial[(static_cast<int64_t>(b + u * parts) * 2) * C + c];
-        v2[u] = partial[(static_cast<int64_t>(b + u * parts) * 2 + 1) * C + c];
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        s1 += static_cast<double>(v1[u]);
-        s2 += static_cast<double>(v2[u]);
-      }
-    }
-    for (; b < nblk; b += parts) {
-      s1 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2) * C + c]);
-      s2 += static_cast<double>(partial[(static_cast<int64_t>(b) * 2 + 1) * C + c]);
-    }
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+// Combines (s1, s2) over the waves of a channel; true in lane 0 of the channel's first wave, with the totals.
+__device__ __forceinline__ bool finalize_combine(double* s1, double* s2, int wpc, int c, int C) {
+  __shared__ double red[2][4];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  double a = wave_sum_double(*s1), b = wave_sum_double(*s2);
+  if (wpc == 1) {
+    *s1 = a; *s2 = b;
+    return lane == 0 && c < C;
   }
-  red[0][threadIdx.x] = s1;
-  red[1][threadIdx.x] = s2;
+  if (lane == 0) {
+    red[0][wave] = a;
+    red[1][wave] = b;
+  }
   __syncthreads();
-  *c_out = c;
-  if (part != 0 || c >= C) return false;
-  s1 = 0.0; s2 = 0.0;
-  for (int k = 0; k < parts; ++k) {
-    s1 += red[0][k * cpb + cl];
-    s2 += red[1][k * cpb + cl];
-  }
-  *s1_out = s1;
-  *s2_out = s2;
-  return true;
+  *s1 = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
+  *s2 = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
+  return threadIdx.x == 0 && c < C;
 }
-static int finalize_cpb_log2(int C) { return C >= 1024 ? 3 : 2; }
+static int finalize_wpc(int nrows) { return nrows >= 512 ? 4 : 1; }
+static int finalize_grid(int C, int nrows) { return static_cast<int>(ceil_div(C * finalize_wpc(nrows), 4)); }
 
-// The forward statistics come as rows [shift, S1, S2] over `rpp` consecutive rows of x each (the last row
-// of partials may cover fewer), every row with a shift of its own: S1 = sum(x - shift), S2 = sum((x -
-// shift)^2).  They are moved to the first row's shift K0 exactly, in double,
-//   sum(x - K0) = S1 + n e,  sum((x - K0)^2) = S2 + 2 e S1 + n e^2,  e = shift - K0,
-// and added as in finalize_sums.
-__device__ __forceinline__ bool finalize_stats(const float* __restrict__ partial, int nrows, int rpp, int64_t m,
-                                               int C, int cpb_log2, double* s1_out, double* s2_out,
-                                               double* k0_out, int* c_out) {
-  __shared__ double red[2][256];
-  const int cpb = 1 << cpb_log2, parts = 256 >> cpb_log2;
-  const int cl = threadIdx.x & (cpb - 1), part = threadIdx.x >> cpb_log2;
-  const int c = blockIdx.x * cpb + cl;
+// Forward statistics: rows [shift, S1, S2] over `rpp` consecutive rows of x each (the last may cover
+// fewer), every row with a shift of its own: S1 = sum(x - shift), S2 = sum((x - shift)^2).  They are moved
+// to the first row's shift K0 exactly, in double,
+//   sum(x - K0) = S1 + n e,  sum((x - K0)^2) = S2 + 2 e S1 + n e^2,  e = shift - K0.
+__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partial, int nrows, int rpp,
+                                                          int64_t m, int C, int wpc, float eps,
+                                                          float* __restrict__ mean_out,
+                                                          float* __restrict__ rstd_out,
+                                                          float* running_mean, float* running_var,
+                                                          float momentum) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c = wpc == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
+  const int first = (wpc == 1 ? 0 : wave * 64) + lane, step = 64 * wpc;
   double s1 = 0.0, s2 = 0.0, k0 = 0.0;
   if (c < C) {
-    k0 = static_cast<double>(partial[c]);
+    const float* pk = partial + static_cast<int64_t>(c) * nrows;
+    const float* p1 = pk + static_cast<int64_t>(C) * nrows;
+    const float* p2 = p1 + static_cast<int64_t>(C) * nrows;
+    k0 = static_cast<double>(pk[0]);
     constexpr int U = 4;
-    int b = part;
-    for (; b + (U - 1) * parts < nrows; b += U * parts) {
+    int b = first;
+    for (; b + (U - 1) * step < nrows; b += U * step) {
       float vk[U], v1[U], v2[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const float* p = partial + (static_cast<int64_t>(b + u * parts) * 3) * C + c;
-        vk[u] = p[0];
-        v1[u] = p[C];
-        v2[u] = p[2 * C];
+        vk[u] = pk[b + u * step];
+        v1[u] = p1[b + u * step];
+        v2[u] = p2[b + u * step];
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int64_t left = m - static_cast<int64_t>(b + u * parts) * rpp;
+        const int64_t left = m - static_cast<int64_t>(b + u * step) * rpp;
         const double n = static_cast<double>(left < rpp ? left : rpp);
         const double e = static_cast<double>(vk[u]) - k0, a1 = static_cast<double>(v1[u]);
         s1 += a1 + n * e;
         s2 += static_cast<double>(v2[u]) + e * (2.0 * a1 + n * e);
       }
     }
-    for (; b < nrows; b += parts) {
-      const float* p = partial + (static_cast<int64_t>(b) * 3) * C + c;
+    for (; b < nrows; b += step) {
       const int64_t left = m - static_cast<int64_t>(b) * rpp;
       const double n = static_cast<double>(left < rpp ? left : rpp);
-      const double e = static_cast<double>(p[0]) - k0, a1 = static_cast<double>(p[C]);
+      const double e = static_cast<double>(pk[b]) - k0, a1 = static_cast<double>(p1[b]);
       s1 += a1 + n * e;
-      s2 += static_cast<double>(p[2 * C]) + e * (2.0 * a1 + n * e);
+      s2 += static_cast<double>(p2[b]) + e * (2.0 * a1 + n * e);
     }
   }
-  red[0][threadIdx.x] = s1;
-  red[1][threadIdx.x] = s2;
-  __syncthreads();
-  *c_out = c;
-  if (part != 0 || c >= C) return false;
-  s1 = 0.0; s2 = 0.0;
-  for (int k = 0; k < parts; ++k) {
-    s1 += red[0][k * cpb + cl];
-    s2 += red[1][k * cpb + cl];
-  }
-  *s1_out = s1;
-  *s2_out = s2;
-  *k0_out = k0;
-  return true;
-}
-
-__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partial, int nrows, int rpp,
-                                                          int64_t m, int C, int cpb_log2, float eps,
-                                                          float* __restrict__ mean_out,
-                                                          float* __restrict__ rstd_out,
-                                                          float* running_mean, float* running_var,
-                                                          float momentum) {
-  double s1, s2, K;
-  int c;
-  if (!finalize_stats(partial, nrows, rpp, m, C, cpb_log2, &s1, &s2, &K, &c)) return;
+  if (!finalize_combine(&s1, &s2, wpc, c, C)) return;
   const double d = s1 / static_cast<double>(m);
   double var = s2 / static_cast<double>(m) - d * d;
   if (var < 0.0) var = 0.0;
-  const double mean = K + d;
+  const double mean = k0 + d;
   mean_out[c] = static_cast<float>(mean);
   rstd_out[c] = static_cast<float>(1.0 / sqrt(var + static_cast<double>(eps)));
   if (running_mean) running_mean[c] = momentum * running_mean[c] + (1.f - momentum) * static_cast<float>(mean);
@@ -410,23 +372,48 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
   }
   combine_rows<2 * V>(acc, lds, tx_log2);
   if (active && trow == 0) {
-    float* o1 = partial + (static_cast<int64_t>(blockIdx.x) * 2) * C + col * V;
-    float* o2 = o1 + C;
+    const int64_t nrows = gridDim.x;
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-      o1[j] = acc[j];
-      o2[j] = acc[V + j];
+      float* o = partial + static_cast<int64_t>(col * V + j) * nrows + blockIdx.x;
+      o[0] = acc[j];
+      o[C * nrows] = acc[V + j];
     }
   }
 }
 
 __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partial,
-                                                              int nblk, int C, int cpb_log2,
+                                                              int nrows, int C, int wpc,
                                                               float* __restrict__ dgamma,
                                                               float* __restrict__ dbeta) {
-  double s1, s2;
-  int c;
-  if (!finalize_sums(partial, nblk, C, cpb_log2, &s1, &s2, &c)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c = wpc == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
+  const int first = (wpc == 1 ? 0 : wave * 64) + lane, step = 64 * wpc;
+  double s1 = 0.0, s2 = 0.0;
+  if (c < C) {
+    const float* p1 = partial + static_cast<int64_t>(c) * nrows;
+    const float* p2 = p1 + static_cast<int64_t>(C) * nrows;
+    constexpr int U = 4;
+    int b = first;
+    for (; b + (U - 1) * step < nrows; b += U * step) {
+      float v1[U], v2[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        v1[u] = p1[b + u * step];
+        v2[u] = p2[b + u * step];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        s1 += static_cast<double>(v1[u]);
+        s2 += static_cast<double>(v2[u]);
+      }
+    }
+    for (; b < nrows; b += step) {
+      s1 += static_cast<double>(p1[b]);
+      s2 += static_cast<double>(p2[b]);
+    }
+  }
+  if (!finalize_combine(&s1, &s2, wpc, c, C)) return;
   dbeta[c] = static_cast<float>(s1);
   dgamma[c] = static_cast<float>(s2);
 }
@@ -501,16 +488,16 @@ static size_t bn_ws_bytes(const rn50_bn_desc* d) {
   return align_up(static_cast<size_t>(g.nblk) * 3 * d->C * sizeof(float), 256);
 }
 
-// finalize + apply from partial statistics rows (see finalize_stats)
+// finalize + apply from partial statistics rows (see bn_finalize_kernel)
 template <typename T>
 static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* x,
                             const float* gamma, const float* beta, const void* residual, void* y,
                             float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
                             const float* partial, int nrows, int rpp, hipStream_t s) {
   RN50_TIMED("bn_finalize", s,
-             hipLaunchKernelGGL(bn_finalize_kernel, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
+             hipLaunchKernelGGL(bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)),
                                 dim3(256), 0, s, partial, nrows, rpp, m, d->C,
-                                finalize_cpb_log2(d->C), d->eps,
+                                finalize_wpc(nrows), d->eps,
                                 save_mean, save_rstd, rm, rv, momentum));
   RN50_TIMED("bn_apply", s,
              hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
@@ -540,8 +527,8 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             void* dres, float* dgamma, float* dbeta, const float* partial, int nrows,
                             hipStream_t s) {
   RN50_TIMED("bn_bwd_finalize", s,
-             hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(d->C, 1 << finalize_cpb_log2(d->C))),
-                                dim3(256), 0, s, partial, nrows, d->C, finalize_cpb_log2(d->C), dgamma,
+             hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)),
+                                dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma,
                                 dbeta));
   RN50_TIMED("bn_bwd_apply", s,
              hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,

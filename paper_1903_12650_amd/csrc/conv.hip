@@ -99,8 +99,8 @@ struct IgemmArgs {
   int ntn;          // number of column tiles
   int mode;         // host side only: selects the MODE template argument
   // Optional batch-norm sums over the rows of each output tile, taken from the rounded values that are
-  // stored (null: none).  Forward: partial[mt][3][Ncols] = shift (the tile's first row), sum(y - shift),
-  // sum((y - shift)^2).  Data gradient: partial[mt][2][Ncols] = sum(g), sum(g * xhat) with g the output
+  // stored (null: none).  Forward: partial[3][Ncols][tiles] = shift (the tile's first row), sum(y - shift),
+  // sum((y - shift)^2).  Data gradient: partial[2][Ncols][tiles] = sum(g), sum(g * xhat) with g the output
   // gradient masked by the ReLU of the BN layer whose conv output is bn_x [M][Ncols], xhat its
   // normalized input.
   float* partial;
@@ -397,15 +397,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   if (tid < BN && n0 + tid < a.Ncols) {
     const float t1 = ((red[0][0][tid] + red[1][0][tid]) + red[2][0][tid]) + red[3][0][tid];
     const float t2 = ((red[0][1][tid] + red[1][1][tid]) + red[2][1][tid]) + red[3][1][tid];
+    // partial[plane][channel][tile row]: the rows of one channel are contiguous for the finalize pass
+    const int64_t nrows = (a.M + BM - 1) / BM, plane = static_cast<int64_t>(a.Ncols) * nrows;
+    float* o = a.partial + static_cast<int64_t>(n0 + tid) * nrows + mt;
     if (MODE == 0) {
-      float* o = a.partial + static_cast<int64_t>(mt) * 3 * a.Ncols + n0 + tid;
       o[0] = Elem<T>::load(reinterpret_cast<const T*>(smem) + tid);
-      o[a.Ncols] = t1;
-      o[2 * a.Ncols] = t2;
+      o[plane] = t1;
+      o[2 * plane] = t2;
     } else {
-      float* o = a.partial + static_cast<int64_t>(mt) * 2 * a.Ncols + n0 + tid;
       o[0] = t1;
-      o[a.Ncols] = t2;
+      o[plane] = t2;
     }
   }
 }

@@ -21,12 +21,12 @@ struct PartialRows {
 };
 PartialRows fwd_partial_rows(const rn50_conv_desc* d);    // tiles of the forward convolution's output
 PartialRows dgrad_partial_rows(const rn50_conv_desc* d);  // tiles of the data gradient
-// bn_partial (null: none): float[num][3][Cout] = shift, sum(y - shift), sum((y - shift)^2) per tile.
+// bn_partial (null: none): float[3][Cout][num] = shift, sum(y - shift), sum((y - shift)^2) per tile.
 void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
                      hipStream_t s);
 void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s);
 // The BN layer (with ReLU, no residual) whose output gradient a data gradient produces: x is that
-// layer's input [N*H*W][Cin]; partial receives float[num][2][Cin] = sum(g), sum(g * xhat) per tile.
+// layer's input [N*H*W][Cin]; partial receives float[2][Cin][num] = sum(g), sum(g * xhat) per tile.
 struct BnBwdSums {
   const void* x;
   const float *gamma, *beta, *mean, *rstd;
