@@ -54,6 +54,21 @@ static BnGeom bn_geom(int64_t m, int C, int dtype) {
   return g;
 }
 
+// The elementwise passes have no sums to combine, so their geometry is free.  Measured on the layer
+// shapes of ResNet-50: best is about `target` workgroups in all (1-3 per CU), each thread streaming
+// 4 to 32 rows; small tensors then still give every CU a workgroup and need one round of loads.
+static BnGeom bn_apply_geom(int64_t m, int C, int dtype, int target) {
+  BnGeom g = bn_geom(m, C, dtype);
+  const int TY = 256 >> g.tx_log2;
+  int64_t rpt = ceil_div(m * g.gy, static_cast<int64_t>(TY) * target);
+  if (const char* e = getenv("RN50_BN_APPLY_RPT")) rpt = atoi(e) > 0 ? atoi(e) : rpt;  // tuning aid
+  rpt = ceil_div(rpt, kBnRows) * kBnRows;
+  if (rpt > 32) rpt = 32;
+  g.rpb = static_cast<int>(rpt) * TY;
+  g.nblk = static_cast<int>(ceil_div(m, g.rpb));
+  return g;
+}
+
 // Tree-combine NV floats per thread over the TY rows of the workgroup; the
 // result lands in the threads of row 0.
 template <int NV>
@@ -499,11 +514,12 @@ static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                                 dim3(256), 0, s, partial, nrows, rpp, m, d->C,
                                 finalize_wpc(nrows), d->eps,
                                 save_mean, save_rstd, rm, rv, momentum));
+  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 768);
   RN50_TIMED("bn_apply", s,
-             hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
+             hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s,
                                 static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
                                 static_cast<const T*>(residual), static_cast<T*>(y), m, d->C,
-                                g.tx_log2, g.rpb, d->mode));
+                                ga.tx_log2, ga.rpb, d->mode));
 }
 
 template <typename T>
@@ -530,12 +546,13 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
              hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)),
                                 dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma,
                                 dbeta));
+  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 384);
   RN50_TIMED("bn_bwd_apply", s,
-             hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(g.nblk, g.gy), dim3(256), 0, s,
+             hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s,
                                 static_cast<const T*>(dz), static_cast<const T*>(dz2),
                                 static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
                                 mean, rstd, dgamma, dbeta, static_cast<T*>(dx),
-                                static_cast<T*>(dres), m, d->C, g.tx_log2, g.rpb, d->mode));
+                                static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode));
 }
 
 template <typename T>
