@@ -97,6 +97,8 @@ struct IgemmArgs {
   int R, S, stride, pad;
   int cpt;          // 128-byte chunks per tap
   int ntn;          // number of column tiles
+  int nimg;         // images (M = nimg*P*Q)
+  int tiles_per_class;  // stride-2 data gradient: row tiles per parity class of the output pixels
   int mode;         // host side only: selects the MODE template argument
   // Optional batch-norm sums over the rows of each output tile, taken from the rounded values that are
   // stored (null: none).  Forward: partial[3][Ncols][tiles] = shift (the tile's first row), sum(y - shift),
@@ -123,7 +125,11 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
 }
 
 // MODE 0: forward gather  ih = p*stride - pad + r.
-// MODE 1: data-gradient gather  ih = (p + pad - r)/stride when divisible (stride 1 or 2).
+// MODE 1: data-gradient gather  ih = (p + pad - r)/stride when divisible (stride 1 or 2).  With stride 2
+// an output pixel only receives the taps r = (p + pad) mod 2, s = (q + pad) mod 2 (mod 2), so the pixels
+// are processed in four parity classes (p mod 2, q mod 2): a row tile holds pixels of one class and loops
+// over that class's taps only (a quarter of the taps on average, none for three classes of a 1x1 filter,
+// whose tiles just store zeros).
 template <typename T, int BM, int BN, int WM, int WN, int MODE>
 __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   constexpr int V = 16 / sizeof(T);
@@ -141,20 +147,43 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   const int wm = wave % WM, wn = wave / WM;
   const int bid = xcd_remap(blockIdx.x, gridDim.x);
   const int nt = bid % a.ntn, mt = bid / a.ntn;
-  const int m0 = mt * BM, n0 = nt * BN;
+  const int n0 = nt * BN;
   const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a.act, a.act_bytes), rsB = make_rsrc(a.wgt, a.wgt_bytes);
+
+  // Rows of this tile: pixels m0.. of the whole output grid, or of one parity class of it.
+  const bool classes = MODE == 1 && a.stride == 2;
+  __shared__ int pix_s[BM];  // classes only: output pixel index of every tile row
+  int ph = 0, pw = 0, Hc = a.P, Wc = a.Q, Mc = a.M, m0 = mt * BM;
+  int r0 = 0, s0 = 0, tstep = 1;
+  if (classes) {
+    // the four classes of one pixel range are neighbours in the tile order: they read the same rows of
+    // the incoming gradient, and every XCD gets its share of the classes that have taps
+    const int cls = mt & 3;
+    m0 = (mt >> 2) * BM;
+    ph = cls >> 1; pw = cls & 1;
+    Hc = (a.P - ph + 1) >> 1; Wc = (a.Q - pw + 1) >> 1;
+    Mc = a.nimg * Hc * Wc;
+    r0 = (ph + a.pad) & 1; s0 = (pw + a.pad) & 1; tstep = 2;
+  }
+  const int nr = r0 < a.R ? (a.R - r0 + tstep - 1) / tstep : 0, ns = s0 < a.S ? (a.S - s0 + tstep - 1) / tstep : 0;
 
   // per-thread rows of the A tile: decode the output pixel once
   int a_h0[RA], a_w0[RA], a_base[RA];
 #pragma unroll
   for (int i = 0; i < RA; ++i) {
     const int m = m0 + lrow + 32 * i;
-    const bool ok = m < a.M;
+    const bool ok = m < Mc;
     const int mm = ok ? m : 0;
-    const int q = mm % a.Q, t = mm / a.Q;
-    const int p = t % a.P, n = t / a.P;
+    int q = mm % Wc;
+    const int t = mm / Wc;
+    int p = t % Hc;
+    const int n = t / Hc;
+    if (classes) {
+      p = 2 * p + ph; q = 2 * q + pw;
+      if (piece == 0) pix_s[lrow + 32 * i] = ok ? (n * a.P + p) * a.Q + q : 0;
+    }
     a_base[i] = n * a.H * a.W;
-    // a row beyond M gets coordinates that fail every bounds check below
+    // a row beyond the last gets coordinates that fail every bounds check below
     a_h0[i] = ok ? (MODE == 0 ? p * a.stride - a.pad : p + a.pad) : -(1 << 20);
     a_w0[i] = MODE == 0 ? q * a.stride - a.pad : q + a.pad;
   }
@@ -167,9 +196,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 
   // Load cursor: tap (r,s), chunk cc within the tap.  Per tap, the byte offset of every row's pixel (or
   // kOob); within a tap successive chunks only differ by a scalar offset.
-  const int nchunks = a.R * a.S * a.cpt;
-  int cur_r = 0, cur_s = 0, cur_cc = 0, cur = 0;
-  uint32_t a_off[RA], b_tap = 0;
+  const int nchunks = nr * ns * a.cpt;
+  int cur_r = r0, cur_s = s0, cur_cc = 0, cur = 0;
+  uint32_t a_off[RA], b_tap = static_cast<uint32_t>((r0 * a.S + s0) * a.Cg) * sizeof(T);
   const bool ragged = (a.Cg % BK) != 0;
   auto tap_setup = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -207,11 +236,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     // advance the cursor
     if (++cur_cc == a.cpt) {
       cur_cc = 0;
-      b_tap += static_cast<uint32_t>(a.Cg) * sizeof(T);
-      if (++cur_s == a.S) {
-        cur_s = 0;
-        ++cur_r;
+      cur_s += tstep;
+      if (cur_s >= a.S) {
+        cur_s = s0;
+        cur_r += tstep;
       }
+      b_tap = static_cast<uint32_t>((cur_r * a.S + cur_s) * a.Cg) * sizeof(T);
       tap_setup();
     }
   };
@@ -305,9 +335,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     for (int pass = 0; pass < NPASS; ++pass) {
       const int row = orow + pass * RPP;
       const int m = m0 + row;
-      if (m < a.M && n < a.Ncols)
-        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) =
+      if (m < Mc && n < a.Ncols) {
+        const int pix = classes ? pix_s[row] : m;
+        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(pix) * a.Ncols + n)) =
             *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+      }
     }
     return;
   }
@@ -327,7 +359,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     for (int pass = 0; pass < NPASS; ++pass) {
       const int row = orow + pass * RPP;
       const int m = m0 + row;
-      if (m < a.M && col_ok) {
+      if (m < Mc && col_ok) {
         Vec16 v;
         v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
         *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) = v.u;
@@ -345,10 +377,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const T* bx = static_cast<const T*>(a.bn_x);
     const int nc = col_ok ? n : 0;
     Vec16 xv[NPASS];
+    int pix[NPASS];
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
-      const int m = min(m0 + orow + pass * RPP, a.M - 1);
-      xv[pass] = load16(bx + (static_cast<int64_t>(m) * a.Ncols + nc));
+      const int row = orow + pass * RPP;
+      pix[pass] = classes ? pix_s[row] : min(m0 + row, a.M - 1);  // rows past the last read a valid pixel
+      xv[pass] = load16(bx + (static_cast<int64_t>(pix[pass]) * a.Ncols + nc));
     }
     float scale[V], bias[V], rs[V], nmr[V];
 #pragma unroll
@@ -360,11 +394,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
       const int row = orow + pass * RPP;
-      const int m = m0 + row;
-      if (m < a.M && col_ok) {
+      if (m0 + row < Mc && col_ok) {
         Vec16 v;
         v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
-        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(m) * a.Ncols + n)) = v.u;
+        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(pix[pass]) * a.Ncols + n)) = v.u;
         float g[V], xf[V];
         Elem<T>::unpack(v, g);
         Elem<T>::unpack(xv[pass], xf);
@@ -398,7 +431,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const float t1 = ((red[0][0][tid] + red[1][0][tid]) + red[2][0][tid]) + red[3][0][tid];
     const float t2 = ((red[0][1][tid] + red[1][1][tid]) + red[2][1][tid]) + red[3][1][tid];
     // partial[plane][channel][tile row]: the rows of one channel are contiguous for the finalize pass
-    const int64_t nrows = (a.M + BM - 1) / BM, plane = static_cast<int64_t>(a.Ncols) * nrows;
+    const int64_t nrows = gridDim.x / a.ntn, plane = static_cast<int64_t>(a.Ncols) * nrows;
     float* o = a.partial + static_cast<int64_t>(n0 + tid) * nrows + mt;
     if (MODE == 0) {
       o[0] = Elem<T>::load(reinterpret_cast<const T*>(smem) + tid);
@@ -756,15 +789,17 @@ static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid,
 template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   a.ntn = static_cast<int>(ceil_div(a.Ncols, BN));
-  const int64_t grid = ceil_div(a.M, BM) * a.ntn;
+  a.nimg = a.M / (a.P * a.Q);
+  a.tiles_per_class = static_cast<int>(ceil_div(static_cast<int64_t>(a.nimg) * ((a.P + 1) / 2) * ((a.Q + 1) / 2), BM));
+  const bool classes = a.mode == 1 && a.stride == 2;
+  const int64_t grid = (classes ? 4 * a.tiles_per_class : ceil_div(a.M, BM)) * a.ntn;
   if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0>(a, tag, grid, s);
   else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
 }
 
 // Tile choice, from per-layer timings of ResNet-50's shapes at batch 40: these kernels are bound by the
 // latency of a workgroup's load -> LDS -> MFMA chain, not by L2 bandwidth, so many small workgroups beat
-// fewer large ones almost everywhere.  The exception is the stride-2 data gradient, where three quarters
-// of the gathered taps are padding and the larger tile amortizes them.
+// fewer large ones on every layer; the larger tiles stay available through RN50_IGEMM_TILE.
 struct TileShape {
   int bm, bn;
 };
@@ -772,7 +807,7 @@ static TileShape igemm_tile(int64_t M, int Ncols, bool strided_dgrad) {
   int fbm = 0, fbn = 0;  // tuning aid: RN50_IGEMM_TILE=bm,bn forces a tile shape
   if (const char* e = getenv("RN50_IGEMM_TILE")) sscanf(e, "%d,%d", &fbm, &fbn);
   if ((fbm == 128 || fbm == 64) && (fbn == 128 || fbn == 64)) return TileShape{fbm, fbn};
-  if (strided_dgrad && Ncols >= 128 && ceil_div(M, 128) * ceil_div(Ncols, 128) >= 256) return TileShape{128, 128};
+  (void)M; (void)Ncols; (void)strided_dgrad;
   return TileShape{64, 64};
 }
 template <typename T>
@@ -923,12 +958,24 @@ static PartialRows tile_rows(int64_t M, int Ncols, bool strided_dgrad) {
   const int bm = igemm_tile(M, Ncols, strided_dgrad).bm;
   return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
 }
+// stride-2 data gradient: four parity classes of ceil(N * ceil(H/2) * ceil(W/2) / bm) row tiles each
+static PartialRows class_tile_rows(const rn50_conv_desc* d) {
+  const int bm = igemm_tile(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin, true).bm;
+  const int64_t per_class = ceil_div(static_cast<int64_t>(d->N) * ((d->H + 1) / 2) * ((d->W + 1) / 2), bm);
+  return PartialRows{bm, static_cast<int>(4 * per_class)};
+}
 PartialRows fwd_partial_rows(const rn50_conv_desc* d) {
   const int64_t M = static_cast<int64_t>(d->N) * out_dim(d->H, d->pad, d->R, d->stride) * out_dim(d->W, d->pad, d->S, d->stride);
   return tile_rows(M, d->Cout, false);
 }
+int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d) {
+  const int64_t plain = ceil_div(static_cast<int64_t>(d->N) * d->H * d->W, 64);
+  const int64_t classes = 4 * ceil_div(static_cast<int64_t>(d->N) * ((d->H + 1) / 2) * ((d->W + 1) / 2), 64);
+  return d->stride == 2 && classes > plain ? classes : plain;
+}
 PartialRows dgrad_partial_rows(const rn50_conv_desc* d) {
-  return tile_rows(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin, d->stride == 2);
+  if (d->stride == 2) return class_tile_rows(d);
+  return tile_rows(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin, false);
 }
 
 static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const void* wp, void* y) {
@@ -1159,7 +1206,7 @@ extern "C" size_t conv_bn_sums_bytes(const rn50_conv_desc* d) {
   // one row per output tile of at least 64 pixels; three planes forward, two backward
   const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
   const size_t fwd = static_cast<size_t>(ceil_div(static_cast<int64_t>(d->N) * P * Q, 64)) * 3 * d->Cout;
-  const size_t bwd = static_cast<size_t>(ceil_div(static_cast<int64_t>(d->N) * d->H * d->W, 64)) * 2 * d->Cin;
+  const size_t bwd = static_cast<size_t>(dgrad_partial_rows_bound(d)) * 2 * d->Cin;
   return align_up((fwd > bwd ? fwd : bwd) * sizeof(float), 256);
 }
 

@@ -21,6 +21,7 @@ struct PartialRows {
 };
 PartialRows fwd_partial_rows(const rn50_conv_desc* d);    // tiles of the forward convolution's output
 PartialRows dgrad_partial_rows(const rn50_conv_desc* d);  // tiles of the data gradient
+int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d);  // most rows any tile choice gives (tiles of >= 64 pixels)
 // bn_partial (null: none): float[3][Cout][num] = shift, sum(y - shift), sum((y - shift)^2) per tile.
 void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
                      hipStream_t s);

@@ -52,6 +52,9 @@ SMALL = [  # N,H,W,C,K,R,stride,pad : ragged tiles, tails, every stride/pad/filt
     (1, 20, 20, 8, 8, 7, 2, 3),
     (2, 6, 6, 16, 16, 5, 1, 2),
     (1, 1, 1, 8, 8, 1, 1, 0),
+    (2, 9, 7, 16, 16, 1, 2, 0),      # stride 2, odd sizes: the four pixel parity classes differ in size
+    (1, 1, 5, 8, 8, 3, 2, 1),        # a single row: two parity classes are empty
+    (2, 5, 4, 8, 16, 2, 2, 0),       # even filter, stride 2
 ]
 
 
