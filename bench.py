@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--roofline-kernel", default=None, help="kernel tag to time (default: the dominant one)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of known size (the float master arena) before the steps: "
+                         "the reference dispatch that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -102,6 +105,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        scratch = torch.empty_like(S["M"])
+        scratch.copy_(S["M"])          # reads and writes 4 * arena_elems bytes
+        torch.cuda.synchronize()
+        print("calibration copy: %d bytes read, %d bytes written" % (4 * plan.arena_elems, 4 * plan.arena_elems),
+              file=sys.stderr)
     tag = None
     if not args.no_roofline:
         tag = args.roofline_kernel or rl.DOMINANT_KERNEL

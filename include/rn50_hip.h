@@ -48,14 +48,16 @@ const char* rn50_last_error(void);
 /* Library version, for the binding's sanity check. */
 int rn50_version(void);
 
-/* Measurement aid (not part of the method): while enabled, the library records a
- * HIP event pair on the launch stream around every launch whose kernel tag begins
- * with `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad" (which also covers
- * "conv_wgrad_reduce"), "bn_stats", "bn_apply", "bn_bwd_reduce", "bn_bwd_apply",
- * "lars_norms", "lars_apply", ...), up to max_records launches.  rn50_profile_end waits for the last recorded event, writes
- * the elapsed milliseconds of each recorded launch in launch order to ms_out (host,
- * capacity floats), disables recording and returns the number of records.  Events
- * are the only resource created; both calls are host-side and not thread-safe. */
+/* Measurement aid (not part of the method): while enabled, every launch whose kernel
+ * tag begins with `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad" (which also
+ * covers "conv_wgrad_reduce"), "bn_stats", "bn_finalize", "bn_apply", "bn_bwd_reduce",
+ * "bn_bwd_finalize", "bn_bwd_apply", "lars_norms", "lars_apply", "fc_bwd_da") is
+ * given a HIP event pair that receives the begin and end timestamps of that dispatch
+ * on the launch stream, up to max_records launches.  rn50_profile_end waits for the
+ * last recorded launch, writes the milliseconds each recorded kernel ran, in launch
+ * order, to ms_out (host, capacity floats), disables recording and returns the number
+ * of records.  Events are the only resource created; both calls are host-side and not
+ * thread-safe. */
 int rn50_profile_begin(const char* kernel_tag, int max_records);
 int rn50_profile_end(float* ms_out, int capacity);
 

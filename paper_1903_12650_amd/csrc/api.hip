@@ -25,18 +25,16 @@ static char g_prof_tag[64] = "";
 static size_t g_prof_max = 0, g_prof_used = 0;
 static std::vector<hipEvent_t> g_prof_events;  // start/stop pairs, grown on demand, reused
 
-ScopedKernelTimer::ScopedKernelTimer(const char* tag, hipStream_t s) : stream_(s), slot_(-1) {
+KernelTimer::KernelTimer(const char* tag) {
   if (!g_prof_on || g_prof_used >= g_prof_max || strncmp(tag, g_prof_tag, strlen(g_prof_tag)) != 0) return;
-  slot_ = static_cast<long>(g_prof_used++);
-  while (g_prof_events.size() < 2 * g_prof_used) {
+  while (g_prof_events.size() < 2 * (g_prof_used + 1)) {
     hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) { slot_ = -1; --g_prof_used; return; }
+    if (hipEventCreate(&e) != hipSuccess) return;
     g_prof_events.push_back(e);
   }
-  (void)hipEventRecord(g_prof_events[2 * slot_], stream_);
-}
-ScopedKernelTimer::~ScopedKernelTimer() {
-  if (slot_ >= 0) (void)hipEventRecord(g_prof_events[2 * slot_ + 1], stream_);
+  start_ = g_prof_events[2 * g_prof_used];
+  stop_ = g_prof_events[2 * g_prof_used + 1];
+  ++g_prof_used;
 }
 }  // namespace rn50
 

@@ -509,17 +509,9 @@ static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             const float* gamma, const float* beta, const void* residual, void* y,
                             float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
                             const float* partial, int nrows, int rpp, hipStream_t s) {
-  RN50_TIMED("bn_finalize", s,
-             hipLaunchKernelGGL(bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)),
-                                dim3(256), 0, s, partial, nrows, rpp, m, d->C,
-                                finalize_wpc(nrows), d->eps,
-                                save_mean, save_rstd, rm, rv, momentum));
+  RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), d->eps, save_mean, save_rstd, rm, rv, momentum);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 768);
-  RN50_TIMED("bn_apply", s,
-             hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s,
-                                static_cast<const T*>(x), gamma, beta, save_mean, save_rstd,
-                                static_cast<const T*>(residual), static_cast<T*>(y), m, d->C,
-                                ga.tx_log2, ga.rpb, d->mode));
+  RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), m, d->C, ga.tx_log2, ga.rpb, d->mode);
 }
 
 template <typename T>
@@ -528,9 +520,7 @@ static void launch_fwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                        float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
                        float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
-  RN50_TIMED("bn_stats", s,
-             hipLaunchKernelGGL(bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
-                                static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial));
+  RN50_LAUNCH("bn_stats", bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial);
   launch_fwd_tail<T>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
                      g.nblk, g.rpb, s);
 }
@@ -542,17 +532,9 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             const float* beta, const float* mean, const float* rstd, void* dx,
                             void* dres, float* dgamma, float* dbeta, const float* partial, int nrows,
                             hipStream_t s) {
-  RN50_TIMED("bn_bwd_finalize", s,
-             hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)),
-                                dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma,
-                                dbeta));
+  RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 384);
-  RN50_TIMED("bn_bwd_apply", s,
-             hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s,
-                                static_cast<const T*>(dz), static_cast<const T*>(dz2),
-                                static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
-                                mean, rstd, dgamma, dbeta, static_cast<T*>(dx),
-                                static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode));
+  RN50_LAUNCH("bn_bwd_apply", bn_bwd_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta, mean, rstd, dgamma, dbeta, static_cast<T*>(dx), static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode);
 }
 
 template <typename T>
@@ -561,11 +543,7 @@ static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                        const float* beta, const float* mean, const float* rstd, void* dx,
                        void* dres, float* dgamma, float* dbeta, float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
-  RN50_TIMED("bn_bwd_reduce", s,
-             hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s,
-                                static_cast<const T*>(dz), static_cast<const T*>(dz2),
-                                static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta,
-                                mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial));
+  RN50_LAUNCH("bn_bwd_reduce", bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta, mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial);
   launch_bwd_tail<T>(d, g, m, dz, dz2, x, z, gamma, beta, mean, rstd, dx, dres, dgamma, dbeta, partial, g.nblk, s);
 }
 

@@ -2,6 +2,7 @@
 // conversion, 16-byte vector access, wave/block reductions).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -27,20 +28,22 @@ inline int launch_status(const char* what) {
   return RN50_OK;
 }
 
-// Records an event pair around the launches issued during its lifetime when launch
-// timing is enabled for `tag` (see rn50_profile_begin); otherwise does nothing.
-class ScopedKernelTimer {
+// Launch timing (see rn50_profile_begin): when it is enabled for `tag`, the launch below hands the runtime an
+// event pair that receives the dispatch's own begin and end timestamps, i.e. the kernel's duration on
+// the GPU without the cost of separate event packets; otherwise both events are null and the launch is
+// an ordinary one.
+class KernelTimer {
  public:
-  ScopedKernelTimer(const char* tag, hipStream_t s);
-  ~ScopedKernelTimer();
+  explicit KernelTimer(const char* tag);
+  hipEvent_t start() const { return start_; }
+  hipEvent_t stop() const { return stop_; }
  private:
-  hipStream_t stream_;
-  long slot_;
+  hipEvent_t start_ = nullptr, stop_ = nullptr;
 };
-#define RN50_TIMED(tag, stream, launch)              \
-  do {                                               \
-    ::rn50::ScopedKernelTimer timer_((tag), (stream)); \
-    launch;                                          \
+#define RN50_LAUNCH(tag, kernel, grid, block, lds, stream, ...)                                          \
+  do {                                                                                                   \
+    ::rn50::KernelTimer timer_((tag));                                                                   \
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, timer_.start(), timer_.stop(), 0, __VA_ARGS__); \
   } while (0)
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -784,7 +784,7 @@ static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid,
   constexpr int lds = 2 * (BM + BN) * kPitch;
   static std::once_flag once;
   std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE>, lds); });
-  RN50_TIMED(tag, s, hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, MODE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a));
+  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a);
 }
 template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
@@ -869,7 +869,7 @@ static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   WgradArgs b = a;
   b.tiles_per_split = a.R * a.S * a.ctiles * static_cast<int>(ceil_div(a.Cout, BMO));
   const dim3 grid(static_cast<unsigned>(b.tiles_per_split) * splits);
-  RN50_TIMED("conv_wgrad", s, hipLaunchKernelGGL((wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, b));
+  RN50_LAUNCH("conv_wgrad", (wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, b);
 }
 
 template <typename T>
@@ -886,9 +886,7 @@ static void launch_wgrad(WgradArgs a, const WgradPlan& p, float* dw, float* part
   else launch_wgrad_cfg<T, 64, 64>(a, p.splits, s);
   if (p.splits > 1) {
     const int64_t n = a.split_stride;
-    RN50_TIMED("conv_wgrad_reduce", s,
-               hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 64))),
-                                  dim3(256), 0, s, partial, p.splits, n, dw));
+    RN50_LAUNCH("conv_wgrad_reduce", splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 64))), dim3(256), 0, s, partial, p.splits, n, dw);
   }
 }
 
@@ -1060,7 +1058,8 @@ void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, flo
     hipLaunchKernelGGL(stem_unpad_dw_kernel, dim3(ceil_div(d->Cout * 147, 256)), dim3(256), 0, s, target, dw, d->Cout);
 }
 
-void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s) {
+void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s,
+             const char* tag) {
   IgemmArgs a{};
   a.act = x; a.wgt = w; a.out = y; a.partial = bn_partial;
   a.P = out_dim(d->H, d->pad, d->R, d->stride); a.Q = out_dim(d->W, d->pad, d->S, d->stride);
@@ -1070,7 +1069,7 @@ void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, flo
   a.act_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * d->H * d->W * d->Cin * esize(d->dtype));
   a.wgt_bytes = static_cast<uint32_t>(static_cast<size_t>(d->Cout) * a.Ktot * esize(d->dtype));
   a.cpt = static_cast<int>(ceil_div(d->Cin * esize(d->dtype), 128));
-  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, "conv_fwd", s); else launch_igemm<float>(a, "conv_fwd", s);
+  if (d->dtype == RN50_BF16) launch_igemm<uint16_t>(a, tag, s); else launch_igemm<float>(a, tag, s);
 }
 
 size_t dgrad_wt_bytes(const rn50_conv_desc* d) {

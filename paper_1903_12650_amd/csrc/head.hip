@@ -569,7 +569,7 @@ extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const voi
     const rn50_conv_desc wdesc{1, 1, 1, Cin, K, 1, 1, 1, 0, dtype};  // W [K][Cin] -> wT [Cin][K]
     dgrad_transpose_weights(&wdesc, W, wT, s);
     const rn50_conv_desc d = fc_dgrad_desc(N, Cin, K, dtype);
-    fwd_run(&d, dl_t, wT, da, nullptr, s);
+    fwd_run(&d, dl_t, wT, da, nullptr, s, "fc_bwd_da");
   } else {
     DISPATCH_T(dtype, {
       small_gemm<float, T, T>(dlogits, K, 1, static_cast<const T*>(W), Cin, 1, nullptr,

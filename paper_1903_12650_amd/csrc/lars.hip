@@ -222,8 +222,8 @@ void lars_arena_run(const LarsArenaSpec& sp, float* master, const float* grads, 
       a.chunk_prefix[t + 1] = a.chunk_prefix[t] + static_cast<int>(ceil_div(sp.count[t0 + t], kLarsChunk));
     }
     const int grid = a.chunk_prefix[a.num];
-    RN50_TIMED("lars_norms", s, hipLaunchKernelGGL((lars_norms_kernel<false, LarsArenaArgs>), dim3(grid), dim3(256), 0, s, a));
-    RN50_TIMED("lars_apply", s, hipLaunchKernelGGL((lars_apply_kernel<false, LarsArenaArgs>), dim3(grid), dim3(256), 0, s, a));
+    RN50_LAUNCH("lars_norms", (lars_norms_kernel<false, LarsArenaArgs>), dim3(grid), dim3(256), 0, s, a);
+    RN50_LAUNCH("lars_apply", (lars_apply_kernel<false, LarsArenaArgs>), dim3(grid), dim3(256), 0, s, a);
     partial += 2 * static_cast<size_t>(grid);
   }
 }
@@ -266,11 +266,11 @@ extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* tabl
       a.chunk_prefix[t + 1] = a.chunk_prefix[t] + static_cast<int>(ceil_div(table_host[t0 + t].n, kLarsChunk));
     const int grid = a.chunk_prefix[a.num];
     if (a.grad_bf16) {
-      RN50_TIMED("lars_norms", s, hipLaunchKernelGGL((lars_norms_kernel<true, LarsArgs>), dim3(grid), dim3(256), 0, s, a));
-      RN50_TIMED("lars_apply", s, hipLaunchKernelGGL((lars_apply_kernel<true, LarsArgs>), dim3(grid), dim3(256), 0, s, a));
+      RN50_LAUNCH("lars_norms", (lars_norms_kernel<true, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
+      RN50_LAUNCH("lars_apply", (lars_apply_kernel<true, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
     } else {
-      RN50_TIMED("lars_norms", s, hipLaunchKernelGGL((lars_norms_kernel<false, LarsArgs>), dim3(grid), dim3(256), 0, s, a));
-      RN50_TIMED("lars_apply", s, hipLaunchKernelGGL((lars_apply_kernel<false, LarsArgs>), dim3(grid), dim3(256), 0, s, a));
+      RN50_LAUNCH("lars_norms", (lars_norms_kernel<false, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
+      RN50_LAUNCH("lars_apply", (lars_apply_kernel<false, LarsArgs>), dim3(grid), dim3(256), 0, s, a);
     }
     partial += 2 * static_cast<size_t>(grid);
   }

@@ -25,7 +25,8 @@ int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d);  // most rows any til
 // bn_partial (null: none): float[3][Cout][num] = shift, sum(y - shift), sum((y - shift)^2) per tile.
 void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
                      hipStream_t s);
-void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s);
+void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s,
+             const char* tag = "conv_fwd");
 // The BN layer (with ReLU, no residual) whose output gradient a data gradient produces: x is that
 // layer's input [N*H*W][Cin]; partial receives float[2][Cin][num] = sum(g), sum(g * xhat) per tile.
 struct BnBwdSums {

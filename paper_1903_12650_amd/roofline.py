@@ -5,19 +5,31 @@ Per unit of work (elements are activation elements of the BN's tensor, bf16 = 2 
   conv_fwd / conv_dgrad  2*M*N*K flop;  bytes = es*(|in| + |out| + |w|), a 1x1 stride-2 conv only
                          needs (and is only charged) every other row and column of its input
   conv_wgrad             2*M*N*K flop;  bytes = es*(|x| + |dy|) + 4*|dw|
-  bn_stats               es bytes/element (read x)
   bn_apply               2*es bytes/element (read x, write y) + es for the residual read (mode 2)
-  bn_bwd_reduce          2*es bytes/element (read dz, x)
+  bn_bwd_reduce          2*es bytes/element (read dz, x); launched only for the layers whose sums are not
+                         taken in the output stage of the data gradient that produces dz (the stem, the
+                         residual-add layers and the projection shortcuts)
   bn_bwd_apply           3*es bytes/element (read dz, x, write dx) + es for dresidual (mode 2)
   lars_norms             8 bytes/parameter (read w, g)
   lars_apply             20 bytes/parameter (read w, g, v; write w, v) + 2 for the bf16 copy
+The forward BN statistics and the other backward sums are part of conv_fwd / conv_dgrad (no bytes of
+their own: they are taken from the output tile before it leaves the workgroup).
 Peaks (MI355X, published): HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s; fp32 MFMA 157.3 TFLOP/s.
 """
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
-DOMINANT_KERNEL = "bn_bwd_apply"
+DOMINANT_KERNEL = "conv_fwd"   # largest share of the step's kernel time (rocprofv3 summary under profiles/)
+
+# HBM bytes per launch (fetch + write) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs summarized in
+# profiles/resnet50_step_batch40_bf16_hbm_traffic.txt (batch 40, bf16), already scaled by the calibration
+# copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
+# dirty in L2 are written back during later kernels.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
+    "conv_fwd": 40.34e6, "conv_dgrad": 45.29e6, "conv_wgrad": 52.16e6, "bn_apply": 42.03e6,
+    "bn_bwd_reduce": 112.55e6, "bn_bwd_apply": 75.40e6, "lars_norms": 204.55e6, "lars_apply": 562.44e6,
+}
 
 
 def layers(plan):
@@ -72,11 +84,12 @@ def per_launch_cost(tag, plan):
         return [conv_cost(l) for l in _bwd_order(L) if l["Cin"] != 3]
     if tag == "conv_wgrad":
         return [conv_cost(l, True) for l in _bwd_order(L)]
-    per_elem = {"bn_stats": (es, 0), "bn_apply": (2 * es, es), "bn_bwd_reduce": (2 * es, 0),
-                "bn_bwd_apply": (3 * es, es)}
+    per_elem = {"bn_apply": (2 * es, es), "bn_bwd_reduce": (2 * es, 0), "bn_bwd_apply": (3 * es, es)}
     if tag in per_elem:
         base, extra = per_elem[tag]
-        seq = _fwd_order(L, L) if tag in ("bn_stats", "bn_apply") else _bwd_order(L)
+        seq = _fwd_order(L, L) if tag == "bn_apply" else _bwd_order(L)
+        if tag == "bn_bwd_reduce":  # the BN+ReLU layers inside a block get their sums from the data gradient above
+            seq = [l for l in seq if l["mode"] != 1 or l["Cin"] == 3]
         return [(0.0, elems(l) * (base + (extra if l["mode"] == 2 else 0))) for l in seq]
     n_params = sum(plan.sizes)
     if tag == "lars_norms":
@@ -141,5 +154,6 @@ def roofline(tag, plan, durations_ms, steps):
         rec.update(bound="hbm", achieved=a, peak=HBM_PEAK_GBS, unit="GB/s", frac=a / HBM_PEAK_GBS)
     rec["algorithmic_bytes_per_launch"] = nbytes / len(durations_ms)
     rec["algorithmic_flops_per_launch"] = flops / len(durations_ms)
-    rec["traffic"] = None
+    t = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(tag) if (plan.dtype == 1 and plan.cfg.N == 40) else None
+    rec["traffic"] = t
     return rec
