@@ -51,6 +51,14 @@ struct rn50_plan {
   size_t bn_scratch_bytes = 0, fc_scratch_bytes = 0;
   std::vector<rn50::TransposeEntry> transposes;
   rn50::LarsArenaSpec lars;
+  // Second stream for the work that is off the step's critical path (weight gradients, the weight
+  // transposition), with the events that order it against the caller's stream.  Created at the first
+  // step (default priority), destroyed with the plan.
+  static constexpr int kDyRing = 8;  // two blocks of at most four units
+  size_t dy_ring[kDyRing] = {0, 0, 0, 0, 0, 0, 0, 0};
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_wt = nullptr;
+  std::vector<hipEvent_t> ev_dy, ev_wg;  // per block: its dy tensors are ready / its weight gradients are done
 };
 
 using namespace rn50;
@@ -165,6 +173,7 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->dlogits = bump(&top, static_cast<size_t>(N) * cfg->classes * sizeof(float));
   p->row_loss = bump(&top, static_cast<size_t>(N) * sizeof(float));
   for (int i = 0; i < 5; ++i) p->g[i] = bump(&top, max_act * es);
+  for (int i = 0; i < rn50_plan::kDyRing; ++i) p->dy_ring[i] = bump(&top, max_act * es);
   (void)max_wT;
   p->wT = bump(&top, static_cast<size_t>(p->arena_elems) * es);  // transposed copy of every conv weight
   for (const Unit& u : p->units)
@@ -188,7 +197,37 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   return RN50_OK;
 }
 
-extern "C" void resnet_plan_destroy(rn50_plan* plan) { delete plan; }
+extern "C" void resnet_plan_destroy(rn50_plan* plan) {
+  if (!plan) return;
+  if (plan->side) {
+    (void)hipStreamSynchronize(plan->side);
+    (void)hipStreamDestroy(plan->side);
+  }
+  if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
+  if (plan->ev_wt) (void)hipEventDestroy(plan->ev_wt);
+  for (hipEvent_t e : plan->ev_dy) (void)hipEventDestroy(e);
+  for (hipEvent_t e : plan->ev_wg) (void)hipEventDestroy(e);
+  delete plan;
+}
+
+namespace {
+// The side stream and its events (host-side handles only; no device memory).
+int ensure_side_stream(rn50_plan* p) {
+  if (p->side) return RN50_OK;
+  auto ok = [](hipError_t e) { return e == hipSuccess; };
+  bool good = ok(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking)) &&
+              ok(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming)) &&
+              ok(hipEventCreateWithFlags(&p->ev_wt, hipEventDisableTiming));
+  for (size_t i = 0; good && i < p->blocks.size() + 1; ++i) {  // the blocks and the stem
+    hipEvent_t a = nullptr, b = nullptr;
+    good = ok(hipEventCreateWithFlags(&a, hipEventDisableTiming)) && ok(hipEventCreateWithFlags(&b, hipEventDisableTiming));
+    if (a) p->ev_dy.push_back(a);
+    if (b) p->ev_wg.push_back(b);
+  }
+  if (!good) return fail(RN50_ERR_HIP, "resnet_step: could not create the side stream or its events");
+  return RN50_OK;
+}
+}  // namespace
 extern "C" int resnet_plan_num_tensors(const rn50_plan* plan) {
   return plan ? static_cast<int>(plan->tensors.size()) : 0;
 }
@@ -240,6 +279,16 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   RN50_REQUIRE(cfg.dtype == RN50_F32 || master, RN50_ERR_INVALID,
                "resnet_step: BF16 mode reads BN gamma/beta and the FC bias from the float master arena");
 
+  // The side stream starts after whatever the caller's stream holds so far (the previous step's update
+  // of the model weights, for one) and transposes the weights for the data gradients while the forward
+  // pass runs: [Cout][R][S][Cin] -> [Cin][R][S][Cout], every convolution in one launch.
+  STEP_TRY(ensure_side_stream(plan));
+  hipStream_t side = plan->side;
+  (void)hipEventRecord(plan->ev_fork, s);
+  (void)hipStreamWaitEvent(side, plan->ev_fork, 0);
+  transpose_batch_run(plan->transposes, dt, model, ws + plan->wT, side);
+  (void)hipEventRecord(plan->ev_wt, side);
+
   // --------------------------------------------------------------- forward
   Unit& u0 = plan->units[0];
   stem_pad_input(&u0.conv, images, ws + plan->xp, s);
@@ -283,20 +332,43 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   // -------------------------------------------------------------- backward
   STEP_TRY(fc_bwd(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, W(fcw), F(plan->dlogits), ws + plan->davg,
                   G(fcw), G(fcb), ws + plan->fc_scratch, plan->fc_scratch_bytes, s));
-  // every convolution's weights in [Cin][R][S][Cout] form for the data gradients: one launch
-  transpose_batch_run(plan->transposes, dt, model, ws + plan->wT, s);
+  (void)hipStreamWaitEvent(s, plan->ev_wt, 0);  // the transposed weights
   unsigned char* g[5];
   for (int i = 0; i < 5; ++i) g[i] = ws + plan->g[i];
   // g[0], g[1]: the two summands of the gradient w.r.t. the current block output (g[1] may be unused)
   STEP_TRY(avgpool_bwd(cfg.N, HW, plan->fc_in, dt, ws + plan->davg, g[0], s));
   bool have2 = false;
   int dgrad_sums_rows = 0;
-  // BN backward + wgrad + dgrad of one unit.  dz (+dz2) -> dy in `dy`; dgrad into `dx` (skipped if null).
+  // BN backward + wgrad + dgrad of one unit.  dz (+dz2) -> dy; dgrad into `dx` (skipped if null).
   // `sums_ready`: the data gradient that produced dz already left this BN layer's sums in bn_ws.
   // `below`: the unit whose BN output is this unit's only input use (dx is its complete dz): the data
   // gradient then leaves that layer's sums in bn_ws.
-  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dy, void* dres, void* dx,
+  // The weight gradients are off the critical path (nothing in the backward pass reads them): they run
+  // on the side stream, a block's worth at a time (one event each way per block: an event is a packet
+  // the stream has to drain for).  dy lives in a ring of buffers, two blocks deep, so the next block's BN
+  // backward need not wait; a slot is rewritten only after the weight gradient that read it.
+  struct PendingWgrad {
+    Unit* u;
+    const void* in;
+    void* dy;
+  };
+  PendingWgrad pending[4];
+  int npending = 0, seq = 0, blk = 0;  // units / blocks processed so far in this backward pass
+  auto block_begin = [&]() {
+    if (blk >= 2) (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 2], 0);
+  };
+  auto block_end = [&]() {
+    (void)hipEventRecord(plan->ev_dy[blk], s);
+    (void)hipStreamWaitEvent(side, plan->ev_dy[blk], 0);
+    for (int i = 0; i < npending; ++i)
+      wgrad_run(&pending[i].u->conv, pending[i].in, pending[i].dy, G(pending[i].u->iw), ws + plan->wgrad_scratch, side);
+    (void)hipEventRecord(plan->ev_wg[blk], side);
+    npending = 0;
+    ++blk;
+  };
+  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, void* dx,
                       bool sums_ready, Unit* below) -> int {
+    void* dy = ws + plan->dy_ring[seq % rn50_plan::kDyRing];
     if (sums_ready) {
       bn_bwd_from_partials(&u.bn, dz, ws + u.y, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), sums,
                            dgrad_sums_rows, dy, G(u.ig), G(u.ib), s);
@@ -305,7 +377,7 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
       STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, z, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
                            G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
     }
-    wgrad_run(&u.conv, in, dy, G(u.iw), ws + plan->wgrad_scratch, s);
+    pending[npending++] = PendingWgrad{&u, in, dy};
     if (dx) {
       BnBwdSums fuse{};
       if (below) {
@@ -314,6 +386,7 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
       }
       dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, below ? &fuse : nullptr, s);
     }
+    ++seq;
     return RN50_OK;
   };
   for (int bi = static_cast<int>(plan->blocks.size()) - 1; bi >= 0; --bi) {
@@ -321,18 +394,23 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
     const void* block_in = bi == 0 ? static_cast<const void*>(ws + plan->pool)
                                    : static_cast<const void*>(ws + plan->units[plan->blocks[bi - 1].u3].z);
-    STEP_TRY(unit_bwd(u3, ws + u2.z, g[0], have2 ? g[1] : nullptr, g[2], g[3], g[4], false, &u2));
-    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, g[2], nullptr, g[4], true, &u1));
-    STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, g[2], nullptr, g[0], true, nullptr));
+    block_begin();
+    STEP_TRY(unit_bwd(u3, ws + u2.z, g[0], have2 ? g[1] : nullptr, g[3], g[4], false, &u2));
+    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, nullptr, g[4], true, &u1));
+    STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, nullptr, g[0], true, nullptr));
     if (b.up >= 0) {
-      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, g[2], nullptr, g[1], false, nullptr));
+      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, nullptr, g[1], false, nullptr));
     } else {
       unsigned char* t = g[1]; g[1] = g[3]; g[3] = t;
     }
+    block_end();
     have2 = true;
   }
   STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, g[0], g[1], g[2], s));
-  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, g[4], nullptr, nullptr, false, nullptr));
+  block_begin();
+  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, nullptr, nullptr, false, nullptr));
+  block_end();
+  (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 1], 0);  // join: the side stream runs in order
 
   // ------------------------------------------------------------------ LARS
   if (update)
