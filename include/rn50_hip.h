@@ -56,9 +56,12 @@ int rn50_version(void);
  * on the launch stream, up to max_records launches.  rn50_profile_end waits for the
  * last recorded launch, writes the milliseconds each recorded kernel ran, in launch
  * order, to ms_out (host, capacity floats), disables recording and returns the number
- * of records.  Events are the only resource created; both calls are host-side and not
- * thread-safe. */
+ * of records.  A timed launch costs a few microseconds more than a plain one, so a caller
+ * timing whole steps can sample: rn50_profile_pause(1) suspends recording (launches are
+ * plain again), rn50_profile_pause(0) resumes it.  Events are the only resource created;
+ * all three calls are host-side and not thread-safe. */
 int rn50_profile_begin(const char* kernel_tag, int max_records);
+void rn50_profile_pause(int paused);
 int rn50_profile_end(float* ms_out, int capacity);
 
 /* ------------------------------------------------------------------ convolution
@@ -111,20 +114,23 @@ size_t bn_relu_bwd_workspace_bytes(const rn50_bn_desc* d);
  * save_mean, save_rstd: device float[C] (save_* are outputs kept for backward).
  * running_mean / running_var: device float[C] or NULL; when given they are
  * updated in place as running = momentum*running + (1-momentum)*batch statistic
- * (biased variance). */
+ * (biased variance).  relu_mask: device uint8 [m*C/V] or NULL, V = 8 (bf16) / 4 (f32)
+ * elements per 16-byte vector; when given (modes 1, 2) it receives, per vector, bit j =
+ * [stored y_j > 0]: the ReLU decisions, for a backward pass that then need not read y. */
 int bn_relu_fwd(const rn50_bn_desc* d, const void* x, const float* gamma, const float* beta,
-                const void* residual, void* y, float* save_mean, float* save_rstd,
-                float* running_mean, float* running_var, float momentum, void* workspace,
-                size_t workspace_bytes, void* stream);
+                const void* residual, void* y, uint8_t* relu_mask, float* save_mean,
+                float* save_rstd, float* running_mean, float* running_var, float momentum,
+                void* workspace, size_t workspace_bytes, void* stream);
 /* Backward of the above.  dz (and optional dz2, summed with it: the two branches
  * that consume a block's output), x: device [m,C] dtype.  The ReLU mask is
- * z > 0, taken from z (the forward output) when z != NULL; in mode 1, z may be
- * NULL and the mask is recomputed from x, gamma, beta (required then).  Mode 2
- * needs z.   g = (dz+dz2)*mask;  dbeta = sum_m g;  dgamma = sum_m g*xhat;
+ * z > 0, taken from relu_mask (the bits bn_relu_fwd recorded) when it is given, else
+ * from z (the forward output) when z != NULL; in mode 1 both may be NULL and the mask
+ * is recomputed from x, gamma, beta (required then).  Mode 2 needs relu_mask or z.
+ * g = (dz+dz2)*mask;  dbeta = sum_m g;  dgamma = sum_m g*xhat;
  * dx = gamma*rstd*(g - dbeta/m - xhat*dgamma/m);  mode 2: dresidual = g.
  * dx, dresidual: device [m,C] dtype; dgamma, dbeta: device float[C]. */
 int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const void* x,
-                const void* z, const float* gamma, const float* beta, const float* save_mean,
+                const void* z, const uint8_t* relu_mask, const float* gamma, const float* beta, const float* save_mean,
                 const float* save_rstd, void* dx, void* dresidual, float* dgamma, float* dbeta,
                 void* workspace, size_t workspace_bytes, void* stream);
 
@@ -148,8 +154,9 @@ int conv_fwd_bn_sums(const rn50_conv_desc* d, const void* x, const void* w, void
                      size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream);
 int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* x,
                           const float* sums, const float* gamma, const float* beta,
-                          const void* residual, void* y, float* save_mean, float* save_rstd,
-                          float* running_mean, float* running_var, float momentum, void* stream);
+                          const void* residual, void* y, uint8_t* relu_mask, float* save_mean,
+                          float* save_rstd, float* running_mean, float* running_var, float momentum,
+                          void* stream);
 int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
                        const void* bn_x, const float* gamma, const float* beta,
                        const float* save_mean, const float* save_rstd, float* sums,

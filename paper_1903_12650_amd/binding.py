@@ -11,10 +11,10 @@ import torch
 
 __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd",
            "bn_relu_bwd", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "fc_fwd", "fc_bwd",
-           "xent_fwd_bwd", "lars_update", "LarsTable", "profile_begin", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
+           "xent_fwd_bwd", "lars_update", "LarsTable", "profile_begin", "profile_pause", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
-           "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums"]
+           "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums"]
 
 F32, BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -172,22 +172,28 @@ def bn_relu_bwd_workspace_bytes(desc):
     return raw.bn_relu_bwd_workspace_bytes(ctypes.byref(desc))
 
 
+def relu_mask_like(x):
+    V = 8 if x.dtype == torch.bfloat16 else 4
+    return torch.empty(x.numel() // V, dtype=torch.uint8, device=x.device)
+
+
 def bn_relu_fwd(x, gamma, beta, residual=None, eps=1e-5, mode=1, running_mean=None, running_var=None,
-                momentum=0.9, workspace=None):
-    """Returns y, save_mean, save_rstd."""
+                momentum=0.9, workspace=None, relu_mask=None):
+    """Returns y, save_mean, save_rstd.  relu_mask: optional uint8 tensor (see relu_mask_like) to fill."""
     d = _bn_desc(x, eps, mode)
     y = torch.empty_like(x)
     mean = torch.empty(d.C, dtype=torch.float32, device=x.device)
     rstd = torch.empty(d.C, dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace = _ws(bn_relu_fwd_workspace_bytes(d), x.device)
-    _check(raw.bn_relu_fwd(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y), _ptr(mean),
+    _check(raw.bn_relu_fwd(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y),
+                           _ptr(relu_mask), _ptr(mean),
                            _ptr(rstd), _ptr(running_mean), _ptr(running_var), ctypes.c_float(momentum),
                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
     return y, mean, rstd
 
 
-def bn_relu_bwd(dz, x, z, gamma, mean, rstd, mode=1, beta=None, dz2=None, eps=1e-5, workspace=None):
+def bn_relu_bwd(dz, x, z, gamma, mean, rstd, mode=1, beta=None, dz2=None, eps=1e-5, workspace=None, relu_mask=None):
     """Returns dx, dresidual (None unless mode 2), dgamma, dbeta."""
     d = _bn_desc(x, eps, mode)
     dx = torch.empty_like(x)
@@ -196,7 +202,8 @@ def bn_relu_bwd(dz, x, z, gamma, mean, rstd, mode=1, beta=None, dz2=None, eps=1e
     dbeta = torch.empty(d.C, dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace = _ws(bn_relu_bwd_workspace_bytes(d), x.device)
-    _check(raw.bn_relu_bwd(ctypes.byref(d), _ptr(dz), _ptr(dz2), _ptr(x), _ptr(z), _ptr(gamma), _ptr(beta),
+    _check(raw.bn_relu_bwd(ctypes.byref(d), _ptr(dz), _ptr(dz2), _ptr(x), _ptr(z), _ptr(relu_mask), _ptr(gamma),
+                           _ptr(beta),
                            _ptr(mean), _ptr(rstd), _ptr(dx), _ptr(dres), _ptr(dgamma), _ptr(dbeta),
                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
     return dx, dres, dgamma, dbeta
@@ -224,7 +231,7 @@ def conv_fwd_bn_sums(x, w, stride, pad, y=None, workspace=None, sums=None):
 
 
 def bn_relu_fwd_from_sums(x, handle, gamma, beta, residual=None, eps=1e-5, mode=1, running_mean=None,
-                          running_var=None, momentum=0.9):
+                          running_var=None, momentum=0.9, relu_mask=None):
     """Returns y, save_mean, save_rstd."""
     producer, sums = handle
     d = _bn_desc(x, eps, mode)
@@ -232,7 +239,8 @@ def bn_relu_fwd_from_sums(x, handle, gamma, beta, residual=None, eps=1e-5, mode=
     mean = torch.empty(d.C, dtype=torch.float32, device=x.device)
     rstd = torch.empty(d.C, dtype=torch.float32, device=x.device)
     _check(raw.bn_relu_fwd_from_sums(ctypes.byref(d), ctypes.byref(producer), _ptr(x), _ptr(sums), _ptr(gamma),
-                                     _ptr(beta), _ptr(residual), _ptr(y), _ptr(mean), _ptr(rstd), _ptr(running_mean),
+                                     _ptr(beta), _ptr(residual), _ptr(y), _ptr(relu_mask), _ptr(mean), _ptr(rstd),
+                                     _ptr(running_mean),
                                      _ptr(running_var), ctypes.c_float(momentum), _stream()))
     return y, mean, rstd
 
@@ -409,6 +417,10 @@ def resnet_step(plan, images, labels, master, velocity, grads, model, lr, worksp
 def profile_begin(kernel_tag, max_records):
     _check(raw.rn50_profile_begin(kernel_tag.encode(), int(max_records)))
     profile_begin._cap = int(max_records)
+
+
+def profile_pause(paused):
+    raw.rn50_profile_pause(ctypes.c_int(1 if paused else 0))
 
 
 def profile_end():

@@ -23,10 +23,11 @@ void clear_error() { g_err[0] = 0; }
 static bool g_prof_on = false;
 static char g_prof_tag[64] = "";
 static size_t g_prof_max = 0, g_prof_used = 0;
+static bool g_prof_paused = false;
 static std::vector<hipEvent_t> g_prof_events;  // start/stop pairs, grown on demand, reused
 
 KernelTimer::KernelTimer(const char* tag) {
-  if (!g_prof_on || g_prof_used >= g_prof_max || strncmp(tag, g_prof_tag, strlen(g_prof_tag)) != 0) return;
+  if (!g_prof_on || g_prof_paused || g_prof_used >= g_prof_max || strncmp(tag, g_prof_tag, strlen(g_prof_tag)) != 0) return;
   while (g_prof_events.size() < 2 * (g_prof_used + 1)) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return;
@@ -46,8 +47,10 @@ extern "C" int rn50_profile_begin(const char* kernel_tag, int max_records) {
   rn50::g_prof_max = static_cast<size_t>(max_records);
   rn50::g_prof_used = 0;
   rn50::g_prof_on = true;
+  rn50::g_prof_paused = false;
   return RN50_OK;
 }
+extern "C" void rn50_profile_pause(int paused) { rn50::g_prof_paused = paused != 0; }
 extern "C" int rn50_profile_end(float* ms_out, int capacity) {
   using namespace rn50;
   g_prof_on = false;

@@ -237,8 +237,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
                                                        const float* __restrict__ mean,
                                                        const float* __restrict__ rstd,
                                                        const T* __restrict__ residual,
-                                                       T* __restrict__ y, int64_t m, int C,
-                                                       int tx_log2, int rpb, int mode) {
+                                                       T* __restrict__ y, uint8_t* __restrict__ relu_mask,
+                                                       int64_t m, int C, int tx_log2, int rpb, int mode) {
   constexpr int V = Elem<T>::VEC;
   const int TX = 1 << tx_log2, TY = 256 >> tx_log2;
   const int tcol = threadIdx.x & (TX - 1), trow = threadIdx.x >> tx_log2;
@@ -284,6 +284,14 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
         Vec16 o;
         Elem<T>::pack(f, o);
         store16(y + off[u], o);
+        if (relu_mask) {  // bit j: stored output j is positive; one byte per 16-byte vector
+          float zf[V];
+          Elem<T>::unpack(o, zf);
+          uint32_t bits = 0;
+#pragma unroll
+          for (int j = 0; j < V; ++j) bits |= (zf[j] > 0.f ? 1u : 0u) << j;
+          relu_mask[off[u] / V] = static_cast<uint8_t>(bits);
+        }
       }
     }
   }
@@ -293,11 +301,13 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
 // The operands of kBnRows rows, loaded before any is used.
 struct BwdRows {
   Vec16 x[kBnRows], dz[kBnRows], dz2[kBnRows], z[kBnRows];
+  uint32_t zbits[kBnRows];  // when the forward pass recorded the ReLU decision bits instead
   int64_t off[kBnRows];
 };
 template <typename T>
 __device__ __forceinline__ void load_bwd_rows(BwdRows& b, const T* dz, const T* dz2, const T* x, const T* z,
-                                              int64_t r, int64_t r1, int TY, int C, int col) {
+                                              const uint8_t* zmask, int64_t r, int64_t r1, int TY, int C,
+                                              int col) {
   constexpr int V = Elem<T>::VEC;
 #pragma unroll
   for (int u = 0; u < kBnRows; ++u) {
@@ -309,7 +319,10 @@ __device__ __forceinline__ void load_bwd_rows(BwdRows& b, const T* dz, const T* 
 #pragma unroll
     for (int u = 0; u < kBnRows; ++u) b.dz2[u] = load16(dz2 + b.off[u]);
   }
-  if (z) {
+  if (zmask) {
+#pragma unroll
+    for (int u = 0; u < kBnRows; ++u) b.zbits[u] = zmask[b.off[u] / V];
+  } else if (z) {
 #pragma unroll
     for (int u = 0; u < kBnRows; ++u) b.z[u] = load16(z + b.off[u]);
   }
@@ -317,9 +330,9 @@ __device__ __forceinline__ void load_bwd_rows(BwdRows& b, const T* dz, const T* 
 
 // g = (dz + dz2) * mask for one 16-byte vector.
 template <typename T>
-__device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2, const Vec16& vz, bool has_dz2,
-                                            bool has_z, const float* xf, const float* scale, const float* bias,
-                                            int mode, float* g) {
+__device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2, const Vec16& vz, uint32_t zbits,
+                                            bool has_dz2, bool has_z, bool has_zbits, const float* xf,
+                                            const float* scale, const float* bias, int mode, float* g) {
   constexpr int V = Elem<T>::VEC;
   Elem<T>::unpack(vdz, g);
   if (has_dz2) {
@@ -329,7 +342,10 @@ __device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2,
     for (int j = 0; j < V; ++j) g[j] += g2[j];
   }
   if (mode >= 1) {
-    if (has_z) {
+    if (has_zbits) {
+#pragma unroll
+      for (int j = 0; j < V; ++j) g[j] = (zbits >> j) & 1u ? g[j] : 0.f;
+    } else if (has_z) {
       float zf[V];
       Elem<T>::unpack(vz, zf);
 #pragma unroll
@@ -344,7 +360,8 @@ __device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2,
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const T* __restrict__ dz, const T* __restrict__ dz2, const T* __restrict__ x,
-    const T* __restrict__ z, const float* __restrict__ gamma, const float* __restrict__ beta,
+    const T* __restrict__ z, const uint8_t* __restrict__ zmask, const float* __restrict__ gamma,
+    const float* __restrict__ beta,
     const float* __restrict__ mean, const float* __restrict__ rstd, int64_t m, int C, int tx_log2,
     int rpb, int mode, float* __restrict__ partial) {
   constexpr int V = Elem<T>::VEC;
@@ -369,13 +386,14 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const int64_t r1 = min(r0 + rpb, m);
     for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
       BwdRows b;
-      load_bwd_rows<T>(b, dz, dz2, x, z, r, r1, TY, C, col);
+      load_bwd_rows<T>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
 #pragma unroll
       for (int u = 0; u < kBnRows; ++u) {
         if (r + u * TY < r1) {
           float xf[V], g[V];
           Elem<T>::unpack(b.x[u], xf);
-          masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], dz2 != nullptr, z != nullptr, xf, scale, bias, mode, g);
+          masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], b.zbits[u], dz2 != nullptr, z != nullptr, zmask != nullptr, xf, scale, bias,
+                         mode, g);
 #pragma unroll
           for (int j = 0; j < V; ++j) {
             acc[j] += g[j];
@@ -436,7 +454,8 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     const T* __restrict__ dz, const T* __restrict__ dz2, const T* __restrict__ x,
-    const T* __restrict__ z, const float* __restrict__ gamma, const float* __restrict__ beta,
+    const T* __restrict__ z, const uint8_t* __restrict__ zmask, const float* __restrict__ gamma,
+    const float* __restrict__ beta,
     const float* __restrict__ mean, const float* __restrict__ rstd,
     const float* __restrict__ dgamma, const float* __restrict__ dbeta, T* __restrict__ dx,
     T* __restrict__ dres, int64_t m, int C, int tx_log2, int rpb, int mode) {
@@ -460,13 +479,14 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
   const int64_t r1 = min(r0 + rpb, m);
   for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
     BwdRows b;
-    load_bwd_rows<T>(b, dz, dz2, x, z, r, r1, TY, C, col);
+    load_bwd_rows<T>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
 #pragma unroll
     for (int u = 0; u < kBnRows; ++u) {
       if (r + u * TY < r1) {
         float xf[V], g[V], o[V];
         Elem<T>::unpack(b.x[u], xf);
-        masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], dz2 != nullptr, z != nullptr, xf, scale, bias, mode, g);
+        masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], b.zbits[u], dz2 != nullptr, z != nullptr, zmask != nullptr, xf, scale, bias,
+                         mode, g);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
           const float xh = fmaf(xf[j], rs[j], nmr[j]);
@@ -507,59 +527,61 @@ static size_t bn_ws_bytes(const rn50_bn_desc* d) {
 template <typename T>
 static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* x,
                             const float* gamma, const float* beta, const void* residual, void* y,
-                            float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
-                            const float* partial, int nrows, int rpp, hipStream_t s) {
+                            uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
+                            float momentum, const float* partial, int nrows, int rpp, hipStream_t s) {
   RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), d->eps, save_mean, save_rstd, rm, rv, momentum);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 768);
-  RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+  RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, ga.tx_log2, ga.rpb, d->mode);
 }
 
 template <typename T>
 static void launch_fwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* x,
                        const float* gamma, const float* beta, const void* residual, void* y,
-                       float* save_mean, float* save_rstd, float* rm, float* rv, float momentum,
-                       float* partial, hipStream_t s) {
+                       uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
+                       float momentum, float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
   RN50_LAUNCH("bn_stats", bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial);
-  launch_fwd_tail<T>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
-                     g.nblk, g.rpb, s);
+  launch_fwd_tail<T>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
+                     partial, g.nblk, g.rpb, s);
 }
 
 // finalize + apply from partial sums rows [sum g, sum g*xhat]
 template <typename T>
 static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* dz,
-                            const void* dz2, const void* x, const void* z, const float* gamma,
-                            const float* beta, const float* mean, const float* rstd, void* dx,
-                            void* dres, float* dgamma, float* dbeta, const float* partial, int nrows,
-                            hipStream_t s) {
+                            const void* dz2, const void* x, const void* z, const uint8_t* zmask,
+                            const float* gamma, const float* beta, const float* mean, const float* rstd,
+                            void* dx, void* dres, float* dgamma, float* dbeta, const float* partial,
+                            int nrows, hipStream_t s) {
   RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 384);
-  RN50_LAUNCH("bn_bwd_apply", bn_bwd_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta, mean, rstd, dgamma, dbeta, static_cast<T*>(dx), static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+  RN50_LAUNCH("bn_bwd_apply", bn_bwd_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, dgamma, dbeta, static_cast<T*>(dx), static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode);
 }
 
 template <typename T>
 static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* dz,
-                       const void* dz2, const void* x, const void* z, const float* gamma,
-                       const float* beta, const float* mean, const float* rstd, void* dx,
+                       const void* dz2, const void* x, const void* z, const uint8_t* zmask,
+                       const float* gamma, const float* beta, const float* mean, const float* rstd, void* dx,
                        void* dres, float* dgamma, float* dbeta, float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
-  RN50_LAUNCH("bn_bwd_reduce", bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), gamma, beta, mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial);
-  launch_bwd_tail<T>(d, g, m, dz, dz2, x, z, gamma, beta, mean, rstd, dx, dres, dgamma, dbeta, partial, g.nblk, s);
+  RN50_LAUNCH("bn_bwd_reduce", bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial);
+  launch_bwd_tail<T>(d, g, m, dz, dz2, x, z, zmask, gamma, beta, mean, rstd, dx, dres, dgamma, dbeta, partial,
+                     g.nblk, s);
 }
 
 // Entry points for the whole-step driver and the fused C-ABI calls: the sums come from the output stage
 // of the convolution that produced x (forward) or dz (backward).
 void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* partial, int nrows, int rpp,
-                          const float* gamma, const float* beta, const void* residual, void* y, float* save_mean,
-                          float* save_rstd, float* rm, float* rv, float momentum, hipStream_t s) {
+                          const float* gamma, const float* beta, const void* residual, void* y,
+                          uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
+                          float momentum, hipStream_t s) {
   const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
-    launch_fwd_tail<uint16_t>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
-                              nrows, rpp, s);
+    launch_fwd_tail<uint16_t>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv,
+                              momentum, partial, nrows, rpp, s);
   else
-    launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, rm, rv, momentum, partial,
-                           nrows, rpp, s);
+    launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
+                           partial, nrows, rpp, s);
 }
 void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const float* gamma,
                           const float* beta, const float* mean, const float* rstd, const float* partial, int nrows,
@@ -567,10 +589,10 @@ void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, 
   const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
-    launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
+    launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
                               partial, nrows, s);
   else
-    launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
+    launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
                            partial, nrows, s);
 }
 
@@ -587,8 +609,8 @@ extern "C" size_t bn_relu_bwd_workspace_bytes(const rn50_bn_desc* d) {
 }
 
 extern "C" int bn_relu_fwd(const rn50_bn_desc* d, const void* x, const float* gamma,
-                           const float* beta, const void* residual, void* y, float* save_mean,
-                           float* save_rstd, float* running_mean, float* running_var,
+                           const float* beta, const void* residual, void* y, uint8_t* relu_mask,
+                           float* save_mean, float* save_rstd, float* running_mean, float* running_var,
                            float momentum, void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   if (int rc = check_desc(d, "bn_relu_fwd")) return rc;
@@ -605,16 +627,16 @@ extern "C" int bn_relu_fwd(const rn50_bn_desc* d, const void* x, const float* ga
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (d->dtype == RN50_BF16)
-    launch_fwd<uint16_t>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, running_mean,
+    launch_fwd<uint16_t>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, running_mean,
                          running_var, momentum, static_cast<float*>(workspace), s);
   else
-    launch_fwd<float>(d, g, m, x, gamma, beta, residual, y, save_mean, save_rstd, running_mean,
+    launch_fwd<float>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, running_mean,
                       running_var, momentum, static_cast<float*>(workspace), s);
   return launch_status("bn_relu_fwd");
 }
 
 extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const void* x,
-                           const void* z, const float* gamma, const float* beta,
+                           const void* z, const uint8_t* relu_mask, const float* gamma, const float* beta,
                            const float* save_mean, const float* save_rstd, void* dx,
                            void* dresidual, float* dgamma, float* dbeta, void* workspace,
                            size_t workspace_bytes, void* stream) {
@@ -622,10 +644,10 @@ extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz
   if (int rc = check_desc(d, "bn_relu_bwd")) return rc;
   RN50_REQUIRE(dz && x && gamma && save_mean && save_rstd && dx && dgamma && dbeta && workspace,
                RN50_ERR_INVALID, "bn_relu_bwd: null pointer");
-  RN50_REQUIRE(d->mode != 2 || (z && dresidual), RN50_ERR_INVALID,
-               "bn_relu_bwd: mode 2 needs z and dresidual");
-  RN50_REQUIRE(d->mode != 1 || z || beta, RN50_ERR_INVALID,
-               "bn_relu_bwd: mode 1 needs z, or beta to recompute the ReLU mask");
+  RN50_REQUIRE(d->mode != 2 || ((z || relu_mask) && dresidual), RN50_ERR_INVALID,
+               "bn_relu_bwd: mode 2 needs z or relu_mask, and dresidual");
+  RN50_REQUIRE(d->mode != 1 || z || relu_mask || beta, RN50_ERR_INVALID,
+               "bn_relu_bwd: mode 1 needs z, relu_mask, or beta to recompute the ReLU mask");
   RN50_REQUIRE(aligned16(dz) && aligned16(dz2) && aligned16(x) && aligned16(z) && aligned16(dx) &&
                    aligned16(dresidual) && aligned16(workspace),
                RN50_ERR_ALIGN, "bn_relu_bwd: pointer not 16-byte aligned");
@@ -635,10 +657,10 @@ extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (d->dtype == RN50_BF16)
-    launch_bwd<uint16_t>(d, g, m, dz, dz2, x, z, gamma, beta, save_mean, save_rstd, dx, dresidual,
+    launch_bwd<uint16_t>(d, g, m, dz, dz2, x, z, relu_mask, gamma, beta, save_mean, save_rstd, dx, dresidual,
                          dgamma, dbeta, static_cast<float*>(workspace), s);
   else
-    launch_bwd<float>(d, g, m, dz, dz2, x, z, gamma, beta, save_mean, save_rstd, dx, dresidual,
+    launch_bwd<float>(d, g, m, dz, dz2, x, z, relu_mask, gamma, beta, save_mean, save_rstd, dx, dresidual,
                       dgamma, dbeta, static_cast<float*>(workspace), s);
   return launch_status("bn_relu_bwd");
 }
@@ -646,8 +668,9 @@ extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz
 // ---- batch norm from sums fused into the producing convolution (conv_fwd_bn_sums / conv_dgrad_bn_sums)
 extern "C" int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* x,
                                      const float* sums, const float* gamma, const float* beta,
-                                     const void* residual, void* y, float* save_mean, float* save_rstd,
-                                     float* running_mean, float* running_var, float momentum, void* stream) {
+                                     const void* residual, void* y, uint8_t* relu_mask, float* save_mean,
+                                     float* save_rstd, float* running_mean, float* running_var, float momentum,
+                                     void* stream) {
   clear_error();
   if (int rc = check_desc(d, "bn_relu_fwd_from_sums")) return rc;
   RN50_REQUIRE(producer && conv_bn_sums_bytes(producer) > 0, RN50_ERR_INVALID,
@@ -665,8 +688,8 @@ extern "C" int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc
                    producer->dtype == d->dtype,
                RN50_ERR_INVALID, "bn_relu_fwd_from_sums: the producer's output is not this layer's input");
   const PartialRows pr = fwd_partial_rows(producer);
-  bn_fwd_from_partials(d, x, sums, pr.num, pr.rows, gamma, beta, residual, y, save_mean, save_rstd, running_mean,
-                       running_var, momentum, static_cast<hipStream_t>(stream));
+  bn_fwd_from_partials(d, x, sums, pr.num, pr.rows, gamma, beta, residual, y, relu_mask, save_mean, save_rstd,
+                       running_mean, running_var, momentum, static_cast<hipStream_t>(stream));
   return launch_status("bn_relu_fwd_from_sums");
 }
 

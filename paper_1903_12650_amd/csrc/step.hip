@@ -20,6 +20,7 @@ struct Unit {  // convolution + BN (+ReLU / +add+ReLU)
   int iw, ig, ib;        // parameter tensor indices: weight, gamma, beta
   size_t y, z;           // workspace offsets of the conv output and the BN output
   size_t mean, rstd;     // workspace offsets (float[C])
+  size_t relu_mask;      // residual-add layers: the ReLU decision bits (1 byte per 16-byte vector of z)
   int P, Q;
 };
 
@@ -153,6 +154,7 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
     const size_t in_elems = static_cast<size_t>(N) * u.conv.H * u.conv.W * u.conv.Cin;
     u.y = bump(&top, out_elems * es);
     u.z = bump(&top, out_elems * es);
+    u.relu_mask = u.bn.mode == 2 ? bump(&top, out_elems * es / 16) : 0;
     u.mean = bump(&top, u.conv.Cout * sizeof(float));
     u.rstd = bump(&top, u.conv.Cout * sizeof(float));
     if (out_elems > max_act) max_act = out_elems;
@@ -296,8 +298,10 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   float* sums = static_cast<float*>(bn_ws);
   auto bn_after_conv = [&](Unit& u, const void* residual) {
     const PartialRows pr = fwd_partial_rows(&u.conv);
-    bn_fwd_from_partials(&u.bn, ws + u.y, sums, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z, F(u.mean),
-                         F(u.rstd), nullptr, nullptr, 0.f, s);
+    // the residual-add layers record their ReLU decisions: their backward pass then reads one byte per
+    // vector instead of z
+    bn_fwd_from_partials(&u.bn, ws + u.y, sums, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z,
+                         u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd), nullptr, nullptr, 0.f, s);
   };
   stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, sums, s);
   bn_after_conv(u0, nullptr);
@@ -373,8 +377,9 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
       bn_bwd_from_partials(&u.bn, dz, ws + u.y, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), sums,
                            dgrad_sums_rows, dy, G(u.ig), G(u.ib), s);
     } else {
-      const void* z = u.bn.mode == 2 ? static_cast<const void*>(ws + u.z) : nullptr;  // mode 1 recomputes the mask
-      STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, z, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
+      // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
+      const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
+      STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, nullptr, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
                            G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
     }
     pending[npending++] = PendingWgrad{&u, in, dy};

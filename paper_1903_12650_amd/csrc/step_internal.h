@@ -48,8 +48,9 @@ void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, flo
 
 // bn.hip: the part of the forward / backward pass that follows the sums
 void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* partial, int nrows, int rpp,
-                          const float* gamma, const float* beta, const void* residual, void* y, float* save_mean,
-                          float* save_rstd, float* rm, float* rv, float momentum, hipStream_t s);
+                          const float* gamma, const float* beta, const void* residual, void* y,
+                          uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
+                          float momentum, hipStream_t s);
 void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const float* gamma,
                           const float* beta, const float* mean, const float* rstd, const float* partial, int nrows,
                           void* dx, float* dgamma, float* dbeta, hipStream_t s);

@@ -43,13 +43,18 @@ class Chain:
         y, sums = rn.conv_fwd_bn_sums(x, w, stride, pad)
         if self.check:
             self.cmp(name + ".conv", y, orc.conv_fwd(_h(x), _h(w), stride, pad))
-        z, mean, rstd = rn.bn_relu_fwd_from_sums(y, sums, gamma, beta, res, 1e-5, mode)
+        bits = rn.relu_mask_like(y) if mode == 2 else None       # as the step: residual-add layers record the mask
+        z, mean, rstd = rn.bn_relu_fwd_from_sums(y, sums, gamma, beta, res, 1e-5, mode, relu_mask=bits)
         if self.check:
             zo, mo, ro = orc.bn_relu_fwd(_h(y), _h(gamma), _h(beta), _h(res) if res is not None else None, 1e-5, mode)
             self.cmp(name + ".bn", z, zo)
             self.cmp(name + ".rstd", rstd, ro, 1e-4)
+        if self.check and bits is not None:
+            V = 8 if z.dtype == torch.bfloat16 else 4
+            want = ((z.reshape(-1, V) > 0).to(torch.int32) << torch.arange(V, device=z.device, dtype=torch.int32)).sum(1)
+            assert torch.equal(bits.to(torch.int32), want), name + ".relu_mask"
         return dict(name=name, x=x, w=w, gamma=gamma, beta=beta, y=y, z=z, mean=mean, rstd=rstd, stride=stride,
-                    pad=pad, mode=mode)
+                    pad=pad, mode=mode, bits=bits)
 
     # backward of conv + BN; returns dx (or None), dres, (dw, dgamma, dbeta), sums handle for `below`.
     # sums: handle left by the data gradient that produced dz (then dz2 is None and the mode is 1);
@@ -62,8 +67,8 @@ class Chain:
             dy, dg, db = rn.bn_relu_bwd_from_sums(dz, t["y"], sums, t["gamma"], t["beta"], t["mean"], t["rstd"])
             dres = None
         else:
-            dy, dres, dg, db = rn.bn_relu_bwd(dz, t["y"], z, t["gamma"], t["mean"], t["rstd"], t["mode"],
-                                              beta=t["beta"], dz2=dz2)
+            dy, dres, dg, db = rn.bn_relu_bwd(dz, t["y"], None if t["bits"] is not None else z, t["gamma"], t["mean"],
+                                              t["rstd"], t["mode"], beta=t["beta"], dz2=dz2, relu_mask=t["bits"])
         if self.check:
             dzs = _h(dz) + (_h(dz2) if dz2 is not None else 0)
             dyo, dro, dgo, dbo = orc.bn_relu_bwd(dzs.astype(np.float32), _h(t["y"]), _h(t["z"]), _h(t["gamma"]),

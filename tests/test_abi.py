@@ -45,7 +45,7 @@ def test_host_side_argument_checks_need_no_gpu():
     assert raw.conv_dgrad(ctypes.byref(d), one, one, one, one, ctypes.c_size_t(16), None) == -3
     assert rn.conv_dgrad_workspace_bytes(d) >= 8 * 9 * 16 * 2
     b = rn.BnDesc(2, 4, 4, 16, 1e-5, rn.BF16, 2)
-    assert raw.bn_relu_fwd(ctypes.byref(b), one, one, one, None, one, one, one, None, None, ctypes.c_float(0.9), one,
+    assert raw.bn_relu_fwd(ctypes.byref(b), one, one, one, None, one, None, one, one, None, None, ctypes.c_float(0.9), one,
                            ctypes.c_size_t(1 << 20), None) == -1                                # mode 2 without residual
     assert raw.xent_fwd_bwd(0, 10, one, one, ctypes.c_float(0), ctypes.c_float(1), one, one, one, None) == -1
 

@@ -62,6 +62,32 @@ def test_bn_fwd_bwd(rn, mode_name, shape, mode):
                 assert_close(dres, dres_o, tol, "dres")
 
 
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [1, 2])
+def test_bn_relu_mask_bits_replace_z(rn, mode_name, mode):
+    """The recorded ReLU decision bits (one byte per 16-byte vector) are exactly z > 0, and the backward
+    pass gives bit-identical results from them and from z."""
+    bf = mode_name == "bf16"
+    N, H, W, C = 3, 9, 11, 40
+    x = synth.activation_nhwc(SEED, "x", N, C, H, W) * 1.3 + 0.1
+    res = synth.activation_nhwc(SEED, "r", N, C, H, W)
+    dz = synth.activation_nhwc(SEED, "dz", N, C, H, W)
+    x, res, dz = inputs(mode_name, x, res, dz)
+    gamma = (1 + 0.3 * synth.normal(SEED, "g", (C,))).astype(np.float32)
+    beta = (0.2 * synth.normal(SEED, "b", (C,))).astype(np.float32)
+    xd, rd = dev(x, bf), (dev(res, bf) if mode == 2 else None)
+    bits = rn.relu_mask_like(xd)
+    z, mean, rstd = rn.bn_relu_fwd(xd, dev(gamma), dev(beta), rd, 1e-5, mode, relu_mask=bits)
+    V = 8 if bf else 4
+    zh = host(z).reshape(-1, V)
+    want = ((zh > 0).astype(np.int64) << np.arange(V)).sum(1)
+    assert np.array_equal(bits.cpu().numpy().astype(np.int64), want)
+    a = rn.bn_relu_bwd(dev(dz, bf), xd, z, dev(gamma), mean, rstd, mode, beta=dev(beta))
+    b = rn.bn_relu_bwd(dev(dz, bf), xd, None, dev(gamma), mean, rstd, mode, beta=dev(beta), relu_mask=bits)
+    for u, v in zip(a, b):
+        assert (u is None and v is None) or torch.equal(u, v)
+
+
 def test_bn_running_stats_and_large_mean(rn):
     N, H, W, C = 4, 14, 14, 32
     x = synth.activation_nhwc(SEED, "x", N, C, H, W) * 0.05 + 30.0          # mean >> std: shifted sums must cope
