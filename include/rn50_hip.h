@@ -138,15 +138,21 @@ int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const vo
  * The same operations, with the per-channel sums of the batch norm taken in the
  * output stage of the convolution that produces the tensor they range over
  * (one row of partial sums per output tile), so that no separate pass re-reads
- * that tensor.  Forward: conv_fwd_bn_sums produces y and `sums`, then
- * bn_relu_fwd_from_sums(d, producer, y, sums, ...) gives what bn_relu_fwd(d, y, ...)
- * gives.  Backward, for a mode-1 BN layer (ReLU, no residual) whose output z feeds
- * exactly one convolution `producer`: conv_dgrad_bn_sums computes dz = that
- * convolution's data gradient and the sums over g = dz*[z>0] and g*xhat of the BN
- * layer (bn_x: the BN layer's input, [N,H,W,Cin] of the convolution; gamma, beta,
- * save_mean, save_rstd: the layer's, device float[Cin]); bn_relu_bwd_from_sums then
- * gives what bn_relu_bwd(d, dz, NULL, x, NULL, ...) gives.  The sums are formed
- * from the rounded values that are stored, in a fixed order.
+ * that tensor.
+ * Forward: conv_fwd_bn_sums produces y and `sums`; bn_relu_fwd_from_sums(d, producer,
+ * y, sums, ...) then gives what bn_relu_fwd(d, y, ...) gives.
+ * Backward, for a BN layer with ReLU (mode 1 or 2) whose output z feeds the
+ * convolution `producer`: conv_dgrad_bn_sums computes
+ *   dz = data gradient of that convolution (+ addend, when z has a second consumer
+ *        whose gradient is already known: device [N,H,W,Cin] dtype or NULL; the sum is
+ *        formed in float and rounded once),
+ * stores it in dx, and takes the sums over g = dz*[z>0] and g*xhat of the BN layer
+ * (bn_x: the BN layer's input, [N,H,W,Cin]; relu_mask: the bits its forward pass
+ * recorded, or NULL in mode 1 to recompute the decision from bn_x; gamma, beta,
+ * save_mean, save_rstd: the layer's, device float[Cin]).  bn_relu_bwd_from_sums then
+ * gives what bn_relu_bwd(d, dz, NULL, x, ...) gives (mode 2: relu_mask and dresidual
+ * required).  The sums are formed from the rounded values that are stored, in a fixed
+ * order.
  * sums: device float, conv_bn_sums_bytes(d) bytes (16-byte aligned), layout private
  * to the pair of calls; `producer` must be the descriptor the sums were made with. */
 size_t conv_bn_sums_bytes(const rn50_conv_desc* d);
@@ -158,13 +164,15 @@ int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer,
                           float* save_rstd, float* running_mean, float* running_var, float momentum,
                           void* stream);
 int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
-                       const void* bn_x, const float* gamma, const float* beta,
-                       const float* save_mean, const float* save_rstd, float* sums,
-                       size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream);
+                       const void* addend, const void* bn_x, const uint8_t* relu_mask,
+                       const float* gamma, const float* beta, const float* save_mean,
+                       const float* save_rstd, float* sums, size_t sums_bytes, void* workspace,
+                       size_t workspace_bytes, void* stream);
 int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* dz,
-                          const void* x, const float* gamma, const float* beta,
-                          const float* save_mean, const float* save_rstd, const float* sums,
-                          void* dx, float* dgamma, float* dbeta, void* stream);
+                          const void* x, const uint8_t* relu_mask, const float* gamma,
+                          const float* beta, const float* save_mean, const float* save_rstd,
+                          const float* sums, void* dx, void* dresidual, float* dgamma, float* dbeta,
+                          void* stream);
 
 /* --------------------------------------------------------------------- pooling
  * Max pooling, window 3x3, stride 2, pad 1 (the appendix's 112 -> 56 step);

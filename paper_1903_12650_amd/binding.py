@@ -246,8 +246,8 @@ def bn_relu_fwd_from_sums(x, handle, gamma, beta, residual=None, eps=1e-5, mode=
 
 
 def conv_dgrad_bn_sums(dy, w, x_shape, stride, pad, bn_x, gamma, beta, mean, rstd, dx=None, workspace=None,
-                       sums=None):
-    """Returns dx and the handle bn_relu_bwd_from_sums takes."""
+                       sums=None, addend=None, relu_mask=None):
+    """Returns dx (= data gradient + addend) and the handle bn_relu_bwd_from_sums takes."""
     d = _conv_desc(x_shape, w.shape, stride, pad, _dt(dy))
     if dx is None:
         dx = torch.empty(tuple(x_shape), dtype=dy.dtype, device=dy.device)
@@ -255,23 +255,25 @@ def conv_dgrad_bn_sums(dy, w, x_shape, stride, pad, bn_x, gamma, beta, mean, rst
         workspace = _ws(conv_dgrad_workspace_bytes(d), dy.device)
     if sums is None:
         sums = _ws(conv_bn_sums_bytes(d), dy.device)
-    _check(raw.conv_dgrad_bn_sums(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(bn_x), _ptr(gamma), _ptr(beta),
-                                  _ptr(mean), _ptr(rstd), _ptr(sums), ctypes.c_size_t(sums.numel()), _ptr(workspace),
-                                  ctypes.c_size_t(workspace.numel()), _stream()))
+    _check(raw.conv_dgrad_bn_sums(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(addend), _ptr(bn_x),
+                                  _ptr(relu_mask), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(rstd), _ptr(sums),
+                                  ctypes.c_size_t(sums.numel()), _ptr(workspace), ctypes.c_size_t(workspace.numel()),
+                                  _stream()))
     return dx, (d, sums)
 
 
-def bn_relu_bwd_from_sums(dz, x, handle, gamma, beta, mean, rstd, eps=1e-5):
-    """Returns dx, dgamma, dbeta (BN + ReLU, no residual)."""
+def bn_relu_bwd_from_sums(dz, x, handle, gamma, beta, mean, rstd, eps=1e-5, mode=1, relu_mask=None):
+    """Returns dx, dresidual (None unless mode 2), dgamma, dbeta."""
     producer, sums = handle
-    d = _bn_desc(x, eps, 1)
+    d = _bn_desc(x, eps, mode)
     dx = torch.empty_like(x)
+    dres = torch.empty_like(x) if mode == 2 else None
     dgamma = torch.empty(d.C, dtype=torch.float32, device=x.device)
     dbeta = torch.empty(d.C, dtype=torch.float32, device=x.device)
-    _check(raw.bn_relu_bwd_from_sums(ctypes.byref(d), ctypes.byref(producer), _ptr(dz), _ptr(x), _ptr(gamma),
-                                     _ptr(beta), _ptr(mean), _ptr(rstd), _ptr(sums), _ptr(dx), _ptr(dgamma),
-                                     _ptr(dbeta), _stream()))
-    return dx, dgamma, dbeta
+    _check(raw.bn_relu_bwd_from_sums(ctypes.byref(d), ctypes.byref(producer), _ptr(dz), _ptr(x), _ptr(relu_mask),
+                                     _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(rstd), _ptr(sums), _ptr(dx),
+                                     _ptr(dres), _ptr(dgamma), _ptr(dbeta), _stream()))
+    return dx, dres, dgamma, dbeta
 
 
 # -------------------------------------------------------------------- pooling

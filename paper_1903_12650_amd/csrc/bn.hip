@@ -583,17 +583,18 @@ void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* par
     launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
                            partial, nrows, rpp, s);
 }
-void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const float* gamma,
-                          const float* beta, const float* mean, const float* rstd, const float* partial, int nrows,
-                          void* dx, float* dgamma, float* dbeta, hipStream_t s) {
+void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const uint8_t* relu_mask,
+                          const float* gamma, const float* beta, const float* mean, const float* rstd,
+                          const float* partial, int nrows, void* dx, void* dres, float* dgamma, float* dbeta,
+                          hipStream_t s) {
   const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
-    launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
-                              partial, nrows, s);
+    launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, relu_mask, gamma, beta, mean, rstd, dx, dres, dgamma,
+                              dbeta, partial, nrows, s);
   else
-    launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, nullptr, gamma, beta, mean, rstd, dx, nullptr, dgamma, dbeta,
-                           partial, nrows, s);
+    launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, relu_mask, gamma, beta, mean, rstd, dx, dres, dgamma,
+                           dbeta, partial, nrows, s);
 }
 
 }  // namespace rn50
@@ -694,23 +695,27 @@ extern "C" int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc
 }
 
 extern "C" int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer, const void* dz,
-                                     const void* x, const float* gamma, const float* beta,
-                                     const float* save_mean, const float* save_rstd, const float* sums,
-                                     void* dx, float* dgamma, float* dbeta, void* stream) {
+                                     const void* x, const uint8_t* relu_mask, const float* gamma,
+                                     const float* beta, const float* save_mean, const float* save_rstd,
+                                     const float* sums, void* dx, void* dresidual, float* dgamma, float* dbeta,
+                                     void* stream) {
   clear_error();
   if (int rc = check_desc(d, "bn_relu_bwd_from_sums")) return rc;
-  RN50_REQUIRE(d->mode == 1, RN50_ERR_UNSUPPORTED, "bn_relu_bwd_from_sums: mode %d (only BN+ReLU)", d->mode);
+  RN50_REQUIRE(d->mode == 1 || d->mode == 2, RN50_ERR_UNSUPPORTED, "bn_relu_bwd_from_sums: mode %d (needs a ReLU)",
+               d->mode);
+  RN50_REQUIRE(d->mode != 2 || (relu_mask && dresidual), RN50_ERR_INVALID,
+               "bn_relu_bwd_from_sums: mode 2 needs relu_mask and dresidual");
   RN50_REQUIRE(producer && conv_bn_sums_bytes(producer) > 0, RN50_ERR_INVALID,
                "bn_relu_bwd_from_sums: bad producer descriptor");
   RN50_REQUIRE(dz && x && gamma && beta && save_mean && save_rstd && sums && dx && dgamma && dbeta,
                RN50_ERR_INVALID, "bn_relu_bwd_from_sums: null pointer");
-  RN50_REQUIRE(aligned16(dz) && aligned16(x) && aligned16(dx) && aligned16(sums), RN50_ERR_ALIGN,
-               "bn_relu_bwd_from_sums: pointer not 16-byte aligned");
+  RN50_REQUIRE(aligned16(dz) && aligned16(x) && aligned16(dx) && aligned16(sums) && aligned16(dresidual),
+               RN50_ERR_ALIGN, "bn_relu_bwd_from_sums: pointer not 16-byte aligned");
   RN50_REQUIRE(producer->N == d->N && producer->H == d->H && producer->W == d->W && producer->Cin == d->C &&
                    producer->dtype == d->dtype,
                RN50_ERR_INVALID, "bn_relu_bwd_from_sums: the producer's input is not this layer's output");
   const PartialRows pr = dgrad_partial_rows(producer);
-  bn_bwd_from_partials(d, dz, x, gamma, beta, save_mean, save_rstd, sums, pr.num, dx, dgamma, dbeta,
-                       static_cast<hipStream_t>(stream));
+  bn_bwd_from_partials(d, dz, x, relu_mask, gamma, beta, save_mean, save_rstd, sums, pr.num, dx,
+                       d->mode == 2 ? dresidual : nullptr, dgamma, dbeta, static_cast<hipStream_t>(stream));
   return launch_status("bn_relu_bwd_from_sums");
 }

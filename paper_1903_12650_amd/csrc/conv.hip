@@ -108,6 +108,12 @@ struct IgemmArgs {
   float* partial;
   const void* bn_x;
   const float *bn_gamma, *bn_beta, *bn_mean, *bn_rstd;
+  // Data gradient with sums only.  addend [M][Ncols] (or null): a second gradient branch, added to the
+  // product in float before the one rounding to the storage type (the stored output is the sum).
+  // bn_zmask (or null): the BN layer's recorded ReLU decision bits, one byte per 16-byte vector of its
+  // output; without them the decision is recomputed from bn_x.
+  const void* addend;
+  const uint8_t* bn_zmask;
 };
 
 constexpr int kPitch = 144;  // LDS row pitch of a 128-byte K chunk (conflict-free 16-byte reads)
@@ -139,7 +145,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   constexpr int STAGE = (BM + BN) * kPitch;
   constexpr int CP = BN * sizeof(T) + 16;  // epilogue pitch
   static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
-  static_assert(BM * CP <= 2 * STAGE, "epilogue tile must fit in the pipeline buffers");
+  constexpr int CPW = BN * 4 + 16;         // pitch of a float output tile (bf16 data gradient with an addend)
+  static_assert(BM * CP <= 2 * STAGE && BM * CPW <= 2 * STAGE, "epilogue tile must fit in the pipeline buffers");
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x, piece = tid & 7, lrow = tid >> 3;
@@ -304,6 +311,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   }
 
   // Epilogue.  acc[i][j][v]: output channel n = j*32 + (v/4)*8 + (lane/32)*4 + v%4, pixel m = i*32 + lane%32.
+  // The tile goes to LDS in the storage type, or in float when a bf16 data gradient has an addend.
+  const bool wide = sizeof(T) == 2 && MODE == 1 && a.partial != nullptr && a.addend != nullptr;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -313,7 +322,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       for (int g = 0; g < 4; ++g) {
         const int col = wn * (BN / WN) + j * 32 + g * 8 + (lane >> 5) * 4;
         unsigned char* dst = smem + row * CP + col * sizeof(T);
-        if (sizeof(T) == 2) {
+        if (wide) {
+          *reinterpret_cast<float4*>(smem + row * CPW + col * 4) =
+              make_float4(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+        } else if (sizeof(T) == 2) {
           uint2 p;
           p.x = float_to_bf16_bits(acc[i][j][g * 4 + 0]) | (static_cast<uint32_t>(float_to_bf16_bits(acc[i][j][g * 4 + 1])) << 16);
           p.y = float_to_bf16_bits(acc[i][j][g * 4 + 2]) | (static_cast<uint32_t>(float_to_bf16_bits(acc[i][j][g * 4 + 3])) << 16);
@@ -376,13 +388,18 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   } else {
     const T* bx = static_cast<const T*>(a.bn_x);
     const int nc = col_ok ? n : 0;
-    Vec16 xv[NPASS];
+    const T* add = static_cast<const T*>(a.addend);
+    Vec16 xv[NPASS], av[NPASS];
+    uint32_t zb[NPASS];
     int pix[NPASS];
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
       const int row = orow + pass * RPP;
       pix[pass] = classes ? pix_s[row] : min(m0 + row, a.M - 1);  // rows past the last read a valid pixel
-      xv[pass] = load16(bx + (static_cast<int64_t>(pix[pass]) * a.Ncols + nc));
+      const int64_t at = static_cast<int64_t>(pix[pass]) * a.Ncols + nc;
+      xv[pass] = load16(bx + at);
+      if (add) av[pass] = load16(add + at);
+      if (a.bn_zmask) zb[pass] = a.bn_zmask[at / V];
     }
     float scale[V], bias[V], rs[V], nmr[V];
 #pragma unroll
@@ -396,14 +413,33 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       const int row = orow + pass * RPP;
       if (m0 + row < Mc && col_ok) {
         Vec16 v;
-        v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
-        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(pix[pass]) * a.Ncols + n)) = v.u;
         float g[V], xf[V];
-        Elem<T>::unpack(v, g);
+        if (add) {
+          float ad[V];
+          Elem<T>::unpack(av[pass], ad);
+          if (wide) {
+            const float4 lo = *reinterpret_cast<const float4*>(smem + row * CPW + op * 32);
+            const float4 hi = *reinterpret_cast<const float4*>(smem + row * CPW + op * 32 + 16);
+            const float t[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+            for (int j = 0; j < V; ++j) g[j] = t[j] + ad[j];
+          } else {
+            v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+            Elem<T>::unpack(v, g);
+#pragma unroll
+            for (int j = 0; j < V; ++j) g[j] += ad[j];
+          }
+          Elem<T>::pack(g, v);
+        } else {
+          v.u = *reinterpret_cast<const uint4*>(smem + row * CP + op * 16);
+        }
+        *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(pix[pass]) * a.Ncols + n)) = v.u;
+        Elem<T>::unpack(v, g);  // the sums range over the stored (rounded) values
         Elem<T>::unpack(xv[pass], xf);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-          const float gm = bn_affine(xf[j], scale[j], bias[j]) > 0.f ? g[j] : 0.f;
+          const bool on = a.bn_zmask ? ((zb[pass] >> j) & 1u) != 0 : bn_affine(xf[j], scale[j], bias[j]) > 0.f;
+          const float gm = on ? g[j] : 0.f;
           s1[j] += gm;
           s2[j] = fmaf(gm, fmaf(xf[j], rs[j], nmr[j]), s2[j]);
         }
@@ -1110,6 +1146,7 @@ void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx
   if (bn) {
     a.partial = bn->partial; a.bn_x = bn->x;
     a.bn_gamma = bn->gamma; a.bn_beta = bn->beta; a.bn_mean = bn->mean; a.bn_rstd = bn->rstd;
+    a.addend = bn->addend; a.bn_zmask = bn->relu_mask;
   }
   a.P = d->H; a.Q = d->W;
   a.H = out_dim(d->H, d->pad, d->R, d->stride); a.W = out_dim(d->W, d->pad, d->S, d->stride);
@@ -1233,7 +1270,8 @@ extern "C" int conv_fwd_bn_sums(const rn50_conv_desc* d, const void* x, const vo
 }
 
 extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
-                                  const void* bn_x, const float* gamma, const float* beta,
+                                  const void* addend, const void* bn_x, const uint8_t* relu_mask,
+                                  const float* gamma, const float* beta,
                                   const float* save_mean, const float* save_rstd, float* sums,
                                   size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
@@ -1244,7 +1282,7 @@ extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const
   RN50_REQUIRE(dy && w && dx && workspace && bn_x && gamma && beta && save_mean && save_rstd && sums,
                RN50_ERR_INVALID, "conv_dgrad_bn_sums: null pointer");
   RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(workspace) && aligned16(bn_x) &&
-                   aligned16(sums),
+                   aligned16(sums) && aligned16(addend),
                RN50_ERR_ALIGN, "conv_dgrad_bn_sums: pointer not 16-byte aligned");
   RN50_REQUIRE(workspace_bytes >= dgrad_wt_bytes(d), RN50_ERR_WORKSPACE,
                "conv_dgrad_bn_sums: workspace %zu < %zu bytes", workspace_bytes, dgrad_wt_bytes(d));
@@ -1252,7 +1290,7 @@ extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const
                sums_bytes, conv_bn_sums_bytes(d));
   hipStream_t s = static_cast<hipStream_t>(stream);
   dgrad_transpose_weights(d, w, workspace, s);
-  const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums};
+  const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums, addend, relu_mask};
   dgrad_run(d, dy, workspace, dx, &bn, s);
   return launch_status("conv_dgrad_bn_sums");
 }

@@ -341,12 +341,12 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   for (int i = 0; i < 5; ++i) g[i] = ws + plan->g[i];
   // g[0], g[1]: the two summands of the gradient w.r.t. the current block output (g[1] may be unused)
   STEP_TRY(avgpool_bwd(cfg.N, HW, plan->fc_in, dt, ws + plan->davg, g[0], s));
-  bool have2 = false;
   int dgrad_sums_rows = 0;
   // BN backward + wgrad + dgrad of one unit.  dz (+dz2) -> dy; dgrad into `dx` (skipped if null).
   // `sums_ready`: the data gradient that produced dz already left this BN layer's sums in bn_ws.
-  // `below`: the unit whose BN output is this unit's only input use (dx is its complete dz): the data
-  // gradient then leaves that layer's sums in bn_ws.
+  // `below`: the unit whose BN output is this unit's input, when dx (+ addend, the gradient of that
+  // output's other consumer) is its complete dz: the data gradient then stores the sum and leaves that
+  // layer's sums in bn_ws.
   // The weight gradients are off the critical path (nothing in the backward pass reads them): they run
   // on the side stream, a block's worth at a time (one event each way per block: an event is a packet
   // the stream has to drain for).  dy lives in a ring of buffers, two blocks deep, so the next block's BN
@@ -371,14 +371,14 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     ++blk;
   };
   auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, void* dx,
-                      bool sums_ready, Unit* below) -> int {
+                      bool sums_ready, Unit* below, const void* addend) -> int {
     void* dy = ws + plan->dy_ring[seq % rn50_plan::kDyRing];
+    // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
+    const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
     if (sums_ready) {
-      bn_bwd_from_partials(&u.bn, dz, ws + u.y, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), sums,
-                           dgrad_sums_rows, dy, G(u.ig), G(u.ib), s);
+      bn_bwd_from_partials(&u.bn, dz, ws + u.y, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), sums,
+                           dgrad_sums_rows, dy, u.bn.mode == 2 ? dres : nullptr, G(u.ig), G(u.ib), s);
     } else {
-      // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
-      const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
       STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, nullptr, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
                            G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
     }
@@ -386,7 +386,8 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     if (dx) {
       BnBwdSums fuse{};
       if (below) {
-        fuse = BnBwdSums{ws + below->y, MP(below->ig), MP(below->ib), F(below->mean), F(below->rstd), sums};
+        fuse = BnBwdSums{ws + below->y, MP(below->ig), MP(below->ib), F(below->mean), F(below->rstd), sums, addend,
+                         below->bn.mode == 2 ? ws + below->relu_mask : nullptr};
         dgrad_sums_rows = dgrad_partial_rows(&u.conv).num;
       }
       dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, below ? &fuse : nullptr, s);
@@ -394,26 +395,36 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     ++seq;
     return RN50_OK;
   };
+  // dzo (+ dzo2): the gradient w.r.t. the current block's output; top_sums: its BN sums are in bn_ws
+  const void *dzo = g[0], *dzo2 = nullptr;
+  bool top_sums = false;
   for (int bi = static_cast<int>(plan->blocks.size()) - 1; bi >= 0; --bi) {
     const Block& b = plan->blocks[bi];
     Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
-    const void* block_in = bi == 0 ? static_cast<const void*>(ws + plan->pool)
-                                   : static_cast<const void*>(ws + plan->units[plan->blocks[bi - 1].u3].z);
+    Unit* prev = bi > 0 ? &plan->units[plan->blocks[bi - 1].u3] : nullptr;  // its BN output is this block's input
+    const void* block_in = prev ? static_cast<const void*>(ws + prev->z) : static_cast<const void*>(ws + plan->pool);
     block_begin();
-    STEP_TRY(unit_bwd(u3, ws + u2.z, g[0], have2 ? g[1] : nullptr, g[3], g[4], false, &u2));
-    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, nullptr, g[4], true, &u1));
-    STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, nullptr, g[0], true, nullptr));
-    if (b.up >= 0) {
-      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, nullptr, g[1], false, nullptr));
+    STEP_TRY(unit_bwd(u3, ws + u2.z, dzo, dzo2, g[3], g[4], top_sums, &u2, nullptr));   // g[3]: gradient of the shortcut
+    STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, nullptr, g[4], true, &u1, nullptr));
+    // The block input has two consumers (conv1 and the shortcut).  The last data gradient into it adds
+    // the other branch and takes the sums of the previous block's last BN layer.
+    if (b.up < 0) {
+      STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, nullptr, g[0], true, prev, g[3]));
+      dzo = g[0]; dzo2 = nullptr; top_sums = prev != nullptr;
     } else {
-      unsigned char* t = g[1]; g[1] = g[3]; g[3] = t;
+      STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, nullptr, g[0], true, nullptr, nullptr));
+      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, nullptr, g[1], false, prev, g[0]));
+      if (prev) {
+        dzo = g[1]; dzo2 = nullptr; top_sums = true;
+      } else {  // the first block: the max-pool's backward pass adds the two branches
+        dzo = g[0]; dzo2 = g[1]; top_sums = false;
+      }
     }
     block_end();
-    have2 = true;
   }
-  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, g[0], g[1], g[2], s));
+  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, dzo, dzo2, g[2], s));
   block_begin();
-  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, nullptr, nullptr, false, nullptr));
+  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, nullptr, nullptr, false, nullptr, nullptr));
   block_end();
   (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 1], 0);  // join: the side stream runs in order
 

@@ -27,12 +27,16 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
                      hipStream_t s);
 void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s,
              const char* tag = "conv_fwd");
-// The BN layer (with ReLU, no residual) whose output gradient a data gradient produces: x is that
+// The BN layer (with ReLU) whose output gradient a data gradient produces: x is that
 // layer's input [N*H*W][Cin]; partial receives float[2][Cin][num] = sum(g), sum(g * xhat) per tile.
+// addend (or null): a second branch of the gradient, [N*H*W][Cin], added to the data gradient before it
+// is stored; relu_mask (or null): the BN layer's recorded ReLU decisions (else recomputed from x).
 struct BnBwdSums {
   const void* x;
   const float *gamma, *beta, *mean, *rstd;
   float* partial;
+  const void* addend = nullptr;
+  const uint8_t* relu_mask = nullptr;
 };
 size_t dgrad_wt_bytes(const rn50_conv_desc* d);
 void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, hipStream_t s);
@@ -51,9 +55,12 @@ void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* par
                           const float* gamma, const float* beta, const void* residual, void* y,
                           uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
                           float momentum, hipStream_t s);
-void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const float* gamma,
-                          const float* beta, const float* mean, const float* rstd, const float* partial, int nrows,
-                          void* dx, float* dgamma, float* dbeta, hipStream_t s);
+// relu_mask: recorded ReLU decisions (required in mode 2, where dres receives the masked gradient), or
+// null: recomputed from x (mode 1).
+void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const uint8_t* relu_mask,
+                          const float* gamma, const float* beta, const float* mean, const float* rstd,
+                          const float* partial, int nrows, void* dx, void* dres, float* dgamma, float* dbeta,
+                          hipStream_t s);
 
 // lars.hip
 struct LarsArenaSpec {

@@ -59,13 +59,13 @@ class Chain:
     # backward of conv + BN; returns dx (or None), dres, (dw, dgamma, dbeta), sums handle for `below`.
     # sums: handle left by the data gradient that produced dz (then dz2 is None and the mode is 1);
     # below: tape of the unit whose BN output is this unit's input and has no other use.
-    def cbn_bwd(self, t, dz, dz2=None, need_dx=True, sums=None, below=None):
+    def cbn_bwd(self, t, dz, dz2=None, need_dx=True, sums=None, below=None, addend=None):
         rn = self.rn
         z = t["z"] if t["mode"] == 2 else None                      # mode 1: mask recomputed, as the step does
         if sums is not None:
-            assert dz2 is None and t["mode"] == 1
-            dy, dg, db = rn.bn_relu_bwd_from_sums(dz, t["y"], sums, t["gamma"], t["beta"], t["mean"], t["rstd"])
-            dres = None
+            assert dz2 is None and t["mode"] in (1, 2)
+            dy, dres, dg, db = rn.bn_relu_bwd_from_sums(dz, t["y"], sums, t["gamma"], t["beta"], t["mean"], t["rstd"],
+                                                        mode=t["mode"], relu_mask=t["bits"])
         else:
             dy, dres, dg, db = rn.bn_relu_bwd(dz, t["y"], None if t["bits"] is not None else z, t["gamma"], t["mean"],
                                               t["rstd"], t["mode"], beta=t["beta"], dz2=dz2, relu_mask=t["bits"])
@@ -85,11 +85,16 @@ class Chain:
         if need_dx:
             if below is not None:
                 dx, out_sums = rn.conv_dgrad_bn_sums(dy, t["w"], t["x"].shape, t["stride"], t["pad"], below["y"],
-                                                     below["gamma"], below["beta"], below["mean"], below["rstd"])
+                                                     below["gamma"], below["beta"], below["mean"], below["rstd"],
+                                                     addend=addend, relu_mask=below["bits"])
             else:
+                assert addend is None
                 dx = rn.conv_dgrad(dy, t["w"], t["x"].shape, t["stride"], t["pad"])
             if self.check:
-                self.cmp(t["name"] + ".dx", dx, orc.conv_dgrad(_h(dy), _h(t["w"]), tuple(t["x"].shape), t["stride"], t["pad"]))
+                want = orc.conv_dgrad(_h(dy), _h(t["w"]), tuple(t["x"].shape), t["stride"], t["pad"])
+                if addend is not None:
+                    want = want + _h(addend)
+                self.cmp(t["name"] + ".dx", dx, want)
         return dx, dres, [dw, dg, db], out_sums
 
 
@@ -146,18 +151,27 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
         ch.cmp("fc.da", da, dao); ch.cmp("fc.dW", dfw, dfwo, 1e-4); ch.cmp("fc.db", dfb, dfbo, 1e-4)
         ch.cmp("avgpool_bwd", d, orc.avgpool_bwd(_h(da), H, W))
     d2 = None
+    top_sums = None
     block_grads = []
-    for (t1, t2, t3, tp) in reversed(tapes):
-        dz2_, dres, g3, s2 = ch.cbn_bwd(t3, d, d2, below=t2)
+    for bi in range(len(tapes) - 1, -1, -1):
+        t1, t2, t3, tp = tapes[bi]
+        prev = tapes[bi - 1][2] if bi > 0 else None          # the previous block's last unit: its z is this block's input
+        dz2_, dres, g3, s2 = ch.cbn_bwd(t3, d, d2, sums=top_sums, below=t2)
         dz1_, _, g2, s1 = ch.cbn_bwd(t2, dz2_, sums=s2, below=t1)
-        dxa, _, g1, _ = ch.cbn_bwd(t1, dz1_, sums=s1)
-        gl = g1 + g2 + g3
-        if tp is not None:
-            dxb, _, gp, _ = ch.cbn_bwd(tp, dres)
-            gl = gl + gp
-            d, d2 = dxa, dxb
+        gl = None
+        if tp is None:
+            # identity shortcut: conv1's data gradient adds the shortcut's gradient and takes the previous block's sums
+            d, _, g1, top_sums = ch.cbn_bwd(t1, dz1_, sums=s1, below=prev, addend=dres)
+            d2 = None
+            gl = g1 + g2 + g3
         else:
-            d, d2 = dxa, dres
+            dxa, _, g1, _ = ch.cbn_bwd(t1, dz1_, sums=s1)
+            dxb, _, gp, top_sums = ch.cbn_bwd(tp, dres, below=prev, addend=dxa if prev is not None else None)
+            gl = g1 + g2 + g3 + gp
+            if prev is not None:
+                d, d2 = dxb, None
+            else:
+                d, d2 = dxa, dxb
         block_grads.append(gl)
     dpool = rn.maxpool_bwd(t0["z"], d, d2, argmax=pool_argmax)
     if check:

@@ -108,7 +108,7 @@ def test_conv_dgrad_bn_sums(rn, mode_name, shape):
     dz, sums = rn.conv_dgrad_bn_sums(dyd, wd, (N, H, W, C), stride, pad, bxd, gd, bd, md, rd)
     assert torch.equal(dz, rn.conv_dgrad(dyd, wd, (N, H, W, C), stride, pad)), "the sums must not change the gradient"
     assert_close(dz, orc.conv_dgrad(dy, w, (N, H, W, C), stride, pad), tol, "dz")
-    dx, dg, db = rn.bn_relu_bwd_from_sums(dz, bxd, sums, gd, bd, md, rd)
+    dx, _, dg, db = rn.bn_relu_bwd_from_sums(dz, bxd, sums, gd, bd, md, rd)
     dx_o, _, dg_o, db_o = orc.bn_relu_bwd(host(dz).astype(np.float32), bx, z_o, gamma, mean_o, rstd_o, 1)
     if N * H * W > 1:
         t2 = max(tol, 2e-3)   # the mask is recomputed from x: it may differ where z rounds to zero
@@ -117,6 +117,48 @@ def test_conv_dgrad_bn_sums(rn, mode_name, shape):
         assert_close(db, db_o, t2, "dbeta")
     # the separate-pass kernels (same mask rule) agree to rounding of the float sums
     dx_u, _, dg_u, db_u = rn.bn_relu_bwd(dz, bxd, None, gd, md, rd, 1, beta=bd)
+    assert_close(dg, host(dg_u), 1e-5, "dgamma vs separate pass")
+    assert_close(db, host(db_u), 1e-5, "dbeta vs separate pass")
+    assert_close(dx, host(dx_u), max(1e-5, tol / 4), "dx vs separate pass")
+
+
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", DGRAD_SHAPES)
+def test_conv_dgrad_bn_sums_residual_layer_with_addend(rn, mode_name, shape):
+    """The BN layer below is a residual-add layer (mode 2) whose output has a second consumer: the data
+    gradient adds that consumer's gradient (one rounding of the sum), takes the mask from the recorded bits."""
+    bf = mode_name == "bf16"
+    tol = TOL[mode_name]
+    N, H, W, C, K, R, stride, pad = shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    bx = synth.activation_nhwc(SEED, "bx", N, C, H, W) * 1.3 + 0.2
+    res = synth.activation_nhwc(SEED, "res", N, C, H, W)
+    dy = synth.activation_nhwc(SEED, "dy", N, K, P, Q)
+    add = synth.activation_nhwc(SEED, "add", N, C, H, W) * 0.7
+    w = synth.conv_weight_krsc(SEED, "w", K, C, R, R)
+    bx, res, dy, add, w = inputs(mode_name, bx, res, dy, add, w)
+    gamma, beta = _vec("g", C, 0.3, 1.0), _vec("b", C, 0.2, 0.0)
+    bxd, resd = dev(bx, bf), dev(res, bf)
+    gd, bd = dev(gamma), dev(beta)
+    bits = rn.relu_mask_like(bxd)
+    z, md, rd = rn.bn_relu_fwd(bxd, gd, bd, resd, 1e-5, 2, relu_mask=bits)      # the layer's own forward pass
+    dz, sums = rn.conv_dgrad_bn_sums(dev(dy, bf), dev(w, bf), (N, H, W, C), stride, pad, bxd, gd, bd, md, rd,
+                                     addend=dev(add, bf), relu_mask=bits)
+    want = orc.conv_dgrad(dy, w, (N, H, W, C), stride, pad) + add
+    assert_close(dz, want, tol, "dz = data gradient + addend")
+    if bf:   # one rounding of the float sum: never further from it than rounding the exact sum twice would be
+        plain = host(rn.conv_dgrad(dev(dy, bf), dev(w, bf), (N, H, W, C), stride, pad))
+        assert orc.rel_l2(host(dz), want) <= orc.rel_l2(synth.round_bf16(plain + add), want) * 1.05 + 1e-7
+    dx, dres, dg, db = rn.bn_relu_bwd_from_sums(dz, bxd, sums, gd, bd, md, rd, mode=2, relu_mask=bits)
+    dx_o, dres_o, dg_o, db_o = orc.bn_relu_bwd(host(dz).astype(np.float32), bx, host(z), gamma, host(md), host(rd), 2)
+    if N * H * W > 1:
+        assert_close(dx, dx_o, tol, "dx")
+        assert_close(dres, dres_o, tol, "dresidual")
+        assert_close(dg, dg_o, max(tol, 1e-3), "dgamma")
+        assert_close(db, db_o, max(tol, 1e-3), "dbeta")
+    # the separate-pass kernels agree to rounding of the float sums
+    dx_u, dres_u, dg_u, db_u = rn.bn_relu_bwd(dz, bxd, z, gd, md, rd, 2, beta=bd)
+    assert torch.equal(dres, dres_u)
     assert_close(dg, host(dg_u), 1e-5, "dgamma vs separate pass")
     assert_close(db, host(db_u), 1e-5, "dbeta vs separate pass")
     assert_close(dx, host(dx_u), max(1e-5, tol / 4), "dx vs separate pass")
