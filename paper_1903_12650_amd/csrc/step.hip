@@ -51,7 +51,8 @@ struct rn50_plan {
   size_t wT = 0, wgrad_scratch = 0, bn_scratch = 0, lars_scratch = 0, pool_argmax = 0, fc_scratch = 0;
   size_t bn_scratch_bytes = 0, fc_scratch_bytes = 0;
   std::vector<rn50::TransposeEntry> transposes;
-  rn50::LarsArenaSpec lars;
+  rn50::LarsArenaSpec lars_rest, lars_stem;  // every tensor but the stem's weight / the stem's weight
+  size_t lars_stem_scratch = 0;
   // Second stream for the work that is off the step's critical path (weight gradients, the weight
   // transposition), with the events that order it against the caller's stream.  Created at the first
   // step (default priority), destroyed with the plan.
@@ -187,13 +188,18 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->wgrad_scratch = bump(&top, max_wg);
   p->bn_scratch = bump(&top, max_bn);
   p->bn_scratch_bytes = max_bn;
-  p->lars.num = static_cast<int>(p->tensors.size());
-  for (const Tensor& t : p->tensors) {
-    p->lars.offset.push_back(t.offset);
-    p->lars.count.push_back(t.count);
-    p->lars.decay.push_back(t.decay ? 1 : 0);
+  // The stem's weight gradient is the last thing the backward pass produces; the update of every other
+  // tensor runs beside it.
+  for (size_t i = 0; i < p->tensors.size(); ++i) {
+    const Tensor& t = p->tensors[i];
+    LarsArenaSpec& sp = i == static_cast<size_t>(p->units[0].iw) ? p->lars_stem : p->lars_rest;
+    sp.offset.push_back(t.offset);
+    sp.count.push_back(t.count);
+    sp.decay.push_back(t.decay ? 1 : 0);
+    ++sp.num;
   }
-  p->lars_scratch = bump(&top, lars_arena_partial_bytes(p->lars));
+  p->lars_scratch = bump(&top, lars_arena_partial_bytes(p->lars_rest));
+  p->lars_stem_scratch = bump(&top, lars_arena_partial_bytes(p->lars_stem));
   p->ws_bytes = top;
   *plan_out = p;
   return RN50_OK;
@@ -426,11 +432,18 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   block_begin();
   STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, nullptr, nullptr, false, nullptr, nullptr));
   block_end();
-  (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 1], 0);  // join: the side stream runs in order
-
   // ------------------------------------------------------------------ LARS
+  // The side stream runs in order: the event of the last block but one covers every weight gradient
+  // except the stem's, which is still running while the other tensors are updated.
+  void* lowp = cfg.dtype == RN50_BF16 ? model : nullptr;
+  if (update) {
+    if (blk >= 2) (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 2], 0);
+    lars_arena_run(plan->lars_rest, master, grads, velocity, lowp, cfg.eta, cfg.momentum, lr, cfg.lars_eps,
+                   cfg.weight_decay, F(plan->lars_scratch), s);
+  }
+  (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 1], 0);  // join
   if (update)
-    lars_arena_run(plan->lars, master, grads, velocity, cfg.dtype == RN50_BF16 ? model : nullptr, cfg.eta,
-                   cfg.momentum, lr, cfg.lars_eps, cfg.weight_decay, F(plan->lars_scratch), s);
+    lars_arena_run(plan->lars_stem, master, grads, velocity, lowp, cfg.eta, cfg.momentum, lr, cfg.lars_eps,
+                   cfg.weight_decay, F(plan->lars_stem_scratch), s);
   return launch_status("resnet_step");
 }

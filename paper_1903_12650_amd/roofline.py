@@ -91,11 +91,13 @@ def per_launch_cost(tag, plan):
         if tag == "bn_bwd_reduce":  # the BN+ReLU layers inside a block get their sums from the data gradient above
             seq = [l for l in seq if l["mode"] != 1 or l["Cin"] == 3]
         return [(0.0, elems(l) * (base + (extra if l["mode"] == 2 else 0))) for l in seq]
-    n_params = sum(plan.sizes)
+    # two launches each: every tensor but the stem's weight, then the stem's weight (whose gradient comes last)
+    n_params, n_stem = sum(plan.sizes), plan.sizes[0]
     if tag == "lars_norms":
-        return [(0.0, 8.0 * n_params)]
+        return [(0.0, 8.0 * (n_params - n_stem)), (0.0, 8.0 * n_stem)]
     if tag == "lars_apply":
-        return [(0.0, (20.0 + (2.0 if plan.dtype == 1 else 0.0)) * n_params)]
+        per = 20.0 + (2.0 if plan.dtype == 1 else 0.0)
+        return [(0.0, per * (n_params - n_stem)), (0.0, per * n_stem)]
     raise KeyError(tag)
 
 
