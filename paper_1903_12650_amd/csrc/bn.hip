@@ -244,17 +244,12 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
   const int tcol = threadIdx.x & (TX - 1), trow = threadIdx.x >> tx_log2;
   const int col = blockIdx.y * TX + tcol;
   if (col >= C / V) return;
-  float scale[V], bias[V];
-#pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const int c = col * V + j;
-    bn_coeffs(gamma[c], beta[c], mean[c], rstd[c], &scale[j], &bias[j]);
-  }
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
   const int64_t r1 = min(r0 + rpb, m);
-  for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
-    int64_t off[kBnRows];
-    Vec16 vx[kBnRows], vr[kBnRows];
+  int64_t r = r0 + trow;
+  int64_t off[kBnRows];
+  Vec16 vx[kBnRows], vr[kBnRows];
+  auto load_rows = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < kBnRows; ++u) {
       off[u] = min(r + u * TY, r1 - 1) * C + static_cast<int64_t>(col) * V;
@@ -264,6 +259,17 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
 #pragma unroll
       for (int u = 0; u < kBnRows; ++u) vr[u] = load16(residual + off[u]);
     }
+  };
+  // the first rows are requested before the per-channel values, so both arrive in one round trip
+  if (r < r1) load_rows();
+  float scale[V], bias[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const int c = col * V + j;
+    bn_coeffs(gamma[c], beta[c], mean[c], rstd[c], &scale[j], &bias[j]);
+  }
+  for (; r < r1; r += kBnRows * TY) {
+    if (r != r0 + trow) load_rows();
 #pragma unroll
     for (int u = 0; u < kBnRows; ++u) {
       if (r + u * TY < r1) {
@@ -298,16 +304,20 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
 }
 
 // ------------------------------------------------------------------ backward
+// The backward kernels are compiled per operand set, so that a thread only holds registers for what its
+// launch reads: DZ2 = a second gradient branch is added; ZK = where the ReLU decision comes from
+// (0: recomputed from x, or no ReLU; 1: the forward output z; 2: the recorded bits).
 // The operands of kBnRows rows, loaded before any is used.
+template <bool DZ2, int ZK>
 struct BwdRows {
-  Vec16 x[kBnRows], dz[kBnRows], dz2[kBnRows], z[kBnRows];
-  uint32_t zbits[kBnRows];  // when the forward pass recorded the ReLU decision bits instead
+  Vec16 x[kBnRows], dz[kBnRows], dz2[DZ2 ? kBnRows : 1], z[ZK == 1 ? kBnRows : 1];
+  uint32_t zbits[ZK == 2 ? kBnRows : 1];
   int64_t off[kBnRows];
 };
-template <typename T>
-__device__ __forceinline__ void load_bwd_rows(BwdRows& b, const T* dz, const T* dz2, const T* x, const T* z,
-                                              const uint8_t* zmask, int64_t r, int64_t r1, int TY, int C,
-                                              int col) {
+template <typename T, bool DZ2, int ZK>
+__device__ __forceinline__ void load_bwd_rows(BwdRows<DZ2, ZK>& b, const T* dz, const T* dz2, const T* x,
+                                              const T* z, const uint8_t* zmask, int64_t r, int64_t r1, int TY,
+                                              int C, int col) {
   constexpr int V = Elem<T>::VEC;
 #pragma unroll
   for (int u = 0; u < kBnRows; ++u) {
@@ -315,25 +325,29 @@ __device__ __forceinline__ void load_bwd_rows(BwdRows& b, const T* dz, const T* 
     b.x[u] = load16(x + b.off[u]);
     b.dz[u] = load16(dz + b.off[u]);
   }
-  if (dz2) {
+  if (DZ2) {
 #pragma unroll
-    for (int u = 0; u < kBnRows; ++u) b.dz2[u] = load16(dz2 + b.off[u]);
+    for (int u = 0; u < kBnRows; ++u) b.dz2[DZ2 ? u : 0] = load16(dz2 + b.off[u]);
   }
-  if (zmask) {
+  if (ZK == 2) {
 #pragma unroll
-    for (int u = 0; u < kBnRows; ++u) b.zbits[u] = zmask[b.off[u] / V];
-  } else if (z) {
+    for (int u = 0; u < kBnRows; ++u) b.zbits[ZK == 2 ? u : 0] = zmask[b.off[u] / V];
+  } else if (ZK == 1) {
 #pragma unroll
-    for (int u = 0; u < kBnRows; ++u) b.z[u] = load16(z + b.off[u]);
+    for (int u = 0; u < kBnRows; ++u) b.z[ZK == 1 ? u : 0] = load16(z + b.off[u]);
   }
 }
 
 // g = (dz + dz2) * mask for one 16-byte vector.
-template <typename T>
-__device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2, const Vec16& vz, uint32_t zbits,
-                                            bool has_dz2, bool has_z, bool has_zbits, const float* xf,
-                                            const float* scale, const float* bias, int mode, float* g) {
+template <typename T, bool DZ2, int ZK>
+__device__ __forceinline__ void masked_grad(const BwdRows<DZ2, ZK>& b, int u, const float* xf, const float* scale,
+                                            const float* bias, int mode, float* g) {
   constexpr int V = Elem<T>::VEC;
+  const Vec16& vdz = b.dz[u];
+  const Vec16& vdz2 = b.dz2[DZ2 ? u : 0];
+  const Vec16& vz = b.z[ZK == 1 ? u : 0];
+  const uint32_t zbits = b.zbits[ZK == 2 ? u : 0];
+  constexpr bool has_dz2 = DZ2, has_z = ZK == 1, has_zbits = ZK == 2;
   Elem<T>::unpack(vdz, g);
   if (has_dz2) {
     float g2[V];
@@ -357,7 +371,7 @@ __device__ __forceinline__ void masked_grad(const Vec16& vdz, const Vec16& vdz2,
   }
 }
 
-template <typename T>
+template <typename T, bool DZ2, int ZK>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const T* __restrict__ dz, const T* __restrict__ dz2, const T* __restrict__ x,
     const T* __restrict__ z, const uint8_t* __restrict__ zmask, const float* __restrict__ gamma,
@@ -385,15 +399,14 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
     const int64_t r1 = min(r0 + rpb, m);
     for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
-      BwdRows b;
-      load_bwd_rows<T>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
+      BwdRows<DZ2, ZK> b;
+      load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
 #pragma unroll
       for (int u = 0; u < kBnRows; ++u) {
         if (r + u * TY < r1) {
           float xf[V], g[V];
           Elem<T>::unpack(b.x[u], xf);
-          masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], b.zbits[u], dz2 != nullptr, z != nullptr, zmask != nullptr, xf, scale, bias,
-                         mode, g);
+          masked_grad<T, DZ2, ZK>(b, u, xf, scale, bias, mode, g);
 #pragma unroll
           for (int j = 0; j < V; ++j) {
             acc[j] += g[j];
@@ -451,7 +464,7 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
   dgamma[c] = static_cast<float>(s2);
 }
 
-template <typename T>
+template <typename T, bool DZ2, int ZK>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     const T* __restrict__ dz, const T* __restrict__ dz2, const T* __restrict__ x,
     const T* __restrict__ z, const uint8_t* __restrict__ zmask, const float* __restrict__ gamma,
@@ -464,6 +477,12 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
   const int tcol = threadIdx.x & (TX - 1), trow = threadIdx.x >> tx_log2;
   const int col = blockIdx.y * TX + tcol;
   if (col >= C / V) return;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
+  const int64_t r1 = min(r0 + rpb, m);
+  int64_t r = r0 + trow;
+  // the first rows are requested before the per-channel values, so both arrive in one round trip
+  BwdRows<DZ2, ZK> b;
+  if (r < r1) load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
   const float inv_m = 1.0f / static_cast<float>(m);
   float scale[V], bias[V], rs[V], nmr[V], mg[V], mgx[V];
 #pragma unroll
@@ -475,18 +494,14 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     mg[j] = dbeta[c] * inv_m;
     mgx[j] = dgamma[c] * inv_m;
   }
-  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
-  const int64_t r1 = min(r0 + rpb, m);
-  for (int64_t r = r0 + trow; r < r1; r += kBnRows * TY) {
-    BwdRows b;
-    load_bwd_rows<T>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
+  for (; r < r1; r += kBnRows * TY) {
+    if (r != r0 + trow) load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
 #pragma unroll
     for (int u = 0; u < kBnRows; ++u) {
       if (r + u * TY < r1) {
         float xf[V], g[V], o[V];
         Elem<T>::unpack(b.x[u], xf);
-        masked_grad<T>(b.dz[u], b.dz2[u], b.z[u], b.zbits[u], dz2 != nullptr, z != nullptr, zmask != nullptr, xf, scale, bias,
-                         mode, g);
+        masked_grad<T, DZ2, ZK>(b, u, xf, scale, bias, mode, g);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
           const float xh = fmaf(xf[j], rs[j], nmr[j]);
@@ -554,7 +569,18 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             int nrows, hipStream_t s) {
   RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 384);
-  RN50_LAUNCH("bn_bwd_apply", bn_bwd_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, dgamma, dbeta, static_cast<T*>(dx), static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+#define RN50_BWD_APPLY(DZ2, ZK)                                                                                  \
+  RN50_LAUNCH("bn_bwd_apply", (bn_bwd_apply_kernel<T, DZ2, ZK>), dim3(ga.nblk, ga.gy), dim3(256), 0, s,            \
+              static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x),                     \
+              static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, dgamma, dbeta, static_cast<T*>(dx),        \
+              static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode)
+  const int zk = d->mode == 0 ? 0 : (zmask ? 2 : (z ? 1 : 0));
+  if (dz2) {
+    if (zk == 2) RN50_BWD_APPLY(true, 2); else if (zk == 1) RN50_BWD_APPLY(true, 1); else RN50_BWD_APPLY(true, 0);
+  } else {
+    if (zk == 2) RN50_BWD_APPLY(false, 2); else if (zk == 1) RN50_BWD_APPLY(false, 1); else RN50_BWD_APPLY(false, 0);
+  }
+#undef RN50_BWD_APPLY
 }
 
 template <typename T>
@@ -563,7 +589,17 @@ static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
                        const float* gamma, const float* beta, const float* mean, const float* rstd, void* dx,
                        void* dres, float* dgamma, float* dbeta, float* partial, hipStream_t s) {
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
-  RN50_LAUNCH("bn_bwd_reduce", bn_bwd_reduce_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x), static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial);
+#define RN50_BWD_REDUCE(DZ2, ZK)                                                                                 \
+  RN50_LAUNCH("bn_bwd_reduce", (bn_bwd_reduce_kernel<T, DZ2, ZK>), dim3(g.nblk, g.gy), dim3(256), lds, s,          \
+              static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x),                     \
+              static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, m, d->C, g.tx_log2, g.rpb, d->mode, partial)
+  const int zk = d->mode == 0 ? 0 : (zmask ? 2 : (z ? 1 : 0));
+  if (dz2) {
+    if (zk == 2) RN50_BWD_REDUCE(true, 2); else if (zk == 1) RN50_BWD_REDUCE(true, 1); else RN50_BWD_REDUCE(true, 0);
+  } else {
+    if (zk == 2) RN50_BWD_REDUCE(false, 2); else if (zk == 1) RN50_BWD_REDUCE(false, 1); else RN50_BWD_REDUCE(false, 0);
+  }
+#undef RN50_BWD_REDUCE
   launch_bwd_tail<T>(d, g, m, dz, dz2, x, z, zmask, gamma, beta, mean, rstd, dx, dres, dgamma, dbeta, partial,
                      g.nblk, s);
 }
