@@ -262,12 +262,13 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
   };
   // the first rows are requested before the per-channel values, so both arrive in one round trip
   if (r < r1) load_rows();
-  float scale[V], bias[V];
+  float scale[V], bias[V], cg[V], cb[V], cm[V], cr[V];
+  load_floats<V>(gamma + col * V, cg);
+  load_floats<V>(beta + col * V, cb);
+  load_floats<V>(mean + col * V, cm);
+  load_floats<V>(rstd + col * V, cr);
 #pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const int c = col * V + j;
-    bn_coeffs(gamma[c], beta[c], mean[c], rstd[c], &scale[j], &bias[j]);
-  }
+  for (int j = 0; j < V; ++j) bn_coeffs(cg[j], cb[j], cm[j], cr[j], &scale[j], &bias[j]);
   for (; r < r1; r += kBnRows * TY) {
     if (r != r0 + trow) load_rows();
 #pragma unroll
@@ -388,13 +389,20 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 #pragma unroll
   for (int j = 0; j < 2 * V; ++j) acc[j] = 0.f;
   if (active) {
-    float scale[V], bias[V], rs[V], nmr[V];
+    float scale[V], bias[V], rs[V], nmr[V], cg[V], cb[V], cm[V];
+    load_floats<V>(gamma + col * V, cg);
+    load_floats<V>(mean + col * V, cm);
+    load_floats<V>(rstd + col * V, rs);
+    if (beta) {
+      load_floats<V>(beta + col * V, cb);
+    } else {
+#pragma unroll
+      for (int j = 0; j < V; ++j) cb[j] = 0.f;
+    }
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-      const int c = col * V + j;
-      rs[j] = rstd[c];
-      nmr[j] = -mean[c] * rs[j];
-      bn_coeffs(gamma[c], beta ? beta[c] : 0.f, mean[c], rs[j], &scale[j], &bias[j]);
+      nmr[j] = -cm[j] * rs[j];
+      bn_coeffs(cg[j], cb[j], cm[j], rs[j], &scale[j], &bias[j]);
     }
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
     const int64_t r1 = min(r0 + rpb, m);
@@ -484,15 +492,24 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
   BwdRows<DZ2, ZK> b;
   if (r < r1) load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
   const float inv_m = 1.0f / static_cast<float>(m);
-  float scale[V], bias[V], rs[V], nmr[V], mg[V], mgx[V];
+  float scale[V], bias[V], rs[V], nmr[V], mg[V], mgx[V], cg[V], cb[V], cm[V];
+  load_floats<V>(gamma + col * V, cg);
+  load_floats<V>(mean + col * V, cm);
+  load_floats<V>(rstd + col * V, rs);
+  load_floats<V>(dbeta + col * V, mg);
+  load_floats<V>(dgamma + col * V, mgx);
+  if (beta) {
+    load_floats<V>(beta + col * V, cb);
+  } else {
+#pragma unroll
+    for (int j = 0; j < V; ++j) cb[j] = 0.f;
+  }
 #pragma unroll
   for (int j = 0; j < V; ++j) {
-    const int c = col * V + j;
-    rs[j] = rstd[c];
-    nmr[j] = -mean[c] * rs[j];
-    bn_coeffs(gamma[c], beta ? beta[c] : 0.f, mean[c], rs[j], &scale[j], &bias[j]);
-    mg[j] = dbeta[c] * inv_m;
-    mgx[j] = dgamma[c] * inv_m;
+    nmr[j] = -cm[j] * rs[j];
+    bn_coeffs(cg[j], cb[j], cm[j], rs[j], &scale[j], &bias[j]);
+    mg[j] *= inv_m;
+    mgx[j] *= inv_m;
   }
   for (; r < r1; r += kBnRows * TY) {
     if (r != r0 + trow) load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
@@ -686,7 +703,8 @@ extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz
   RN50_REQUIRE(d->mode != 1 || z || relu_mask || beta, RN50_ERR_INVALID,
                "bn_relu_bwd: mode 1 needs z, relu_mask, or beta to recompute the ReLU mask");
   RN50_REQUIRE(aligned16(dz) && aligned16(dz2) && aligned16(x) && aligned16(z) && aligned16(dx) &&
-                   aligned16(dresidual) && aligned16(workspace),
+                   aligned16(dresidual) && aligned16(workspace) && aligned16(gamma) && aligned16(beta) &&
+                   aligned16(save_mean) && aligned16(save_rstd) && aligned16(dgamma) && aligned16(dbeta),
                RN50_ERR_ALIGN, "bn_relu_bwd: pointer not 16-byte aligned");
   RN50_REQUIRE(workspace_bytes >= bn_ws_bytes(d), RN50_ERR_WORKSPACE,
                "bn_relu_bwd: workspace %zu < %zu bytes", workspace_bytes, bn_ws_bytes(d));
@@ -745,7 +763,9 @@ extern "C" int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc
                "bn_relu_bwd_from_sums: bad producer descriptor");
   RN50_REQUIRE(dz && x && gamma && beta && save_mean && save_rstd && sums && dx && dgamma && dbeta,
                RN50_ERR_INVALID, "bn_relu_bwd_from_sums: null pointer");
-  RN50_REQUIRE(aligned16(dz) && aligned16(x) && aligned16(dx) && aligned16(sums) && aligned16(dresidual),
+  RN50_REQUIRE(aligned16(dz) && aligned16(x) && aligned16(dx) && aligned16(sums) && aligned16(dresidual) &&
+                   aligned16(gamma) && aligned16(beta) && aligned16(save_mean) && aligned16(save_rstd) &&
+                   aligned16(dgamma) && aligned16(dbeta),
                RN50_ERR_ALIGN, "bn_relu_bwd_from_sums: pointer not 16-byte aligned");
   RN50_REQUIRE(producer->N == d->N && producer->H == d->H && producer->W == d->W && producer->Cin == d->C &&
                    producer->dtype == d->dtype,

@@ -124,6 +124,16 @@ __device__ __forceinline__ void bn_coeffs(float gamma, float beta, float mean, f
   *bias = fmaf(-mean, *scale, beta);
 }
 
+// V (4 or 8) consecutive floats from a 16-byte aligned address, as 16-byte loads.
+template <int V>
+__device__ __forceinline__ void load_floats(const float* __restrict__ p, float* out) {
+#pragma unroll
+  for (int i = 0; i < V / 4; ++i) {
+    const float4 v = *reinterpret_cast<const float4*>(p + 4 * i);
+    out[4 * i] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+  }
+}
+
 // ------------------------------------------------------- device: reductions
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -401,12 +401,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       if (add) av[pass] = load16(add + at);
       if (a.bn_zmask) zb[pass] = a.bn_zmask[at / V];
     }
-    float scale[V], bias[V], rs[V], nmr[V];
+    float scale[V], bias[V], rs[V], nmr[V], cg[V], cb[V], cm[V];
+    load_floats<V>(a.bn_gamma + nc, cg);
+    load_floats<V>(a.bn_beta + nc, cb);
+    load_floats<V>(a.bn_mean + nc, cm);
+    load_floats<V>(a.bn_rstd + nc, rs);
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-      rs[j] = a.bn_rstd[nc + j];
-      nmr[j] = -a.bn_mean[nc + j] * rs[j];
-      bn_coeffs(a.bn_gamma[nc + j], a.bn_beta[nc + j], a.bn_mean[nc + j], rs[j], &scale[j], &bias[j]);
+      nmr[j] = -cm[j] * rs[j];
+      bn_coeffs(cg[j], cb[j], cm[j], rs[j], &scale[j], &bias[j]);
     }
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
@@ -1282,7 +1285,8 @@ extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const
   RN50_REQUIRE(dy && w && dx && workspace && bn_x && gamma && beta && save_mean && save_rstd && sums,
                RN50_ERR_INVALID, "conv_dgrad_bn_sums: null pointer");
   RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(workspace) && aligned16(bn_x) &&
-                   aligned16(sums) && aligned16(addend),
+                   aligned16(sums) && aligned16(addend) && aligned16(gamma) && aligned16(beta) &&
+                   aligned16(save_mean) && aligned16(save_rstd),
                RN50_ERR_ALIGN, "conv_dgrad_bn_sums: pointer not 16-byte aligned");
   RN50_REQUIRE(workspace_bytes >= dgrad_wt_bytes(d), RN50_ERR_WORKSPACE,
                "conv_dgrad_bn_sums: workspace %zu < %zu bytes", workspace_bytes, dgrad_wt_bytes(d));
