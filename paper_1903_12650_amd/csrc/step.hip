@@ -60,6 +60,11 @@ struct rn50_plan {
   size_t dy_ring[kDyRing] = {0, 0, 0, 0, 0, 0, 0, 0};
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_wt = nullptr;
+  // Third stream: the projection shortcut of a stage's first block, forward and backward, runs beside the
+  // block's main branch (its own BN scratch; fork/join events reused block after block).
+  hipStream_t branch = nullptr;
+  hipEvent_t ev_bfork = nullptr, ev_bjoin = nullptr;
+  size_t bn_scratch2 = 0;
   std::vector<hipEvent_t> ev_dy, ev_wg;  // per block: its dy tensors are ready / its weight gradients are done
 };
 
@@ -187,6 +192,7 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->fc_scratch = bump(&top, p->fc_scratch_bytes);
   p->wgrad_scratch = bump(&top, max_wg);
   p->bn_scratch = bump(&top, max_bn);
+  p->bn_scratch2 = bump(&top, max_bn);
   p->bn_scratch_bytes = max_bn;
   // The stem's weight gradient is the last thing the backward pass produces; the update of every other
   // tensor runs beside it.
@@ -211,6 +217,12 @@ extern "C" void resnet_plan_destroy(rn50_plan* plan) {
     (void)hipStreamSynchronize(plan->side);
     (void)hipStreamDestroy(plan->side);
   }
+  if (plan->branch) {
+    (void)hipStreamSynchronize(plan->branch);
+    (void)hipStreamDestroy(plan->branch);
+  }
+  if (plan->ev_bfork) (void)hipEventDestroy(plan->ev_bfork);
+  if (plan->ev_bjoin) (void)hipEventDestroy(plan->ev_bjoin);
   if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
   if (plan->ev_wt) (void)hipEventDestroy(plan->ev_wt);
   for (hipEvent_t e : plan->ev_dy) (void)hipEventDestroy(e);
@@ -224,6 +236,9 @@ int ensure_side_stream(rn50_plan* p) {
   if (p->side) return RN50_OK;
   auto ok = [](hipError_t e) { return e == hipSuccess; };
   bool good = ok(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking)) &&
+              ok(hipStreamCreateWithFlags(&p->branch, hipStreamNonBlocking)) &&
+              ok(hipEventCreateWithFlags(&p->ev_bfork, hipEventDisableTiming)) &&
+              ok(hipEventCreateWithFlags(&p->ev_bjoin, hipEventDisableTiming)) &&
               ok(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming)) &&
               ok(hipEventCreateWithFlags(&p->ev_wt, hipEventDisableTiming));
   for (size_t i = 0; good && i < p->blocks.size() + 1; ++i) {  // the blocks and the stem
@@ -302,33 +317,39 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   stem_pad_input(&u0.conv, images, ws + plan->xp, s);
   // Every convolution leaves the sums its batch norm needs, one row per output tile, in bn_ws.
   float* sums = static_cast<float*>(bn_ws);
-  auto bn_after_conv = [&](Unit& u, const void* residual) {
+  hipStream_t branch = plan->branch;
+  void* bn_ws2 = ws + plan->bn_scratch2;  // the projection branch's own BN scratch
+  float* sums2 = static_cast<float*>(bn_ws2);
+  auto bn_after_conv = [&](Unit& u, const void* residual, float* sm, hipStream_t st) {
     const PartialRows pr = fwd_partial_rows(&u.conv);
     // the residual-add layers record their ReLU decisions: their backward pass then reads one byte per
     // vector instead of z
-    bn_fwd_from_partials(&u.bn, ws + u.y, sums, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z,
-                         u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd), nullptr, nullptr, 0.f, s);
+    bn_fwd_from_partials(&u.bn, ws + u.y, sm, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z,
+                         u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd), nullptr, nullptr, 0.f, st);
   };
   stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, sums, s);
-  bn_after_conv(u0, nullptr);
+  bn_after_conv(u0, nullptr, sums, s);
   STEP_TRY(maxpool_fwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool, ws + plan->pool_argmax, s));
   const unsigned char* cur = ws + plan->pool;
-  auto conv_bn = [&](Unit& u, const void* in, const void* residual) -> int {
-    fwd_run(&u.conv, in, W(u.iw), ws + u.y, sums, s);
-    bn_after_conv(u, residual);
-    return RN50_OK;
+  auto conv_bn = [&](Unit& u, const void* in, const void* residual, float* sm, hipStream_t st) {
+    fwd_run(&u.conv, in, W(u.iw), ws + u.y, sm, st);
+    bn_after_conv(u, residual, sm, st);
   };
   for (const Block& b : plan->blocks) {
     Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
-    STEP_TRY(conv_bn(u1, cur, nullptr));
-    STEP_TRY(conv_bn(u2, ws + u1.z, nullptr));
     const void* shortcut = cur;
-    if (b.up >= 0) {
+    if (b.up >= 0) {  // the projection shortcut runs beside conv1 and conv2
       Unit& up = plan->units[b.up];
-      STEP_TRY(conv_bn(up, cur, nullptr));
+      (void)hipEventRecord(plan->ev_bfork, s);
+      (void)hipStreamWaitEvent(branch, plan->ev_bfork, 0);
+      conv_bn(up, cur, nullptr, sums2, branch);
+      (void)hipEventRecord(plan->ev_bjoin, branch);
       shortcut = ws + up.z;
     }
-    STEP_TRY(conv_bn(u3, ws + u2.z, shortcut));
+    conv_bn(u1, cur, nullptr, sums, s);
+    conv_bn(u2, ws + u1.z, nullptr, sums, s);
+    if (b.up >= 0) (void)hipStreamWaitEvent(s, plan->ev_bjoin, 0);
+    conv_bn(u3, ws + u2.z, shortcut, sums, s);
     cur = ws + u3.z;
   }
   const int HW = plan->final_hw * plan->final_hw;
@@ -376,29 +397,42 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     npending = 0;
     ++blk;
   };
-  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, void* dx,
-                      bool sums_ready, Unit* below, const void* addend) -> int {
+  // Phase 1 of a unit: BN backward, dz (+dz2) -> dy (a ring slot; returned), on stream st with BN scratch wsx.
+  auto unit_bn_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, bool sums_ready,
+                         hipStream_t st, void* wsx, void** dy_out) -> int {
     void* dy = ws + plan->dy_ring[seq % rn50_plan::kDyRing];
     // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
     const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
     if (sums_ready) {
-      bn_bwd_from_partials(&u.bn, dz, ws + u.y, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), sums,
-                           dgrad_sums_rows, dy, u.bn.mode == 2 ? dres : nullptr, G(u.ig), G(u.ib), s);
+      bn_bwd_from_partials(&u.bn, dz, ws + u.y, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd),
+                           static_cast<const float*>(wsx), dgrad_sums_rows, dy, u.bn.mode == 2 ? dres : nullptr,
+                           G(u.ig), G(u.ib), st);
     } else {
       STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, nullptr, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
-                           G(u.ig), G(u.ib), bn_ws, bn_ws_bytes, s));
+                           G(u.ig), G(u.ib), wsx, bn_ws_bytes, st));
     }
     pending[npending++] = PendingWgrad{&u, in, dy};
-    if (dx) {
-      BnBwdSums fuse{};
-      if (below) {
-        fuse = BnBwdSums{ws + below->y, MP(below->ig), MP(below->ib), F(below->mean), F(below->rstd), sums, addend,
-                         below->bn.mode == 2 ? ws + below->relu_mask : nullptr};
-        dgrad_sums_rows = dgrad_partial_rows(&u.conv).num;
-      }
-      dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, below ? &fuse : nullptr, s);
-    }
     ++seq;
+    *dy_out = dy;
+    return RN50_OK;
+  };
+  // Phase 2: the data gradient of dy into dx.  `below`: the unit whose BN output is this unit's input,
+  // when dx (+ addend, the gradient of that output's other consumer) is its complete dz: the data gradient
+  // then stores the sum and leaves that layer's sums in bn_ws.
+  auto unit_dgrad = [&](Unit& u, const void* dy, void* dx, Unit* below, const void* addend, hipStream_t st) {
+    BnBwdSums fuse{};
+    if (below) {
+      fuse = BnBwdSums{ws + below->y, MP(below->ig), MP(below->ib), F(below->mean), F(below->rstd), sums, addend,
+                       below->bn.mode == 2 ? ws + below->relu_mask : nullptr};
+      dgrad_sums_rows = dgrad_partial_rows(&u.conv).num;
+    }
+    dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, below ? &fuse : nullptr, st);
+  };
+  auto unit_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, void* dx,
+                      bool sums_ready, Unit* below, const void* addend) -> int {
+    void* dy = nullptr;
+    STEP_TRY(unit_bn_bwd(u, in, dz, dz2, dres, sums_ready, s, bn_ws, &dy));
+    if (dx) unit_dgrad(u, dy, dx, below, addend, s);
     return RN50_OK;
   };
   // dzo (+ dzo2): the gradient w.r.t. the current block's output; top_sums: its BN sums are in bn_ws
@@ -410,21 +444,32 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     Unit* prev = bi > 0 ? &plan->units[plan->blocks[bi - 1].u3] : nullptr;  // its BN output is this block's input
     const void* block_in = prev ? static_cast<const void*>(ws + prev->z) : static_cast<const void*>(ws + plan->pool);
     block_begin();
-    STEP_TRY(unit_bwd(u3, ws + u2.z, dzo, dzo2, g[3], g[4], top_sums, &u2, nullptr));   // g[3]: gradient of the shortcut
+    // The block input has two consumers (conv1 and the shortcut).  conv1's data gradient comes last: it
+    // adds the shortcut's gradient and takes the sums of the previous block's last BN layer.
+    void* dy3 = nullptr;
+    STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, g[3], top_sums, s, bn_ws, &dy3));   // g[3]: gradient of the shortcut
+    const void* shortcut_grad = g[3];
+    if (b.up >= 0) {  // the projection's backward pass runs beside the main branch, on its own stream
+      Unit& up = plan->units[b.up];
+      (void)hipEventRecord(plan->ev_bfork, s);
+      (void)hipStreamWaitEvent(branch, plan->ev_bfork, 0);
+      void* dyp = nullptr;
+      STEP_TRY(unit_bn_bwd(up, block_in, g[3], nullptr, nullptr, false, branch, bn_ws2, &dyp));
+      unit_dgrad(up, dyp, g[1], nullptr, nullptr, branch);
+      (void)hipEventRecord(plan->ev_bjoin, branch);
+      shortcut_grad = g[1];
+    }
+    unit_dgrad(u3, dy3, g[4], &u2, nullptr, s);
     STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, nullptr, g[4], true, &u1, nullptr));
-    // The block input has two consumers (conv1 and the shortcut).  The last data gradient into it adds
-    // the other branch and takes the sums of the previous block's last BN layer.
-    if (b.up < 0) {
-      STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, nullptr, g[0], true, prev, g[3]));
-      dzo = g[0]; dzo2 = nullptr; top_sums = prev != nullptr;
-    } else {
-      STEP_TRY(unit_bwd(u1, block_in, g[4], nullptr, nullptr, g[0], true, nullptr, nullptr));
-      STEP_TRY(unit_bwd(plan->units[b.up], block_in, g[3], nullptr, nullptr, g[1], false, prev, g[0]));
-      if (prev) {
-        dzo = g[1]; dzo2 = nullptr; top_sums = true;
-      } else {  // the first block: the max-pool's backward pass adds the two branches
-        dzo = g[0]; dzo2 = g[1]; top_sums = false;
-      }
+    void* dy1 = nullptr;
+    STEP_TRY(unit_bn_bwd(u1, block_in, g[4], nullptr, nullptr, true, s, bn_ws, &dy1));
+    if (b.up >= 0) (void)hipStreamWaitEvent(s, plan->ev_bjoin, 0);
+    if (prev) {
+      unit_dgrad(u1, dy1, g[0], prev, shortcut_grad, s);
+      dzo = g[0]; dzo2 = nullptr; top_sums = true;
+    } else {  // the first block: the max-pool's backward pass adds the two branches
+      unit_dgrad(u1, dy1, g[0], nullptr, nullptr, s);
+      dzo = g[0]; dzo2 = shortcut_grad; top_sums = false;
     }
     block_end();
   }

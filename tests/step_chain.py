@@ -165,11 +165,12 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
             d2 = None
             gl = g1 + g2 + g3
         else:
-            dxa, _, g1, _ = ch.cbn_bwd(t1, dz1_, sums=s1)
-            dxb, _, gp, top_sums = ch.cbn_bwd(tp, dres, below=prev, addend=dxa if prev is not None else None)
+            # projection shortcut: its data gradient is plain; conv1's comes last and adds it
+            dxb, _, gp, _ = ch.cbn_bwd(tp, dres)
+            dxa, _, g1, top_sums = ch.cbn_bwd(t1, dz1_, sums=s1, below=prev, addend=dxb if prev is not None else None)
             gl = g1 + g2 + g3 + gp
             if prev is not None:
-                d, d2 = dxb, None
+                d, d2 = dxa, None
             else:
                 d, d2 = dxa, dxb
         block_grads.append(gl)
