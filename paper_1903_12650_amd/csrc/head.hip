@@ -293,6 +293,75 @@ __global__ __launch_bounds__(256) void small_gemm_kernel(const TA* __restrict__ 
 // logits[n][k] = sum_c a[n][c]*W[k][c] + b[k]: one wave per class k.  The wave streams its weight row
 // once per block of 8 batch rows (the activations, N*Cin elements, stay in cache), accumulates in
 // float and finishes each dot product with a wave reduction.
+__device__ __forceinline__ f32x16 mfma_bf16_32x32x16(const Vec16& a, const Vec16& b, f32x16 acc) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a),
+                                                 *reinterpret_cast<const bf16x8*>(&b), acc, 0, 0, 0);
+}
+
+// Matrix-core form for bf16 and a batch of at most 64 rows: a workgroup owns 32 classes; its four waves
+// split the input channels (wave w takes channels 16*(w + 4i)..+15), each multiplying the [32 classes x
+// 16] weight fragment with the [16 x 32 rows] activation fragments read straight from memory
+// (v_mfma_f32_32x32x16_bf16: lane l supplies row l%32, k = 8*(l/32)..+7 of both operands).  The waves'
+// partial tiles are added through LDS in wave order.  Every workgroup reads the activations once.
+__global__ __launch_bounds__(256) void fc_fwd_mfma_kernel(const uint16_t* __restrict__ a,
+                                                          const uint16_t* __restrict__ W,
+                                                          const float* __restrict__ b,
+                                                          float* __restrict__ logits, int N, int Cin, int K) {
+  __shared__ float red[4][2][32 * 32];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int k0 = blockIdx.x * 32;
+  const int krow = min(k0 + (lane & 31), K - 1);
+  const int n_lo = min(lane & 31, N - 1), n_hi = min(32 + (lane & 31), N - 1);
+  const bool hi_ok = 32 + (lane & 31) < N, lo_ok = (lane & 31) < N;
+  const uint16_t* wp = W + static_cast<int64_t>(krow) * Cin + 8 * (lane >> 5);
+  const uint16_t* ap0 = a + static_cast<int64_t>(n_lo) * Cin + 8 * (lane >> 5);
+  const uint16_t* ap1 = a + static_cast<int64_t>(n_hi) * Cin + 8 * (lane >> 5);
+  f32x16 acc0, acc1;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+  constexpr int U = 4;
+  int c = wave * 16;
+  for (; c + (U - 1) * 64 < Cin; c += U * 64) {
+    Vec16 fw[U], f0[U], f1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      fw[u] = load16(wp + c + u * 64);
+      f0[u] = load16(ap0 + c + u * 64);
+      f1[u] = load16(ap1 + c + u * 64);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!lo_ok) f0[u].u = make_uint4(0, 0, 0, 0);
+      if (!hi_ok) f1[u].u = make_uint4(0, 0, 0, 0);
+      acc0 = mfma_bf16_32x32x16(fw[u], f0[u], acc0);
+      acc1 = mfma_bf16_32x32x16(fw[u], f1[u], acc1);
+    }
+  }
+  for (; c < Cin; c += 64) {
+    Vec16 fw = load16(wp + c), f0 = load16(ap0 + c), f1 = load16(ap1 + c);
+    if (!lo_ok) f0.u = make_uint4(0, 0, 0, 0);
+    if (!hi_ok) f1.u = make_uint4(0, 0, 0, 0);
+    acc0 = mfma_bf16_32x32x16(fw, f0, acc0);
+    acc1 = mfma_bf16_32x32x16(fw, f1, acc1);
+  }
+  // D[class][row]: class = (v/4)*8 + (lane/32)*4 + v%4, row = lane%32
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int cls = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+    red[wave][0][cls * 32 + (lane & 31)] = acc0[v];
+    red[wave][1][cls * 32 + (lane & 31)] = acc1[v];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * 32 * 32; i += 256) {
+    const int t = i >> 10, cls = (i >> 5) & 31, row = t * 32 + (i & 31);
+    const int k = k0 + cls;
+    if (k < K && row < N) {
+      const int j = cls * 32 + (i & 31);
+      logits[static_cast<int64_t>(row) * K + k] = ((red[0][t][j] + red[1][t][j]) + red[2][t][j]) + red[3][t][j] + b[k];
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void fc_fwd_kernel(const T* __restrict__ a, const T* __restrict__ W,
                                                      const float* __restrict__ b,
@@ -518,6 +587,11 @@ extern "C" int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const voi
   RN50_REQUIRE(Cin % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "fc_fwd: Cin=%d", Cin);
   RN50_REQUIRE(aligned16(a) && aligned16(W), RN50_ERR_ALIGN, "fc_fwd: pointer not 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == RN50_BF16 && N <= 64 && Cin % 16 == 0) {
+    RN50_LAUNCH("fc_fwd", fc_fwd_mfma_kernel, dim3(ceil_div(K, 32)), dim3(256), 0, s, static_cast<const uint16_t*>(a),
+                static_cast<const uint16_t*>(W), b, logits, N, Cin, K);
+    return launch_status("fc_fwd");
+  }
   DISPATCH_T(dtype, {
     hipLaunchKernelGGL(fc_fwd_kernel<T>, dim3(ceil_div(K, 4)), dim3(256), 0, s, static_cast<const T*>(a),
                        static_cast<const T*>(W), b, logits, N, Cin, K);

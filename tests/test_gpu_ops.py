@@ -195,6 +195,19 @@ def test_fc_ragged_sizes(rn):
     assert_close(da, da_o, 1e-6, "da"); assert_close(dW, dW_o, 1e-6, "dW"); assert_close(db, db_o, 1e-6, "db")
 
 
+@pytest.mark.parametrize("shape", [(40, 2048, 1000), (5, 80, 37), (64, 48, 64), (33, 144, 100), (1, 16, 8)])
+def test_fc_fwd_bf16_matrix_core_path(rn, shape):
+    """bf16 operands, batch <= 64, channels a multiple of 16: the classifier's forward runs on the matrix cores
+    (float accumulation of exact bf16 products: float-level agreement with the oracle on the same rounded inputs)."""
+    N, C, K = shape
+    a = synth.round_bf16(synth.normal(SEED, "a", (N, C)))
+    W = synth.round_bf16(synth.normal(SEED, "W", (K, C)) * 0.05)
+    b = synth.normal(SEED, "b", (K,))
+    got = rn.fc_fwd(dev(a, True), dev(W, True), dev(b))
+    assert got.dtype == torch.float32 and tuple(got.shape) == (N, K)
+    assert_close(got, orc.fc_fwd(a, W, b), 1e-5, "logits")
+
+
 # ------------------------------------------------------------------------ LARS
 def _lars_case(rn, table, grad_bf16=False, with_lowp=True, v_zero=True, apply_trust=None, eps=0.0):
     params = synth.params_from_table(SEED, table)
