@@ -3,12 +3,15 @@ independent of how the kernels are written) and the roofline record bench.py pri
 
 Per unit of work (elements are activation elements of the BN's tensor, bf16 = 2 bytes):
   conv_fwd / conv_dgrad  2*M*N*K flop;  bytes = es*(|in| + |out| + |w|), a 1x1 stride-2 conv only
-                         needs (and is only charged) every other row and column of its input
+                         needs (and is only charged) every other row and column of its input.
+                         A data gradient that also takes the backward sums of the BN layer below reads
+                         that layer's input (es*|dx| more), and, when it closes a block, the other
+                         gradient branch (es*|dx|) and the recorded ReLU bits (|dx|/8 bytes)
   conv_wgrad             2*M*N*K flop;  bytes = es*(|x| + |dy|) + 4*|dw|
   bn_apply               2*es bytes/element (read x, write y) + es for the residual read (mode 2)
   bn_bwd_reduce          2*es bytes/element (read dz, x); launched only for the layers whose sums are not
                          taken in the output stage of the data gradient that produces dz (the stem, the
-                         residual-add layers and the projection shortcuts)
+                         last block's residual-add layer and the projection shortcuts)
   bn_bwd_apply           3*es bytes/element (read dz, x, write dx) + es for dresidual (mode 2)
   lars_norms             8 bytes/parameter (read w, g)
   lars_apply             20 bytes/parameter (read w, g, v; write w, v) + 2 for the bf16 copy
@@ -20,15 +23,15 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
-DOMINANT_KERNEL = "conv_fwd"   # largest share of the step's kernel time (rocprofv3 summary under profiles/)
+DOMINANT_KERNEL = "conv_dgrad"  # largest share of the step's kernel time (rocprofv3 summary under profiles/)
 
 # HBM bytes per launch (fetch + write) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs summarized in
 # profiles/resnet50_step_batch40_bf16_hbm_traffic.txt (batch 40, bf16), already scaled by the calibration
 # copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
 # dirty in L2 are written back during later kernels.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "conv_fwd": 40.34e6, "conv_dgrad": 45.29e6, "conv_wgrad": 52.16e6, "bn_apply": 42.03e6,
-    "bn_bwd_reduce": 112.55e6, "bn_bwd_apply": 75.40e6, "lars_norms": 204.55e6, "lars_apply": 562.44e6,
+    "conv_fwd": 40.34e6, "conv_dgrad": 63.59e6, "conv_wgrad": 52.14e6, "bn_apply": 42.58e6,
+    "bn_bwd_reduce": 73.40e6, "bn_bwd_apply": 59.97e6, "lars_norms": 102.30e6, "lars_apply": 281.25e6,
 }
 
 
@@ -81,15 +84,28 @@ def per_launch_cost(tag, plan):
     if tag == "conv_fwd":
         return _fwd_order(L, [conv_cost(l) for l in L])
     if tag == "conv_dgrad":
-        return [conv_cost(l) for l in _bwd_order(L) if l["Cin"] != 3]
+        out = []
+        blocks = _blocks(L)[1:]
+        for bi in range(len(blocks) - 1, -1, -1):
+            b = blocks[bi]
+            for j, l in enumerate(b):
+                f, by = conv_cost(l)
+                dx = l["N"] * l["H"] * l["H"] * l["Cin"]
+                if j in (1, 2):            # conv2, conv3: sums of the BN+ReLU layer below (its input is read)
+                    by += es * dx
+                elif j == 0 and bi > 0:    # conv1 closes the block: + the shortcut's gradient, the previous
+                    by += 2 * es * dx + dx / 8   # block's BN input and its ReLU bits
+                out.append((f, by))
+        return out
     if tag == "conv_wgrad":
         return [conv_cost(l, True) for l in _bwd_order(L)]
     per_elem = {"bn_apply": (2 * es, es), "bn_bwd_reduce": (2 * es, 0), "bn_bwd_apply": (3 * es, es)}
     if tag in per_elem:
         base, extra = per_elem[tag]
         seq = _fwd_order(L, L) if tag == "bn_apply" else _bwd_order(L)
-        if tag == "bn_bwd_reduce":  # the BN+ReLU layers inside a block get their sums from the data gradient above
-            seq = [l for l in seq if l["mode"] != 1 or l["Cin"] == 3]
+        if tag == "bn_bwd_reduce":  # every other layer gets its sums from the data gradient that produces its dz
+            last_add = [l for l in L if l["mode"] == 2][-1]
+            seq = [l for l in seq if l["mode"] == 0 or l["Cin"] == 3 or l is last_add]
         return [(0.0, elems(l) * (base + (extra if l["mode"] == 2 else 0))) for l in seq]
     # two launches each: every tensor but the stem's weight, then the stem's weight (whose gradient comes last)
     n_params, n_stem = sum(plan.sizes), plan.sizes[0]
