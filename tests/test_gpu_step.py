@@ -237,3 +237,36 @@ def test_step_gradients_only_and_reproducible(rn):
         assert torch.equal(M0, M)                        # update=0: weights untouched
         outs.append((loss.clone(), G))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+def test_profile_hooks_and_plan_lifecycle(rn):
+    """The launch-timing aid counts exactly the tagged launches of the steps it is enabled for (pause
+    skips a step), and plans with their private streams can be created, used and destroyed in turn."""
+    import gc
+    for rep in range(2):
+        N, hw, widths, blocks, stem, classes = 2, 32, (8, 8, 8, 8), (1, 2, 1, 1), 8, 10
+        plan = rn.ResnetPlan(N, rn.BF16, hw, classes, widths, blocks, stem, 4)
+        M = torch.randn(plan.arena_elems, device="cuda") * 0.1
+        V = torch.zeros_like(M); G = torch.zeros_like(M); Mod = M.to(torch.bfloat16)
+        ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+        img = torch.randn(N, hw, hw, 3, device="cuda").to(torch.bfloat16)
+        lab = torch.zeros(N, dtype=torch.int32, device="cuda")
+        step = lambda: rn.resnet_step(plan, img, lab, M, V, G, Mod, 0.1, ws)
+        step()
+        torch.cuda.synchronize()
+        n_units = 1 + sum(blocks) * 3 + 4                       # stem, three per block, one projection per stage
+        rn.profile_begin("conv_wgrad", 1000)
+        step()
+        rn.profile_pause(True)
+        step()
+        rn.profile_pause(False)
+        step()
+        torch.cuda.synchronize()
+        ms = rn.profile_end()
+        assert len(ms) >= 2 * n_units and len(ms) % 2 == 0      # two timed steps; split-K reduces share the tag prefix
+        assert all(0.0 < t < 50.0 for t in ms), ms
+        loss = step()
+        torch.cuda.synchronize()
+        assert np.isfinite(float(loss.item()))
+        del plan
+        gc.collect()
