@@ -268,7 +268,7 @@ typedef struct {
   float eta, momentum, weight_decay, lars_eps; /* LARS; weight decay on conv/FC weights only */
 } rn50_step_config;
 
-typedef struct rn50_plan rn50_plan; /* host-side object; holds no device memory */
+typedef struct rn50_plan rn50_plan; /* host-side object (layout, two streams, events); holds no device memory */
 
 int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_out);
 void resnet_plan_destroy(rn50_plan* plan);
@@ -292,7 +292,13 @@ size_t resnet_plan_workspace_bytes(const rn50_plan* plan);
  * images: device [N,hw,hw,3] dtype (NHWC); labels: device int32[N].
  * loss_out: device float[1]; logits_out: device float[N,classes] or NULL.
  * lr: the learning rate of this step (schedules live with the caller).
- * If update == 0 the step stops after backward (gradients only). */
+ * If update == 0 the step stops after backward (gradients only).
+ * Stream semantics: everything is ordered after the work `stream` holds at the call and
+ * is complete when the work this call enqueues on `stream` is.  Inside, independent parts
+ * (weight gradients, the projection shortcuts, the weight transposition) run on two
+ * streams the plan creates at its first step (default priority; host-side handles, no
+ * device memory) and are forked from / joined into `stream` with events; the fork/join
+ * can be captured into a graph together with `stream`.  One step at a time per plan. */
 int resnet_step(rn50_plan* plan, const void* images, const int32_t* labels, float* master,
                 float* velocity, float* grads, void* model, float lr, int update, float* loss_out,
                 float* logits_out, void* workspace, size_t workspace_bytes, void* stream);
