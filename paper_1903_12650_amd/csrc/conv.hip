@@ -97,6 +97,7 @@ struct IgemmArgs {
   int R, S, stride, pad;
   int cpt;          // 128-byte chunks per tap
   int ntn;          // number of column tiles
+  int pair;         // stem in bf16: a 128-byte chunk holds two filter rows (pieces 0-3: row 2r, 4-7: row 2r+1)
   int nimg;         // images (M = nimg*P*Q)
   int tiles_per_class;  // stride-2 data gradient: row tiles per parity class of the output pixels
   int mode;         // host side only: selects the MODE template argument
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       int ih, iw;
       bool ok = true;
       if (MODE == 0) {
-        ih = a_h0[i] + cur_r;
+        ih = a_h0[i] + (a.pair ? 2 * cur_r + (piece >> 2) : cur_r);
         iw = a_w0[i] + cur_s;
       } else {
         const int th = a_h0[i] - cur_r, tw = a_w0[i] - cur_s;
@@ -224,7 +225,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       }
       ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
            static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
-      a_off[i] = ok ? static_cast<uint32_t>((a_base[i] + ih * a.W + iw) * a.PS + piece * V) * sizeof(T) : kOob;
+      const int pc = (MODE == 0 && a.pair) ? (piece & 3) : piece;
+      a_off[i] = ok ? static_cast<uint32_t>((a_base[i] + ih * a.W + iw) * a.PS + pc * V) * sizeof(T) : kOob;
     }
   };
   struct Staged {
@@ -495,6 +497,7 @@ struct WgradArgs {
   int tiles_per_split; // taps * ctiles * output-channel tiles
   int rows_per_split;  // multiple of the K chunk
   int linear;          // 1x1, stride 1, pad 0: gathered row m is pixel m
+  int pair;            // stem in bf16: a tap is two filter rows (column pieces 0-3: row 2r, 4-7: row 2r+1)
   int64_t split_stride;
   FastDiv divQ, divP;
 };
@@ -602,10 +605,11 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
         const int q = static_cast<int>(mm - t * a.Q);
         const uint32_t n = fdiv(t, a.divP);
         const int p = static_cast<int>(t - n * a.P);
-        const int ih = p * a.stride - a.pad + r, iw = q * a.stride - a.pad + s;
+        const int ih = p * a.stride - a.pad + (a.pair ? 2 * r + (pb >> 2) : r), iw = q * a.stride - a.pad + s;
         ok = ok && static_cast<unsigned>(ih) < static_cast<unsigned>(a.H) &&
              static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
-        const uint32_t off = static_cast<uint32_t>(((static_cast<int>(n) * a.H + ih) * a.W + iw) * a.PS + c0 + pb * V) * sizeof(T);
+        const int pcol = a.pair ? (pb & 3) * V : c0 + pb * V;
+        const uint32_t off = static_cast<uint32_t>(((static_cast<int>(n) * a.H + ih) * a.W + iw) * a.PS + pcol) * sizeof(T);
         st.b[i] = buffer_load16(rsX, ok ? off : kOob, 0);
       }
     }
@@ -796,20 +800,21 @@ __global__ __launch_bounds__(256) void stem_pad_input_kernel(const T* __restrict
   T* d = xp + i * 4;
   d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
 }
-// Stem weights: w [K][7][7][3] -> wp [K][7][8][4] with zeros in tap column 7 and channel 3.
+// Stem weights: w [K][7][7][3] -> wp [K][8][8][4] with zeros in filter row 7, tap column 7 and channel 3.
+constexpr int kStemK = 256;  // padded reduction length of the stem: 8 filter rows x 8 taps x 4 channels
 template <typename T>
 __global__ __launch_bounds__(256) void stem_pad_weight_kernel(const T* __restrict__ w, T* __restrict__ wp, int K) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= K * 7 * 32) return;
-  const int c = i & 3, s = (i >> 2) & 7, r = (i >> 5) % 7, k = i / 224;
-  wp[i] = (c < 3 && s < 7) ? w[((k * 7 + r) * 7 + s) * 3 + c] : static_cast<T>(0);
+  if (i >= K * kStemK) return;
+  const int c = i & 3, s = (i >> 2) & 7, r = (i >> 5) & 7, k = i >> 8;
+  wp[i] = (c < 3 && s < 7 && r < 7) ? w[((k * 7 + r) * 7 + s) * 3 + c] : static_cast<T>(0);
 }
-// dw [K][7][7][3] <- dwp [K][7][8][4]
+// dw [K][7][7][3] <- dwp [K][8][8][4]
 __global__ __launch_bounds__(256) void stem_unpad_dw_kernel(const float* __restrict__ dwp, float* __restrict__ dw, int K) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= K * 147) return;
   const int c = i % 3, s = (i / 3) % 7, r = (i / 21) % 7, k = i / 147;
-  dw[i] = dwp[((k * 7 + r) * 8 + s) * 4 + c];
+  dw[i] = dwp[((k * 8 + r) * 8 + s) * 4 + c];
 }
 
 // ------------------------------------------------------------------ host side
@@ -866,7 +871,7 @@ struct WgradPlan {
 // 8 chunks each; the split partials cost a second launch, which is only worth it while the output tiles
 // alone cannot occupy every CU.  3x3 layers with wide channels take 128x128 tiles (half the operand
 // traffic per flop), everything else 64x64.
-static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype) {
+static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype, bool tunable = true) {
   const int bkm = dtype == RN50_BF16 ? 64 : 32;
   WgradPlan best{};
   auto fill = [&](int bmo, int bc, int64_t want_splits) {
@@ -877,7 +882,8 @@ static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype) {
     best.splits = static_cast<int>(ceil_div(M, rps));
     best.rows_per_split = static_cast<int>(rps);
   };
-  if (const char* e = getenv("RN50_WGRAD_PLAN")) {  // tuning aid: bmo,bc,splits
+  const char* e = tunable ? getenv("RN50_WGRAD_PLAN") : nullptr;
+  if (e) {  // tuning aid: bmo,bc,splits
     int bmo = 0, bc = 0, sp = 0;
     if (sscanf(e, "%d,%d,%d", &bmo, &bc, &sp) == 3 && (bmo == 64 || bmo == 128) && (bc == 64 || bc == 128) && sp >= 1) {
       const int64_t rps = ceil_div(ceil_div(M, sp), bkm) * bkm;
@@ -966,7 +972,7 @@ static StemGeom stem_geom(const rn50_conv_desc* d) {
   g.Hp = d->H + 6;
   g.Wp = (d->W + 6 + 2 + 3) / 4 * 4;  // room for the 8th (zero-weight) tap, row pitch a multiple of 16 bytes
   g.xp_bytes = align_up(static_cast<size_t>(d->N) * g.Hp * g.Wp * 4 * esize(d->dtype), 256);
-  g.wp_bytes = align_up(static_cast<size_t>(d->Cout) * 224 * esize(d->dtype), 256);
+  g.wp_bytes = align_up(static_cast<size_t>(d->Cout) * kStemK * esize(d->dtype), 256);
   return g;
 }
 
@@ -1020,18 +1026,23 @@ static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const 
   IgemmArgs a{};
   a.act = xp; a.wgt = wp; a.out = y;
   a.P = out_dim(d->H, 3, 7, 2); a.Q = out_dim(d->W, 3, 7, 2);
-  a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = 224;
-  a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.Cg = 32; a.R = 7; a.S = 1; a.stride = 2; a.pad = 0; a.mode = 0;
+  a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = kStemK;
+  a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.stride = 2; a.pad = 0; a.mode = 0; a.S = 1;
   a.cpt = 1;
+  // A filter row is 8 padded taps x 4 channels = 32 elements: a whole 128-byte chunk in float, half of
+  // one in bf16, where two filter rows share a chunk (4 "taps" of 64 elements; the 8th row is zero weights).
+  a.pair = d->dtype == RN50_BF16;
+  a.R = a.pair ? 4 : 7;
+  a.Cg = a.pair ? 64 : 32;
   a.act_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * g.Hp * g.Wp * 4 * esize(d->dtype));
-  a.wgt_bytes = static_cast<uint32_t>(static_cast<size_t>(d->Cout) * 224 * esize(d->dtype));
+  a.wgt_bytes = static_cast<uint32_t>(static_cast<size_t>(d->Cout) * kStemK * esize(d->dtype));
   return a;
 }
 
 // Forward of the stem from an already padded input; wp is scratch for the padded weights.
 void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
                      hipStream_t s) {
-  const int nw = d->Cout * 224;
+  const int nw = d->Cout * kStemK;
   IgemmArgs a = stem_igemm_args(d, xp, wp, y);
   a.partial = bn_partial;
   if (d->dtype == RN50_BF16) {
@@ -1061,8 +1072,11 @@ static WgradArgs stem_wgrad_args(const rn50_conv_desc* d, const void* xp, const 
   WgradArgs a{};
   a.x = xp; a.dy = dy;
   a.P = out_dim(d->H, 3, 7, 2); a.Q = out_dim(d->W, 3, 7, 2);
-  a.M = d->N * a.P * a.Q; a.Cout = d->Cout; a.Ktot = 224;
-  a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.Cg = 32; a.R = 7; a.S = 1; a.stride = 2; a.pad = 0;
+  a.M = d->N * a.P * a.Q; a.Cout = d->Cout; a.Ktot = kStemK;
+  a.H = g.Hp; a.W = g.Wp; a.PS = 4; a.S = 1; a.stride = 2; a.pad = 0;
+  a.pair = d->dtype == RN50_BF16;  // as in stem_igemm_args
+  a.R = a.pair ? 4 : 7;
+  a.Cg = a.pair ? 64 : 32;
   a.x_bytes = static_cast<uint32_t>(static_cast<size_t>(d->N) * g.Hp * g.Wp * 4 * esize(d->dtype));
   a.dy_bytes = static_cast<uint32_t>(static_cast<size_t>(a.M) * d->Cout * esize(d->dtype));
   a.linear = 0;
@@ -1073,8 +1087,10 @@ size_t wgrad_partial_bytes(const rn50_conv_desc* d) {
   const bool stem = is_stem(d);
   const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
   const int M = d->N * P * Q;
-  const WgradPlan p = stem ? plan_wgrad(M, d->Cout, 32, 7, d->dtype) : plan_wgrad(M, d->Cout, d->Cin, d->R * d->S, d->dtype);
-  const size_t dw_elems = static_cast<size_t>(d->Cout) * (stem ? 224 : d->R * d->S * d->Cin);
+  const bool pair = d->dtype == RN50_BF16;
+  const WgradPlan p = stem ? plan_wgrad(M, d->Cout, pair ? 64 : 32, pair ? 4 : 7, d->dtype, false)
+                           : plan_wgrad(M, d->Cout, d->Cin, d->R * d->S, d->dtype);
+  const size_t dw_elems = static_cast<size_t>(d->Cout) * (stem ? kStemK : d->R * d->S * d->Cin);
   size_t b = p.splits > 1 ? align_up(dw_elems * p.splits * sizeof(float), 256) : 0;
   if (stem) b += align_up(dw_elems * sizeof(float), 256);  // padded dw
   return b;
@@ -1084,12 +1100,12 @@ size_t wgrad_partial_bytes(const rn50_conv_desc* d) {
 void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s) {
   const bool stem = is_stem(d);
   WgradArgs a = stem ? stem_wgrad_args(d, x_or_xp, dy) : wgrad_args(d, x_or_xp, dy);
-  const WgradPlan p = plan_wgrad(a.M, a.Cout, a.Cg, a.R * a.S, d->dtype);
+  const WgradPlan p = plan_wgrad(a.M, a.Cout, a.Cg, a.R * a.S, d->dtype, !stem);  // the stem's tile is fixed (64x64)
   float* partial = static_cast<float*>(scratch);
   float* target = dw;
   if (stem) {
     target = partial;
-    partial += align_up(static_cast<size_t>(d->Cout) * 224 * sizeof(float), 256) / sizeof(float);
+    partial += align_up(static_cast<size_t>(d->Cout) * kStemK * sizeof(float), 256) / sizeof(float);
   }
   if (d->dtype == RN50_BF16) launch_wgrad<uint16_t>(a, p, target, partial, s);
   else launch_wgrad<float>(a, p, target, partial, s);
