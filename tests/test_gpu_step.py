@@ -270,3 +270,33 @@ def test_profile_hooks_and_plan_lifecycle(rn):
         assert np.isfinite(float(loss.item()))
         del plan
         gc.collect()
+
+
+def test_step_on_a_caller_stream_matches_the_default_stream(rn):
+    """resnet_step forks its private streams from whatever stream the caller passes and joins them back:
+    the same step on a non-default stream, followed only by that stream's synchronization, gives the same bits."""
+    N, hw, widths, blocks, stem, classes = 4, 64, (8, 16, 16, 24), (2, 1, 1, 1), 8, 10
+    plan = rn.ResnetPlan(N, rn.BF16, hw, classes, widths, blocks, stem, 4)
+    M0 = torch.randn(plan.arena_elems, device="cuda") * 0.1
+    img = torch.randn(N, hw, hw, 3, device="cuda").to(torch.bfloat16)
+    lab = torch.arange(N, dtype=torch.int32, device="cuda") % classes
+    outs = []
+    for use_stream in (False, True):
+        M = M0.clone(); V = torch.zeros_like(M); G = torch.zeros_like(M); Mod = M.to(torch.bfloat16)
+        ws = torch.full((plan.workspace_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        torch.cuda.synchronize()
+        if use_stream:
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                for _ in range(2):
+                    rn.resnet_step(plan, img, lab, M, V, G, Mod, 0.1, ws, loss_out=loss)
+            st.synchronize()
+        else:
+            for _ in range(2):
+                rn.resnet_step(plan, img, lab, M, V, G, Mod, 0.1, ws, loss_out=loss)
+            torch.cuda.current_stream().synchronize()
+        outs.append((M.clone(), V.clone(), G.clone(), Mod.clone(), loss.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    assert torch.isfinite(outs[0][2][: plan.sizes[0]]).all()
