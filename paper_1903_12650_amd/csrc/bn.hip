@@ -10,13 +10,17 @@
 //
 // Forward:  stats (per-workgroup partial sums) -> finalize (mean, rstd) -> apply.
 // Backward: reduce (partial sums of g and g*xhat) -> finalize (dgamma, dbeta) -> apply.
+// The first pass of either direction can be left to the convolution that produces
+// the tensor (its output stage writes the same rows of partial sums, one per
+// output tile): the *_from_partials entry points then run finalize + apply only.
 // Partial sums are combined in a fixed order, so results are bitwise reproducible.
 //
-// Variance uses sums shifted by the channel's first element, K = x[0][c]:
-//   mean = K + S1/m, var = S2/m - (S1/m)^2 with S1 = sum(x-K), S2 = sum((x-K)^2),
+// Variance uses shifted sums: every row of partials carries its own shift K (the
+// first element its producer saw), S1 = sum(x-K), S2 = sum((x-K)^2); the finalize
+// pass moves all rows to the first row's shift exactly, in double, and then
+//   mean = K + S1/m, var = S2/m - (S1/m)^2,
 // which removes the cancellation of the plain E[x^2]-E[x]^2 form whenever K lies
-// within a few standard deviations of the mean; partial sums of all workgroups
-// then combine by plain addition (done in double).
+// within a few standard deviations of the mean.
 #include "common.h"
 #include "step_internal.h"
 

@@ -21,6 +21,13 @@
 // copied to LDS untransposed and the bf16 fragments are fetched with the
 // gfx950 transposing LDS read (ds_read_b64_tr_b16); the reduction is split over
 // workgroups and finished by a fixed-order sum (bitwise reproducible).
+//
+// The output stage of igemm_kernel can also take the per-channel sums of the
+// batch norm that consumes the output (forward: shifted sum and sum of squares
+// per tile; data gradient: sum(g), sum(g*xhat) of the BN layer below, with an
+// optional second gradient branch added before the one rounding), so that no
+// separate pass re-reads the tensor.  Stride-2 data gradients process the output
+// pixels in four parity classes, each looping over its own taps only.
 #include <stdlib.h>
 
 #include <mutex>
@@ -70,19 +77,6 @@ __device__ __forceinline__ int xcd_remap(int id, int n) {
   return xcd < rem ? xcd * (q + 1) + idx : rem * (q + 1) + (xcd - rem) * q + idx;
 }
 
-// v if keep, else zeros (component-wise masks: a select between two aggregates would be turned into a
-// select of their addresses and force both into scratch memory).
-__device__ __forceinline__ uint4 keep_or_zero(uint4 v, bool keep) {
-  const uint32_t m = keep ? 0xffffffffu : 0u;
-  return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
-}
-
-__device__ __forceinline__ Vec16 zero16() {
-  Vec16 v;
-  v.u = make_uint4(0, 0, 0, 0);
-  return v;
-}
-
 // ------------------------------------------------- forward / dgrad implicit GEMM
 struct IgemmArgs {
   const void* act;  // gathered activation tensor [N][H][W] pixels of PS elements
@@ -99,7 +93,6 @@ struct IgemmArgs {
   int ntn;          // number of column tiles
   int pair;         // stem in bf16: a 128-byte chunk holds two filter rows (pieces 0-3: row 2r, 4-7: row 2r+1)
   int nimg;         // images (M = nimg*P*Q)
-  int tiles_per_class;  // stride-2 data gradient: row tiles per parity class of the output pixels
   int mode;         // host side only: selects the MODE template argument
   // Optional batch-norm sums over the rows of each output tile, taken from the rounded values that are
   // stored (null: none).  Forward: partial[3][Ncols][tiles] = shift (the tile's first row), sum(y - shift),
@@ -834,9 +827,10 @@ template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   a.ntn = static_cast<int>(ceil_div(a.Ncols, BN));
   a.nimg = a.M / (a.P * a.Q);
-  a.tiles_per_class = static_cast<int>(ceil_div(static_cast<int64_t>(a.nimg) * ((a.P + 1) / 2) * ((a.Q + 1) / 2), BM));
+  // stride-2 data gradient: four parity classes of the output pixels, each with its own row tiles
+  const int64_t tiles_per_class = ceil_div(static_cast<int64_t>(a.nimg) * ((a.P + 1) / 2) * ((a.Q + 1) / 2), BM);
   const bool classes = a.mode == 1 && a.stride == 2;
-  const int64_t grid = (classes ? 4 * a.tiles_per_class : ceil_div(a.M, BM)) * a.ntn;
+  const int64_t grid = (classes ? 4 * tiles_per_class : ceil_div(a.M, BM)) * a.ntn;
   if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0>(a, tag, grid, s);
   else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
 }

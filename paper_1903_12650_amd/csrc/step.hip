@@ -1,6 +1,7 @@
 // resnet_step: the launch sequence of one ResNet-50 v1.5 training step on the
-// local batch (forward, softmax cross-entropy, backward, LARS), all on one
-// stream, using a caller-provided workspace.  Wiring follows the paper's
+// local batch (forward, softmax cross-entropy, backward, LARS) on the caller's
+// stream plus two private streams for work off the critical path (weight
+// gradients, projection shortcuts), using a caller-provided workspace.  Wiring follows the paper's
 // appendix log (stem convolution stride 2 / 64 filters / no bias -> BN -> ReLU
 // -> max-pool 112 -> 56, bottleneck blocks) and He et al.; the gradient exchange
 // between workers (Sec. III-C) would sit between backward and the LARS call.
