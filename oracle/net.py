@@ -21,7 +21,7 @@ the block has a projection shortcut, proj W, g, b; then FC W, FC b.
 """
 import numpy as np
 
-from . import (avgpool_bwd, avgpool_fwd, bn_relu_bwd, bn_relu_fwd, conv_dgrad, conv_fwd,
+from . import (avgpool_bwd, avgpool_fwd, bn_relu_bwd, bn_relu_fwd, bn_running_update, conv_dgrad, conv_fwd,
                conv_wgrad, fc_bwd, fc_fwd, lars_update, maxpool_bwd, maxpool_fwd, xent_fwd_bwd)
 
 
@@ -110,6 +110,7 @@ def forward_backward(images, labels, params, widths=(64, 128, 256, 512), blocks=
     if keep:
         acts["stem.y"] = t0["y"]; acts["stem.z"] = z0; acts["pool"] = cur
     tapes = []
+    bn_inputs = [t0["y"]]  # what every BN layer normalizes, in parameter order (for the moving averages)
     for i, nb in enumerate(blocks):
         for j in range(nb):
             has_proj = j == 0
@@ -117,6 +118,7 @@ def forward_backward(images, labels, params, widths=(64, 128, 256, 512), blocks=
             bp = take(12 if has_proj else 9)
             cur, tp = bottleneck_fwd(cur, bp, stride, has_proj, eps)
             tapes.append(tp)
+            bn_inputs += [t["y"] for t in tp if t is not None]
             if keep:
                 acts[f"s{i}b{j}.out"] = cur
     fw, fb = take(2)
@@ -137,7 +139,7 @@ def forward_backward(images, labels, params, widths=(64, 128, 256, 512), blocks=
     for g in reversed(block_grads):
         grads += g
     grads += [dfw, dfb]
-    out = dict(loss=loss, row_loss=row_loss, logits=logits, dlogits=dlogits, grads=grads)
+    out = dict(loss=loss, row_loss=row_loss, logits=logits, dlogits=dlogits, grads=grads, bn_inputs=bn_inputs)
     if keep:
         out["acts"] = acts
     return out
@@ -159,3 +161,62 @@ def train_step(images, labels, master, model, velocity, table, *, eta=0.001, mom
     w_new, v_new, norms = lars_update(master, fb["grads"], velocity, eta, momentum, lr, wds, lars_eps)
     fb.update(w_new=w_new, v_new=v_new, norms=norms)
     return fb
+
+
+def learning_rate(t, base_lr, warmup_steps=0, warmup_start_lr=0.0, decay="none", total_steps=0, end_lr=0.0,
+                  power=2.0, step_every=1, step_factor=0.1, table=None):
+    """Learning rate of step t = 0, 1, ... (Sec. III-A1: gradual warm-up, then one of the decay patterns
+    the paper lists -- step, polynomial, linear -- or any user-supplied table).  In double.
+
+    t < warmup_steps:  start + (base - start) * t / warmup_steps   (reaches base at t = warmup_steps)
+    afterwards, with u = t - warmup_steps and D = total_steps - warmup_steps:
+      none        base
+      step        base * step_factor ** floor(u / step_every)
+      polynomial  end + (base - end) * (1 - min(u, D)/D) ** power
+      linear      the polynomial with power 1
+      table       table[min(t, len(table) - 1)]  (the table covers warm-up too: warmup_steps is ignored)
+    """
+    t = int(t)
+    if decay == "table":
+        return float(table[min(t, len(table) - 1)])
+    if t < warmup_steps:
+        return float(warmup_start_lr + (base_lr - warmup_start_lr) * (t / warmup_steps))
+    u = t - warmup_steps
+    if decay == "none":
+        return float(base_lr)
+    if decay == "step":
+        return float(base_lr * step_factor ** (u // step_every))
+    if decay in ("polynomial", "linear"):
+        D = total_steps - warmup_steps
+        frac = 1.0 - min(u, D) / D
+        return float(end_lr + (base_lr - end_lr) * frac ** (power if decay == "polynomial" else 1.0))
+    raise ValueError(decay)
+
+
+def train_loop(batches, master, velocity, table, schedule, steps, *, first_step=0, round_model=None,
+               bn_momentum=0.9, running_mean=None, running_var=None, **step_kw):
+    """`steps` training steps (the inner loop of the paper's training: Sec. III-A).  Step t uses batch
+    batches[t % len(batches)] = (images, labels) and the learning rate learning_rate(first_step + t,
+    **schedule); the forward/backward passes read round_model(master) (the half-precision copy of
+    Sec. IV; None: the master weights themselves); the moving averages of every BN layer's batch mean
+    and biased variance follow with `bn_momentum` (appendix log: 0.9; start: mean 0, variance 1).
+    Returns dict(losses, lrs, master, velocity, running_mean, running_var, last)."""
+    master = [np.array(w, copy=True) for w in master]
+    velocity = [np.array(v, copy=True) for v in velocity]
+    n_bn = sum(1 for (_, _, kind) in table if kind == "gamma")
+    gam = [w for w, (_, _, kind) in zip(master, table) if kind == "gamma"]
+    rm = [np.zeros_like(g) for g in gam] if running_mean is None else [np.array(a, copy=True) for a in running_mean]
+    rv = [np.ones_like(g) for g in gam] if running_var is None else [np.array(a, copy=True) for a in running_var]
+    losses, lrs, fb = [], [], None
+    for t in range(steps):
+        images, labels = batches[t % len(batches)]
+        lr = learning_rate(first_step + t, **schedule)
+        model = master if round_model is None else [round_model(w) for w in master]
+        fb = train_step(images, labels, master, model, velocity, table, lr=lr, **step_kw)
+        assert len(fb["bn_inputs"]) == n_bn
+        for i, y in enumerate(fb["bn_inputs"]):
+            rm[i], rv[i] = bn_running_update(y, rm[i], rv[i], bn_momentum)
+        master, velocity = fb["w_new"], fb["v_new"]
+        losses.append(float(fb["loss"]))
+        lrs.append(lr)
+    return dict(losses=losses, lrs=lrs, master=master, velocity=velocity, running_mean=rm, running_var=rv, last=fb)

@@ -45,9 +45,10 @@ def _small_setup(dtype, N=2, HW=32, classes=7):
     return table, params, images, labels
 
 
-def _torch_forward(images, labels, params, table, blocks, ls, expansion=2):
+def _torch_forward(images, labels, params, table, blocks, ls, expansion=2, bn_inputs=None):
     """The same network written with torch CPU ops (NCHW, autograd): an independent
-    implementation of the wiring and of every operation."""
+    implementation of the wiring and of every operation.  bn_inputs: a list that receives what every
+    BN layer normalizes (NHWC numpy arrays, parameter order)."""
     import torch
     import torch.nn.functional as F
     P = [torch.tensor(p, dtype=torch.float64, requires_grad=True) for p in params]
@@ -56,6 +57,8 @@ def _torch_forward(images, labels, params, table, blocks, ls, expansion=2):
     def cbn(x, stride, pad, relu=True, res=None):
         w, g, b = next(it), next(it), next(it)
         y = F.conv2d(x, w.permute(0, 3, 1, 2), None, stride, pad)
+        if bn_inputs is not None:
+            bn_inputs.append(y.detach().permute(0, 2, 3, 1).numpy())
         y = F.batch_norm(y, None, None, g, b, True, 0.1, 1e-5)
         if res is not None:
             y = y + res
@@ -75,7 +78,10 @@ def _torch_forward(images, labels, params, table, blocks, ls, expansion=2):
                 sc = cbn(inp, stride, 0, relu=False)
             else:
                 sc = inp
-            y3 = F.batch_norm(F.conv2d(z2, w3.permute(0, 3, 1, 2)), None, None, g3, b3, True, 0.1, 1e-5)
+            c3 = F.conv2d(z2, w3.permute(0, 3, 1, 2))
+            if bn_inputs is not None:  # conv3 precedes the projection in parameter order
+                bn_inputs.insert(len(bn_inputs) - (1 if j == 0 else 0), c3.detach().permute(0, 2, 3, 1).numpy())
+            y3 = F.batch_norm(c3, None, None, g3, b3, True, 0.1, 1e-5)
             cur = F.relu(y3 + sc)
     a = cur.mean(dim=(2, 3))
     fw, fb = next(it), next(it)
@@ -184,3 +190,84 @@ def test_round_bf16_helper():
     import torch
     np.testing.assert_array_equal(r, torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy())
     assert synth.bf16_bits(r).dtype == np.uint16
+
+
+# ------------------------------------------------------------------ learning-rate control, training loop
+def test_learning_rate_warmup_and_decay_patterns():
+    """Sec. III-A1: gradual warm-up, then step / polynomial / linear decay -- against hand-computed values."""
+    lr = net.learning_rate
+    kw = dict(base_lr=8.0, warmup_steps=4, warmup_start_lr=2.0)
+    assert [lr(t, **kw) for t in range(6)] == [2.0, 3.5, 5.0, 6.5, 8.0, 8.0]          # linear ramp, then flat
+    assert lr(3, base_lr=1.0) == 1.0                                                   # no warm-up, no decay
+    st = dict(kw, decay="step", step_every=3, step_factor=0.5)
+    assert [lr(t, **st) for t in (4, 6, 7, 9, 10, 13)] == [8.0, 8.0, 4.0, 4.0, 2.0, 1.0]
+    po = dict(kw, decay="polynomial", total_steps=14, end_lr=1.0, power=2.0)
+    assert lr(4, **po) == 8.0 and lr(14, **po) == 1.0 and lr(40, **po) == 1.0           # ends at end_lr and stays
+    assert abs(lr(9, **po) - (1.0 + 7.0 * 0.25)) < 1e-15                                # halfway: (1/2)^2
+    li = dict(kw, decay="linear", total_steps=14, end_lr=1.0)
+    assert abs(lr(9, **li) - 4.5) < 1e-15 and abs(lr(13, **li) - 1.7) < 1e-12
+    assert all(abs(lr(t, **li) - lr(t, **dict(po, power=1.0))) < 1e-15 for t in range(20))
+    for sched in (st, po, li):                                                          # never rises after warm-up
+        v = [lr(t, **sched) for t in range(4, 30)]
+        assert all(a >= b for a, b in zip(v, v[1:]))
+    tb = dict(base_lr=0.0, decay="table", table=[0.1, 0.4, 0.2])
+    assert [lr(t, **tb) for t in range(5)] == [0.1, 0.4, 0.2, 0.2, 0.2]
+
+
+def _lars_by_hand(w, g, v, lr, wd, eta=0.001, mu=0.9):
+    w = w.astype(np.float64); g = g.astype(np.float64)
+    wn, gn = np.sqrt((w * w).sum()), np.sqrt((g * g).sum())
+    local = eta * wn / (gn + wd * wn) if wn > 0 and gn > 0 else 1.0
+    v = mu * v + lr * local * (g + wd * w)
+    return w - v, v
+
+
+def test_train_loop_matches_torch_autograd_steps_with_handwritten_updates():
+    """Three steps over two alternating batches: gradients from torch autograd, the LARS update and the
+    moving averages written out here in numpy; the loop must land on the same weights, velocities, losses
+    and BN moving averages."""
+    table, params, images, labels = _small_setup(np.float64)
+    images2 = synth.activation_nhwc(SEED + 1, "img", 2, 3, 32, 32, 1.0, np.float64)
+    labels2 = synth.labels(SEED + 1, "lab", 2, 7)
+    batches = [(images, labels), (images2, labels2)]
+    sched = dict(base_lr=3.0, warmup_steps=2, warmup_start_lr=1.0, decay="linear", total_steps=6, end_lr=0.5)
+    out = net.train_loop(batches, params, [np.zeros_like(p) for p in params], table, sched, 3,
+                         widths=SMALL["widths"], blocks=SMALL["blocks"], label_smoothing=0.1)
+    assert out["lrs"] == [1.0, 2.0, 3.0]
+    wds = net.lars_hyper(table, 5e-5)
+    n_bn = sum(k == "gamma" for _, _, k in table)
+    w = [p.copy() for p in params]
+    v = [np.zeros_like(p) for p in params]
+    rm = [0.0] * n_bn
+    rv = [1.0] * n_bn
+    for t in range(3):
+        ys = []
+        tl, _, tg = _torch_forward(*batches[t % 2], w, table, SMALL["blocks"], 0.1, bn_inputs=ys)
+        assert abs(out["losses"][t] - tl) < 1e-9
+        assert len(ys) == n_bn
+        for i, y in enumerate(ys):
+            y2 = y.reshape(-1, y.shape[-1])
+            rm[i] = 0.9 * rm[i] + 0.1 * y2.mean(0)
+            rv[i] = 0.9 * rv[i] + 0.1 * y2.var(0)   # biased variance
+        for i in range(len(w)):
+            w[i], v[i] = _lars_by_hand(w[i], tg[i], v[i], out["lrs"][t], wds[i])
+    for i, (name, _, _) in enumerate(table):
+        assert orc.rel_l2(out["master"][i], w[i]) < 1e-7, name
+        assert orc.rel_l2(out["velocity"][i], v[i]) < 1e-6, name
+    for i in range(n_bn):
+        np.testing.assert_allclose(out["running_mean"][i], rm[i], rtol=1e-7, atol=1e-9)
+        np.testing.assert_allclose(out["running_var"][i], rv[i], rtol=1e-7, atol=1e-9)
+
+
+def test_train_loop_lowers_the_loss_on_a_fixed_batch():
+    table, params, images, labels = _small_setup(np.float32, N=4)
+    sched = dict(base_lr=20.0, warmup_steps=2, warmup_start_lr=5.0)
+    out = net.train_loop([(images, labels)], params, [np.zeros_like(p) for p in params], table, sched, 8,
+                         round_model=synth.round_bf16, widths=SMALL["widths"], blocks=SMALL["blocks"])
+    assert out["losses"][-1] < 0.7 * out["losses"][0], out["losses"]
+    one = net.train_step(images, labels, params, [synth.round_bf16(p) for p in params],
+                         [np.zeros_like(p) for p in params], table, lr=5.0, widths=SMALL["widths"], blocks=SMALL["blocks"])
+    again = net.train_loop([(images, labels)], params, [np.zeros_like(p) for p in params], table, sched, 1,
+                           round_model=synth.round_bf16, widths=SMALL["widths"], blocks=SMALL["blocks"])
+    for a, b in zip(one["w_new"], again["master"]):   # one step of the loop is train_step
+        np.testing.assert_array_equal(a, b)
