@@ -7,7 +7,10 @@ paper's 81,920-image minibatch), with inputs, parameters and workspace resident 
 the timed region, plus
   "roofline":     achieved vs peak for the step's dominant kernel, from HIP events recorded by the
                   library around every launch of that kernel inside the timed steps, and
-  "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload.
+  "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload,
+  "train_loop":   the same step inside the training loop (device-side learning-rate schedule and step
+                  counter, BN moving averages, label smoothing), launched eagerly and as replays of one
+                  captured HIP graph.
 Synthetic data: N(0,1) images of ImageNet's shape, uniform labels, He-normal weights.
 """
 import argparse
@@ -29,6 +32,7 @@ def parse():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-train-loop", action="store_true")
     ap.add_argument("--roofline-kernel", default=None, help="kernel tag to time (default: the dominant one)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of known size (the float master arena) before the steps: "
@@ -85,6 +89,47 @@ def cpu_baseline(batch_sample=40):
                       f"{dt:.1f} s wall"}
 
 
+def train_loop_record(rn, torch, S, steps, warmup, batch):
+    """ms/step of resnet_train_step (warm-up + polynomial decay on the device, moving averages on),
+    eager and as replays of one captured graph."""
+    plan = S["plan"]
+    state = rn.TrainState(plan)
+    sched = rn.LrSchedule(base_lr=1.0, warmup_steps=5, warmup_start_lr=0.1, decay="polynomial", total_steps=100000,
+                          end_lr=1e-4, power=2.0)
+
+    def step():
+        rn.resnet_train_step(plan, sched, state, S["images"], S["labels"], S["M"], S["V"], S["G"], S["Mod"], S["ws"],
+                             loss_out=S["loss"])
+
+    def timed(f):
+        for _ in range(warmup):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    rec = {"schedule": "linear warm-up 5 steps, polynomial (power 2) decay", "bn_momentum": 0.9}
+    ms = timed(step)
+    rec.update(ms_per_step_eager=ms, images_per_s_eager=batch / (ms * 1e-3))
+    try:
+        st = torch.cuda.Stream()
+        st.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            step()
+        torch.cuda.synchronize()
+        ms = timed(g.replay)
+        rec.update(ms_per_step_graph=ms, images_per_s_graph=batch / (ms * 1e-3))
+    except Exception as e:  # the eager figure stands on its own
+        rec["graph_error"] = str(e)[:200]
+    rec["steps_taken"] = state.step
+    rec["loss"] = float(S["loss"].item())
+    return rec
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -138,6 +183,8 @@ def main():
         durations_ms = rn.profile_end()
         out["roofline"] = rl.roofline(tag, plan, durations_ms, sampled)
         out["roofline"]["timed_steps"] = sampled
+    if not args.no_train_loop:
+        out["train_loop"] = train_loop_record(rn, torch, S, args.steps, args.warmup, args.batch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

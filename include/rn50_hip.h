@@ -303,6 +303,65 @@ int resnet_step(rn50_plan* plan, const void* images, const int32_t* labels, floa
                 float* velocity, float* grads, void* model, float lr, int update, float* loss_out,
                 float* logits_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------- training loop
+ * The inner loop of the paper's training with its optimizer controls (Sec. III-A): the
+ * learning rate follows a gradual warm-up and then one of the decay patterns the paper
+ * lists (step, polynomial, linear) or a table the caller supplies; label smoothing is the
+ * plan's; every BN layer keeps moving averages of its batch mean and (biased) batch
+ * variance (Sec. III-A2; appendix log: momentum 0.9).  The step counter, the learning rate
+ * and the moving averages live in device memory, so a step takes no per-step host values
+ * and a captured graph of it can be replayed step after step.
+ *
+ * lr(t), t = 0, 1, ... (computed on the device in double, stored as float):
+ *   t < warmup_steps:  warmup_start_lr + (base_lr - warmup_start_lr)*t/warmup_steps
+ *   else, u = t - warmup_steps, D = total_steps - warmup_steps:
+ *     RN50_DECAY_NONE    base_lr
+ *     RN50_DECAY_STEP    base_lr * step_factor^floor(u/step_every)
+ *     RN50_DECAY_POLY    end_lr + (base_lr - end_lr)*(1 - min(u,D)/D)^power
+ *     RN50_DECAY_LINEAR  the polynomial with power 1
+ *   RN50_DECAY_TABLE     table[min(t, table_len-1)] for every t (warm-up fields ignored) */
+#define RN50_DECAY_NONE 0
+#define RN50_DECAY_STEP 1
+#define RN50_DECAY_POLY 2
+#define RN50_DECAY_LINEAR 3
+#define RN50_DECAY_TABLE 4
+typedef struct {
+  float base_lr, warmup_start_lr;
+  int warmup_steps;
+  int decay;          /* RN50_DECAY_*                                        */
+  int total_steps;    /* POLY, LINEAR: > warmup_steps                        */
+  float end_lr, power;
+  int step_every;     /* STEP: > 0                                           */
+  float step_factor;
+  const float* table; /* TABLE: device float[table_len], read at every step  */
+  int table_len;
+} rn50_lr_schedule;
+
+/* Training state: one device buffer of resnet_train_state_bytes(plan) bytes, owned by the caller:
+ *   byte 0    int64  t, the number of steps taken (the next step uses lr(t))
+ *   byte 8    float  the learning rate of the last step taken
+ *   byte 256  float  running_mean[resnet_plan_bn_channels(plan)]
+ *   then      float  running_var [resnet_plan_bn_channels(plan)]
+ * BN layer i (0 .. resnet_plan_num_bn-1, parameter order: stem, then per block conv1, conv2,
+ * conv3, projection) owns the C_i entries starting at resnet_plan_bn_offset(plan, i, &C_i) of
+ * both arrays (offsets are multiples of 64; the entries in the gaps are not used). */
+int resnet_plan_num_bn(const rn50_plan* plan);
+int64_t resnet_plan_bn_channels(const rn50_plan* plan);
+int64_t resnet_plan_bn_offset(const rn50_plan* plan, int i, int* channels_out);
+size_t resnet_train_state_bytes(const rn50_plan* plan);
+/* t = first_step, running means 0, running variances 1.  Enqueued on `stream`. */
+int resnet_train_state_init(const rn50_plan* plan, void* state, size_t state_bytes, int64_t first_step,
+                            void* stream);
+/* One step of the loop: resnet_step (same arenas, workspace and stream semantics, update
+ * always on) with lr = lr(t) taken from the state on the device, the moving averages
+ * updated as running <- bn_momentum*running + (1-bn_momentum)*batch statistic, and t
+ * advanced by one.  `schedule` is read at the call (its table at run time).  Errors as
+ * resnet_step, plus RN50_ERR_INVALID for an inconsistent schedule. */
+int resnet_train_step(rn50_plan* plan, const rn50_lr_schedule* schedule, void* state, float bn_momentum,
+                      const void* images, const int32_t* labels, float* master, float* velocity,
+                      float* grads, void* model, float* loss_out, float* logits_out, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,7 +14,9 @@ __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "co
            "xent_fwd_bwd", "lars_update", "LarsTable", "profile_begin", "profile_pause", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
-           "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums"]
+           "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
+           "LrSchedule", "TrainState", "resnet_train_step", "DECAY_NONE", "DECAY_STEP", "DECAY_POLY", "DECAY_LINEAR",
+           "DECAY_TABLE"]
 
 F32, BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -66,10 +68,11 @@ class StepConfig(ctypes.Structure):
 raw.rn50_last_error.restype = ctypes.c_char_p
 for _n in ("conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "lars_update_workspace_bytes",
-           "resnet_plan_workspace_bytes", "conv_bn_sums_bytes"):
+           "resnet_plan_workspace_bytes", "conv_bn_sums_bytes", "resnet_train_state_bytes"):
     if hasattr(raw, _n):
         getattr(raw, _n).restype = ctypes.c_size_t
-for _n in ("resnet_plan_tensor_shape", "resnet_plan_tensor_offset", "resnet_plan_arena_elems"):
+for _n in ("resnet_plan_tensor_shape", "resnet_plan_tensor_offset", "resnet_plan_arena_elems", "resnet_plan_bn_channels",
+           "resnet_plan_bn_offset"):
     if hasattr(raw, _n):
         getattr(raw, _n).restype = ctypes.c_int64
 
@@ -412,6 +415,79 @@ def resnet_step(plan, images, labels, master, velocity, grads, model, lr, worksp
     _check(raw.resnet_step(plan.handle, _ptr(images), _ptr(labels), _ptr(master), _ptr(velocity), _ptr(grads),
                            _ptr(model), ctypes.c_float(lr), int(bool(update)), _ptr(loss_out), _ptr(logits_out),
                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    return loss_out
+
+
+# ------------------------------------------------------------ training loop
+DECAY_NONE, DECAY_STEP, DECAY_POLY, DECAY_LINEAR, DECAY_TABLE = range(5)
+_DECAY = {"none": DECAY_NONE, "step": DECAY_STEP, "polynomial": DECAY_POLY, "linear": DECAY_LINEAR, "table": DECAY_TABLE}
+
+
+class LrSchedule(ctypes.Structure):
+    """rn50_lr_schedule.  `table`: a float32 device tensor (kept alive by this object)."""
+    _fields_ = [("base_lr", ctypes.c_float), ("warmup_start_lr", ctypes.c_float), ("warmup_steps", ctypes.c_int),
+                ("decay", ctypes.c_int), ("total_steps", ctypes.c_int), ("end_lr", ctypes.c_float),
+                ("power", ctypes.c_float), ("step_every", ctypes.c_int), ("step_factor", ctypes.c_float),
+                ("table", ctypes.c_void_p), ("table_len", ctypes.c_int)]
+
+    def __init__(self, base_lr=0.0, warmup_steps=0, warmup_start_lr=0.0, decay="none", total_steps=0, end_lr=0.0,
+                 power=2.0, step_every=1, step_factor=0.1, table=None):
+        super().__init__(base_lr, warmup_start_lr, warmup_steps, _DECAY.get(decay, decay), total_steps, end_lr, power,
+                         step_every, step_factor, _ptr(table), 0 if table is None else table.numel())
+        self._table = table
+
+
+class TrainState:
+    """The device-side training state of a plan: step counter, learning rate, BN moving averages."""
+
+    def __init__(self, plan, device="cuda", first_step=0):
+        self.plan = plan
+        self.num_bn = raw.resnet_plan_num_bn(plan.handle)
+        self.bn_channels = int(raw.resnet_plan_bn_channels(plan.handle))
+        self.bn_slices = []
+        for i in range(self.num_bn):
+            c = ctypes.c_int()
+            off = int(raw.resnet_plan_bn_offset(plan.handle, i, ctypes.byref(c)))
+            self.bn_slices.append((off, c.value))
+        nbytes = int(raw.resnet_train_state_bytes(plan.handle))
+        assert nbytes == 256 + 8 * self.bn_channels
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.reset(first_step)
+
+    def reset(self, first_step=0):
+        _check(raw.resnet_train_state_init(self.plan.handle, _ptr(self.buf), ctypes.c_size_t(self.buf.numel()),
+                                           ctypes.c_int64(first_step), _stream()))
+
+    @property
+    def step(self):
+        return int(self.buf[:8].view(torch.int64).item())
+
+    @property
+    def lr(self):
+        return float(self.buf[8:12].view(torch.float32).item())
+
+    def _running(self, which):
+        n = self.bn_channels
+        arr = self.buf[256 + 4 * n * which:256 + 4 * n * (which + 1)].view(torch.float32)
+        return [arr[o:o + c] for o, c in self.bn_slices]
+
+    @property
+    def running_mean(self):
+        return self._running(0)
+
+    @property
+    def running_var(self):
+        return self._running(1)
+
+
+def resnet_train_step(plan, schedule, state, images, labels, master, velocity, grads, model, workspace, bn_momentum=0.9,
+                      loss_out=None, logits_out=None):
+    if loss_out is None:
+        loss_out = torch.empty(1, dtype=torch.float32, device=images.device)
+    _check(raw.resnet_train_step(plan.handle, ctypes.byref(schedule), _ptr(state.buf), ctypes.c_float(bn_momentum),
+                                 _ptr(images), _ptr(labels), _ptr(master), _ptr(velocity), _ptr(grads), _ptr(model),
+                                 _ptr(loss_out), _ptr(logits_out), _ptr(workspace), ctypes.c_size_t(workspace.numel()),
+                                 _stream()))
     return loss_out
 
 

@@ -22,6 +22,7 @@ struct LarsArgs {
   int num;
   int grad_bf16;
   float eta, momentum, lr, eps;
+  const float* lr_dev;  // when set, the learning rate is read from here at run time instead of `lr`
   float* partial;    // [total_chunks][2]
   float* norms_out;  // [num][2] or null, offset like table
   int chunk_prefix[kLarsMaxTensors + 1];
@@ -39,6 +40,7 @@ struct LarsArenaArgs {
   int num;
   int grad_bf16;
   float eta, momentum, lr, eps, weight_decay;
+  const float* lr_dev;  // as in LarsArgs
   float* partial;
   float* norms_out;
   uint32_t offset[kLarsArenaMaxTensors];  // elements
@@ -136,7 +138,8 @@ __global__ __launch_bounds__(256) void lars_apply_kernel(const Args a) {
   const float wn = sqrtf(sw), gn = sqrtf(sg);
   float local = 1.0f;
   if (T.apply_trust && wn > 0.f && gn > 0.f) local = a.eta * wn / (gn + T.weight_decay * wn + a.eps);
-  const float step = a.lr * local, wd = T.weight_decay, mu = a.momentum;
+  const float lr = a.lr_dev ? *a.lr_dev : a.lr;
+  const float step = lr * local, wd = T.weight_decay, mu = a.momentum;
   if (chunk == c0 && threadIdx.x == 0 && a.norms_out) {
     a.norms_out[2 * t] = wn;
     a.norms_out[2 * t + 1] = gn;
@@ -205,14 +208,14 @@ size_t lars_arena_partial_bytes(const LarsArenaSpec& sp) {
 }
 
 void lars_arena_run(const LarsArenaSpec& sp, float* master, const float* grads, float* velocity, void* lowp,
-                    float eta, float momentum, float lr, float eps, float weight_decay, float* partial,
-                    hipStream_t s) {
+                    float eta, float momentum, float lr, const float* lr_dev, float eps, float weight_decay,
+                    float* partial, hipStream_t s) {
   for (int t0 = 0; t0 < sp.num; t0 += kLarsArenaMaxTensors) {
     LarsArenaArgs a{};
     a.num = sp.num - t0 < kLarsArenaMaxTensors ? sp.num - t0 : kLarsArenaMaxTensors;
     a.master = master; a.grads = grads; a.velocity = velocity; a.lowp = static_cast<uint16_t*>(lowp);
     a.grad_bf16 = 0;
-    a.eta = eta; a.momentum = momentum; a.lr = lr; a.eps = eps; a.weight_decay = weight_decay;
+    a.eta = eta; a.momentum = momentum; a.lr = lr; a.lr_dev = lr_dev; a.eps = eps; a.weight_decay = weight_decay;
     a.partial = partial; a.norms_out = nullptr;
     a.chunk_prefix[0] = 0;
     for (int t = 0; t < a.num; ++t) {
@@ -259,6 +262,7 @@ extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* tabl
     a.table = table_dev + t0;
     a.grad_bf16 = d->grad_dtype == RN50_BF16;
     a.eta = d->eta; a.momentum = d->momentum; a.lr = d->lr; a.eps = d->eps;
+    a.lr_dev = nullptr;
     a.partial = partial;
     a.norms_out = norms_out ? norms_out + 2 * t0 : nullptr;
     a.chunk_prefix[0] = 0;

@@ -22,6 +22,7 @@ struct Unit {  // convolution + BN (+ReLU / +add+ReLU)
   size_t y, z;           // workspace offsets of the conv output and the BN output
   size_t mean, rstd;     // workspace offsets (float[C])
   size_t relu_mask;      // residual-add layers: the ReLU decision bits (1 byte per 16-byte vector of z)
+  int64_t bn_off;        // first entry of this BN layer in the moving-average arrays of a training state
   int P, Q;
 };
 
@@ -43,6 +44,7 @@ struct rn50_plan {
   std::vector<rn50::Unit> units;
   std::vector<rn50::Block> blocks;
   int64_t arena_elems = 0;
+  int64_t bn_channels = 0;  // length of the moving-average arrays (every layer's share rounded up to 64)
   int es = 2;  // element size of the activation dtype
   int fc_in = 0, final_hw = 0;
   // workspace layout (byte offsets)
@@ -95,6 +97,8 @@ int add_unit(rn50_plan* p, int N, int H, int W, int Cin, int Cout, int R, int st
   u.iw = add_tensor(p, Cout, R, R, Cin, true);
   u.ig = add_tensor(p, Cout, 0, 0, 0, false);
   u.ib = add_tensor(p, Cout, 0, 0, 0, false);
+  u.bn_off = p->bn_channels;
+  p->bn_channels += (Cout + 63) / 64 * 64;
   p->units.push_back(u);
   return static_cast<int>(p->units.size()) - 1;
 }
@@ -273,10 +277,62 @@ extern "C" size_t resnet_plan_workspace_bytes(const rn50_plan* plan) { return pl
     if (rc_ != RN50_OK) return rc_; \
   } while (0)
 
-extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* labels, float* master,
-                           float* velocity, float* grads, void* model, float lr, int update, float* loss_out,
-                           float* logits_out, void* workspace, size_t workspace_bytes, void* stream) {
-  clear_error();
+namespace {
+
+// What resnet_train_step adds to a step: the device-side learning rate and step counter, the moving averages.
+struct TrainCtl {
+  rn50_lr_schedule sched;
+  int64_t* t;        // device: steps taken
+  float* lr;         // device: the learning rate of the step
+  float *run_mean, *run_var;
+  float bn_momentum;
+};
+
+// lr(t) of the schedule (in double), and t <- t + 1.
+__global__ void lr_tick_kernel(const rn50_lr_schedule sc, int64_t* t_ptr, float* lr_out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const int64_t t = *t_ptr;
+  const double base = sc.base_lr, end = sc.end_lr;
+  double lr;
+  if (sc.decay == RN50_DECAY_TABLE) {
+    lr = sc.table[t < sc.table_len ? (t < 0 ? 0 : t) : sc.table_len - 1];
+  } else if (t < sc.warmup_steps) {
+    const double start = sc.warmup_start_lr;
+    lr = start + (base - start) * (static_cast<double>(t) / sc.warmup_steps);
+  } else {
+    const int64_t u = t - sc.warmup_steps;
+    if (sc.decay == RN50_DECAY_STEP) {
+      lr = base * pow(static_cast<double>(sc.step_factor), static_cast<double>(u / sc.step_every));
+    } else if (sc.decay == RN50_DECAY_POLY || sc.decay == RN50_DECAY_LINEAR) {
+      const int64_t D = sc.total_steps - sc.warmup_steps;
+      const double frac = 1.0 - static_cast<double>(u < D ? u : D) / static_cast<double>(D);
+      lr = end + (base - end) * (sc.decay == RN50_DECAY_LINEAR ? frac : pow(frac, static_cast<double>(sc.power)));
+    } else {
+      lr = base;
+    }
+  }
+  *lr_out = static_cast<float>(lr);
+  *t_ptr = t + 1;
+}
+
+__global__ void train_state_init_kernel(int64_t* t_ptr, float* lr, float* run_mean, float* run_var, int64_t n,
+                                        int64_t first_step) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i == 0) {
+    *t_ptr = first_step;
+    *lr = 0.f;
+  }
+  if (i < n) {
+    run_mean[i] = 0.f;
+    run_var[i] = 1.f;
+  }
+}
+
+constexpr size_t kStateHeader = 256;  // bytes before the moving averages
+
+int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t* labels, float* master,
+             float* velocity, float* grads, void* model, float lr, const TrainCtl* ctl, int update, float* loss_out,
+             float* logits_out, void* workspace, size_t workspace_bytes, void* stream) {
   RN50_REQUIRE(plan && images && labels && grads && model && loss_out && workspace, RN50_ERR_INVALID,
                "resnet_step: null pointer");
   RN50_REQUIRE(!update || (master && velocity), RN50_ERR_INVALID, "resnet_step: update needs master and velocity");
@@ -310,8 +366,14 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   hipStream_t side = plan->side;
   (void)hipEventRecord(plan->ev_fork, s);
   (void)hipStreamWaitEvent(side, plan->ev_fork, 0);
+  // the learning rate of this step (read by the update at the end, which waits for the side stream)
+  if (ctl) hipLaunchKernelGGL(lr_tick_kernel, dim3(1), dim3(64), 0, side, ctl->sched, ctl->t, ctl->lr);
   transpose_batch_run(plan->transposes, dt, model, ws + plan->wT, side);
   (void)hipEventRecord(plan->ev_wt, side);
+  float* const run_mean = ctl ? ctl->run_mean : nullptr;
+  float* const run_var = ctl ? ctl->run_var : nullptr;
+  const float bn_momentum = ctl ? ctl->bn_momentum : 0.f;
+  const float* const lr_dev = ctl ? ctl->lr : nullptr;
 
   // --------------------------------------------------------------- forward
   Unit& u0 = plan->units[0];
@@ -326,7 +388,8 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
     // the residual-add layers record their ReLU decisions: their backward pass then reads one byte per
     // vector instead of z
     bn_fwd_from_partials(&u.bn, ws + u.y, sm, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z,
-                         u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd), nullptr, nullptr, 0.f, st);
+                         u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd),
+                         run_mean ? run_mean + u.bn_off : nullptr, run_var ? run_var + u.bn_off : nullptr, bn_momentum, st);
   };
   stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, sums, s);
   bn_after_conv(u0, nullptr, sums, s);
@@ -484,12 +547,83 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   void* lowp = cfg.dtype == RN50_BF16 ? model : nullptr;
   if (update) {
     if (blk >= 2) (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 2], 0);
-    lars_arena_run(plan->lars_rest, master, grads, velocity, lowp, cfg.eta, cfg.momentum, lr, cfg.lars_eps,
+    lars_arena_run(plan->lars_rest, master, grads, velocity, lowp, cfg.eta, cfg.momentum, lr, lr_dev, cfg.lars_eps,
                    cfg.weight_decay, F(plan->lars_scratch), s);
   }
   (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 1], 0);  // join
   if (update)
-    lars_arena_run(plan->lars_stem, master, grads, velocity, lowp, cfg.eta, cfg.momentum, lr, cfg.lars_eps,
+    lars_arena_run(plan->lars_stem, master, grads, velocity, lowp, cfg.eta, cfg.momentum, lr, lr_dev, cfg.lars_eps,
                    cfg.weight_decay, F(plan->lars_stem_scratch), s);
-  return launch_status("resnet_step");
+  return launch_status(who);
+}
+
+}  // namespace
+
+extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* labels, float* master,
+                           float* velocity, float* grads, void* model, float lr, int update, float* loss_out,
+                           float* logits_out, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  return run_step("resnet_step", plan, images, labels, master, velocity, grads, model, lr, nullptr, update, loss_out,
+                  logits_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int resnet_plan_num_bn(const rn50_plan* plan) { return plan ? static_cast<int>(plan->units.size()) : 0; }
+extern "C" int64_t resnet_plan_bn_channels(const rn50_plan* plan) { return plan ? plan->bn_channels : 0; }
+extern "C" int64_t resnet_plan_bn_offset(const rn50_plan* plan, int i, int* channels_out) {
+  if (!plan || i < 0 || i >= static_cast<int>(plan->units.size())) return -1;
+  if (channels_out) *channels_out = plan->units[i].conv.Cout;
+  return plan->units[i].bn_off;
+}
+extern "C" size_t resnet_train_state_bytes(const rn50_plan* plan) {
+  return plan ? kStateHeader + 2 * static_cast<size_t>(plan->bn_channels) * sizeof(float) : 0;
+}
+
+extern "C" int resnet_train_state_init(const rn50_plan* plan, void* state, size_t state_bytes, int64_t first_step,
+                                       void* stream) {
+  clear_error();
+  RN50_REQUIRE(plan && state, RN50_ERR_INVALID, "resnet_train_state_init: null pointer");
+  RN50_REQUIRE(aligned16(state), RN50_ERR_ALIGN, "resnet_train_state_init: state not 16-byte aligned");
+  RN50_REQUIRE(state_bytes >= resnet_train_state_bytes(plan), RN50_ERR_WORKSPACE,
+               "resnet_train_state_init: state %zu < %zu bytes", state_bytes, resnet_train_state_bytes(plan));
+  RN50_REQUIRE(first_step >= 0, RN50_ERR_INVALID, "resnet_train_state_init: first_step < 0");
+  unsigned char* st = static_cast<unsigned char*>(state);
+  float* rm = reinterpret_cast<float*>(st + kStateHeader);
+  const int64_t n = plan->bn_channels;
+  hipLaunchKernelGGL(train_state_init_kernel, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), reinterpret_cast<int64_t*>(st), reinterpret_cast<float*>(st + 8),
+                     rm, rm + n, n, first_step);
+  return launch_status("resnet_train_state_init");
+}
+
+extern "C" int resnet_train_step(rn50_plan* plan, const rn50_lr_schedule* sc, void* state, float bn_momentum,
+                                 const void* images, const int32_t* labels, float* master, float* velocity,
+                                 float* grads, void* model, float* loss_out, float* logits_out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  clear_error();
+  RN50_REQUIRE(plan && sc && state && master && velocity, RN50_ERR_INVALID, "resnet_train_step: null pointer");
+  RN50_REQUIRE(aligned16(state), RN50_ERR_ALIGN, "resnet_train_step: state not 16-byte aligned");
+  RN50_REQUIRE(sc->decay >= RN50_DECAY_NONE && sc->decay <= RN50_DECAY_TABLE, RN50_ERR_INVALID,
+               "resnet_train_step: decay = %d", sc->decay);
+  if (sc->decay == RN50_DECAY_TABLE) {
+    RN50_REQUIRE(sc->table && sc->table_len > 0, RN50_ERR_INVALID, "resnet_train_step: empty learning-rate table");
+  } else {
+    RN50_REQUIRE(sc->warmup_steps >= 0, RN50_ERR_INVALID, "resnet_train_step: warmup_steps = %d", sc->warmup_steps);
+    RN50_REQUIRE(sc->decay != RN50_DECAY_STEP || sc->step_every > 0, RN50_ERR_INVALID,
+                 "resnet_train_step: step_every = %d", sc->step_every);
+    RN50_REQUIRE((sc->decay != RN50_DECAY_POLY && sc->decay != RN50_DECAY_LINEAR) || sc->total_steps > sc->warmup_steps,
+                 RN50_ERR_INVALID, "resnet_train_step: total_steps %d <= warmup_steps %d", sc->total_steps,
+                 sc->warmup_steps);
+  }
+  RN50_REQUIRE(bn_momentum >= 0.f && bn_momentum <= 1.f, RN50_ERR_INVALID, "resnet_train_step: bn_momentum = %g",
+               bn_momentum);
+  unsigned char* st = static_cast<unsigned char*>(state);
+  TrainCtl ctl;
+  ctl.sched = *sc;
+  ctl.t = reinterpret_cast<int64_t*>(st);
+  ctl.lr = reinterpret_cast<float*>(st + 8);
+  ctl.run_mean = reinterpret_cast<float*>(st + kStateHeader);
+  ctl.run_var = ctl.run_mean + plan->bn_channels;
+  ctl.bn_momentum = bn_momentum;
+  return run_step("resnet_train_step", plan, images, labels, master, velocity, grads, model, 0.f, &ctl, 1, loss_out,
+                  logits_out, workspace, workspace_bytes, stream);
 }

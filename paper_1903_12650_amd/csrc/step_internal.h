@@ -70,7 +70,7 @@ struct LarsArenaSpec {
 };
 size_t lars_arena_partial_bytes(const LarsArenaSpec& sp);
 void lars_arena_run(const LarsArenaSpec& sp, float* master, const float* grads, float* velocity, void* lowp,
-                    float eta, float momentum, float lr, float eps, float weight_decay, float* partial,
-                    hipStream_t s);
+                    float eta, float momentum, float lr, const float* lr_dev, float eps, float weight_decay,
+                    float* partial, hipStream_t s);
 
 }  // namespace rn50

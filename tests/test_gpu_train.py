@@ -1,0 +1,226 @@
+"""GPU parity of the training loop (resnet_train_step): device-side learning-rate schedule and step
+counter, BN moving averages, several steps in a row against the oracle's loop, graph replay."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import synth
+from oracle import net
+from gpu_util import TOL, assert_close, dev, host
+from test_gpu_step import setup_step
+
+pytestmark = pytest.mark.gpu
+SEED = synth.DEFAULT_SEED
+
+SMALL = (4, 64, (8, 12, 16, 24), (2, 1, 2, 1), 8, 10)   # N, hw, widths, blocks, stem, classes
+SMALL_BF = (4, 64, (8, 16, 24, 32), (2, 1, 2, 1), 8, 16)  # bf16: channel counts in multiples of 8
+TINY = (2, 32, (8, 8, 8, 8), (1, 1, 1, 1), 8, 10)
+
+
+@pytest.fixture(scope="module")
+def rn():
+    import paper_1903_12650_amd as rn
+    return rn
+
+
+def _schedule(rn, kw, table_dev=None):
+    kw = dict(kw)
+    if "table" in kw:
+        kw["table"] = table_dev
+    return rn.LrSchedule(**kw)
+
+
+SCHEDULES = [
+    dict(base_lr=8.0, warmup_steps=4, warmup_start_lr=2.0),
+    dict(base_lr=8.0, warmup_steps=4, warmup_start_lr=2.0, decay="step", step_every=3, step_factor=0.5),
+    dict(base_lr=6.0, warmup_steps=5, warmup_start_lr=0.5, decay="polynomial", total_steps=40, end_lr=0.01, power=2.0),
+    dict(base_lr=6.0, warmup_steps=0, decay="polynomial", total_steps=33, end_lr=0.0, power=0.5),
+    dict(base_lr=3.0, warmup_steps=2, warmup_start_lr=1.0, decay="linear", total_steps=17, end_lr=0.25),
+    dict(base_lr=0.0, decay="table", table=[0.1, 0.4, 0.2, 0.05]),
+]
+
+
+@pytest.mark.parametrize("kw", SCHEDULES, ids=lambda k: k.get("decay", "none"))
+def test_device_schedule_matches_the_oracle(rn, kw):
+    """lr(t) as the device computes it (one step of a tiny net per sample) against the oracle's
+    learning_rate, to float rounding; t advances by one per step."""
+    S = setup_step(rn, "bf16", *TINY)
+    plan = S["plan"]
+    st = rn.TrainState(plan)
+    tab = dev(np.asarray(kw["table"], np.float32)) if "table" in kw else None
+    sc = _schedule(rn, kw, tab)
+    img, lab = dev(S["images"], True), dev(S["labels"])
+    for t in (0, 1, 2, 3, 4, 5, 6, 7, 9, 10, 16, 17, 21, 32, 33, 39, 40, 41, 1000, 3_000_000_000):
+        st.reset(first_step=t)
+        rn.resnet_train_step(plan, sc, st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"])
+        torch.cuda.synchronize()
+        want = net.learning_rate(t, **kw)
+        assert st.step == t + 1
+        assert abs(st.lr - want) <= 1e-6 * abs(want) + 1e-12, (t, st.lr, want)
+
+
+def test_train_step_rejects_inconsistent_schedules(rn):
+    S = setup_step(rn, "bf16", *TINY)
+    plan = S["plan"]
+    st = rn.TrainState(plan)
+    img, lab = dev(S["images"], True), dev(S["labels"])
+    bad = [rn.LrSchedule(1.0, decay=7), rn.LrSchedule(1.0, warmup_steps=-1), rn.LrSchedule(1.0, decay="step", step_every=0),
+           rn.LrSchedule(1.0, warmup_steps=5, decay="linear", total_steps=5), rn.LrSchedule(1.0, decay="table")]
+    M0 = S["M"].clone()
+    for sc in bad:
+        with pytest.raises(rn.Rn50Error) as e:
+            rn.resnet_train_step(plan, sc, st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"])
+        assert e.value.code == -1
+    with pytest.raises(rn.Rn50Error):
+        rn.resnet_train_step(plan, rn.LrSchedule(1.0), st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"], bn_momentum=1.5)
+    torch.cuda.synchronize()
+    assert st.step == 0 and torch.equal(S["M"], M0)          # nothing was launched
+
+
+def test_train_step_is_resnet_step_at_the_schedules_rate(rn):
+    """Three steps of the loop give the same bits as three resnet_step calls that are handed lr(t) as a
+    host value; the step counter and the moving averages are the only additions."""
+    kw = dict(base_lr=3.0, warmup_steps=2, warmup_start_lr=1.0, decay="linear", total_steps=6, end_lr=0.5)
+    outs = []
+    for loop in (True, False):
+        S = setup_step(rn, "bf16", *SMALL_BF, ls=0.1)
+        plan = S["plan"]
+        img, lab = dev(S["images"], True), dev(S["labels"])
+        st = rn.TrainState(plan)
+        for t in range(3):
+            if loop:
+                rn.resnet_train_step(plan, rn.LrSchedule(**kw), st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"])
+            else:
+                rn.resnet_step(plan, img, lab, S["M"], S["V"], S["G"], S["Mod"], net.learning_rate(t, **kw), S["ws"])
+        torch.cuda.synchronize()
+        outs.append((S["M"].clone(), S["V"].clone(), S["G"].clone(), S["Mod"].clone()))
+        if loop:
+            assert st.step == 3 and st.lr == 3.0
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_train_loop_f32_against_the_oracle(rn):
+    """Four steps over two alternating batches, float mode, warm-up then polynomial decay, label
+    smoothing on: losses, learning rates, final weights, velocities and BN moving averages against the
+    oracle's loop.  Bounds: the first step is at the float bar; each later step starts from weights that
+    differ by the previous steps' error, so the bound grows with the step (the same ReLU-flip argument as
+    for a single step's gradients)."""
+    ls = 0.1
+    S = setup_step(rn, "f32", *SMALL, ls=ls)
+    plan, table, master = S["plan"], S["table"], S["master"]
+    N, hw, widths, blocks, stem, classes = SMALL
+    images2 = synth.activation_nhwc(SEED + 1, "img", N, 3, hw, hw)
+    labels2 = synth.labels(SEED + 1, "lab", N, classes)
+    batches = [(S["images"], S["labels"]), (images2, labels2)]
+    kw = dict(base_lr=4.0, warmup_steps=2, warmup_start_lr=1.0, decay="polynomial", total_steps=8, end_lr=0.1, power=2.0)
+    steps = 4
+    o = net.train_loop(batches, master, [np.zeros_like(p) for p in master], table, kw, steps, widths=widths,
+                       blocks=blocks, label_smoothing=ls)
+    st = rn.TrainState(plan)
+    sc = rn.LrSchedule(**kw)
+    dbatches = [(dev(i), dev(l)) for i, l in batches]
+    losses = []
+    for t in range(steps):
+        img, lab = dbatches[t % 2]
+        loss = rn.resnet_train_step(plan, sc, st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"])
+        torch.cuda.synchronize()
+        losses.append(float(loss.item()))
+        assert abs(st.lr - o["lrs"][t]) <= 1e-6 * o["lrs"][t]
+    assert st.step == steps
+    print("losses", losses, "oracle", o["losses"])
+    for t in range(steps):
+        assert abs(losses[t] - o["losses"][t]) <= (t + 1) * TOL["f32"] * abs(o["losses"][t]), (t, losses[t], o["losses"][t])
+    tol = steps * 10 * TOL["f32"]
+    for i, (name, _, _) in enumerate(table):
+        moved = np.linalg.norm((o["master"][i].astype(np.float64) - master[i]).ravel())
+        wn = np.linalg.norm(o["master"][i].astype(np.float64).ravel())
+        assert_close(plan.view(S["M"], i), o["master"][i], tol * moved / wn + TOL["lars"], name + " w after the loop")
+        assert_close(plan.view(S["V"], i), o["velocity"][i], tol, name + " v after the loop")
+    for i, (rm, rv) in enumerate(zip(st.running_mean, st.running_var)):
+        assert rm.numel() == o["running_mean"][i].size
+        assert_close(rm, o["running_mean"][i], steps * TOL["f32"], f"running mean of BN {i}")
+        assert_close(rv, o["running_var"][i], steps * TOL["f32"], f"running variance of BN {i}")
+
+
+def test_moving_averages_after_one_bf16_step(rn):
+    """bf16 mode: one step from (mean 0, variance 1) leaves 0.1*batch mean and 0.9 + 0.1*batch variance of
+    what each BN layer normalized, at the bf16 bar, for a momentum other than the default too."""
+    S = setup_step(rn, "bf16", 8, 64, (8, 16, 24, 32), (1, 1, 1, 1), 8, 16)
+    plan = S["plan"]
+    o = net.forward_backward(S["images"], S["labels"], S["model"], S["widths"], S["blocks"])
+    for mom in (0.9, 0.5):
+        st = rn.TrainState(plan)
+        M, V = S["M"].clone(), S["V"].clone()
+        rn.resnet_train_step(plan, rn.LrSchedule(1.0), st, dev(S["images"], True), dev(S["labels"]), M, V, S["G"],
+                             S["Mod"].clone(), S["ws"], bn_momentum=mom)
+        torch.cuda.synchronize()
+        for i, y in enumerate(o["bn_inputs"]):
+            rm, rv = orc.bn_running_update(y, np.zeros(y.shape[-1], np.float32), np.ones(y.shape[-1], np.float32), mom)
+            assert_close(st.running_mean[i], rm, TOL["bf16"], f"running mean {i}")
+            assert_close(st.running_var[i], rv, TOL["bf16"], f"running variance {i}")
+
+
+def test_train_step_graph_replays_equal_eager_steps(rn):
+    """A captured graph of one loop step, replayed with eager work and synchronizations in between,
+    walks through the same states as eager steps: the schedule, the counter and the moving averages all
+    live on the device."""
+    kw = dict(base_lr=3.0, warmup_steps=3, warmup_start_lr=0.5, decay="step", step_every=2, step_factor=0.5)
+    S = setup_step(rn, "bf16", *SMALL_BF, ls=0.1)
+    plan = S["plan"]
+    img, lab = dev(S["images"], True), dev(S["labels"])
+    sc = rn.LrSchedule(**kw)
+    loss = torch.zeros(1, device="cuda")
+    M0, Mod0 = S["M"].clone(), S["Mod"].clone()
+
+    def fresh():
+        S["M"].copy_(M0); S["Mod"].copy_(Mod0); S["V"].zero_(); S["G"].zero_()
+
+    def one(st):
+        rn.resnet_train_step(plan, sc, st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"], loss_out=loss)
+
+    st = rn.TrainState(plan)
+    eager = []
+    for t in range(6):
+        one(st)
+        torch.cuda.synchronize()
+        eager.append((S["M"].clone(), S["V"].clone(), st.buf.clone(), loss.clone()))
+    # capture (the plan's private streams exist by now), then replay from the same start
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        one(st)
+    fresh()
+    st.reset(0)
+    torch.cuda.synchronize()
+    for t in range(6):
+        g.replay()
+        torch.cuda.synchronize()
+        junk = torch.randn(1 << 16, device="cuda").sum()      # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        M, V, buf, l = eager[t]
+        assert torch.equal(S["M"], M) and torch.equal(S["V"], V), f"replay {t}: weights differ from the eager step"
+        assert torch.equal(st.buf, buf), f"replay {t}: training state differs"
+        assert torch.equal(loss, l)
+    assert st.step == 6 and abs(st.lr - net.learning_rate(5, **kw)) < 1e-6
+
+
+def test_loop_lowers_the_loss_resnet50_batch40_bf16(rn):
+    """The full network at the measured configuration: twelve steps of the loop on one fixed synthetic
+    batch (warm-up, then constant rate; label smoothing 0.1) lower the loss and keep everything finite."""
+    S = setup_step(rn, "bf16", 40, 224, (64, 128, 256, 512), (3, 4, 6, 3), 64, 1000, ls=0.1)
+    plan = S["plan"]
+    st = rn.TrainState(plan)
+    sc = rn.LrSchedule(base_lr=10.0, warmup_steps=4, warmup_start_lr=2.0)
+    img, lab = dev(S["images"], True), dev(S["labels"])
+    losses = []
+    for t in range(12):
+        loss = rn.resnet_train_step(plan, sc, st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"])
+        losses.append(float(loss.item()))
+    print("losses", [round(v, 4) for v in losses])
+    assert all(np.isfinite(losses)) and torch.isfinite(S["M"]).all() and torch.isfinite(st.buf[256:].view(torch.float32)).all()
+    assert losses[-1] < losses[0] - 0.05, losses
+    assert st.step == 12
