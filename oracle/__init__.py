@@ -111,6 +111,27 @@ def bn_running_update(x, running_mean, running_var, momentum=0.9):
     return rm, rv
 
 
+def bn_infer(x, gamma, beta, running_mean, running_var, residual=None, eps=1e-5, mode=1):
+    """BN in evaluation mode: the moving averages stand in for the batch statistics,
+    y = gamma*(x - running_mean)/sqrt(running_var + eps) + beta, then the mode's tail (0: none, 1: ReLU,
+    2: + residual, ReLU).  Plain numpy in double; the result has x's dtype."""
+    x = _c(x)
+    z = (x.astype(np.float64) - np.asarray(running_mean, np.float64)) / np.sqrt(np.asarray(running_var, np.float64) + eps)
+    z = z * np.asarray(gamma, np.float64) + np.asarray(beta, np.float64)
+    assert (mode == 2) == (residual is not None)
+    if mode == 2:
+        z = z + np.asarray(residual, np.float64)
+    if mode >= 1:
+        z = np.maximum(z, 0.0)
+    return z.astype(x.dtype)
+
+
+def top1(logits, labels):
+    """Predicted class per row (the first maximum wins) and the number of rows whose prediction is the label."""
+    pred = np.argmax(np.asarray(logits), axis=1).astype(np.int32)
+    return pred, int((pred == np.asarray(labels)).sum())
+
+
 def bn_relu_bwd(dz, x, z, gamma, mean, rstd, mode=1):
     """Returns dx, dresidual (None unless mode 2), dgamma, dbeta."""
     dz = _c(dz); dt = dz.dtype

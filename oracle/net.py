@@ -21,8 +21,8 @@ the block has a projection shortcut, proj W, g, b; then FC W, FC b.
 """
 import numpy as np
 
-from . import (avgpool_bwd, avgpool_fwd, bn_relu_bwd, bn_relu_fwd, bn_running_update, conv_dgrad, conv_fwd,
-               conv_wgrad, fc_bwd, fc_fwd, lars_update, maxpool_bwd, maxpool_fwd, xent_fwd_bwd)
+from . import (avgpool_bwd, avgpool_fwd, bn_infer, bn_relu_bwd, bn_relu_fwd, bn_running_update, conv_dgrad, conv_fwd,
+               conv_wgrad, fc_bwd, fc_fwd, lars_update, maxpool_bwd, maxpool_fwd, top1, xent_fwd_bwd)
 
 
 def param_table(widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem=64, classes=1000, in_ch=3,
@@ -220,3 +220,96 @@ def train_loop(batches, master, velocity, table, schedule, steps, *, first_step=
         losses.append(float(fb["loss"]))
         lrs.append(lr)
     return dict(losses=losses, lrs=lrs, master=master, velocity=velocity, running_mean=rm, running_var=rv, last=fb)
+
+
+# ------------------------------------------------------------------ seeded parallel initialization
+# Sec. III-B1: every process holds the same seed and initializes all weights itself, in parallel, instead
+# of receiving them by broadcast.  For that each value must be a pure function of (seed, tensor, element):
+# a counter-based generator.  Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+# as 1, 2, 3", SC'11) is used, written out below from its definition.
+_PHILOX_M = (0xD2511F53, 0xCD9E8D57)   # round multipliers
+_PHILOX_W = (0x9E3779B9, 0xBB67AE85)   # key increments (golden ratio, sqrt(3) - 1)
+TRUNC = 2.0                            # the initializer's normal is cut at +-2 standard deviations
+
+
+def philox4x32_10(counter, key):
+    """counter: uint32 array [..., 4]; key: two uint32 (scalars or arrays broadcastable to counter[..., 0]).
+    Ten rounds; per round (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0)),
+    then the key is bumped by (W0, W1)."""
+    c = [np.asarray(counter[..., i], np.uint64) for i in range(4)]
+    k0 = np.asarray(key[0], np.uint64); k1 = np.asarray(key[1], np.uint64)
+    mask = np.uint64(0xFFFFFFFF)
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M[0]) * c[0]
+        p1 = np.uint64(_PHILOX_M[1]) * c[2]
+        c = [(p1 >> np.uint64(32)) ^ c[1] ^ k0, p1 & mask, (p0 >> np.uint64(32)) ^ c[3] ^ k1, p0 & mask]
+        k0 = (k0 + np.uint64(_PHILOX_W[0])) & mask
+        k1 = (k1 + np.uint64(_PHILOX_W[1])) & mask
+    return np.stack([v.astype(np.uint32) for v in c], axis=-1)
+
+
+def truncated_normal(seed, tensor_index, n, first=0):
+    """Elements first .. first+n-1 of tensor `tensor_index`'s stream: standard normal restricted to
+    [-TRUNC, TRUNC], by inversion -- u = (x0 + 1/2)/2^32 from the first Philox output for counter
+    (element low word, element high word, tensor index, 0) and key (seed low, seed high);
+    z = Phi^-1(Phi(-TRUNC) + u*(Phi(TRUNC) - Phi(-TRUNC))).  Double precision."""
+    from scipy.special import ndtr, ndtri
+    i = np.arange(first, first + n, dtype=np.uint64)
+    ctr = np.zeros((n, 4), np.uint32)
+    ctr[:, 0] = (i & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+    ctr[:, 1] = (i >> np.uint64(32)).astype(np.uint32)
+    ctr[:, 2] = tensor_index
+    x0 = philox4x32_10(ctr, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))[:, 0]
+    u = (x0.astype(np.float64) + 0.5) / 4294967296.0
+    lo, hi = ndtr(-TRUNC), ndtr(TRUNC)
+    return ndtri(lo + u * (hi - lo))
+
+
+def init_params(table, seed=100000):
+    """Initial parameters (appendix log: truncated-normal initializer, seed 100000): convolution and FC
+    weights std*z with std = sqrt(2/fan_in) (He) and z the truncated normal above, element index = the
+    flat index in the tensor's own layout; BN gamma 1, beta 0, FC bias 0.  float32."""
+    out = []
+    for t, (_, shape, kind) in enumerate(table):
+        n = int(np.prod(shape))
+        if kind in ("conv", "fcw"):
+            fan_in = int(np.prod(shape[1:]))
+            z = truncated_normal(seed, t, n)
+            out.append((np.sqrt(2.0 / fan_in) * z).astype(np.float32).reshape(shape))
+        elif kind == "gamma":
+            out.append(np.ones(shape, np.float32))
+        else:
+            out.append(np.zeros(shape, np.float32))
+    return out
+
+
+# ------------------------------------------------------------------ evaluation
+def eval_forward(images, labels, params, running_mean, running_var, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3),
+                 eps=1e-5):
+    """The network in evaluation mode (appendix log: eval_accuracy): BN uses its moving averages.
+    running_mean / running_var: one array per BN layer, parameter order.  Returns dict(logits, pred, correct)."""
+    it = iter(range(len(params)))
+    bn = iter(range(len(running_mean)))
+
+    def cbn(x, stride, pad, mode, residual=None):
+        w, g, b = (params[next(it)] for _ in range(3))
+        i = next(bn)
+        return bn_infer(conv_fwd(x, w, stride, pad), g, b, running_mean[i], running_var[i], residual, eps, mode)
+
+    cur = maxpool_fwd(cbn(images, 2, 3, 1), 3, 2, 1)
+    for i, nb in enumerate(blocks):
+        for j in range(nb):
+            stride = 2 if (j == 0 and i > 0) else 1
+            z1 = cbn(cur, 1, 0, 1)
+            z2 = cbn(z1, stride, 1, 1)
+            if j == 0:  # parameter order: conv3 before the projection
+                w3, g3, b3 = (params[next(it)] for _ in range(3))
+                i3 = next(bn)
+                sc = cbn(cur, stride, 0, 0)
+                cur = bn_infer(conv_fwd(z2, w3, 1, 0), g3, b3, running_mean[i3], running_var[i3], sc, eps, 2)
+            else:
+                cur = cbn(z2, 1, 0, 2, residual=cur)
+    fw, fb = params[next(it)], params[next(it)]
+    logits = fc_fwd(avgpool_fwd(cur), fw, fb)
+    pred, correct = top1(logits, labels)
+    return dict(logits=logits, pred=pred, correct=correct)

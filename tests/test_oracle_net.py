@@ -271,3 +271,100 @@ def test_train_loop_lowers_the_loss_on_a_fixed_batch():
                            round_model=synth.round_bf16, widths=SMALL["widths"], blocks=SMALL["blocks"])
     for a, b in zip(one["w_new"], again["master"]):   # one step of the loop is train_step
         np.testing.assert_array_equal(a, b)
+
+
+# ------------------------------------------------------------------ seeded initialization, evaluation
+def test_philox4x32_10_known_answers():
+    """Known-answer vectors of Philox4x32-10 (Random123, Salmon et al. SC'11)."""
+    kat = [((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
+           ((0xffffffff,) * 4, (0xffffffff,) * 2, (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
+           ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
+            (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1))]
+    for ctr, key, want in kat:
+        got = net.philox4x32_10(np.array(ctr, np.uint32), key)
+        assert tuple(int(v) for v in got) == want, [hex(int(v)) for v in got]
+    # vectorized = one at a time
+    ctrs = np.array([k[0] for k in kat], np.uint32)
+    keys = (np.array([k[1][0] for k in kat], np.uint32), np.array([k[1][1] for k in kat], np.uint32))
+    assert np.array_equal(net.philox4x32_10(ctrs, keys), np.array([k[2] for k in kat], np.uint32))
+
+
+def test_truncated_normal_stream_properties():
+    from scipy import stats
+    z = net.truncated_normal(100000, 3, 200_000)
+    assert np.abs(z).max() <= 2.0 and np.abs(z).max() > 1.99
+    assert abs(z.mean()) < 0.01
+    assert abs(z.std() - 0.8796256610342398) < 0.005          # std of N(0,1) cut at +-2
+    assert stats.kstest(z, stats.truncnorm(-2, 2).cdf).pvalue > 1e-3
+    # pure function of (seed, tensor, element): any slice can be produced on its own, in any order
+    assert np.array_equal(net.truncated_normal(100000, 3, 1000, first=50_000), z[50_000:51_000])
+    # other tensors and other seeds are other streams
+    for other in (net.truncated_normal(100000, 4, 200_000), net.truncated_normal(100001, 3, 200_000)):
+        assert abs(np.corrcoef(z, other)[0, 1]) < 0.01
+    big = net.truncated_normal(7, 0, 4, first=(1 << 32) - 2)   # the element index crosses 32 bits
+    assert len(set(big.tolist())) == 4
+
+
+def test_init_params_he_scaling_and_vector_tensors():
+    table = net.param_table()
+    params = net.init_params(table[:12], 100000)
+    for (name, shape, kind), p in zip(table[:12], params):
+        assert p.shape == tuple(shape) and p.dtype == np.float32
+        if kind == "conv":
+            fan_in = int(np.prod(shape[1:]))
+            assert np.abs(p).max() <= 2.0 * np.sqrt(2.0 / fan_in) * (1 + 1e-6)
+            if p.size >= 4096:
+                assert abs(p.std() / (0.87962566 * np.sqrt(2.0 / fan_in)) - 1) < 0.05, name
+        elif kind == "gamma":
+            assert np.all(p == 1)
+        else:
+            assert np.all(p == 0)
+    again = net.init_params(table[:12], 100000)
+    assert all(np.array_equal(a, b) for a, b in zip(params, again))
+    assert not np.array_equal(params[0], net.init_params(table[:1], 100001)[0])
+
+
+def _torch_eval(images, params, rm, rv, blocks):
+    import torch
+    import torch.nn.functional as F
+    it = iter([torch.tensor(p, dtype=torch.float64) for p in params])
+    st = iter(range(len(rm)))
+
+    def cbn(x, stride, pad, relu=True, res=None, wgb=None, i=None):
+        w, g, b = wgb if wgb is not None else (next(it), next(it), next(it))
+        i = next(st) if i is None else i
+        y = F.conv2d(x, w.permute(0, 3, 1, 2), None, stride, pad)
+        y = F.batch_norm(y, torch.tensor(rm[i], dtype=torch.float64), torch.tensor(rv[i], dtype=torch.float64), g, b, False, 0.1, 1e-5)
+        if res is not None:
+            y = y + res
+        return F.relu(y) if relu else y
+
+    x = torch.tensor(images, dtype=torch.float64).permute(0, 3, 1, 2)
+    cur = F.max_pool2d(cbn(x, 2, 3), 3, 2, 1)
+    for i, nb in enumerate(blocks):
+        for j in range(nb):
+            stride = 2 if (j == 0 and i > 0) else 1
+            z1 = cbn(cur, 1, 0)
+            z2 = cbn(z1, stride, 1)
+            wgb3 = (next(it), next(it), next(it)); i3 = next(st)
+            sc = cbn(cur, stride, 0, relu=False) if j == 0 else cur
+            cur = cbn(z2, 1, 0, res=sc, wgb=wgb3, i=i3)
+    fw, fb = next(it), next(it)
+    return (cur.mean(dim=(2, 3)) @ fw.T + fb).numpy()
+
+
+def test_eval_forward_matches_torch_eval_mode():
+    table, params, images, labels = _small_setup(np.float64, N=5)
+    rng = np.random.default_rng(3)
+    n_bn = sum(k == "gamma" for _, _, k in table)
+    chans = [s[0] for _, s, k in table if k == "gamma"]
+    rm = [0.3 * rng.standard_normal(c) for c in chans]
+    rv = [0.5 + rng.random(c) for c in chans]
+    out = net.eval_forward(images, labels, params, rm, rv, SMALL["widths"], SMALL["blocks"])
+    want = _torch_eval(images, params, rm, rv, SMALL["blocks"])
+    np.testing.assert_allclose(out["logits"], want, rtol=1e-9, atol=1e-11)
+    assert np.array_equal(out["pred"], want.argmax(1)) and out["correct"] == int((want.argmax(1) == labels).sum())
+    assert n_bn == len(rm)
+    # ties go to the first maximum
+    pred, correct = orc.top1(np.array([[1.0, 3.0, 3.0], [2.0, 2.0, 1.0], [0.0, -1.0, 5.0]]), np.array([1, 1, 2]))
+    assert pred.tolist() == [1, 0, 2] and correct == 2
