@@ -362,6 +362,39 @@ int resnet_train_step(rn50_plan* plan, const rn50_lr_schedule* schedule, void* s
                       float* grads, void* model, float* loss_out, float* logits_out, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------- seeded parallel initialization
+ * Sec. III-B1: every worker holds the same seed and fills its own copy of the parameters,
+ * in parallel, so no broadcast is needed.  Each value is a function of (seed, tensor index,
+ * element index) alone: the first 32-bit output x0 of Philox4x32-10 (Salmon et al., SC'11)
+ * for counter (element low word, element high word, tensor index, 0) and key (seed low word,
+ * seed high word); u = (x0 + 1/2)/2^32; z = Phi^-1(Phi(-2) + u*(Phi(2) - Phi(-2))), the
+ * truncated-normal initializer of the appendix log cut at two standard deviations;
+ * weight = sqrt(2/fan_in)*z (He scaling; fan_in = R*S*Cin, or Cin for the FC layer), BN gamma 1,
+ * BN beta and the FC bias 0, gaps between tensors 0.  The element index is the flat index in
+ * the tensor's own (KRSC) layout.  Fills the whole master arena; velocity (or NULL) is
+ * zeroed; in BF16 mode `model` (or NULL) receives the rounded copy. */
+int resnet_init_params(const rn50_plan* plan, uint64_t seed, float* master, float* velocity, void* model,
+                       void* stream);
+
+/* ------------------------------------------------------------------ evaluation
+ * BN in evaluation mode: y = gamma*(x - running_mean)/sqrt(running_var + eps) + beta, then the
+ * mode's tail as in bn_relu_fwd.  workspace: bn_relu_infer_workspace_bytes (one float per channel). */
+size_t bn_relu_infer_workspace_bytes(const rn50_bn_desc* d);
+int bn_relu_infer(const rn50_bn_desc* d, const void* x, const float* gamma, const float* beta,
+                  const float* running_mean, const float* running_var, const void* residual, void* y,
+                  void* workspace, size_t workspace_bytes, void* stream);
+/* pred_out[n] = the first maximum of logits[n,:] (device int32[N]); correct_out[0] = the number
+ * of rows with pred_out[n] == labels[n] (device int32[1]). */
+int top1_accuracy(int N, int K, const float* logits, const int32_t* labels, int32_t* pred_out,
+                  int32_t* correct_out, void* stream);
+/* The forward pass of the plan's network in evaluation mode on one batch (appendix log:
+ * eval_accuracy), with the moving averages of a training state (read only), then top1_accuracy.
+ * Arenas, images, workspace as in resnet_step (the same workspace size); everything runs on
+ * `stream`; logits_out may be NULL. */
+int resnet_eval(rn50_plan* plan, const void* state, const void* images, const int32_t* labels,
+                const float* master, const void* model, float* logits_out, int32_t* pred_out,
+                int32_t* correct_out, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

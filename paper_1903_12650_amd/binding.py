@@ -16,7 +16,7 @@ __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "co
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
            "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
            "LrSchedule", "TrainState", "resnet_train_step", "DECAY_NONE", "DECAY_STEP", "DECAY_POLY", "DECAY_LINEAR",
-           "DECAY_TABLE"]
+           "DECAY_TABLE", "resnet_init_params", "bn_relu_infer", "top1_accuracy", "resnet_eval"]
 
 F32, BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -68,7 +68,8 @@ class StepConfig(ctypes.Structure):
 raw.rn50_last_error.restype = ctypes.c_char_p
 for _n in ("conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "lars_update_workspace_bytes",
-           "resnet_plan_workspace_bytes", "conv_bn_sums_bytes", "resnet_train_state_bytes"):
+           "resnet_plan_workspace_bytes", "conv_bn_sums_bytes", "resnet_train_state_bytes",
+           "bn_relu_infer_workspace_bytes"):
     if hasattr(raw, _n):
         getattr(raw, _n).restype = ctypes.c_size_t
 for _n in ("resnet_plan_tensor_shape", "resnet_plan_tensor_offset", "resnet_plan_arena_elems", "resnet_plan_bn_channels",
@@ -489,6 +490,39 @@ def resnet_train_step(plan, schedule, state, images, labels, master, velocity, g
                                  _ptr(loss_out), _ptr(logits_out), _ptr(workspace), ctypes.c_size_t(workspace.numel()),
                                  _stream()))
     return loss_out
+
+
+# ------------------------------------------------------------ initialization, evaluation
+def resnet_init_params(plan, seed, master, velocity=None, model=None):
+    _check(raw.resnet_init_params(plan.handle, ctypes.c_uint64(seed), _ptr(master), _ptr(velocity), _ptr(model), _stream()))
+
+
+def bn_relu_infer(x, gamma, beta, running_mean, running_var, residual=None, eps=1e-5, mode=1):
+    d = _bn_desc(x, eps, mode)
+    y = torch.empty_like(x)
+    ws = _ws(raw.bn_relu_infer_workspace_bytes(ctypes.byref(d)), x.device)
+    _check(raw.bn_relu_infer(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(running_mean), _ptr(running_var),
+                             _ptr(residual), _ptr(y), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def top1_accuracy(logits, labels):
+    """Returns (pred int32[N], correct int32[1]) device tensors."""
+    N, K = logits.shape
+    pred = torch.empty(N, dtype=torch.int32, device=logits.device)
+    correct = torch.empty(1, dtype=torch.int32, device=logits.device)
+    _check(raw.top1_accuracy(N, K, _ptr(logits), _ptr(labels), _ptr(pred), _ptr(correct), _stream()))
+    return pred, correct
+
+
+def resnet_eval(plan, state, images, labels, master, model, workspace, logits_out=None):
+    """Returns (pred int32[N], correct int32[1]) device tensors."""
+    pred = torch.empty(plan.N, dtype=torch.int32, device=images.device)
+    correct = torch.empty(1, dtype=torch.int32, device=images.device)
+    _check(raw.resnet_eval(plan.handle, _ptr(state.buf), _ptr(images), _ptr(labels), _ptr(master), _ptr(model),
+                           _ptr(logits_out), _ptr(pred), _ptr(correct), _ptr(workspace),
+                           ctypes.c_size_t(workspace.numel()), _stream()))
+    return pred, correct
 
 
 # ------------------------------------------------------------ launch timing

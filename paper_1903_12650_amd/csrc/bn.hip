@@ -640,6 +640,26 @@ void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* par
     launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
                            partial, nrows, rpp, s);
 }
+// Evaluation mode: 1/sqrt(running_var + eps) per channel, then the training pass's apply kernel with the
+// moving averages in place of the batch statistics.
+__global__ __launch_bounds__(256) void bn_infer_rstd_kernel(const float* __restrict__ running_var, float eps, int C,
+                                                            float* __restrict__ rstd) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < C) rstd[c] = static_cast<float>(1.0 / sqrt(static_cast<double>(running_var[c]) + static_cast<double>(eps)));
+}
+void bn_infer_run(const rn50_bn_desc* d, const void* x, const float* gamma, const float* beta,
+                  const float* running_mean, const float* running_var, const void* residual, void* y,
+                  float* rstd_scratch, hipStream_t s) {
+  const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
+  hipLaunchKernelGGL(bn_infer_rstd_kernel, dim3(static_cast<unsigned>(ceil_div(d->C, 256))), dim3(256), 0, s,
+                     running_var, d->eps, d->C, rstd_scratch);
+  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 768);
+  if (d->dtype == RN50_BF16)
+    RN50_LAUNCH("bn_apply", bn_apply_kernel<uint16_t>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const uint16_t*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const uint16_t*>(residual), static_cast<uint16_t*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+  else
+    RN50_LAUNCH("bn_apply", bn_apply_kernel<float>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const float*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const float*>(residual), static_cast<float*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+}
+
 void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const uint8_t* relu_mask,
                           const float* gamma, const float* beta, const float* mean, const float* rstd,
                           const float* partial, int nrows, void* dx, void* dres, float* dgamma, float* dbeta,
@@ -778,4 +798,28 @@ extern "C" int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc
   bn_bwd_from_partials(d, dz, x, relu_mask, gamma, beta, save_mean, save_rstd, sums, pr.num, dx,
                        d->mode == 2 ? dresidual : nullptr, dgamma, dbeta, static_cast<hipStream_t>(stream));
   return launch_status("bn_relu_bwd_from_sums");
+}
+
+extern "C" size_t bn_relu_infer_workspace_bytes(const rn50_bn_desc* d) {
+  if (!d || d->C <= 0) return 0;
+  return align_up(static_cast<size_t>(d->C) * sizeof(float), 256);
+}
+
+extern "C" int bn_relu_infer(const rn50_bn_desc* d, const void* x, const float* gamma, const float* beta,
+                             const float* running_mean, const float* running_var, const void* residual, void* y,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_desc(d, "bn_relu_infer")) return rc;
+  RN50_REQUIRE(x && gamma && beta && running_mean && running_var && y && workspace, RN50_ERR_INVALID,
+               "bn_relu_infer: null pointer");
+  RN50_REQUIRE((d->mode == 2) == (residual != nullptr), RN50_ERR_INVALID,
+               "bn_relu_infer: residual must be given exactly in mode 2");
+  RN50_REQUIRE(aligned16(x) && aligned16(y) && aligned16(residual) && aligned16(workspace) && aligned16(gamma) &&
+                   aligned16(beta) && aligned16(running_mean) && aligned16(running_var),
+               RN50_ERR_ALIGN, "bn_relu_infer: pointer not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= bn_relu_infer_workspace_bytes(d), RN50_ERR_WORKSPACE,
+               "bn_relu_infer: workspace %zu < %zu bytes", workspace_bytes, bn_relu_infer_workspace_bytes(d));
+  bn_infer_run(d, x, gamma, beta, running_mean, running_var, residual, y, static_cast<float*>(workspace),
+               static_cast<hipStream_t>(stream));
+  return launch_status("bn_relu_infer");
 }

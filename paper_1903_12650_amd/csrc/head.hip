@@ -674,3 +674,62 @@ extern "C" int xent_fwd_bwd(int N, int K, const float* logits, const int32_t* la
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, s, row_loss_out, N, loss_out);
   return launch_status("xent_fwd_bwd");
 }
+
+// ------------------------------------------------------------------ top-1
+namespace rn50 {
+// One workgroup per row: the first maximum of the row (ties go to the lower class index).
+__global__ __launch_bounds__(256) void top1_rows_kernel(const float* __restrict__ logits, int K, int32_t* __restrict__ pred) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  const float* row = logits + static_cast<int64_t>(blockIdx.x) * K;
+  float best = -INFINITY;
+  int at = 0x7fffffff;
+  for (int k = threadIdx.x; k < K; k += 256) {
+    const float v = row[k];
+    if (at == 0x7fffffff || v > best) {  // strictly greater keeps the first
+      best = v;
+      at = k;
+    }
+  }
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = at;
+  __syncthreads();
+  for (int step = 128; step > 0; step >>= 1) {
+    if (threadIdx.x < step) {
+      const float ov = sv[threadIdx.x + step];
+      const int oi = si[threadIdx.x + step];
+      if (oi != 0x7fffffff && (si[threadIdx.x] == 0x7fffffff || ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x]))) {
+        sv[threadIdx.x] = ov;
+        si[threadIdx.x] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) pred[blockIdx.x] = si[0];
+}
+// One workgroup: how many predictions equal their label.
+__global__ __launch_bounds__(256) void top1_count_kernel(const int32_t* __restrict__ pred, const int32_t* __restrict__ labels,
+                                                         int N, int32_t* __restrict__ correct) {
+  __shared__ int sc[256];
+  int c = 0;
+  for (int n = threadIdx.x; n < N; n += 256) c += pred[n] == labels[n];
+  sc[threadIdx.x] = c;
+  __syncthreads();
+  for (int step = 128; step > 0; step >>= 1) {
+    if (threadIdx.x < step) sc[threadIdx.x] += sc[threadIdx.x + step];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) correct[0] = sc[0];
+}
+}  // namespace rn50
+
+extern "C" int top1_accuracy(int N, int K, const float* logits, const int32_t* labels, int32_t* pred_out,
+                             int32_t* correct_out, void* stream) {
+  rn50::clear_error();
+  RN50_REQUIRE(N > 0 && K > 0, RN50_ERR_INVALID, "top1_accuracy: N=%d K=%d", N, K);
+  RN50_REQUIRE(logits && labels && pred_out && correct_out, RN50_ERR_INVALID, "top1_accuracy: null pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(rn50::top1_rows_kernel, dim3(N), dim3(256), 0, s, logits, K, pred_out);
+  hipLaunchKernelGGL(rn50::top1_count_kernel, dim3(1), dim3(256), 0, s, pred_out, labels, N, correct_out);
+  return rn50::launch_status("top1_accuracy");
+}

@@ -34,6 +34,7 @@ struct Tensor {
   int dims[4];
   int64_t count, offset;
   bool decay;
+  int fan_in;  // weights: inputs per output (He scaling of the initializer); 0: BN gamma (ones); -1: zeros
 };
 
 }  // namespace rn50
@@ -75,12 +76,13 @@ using namespace rn50;
 
 namespace {
 
-int add_tensor(rn50_plan* p, int d0, int d1, int d2, int d3, bool decay) {
+int add_tensor(rn50_plan* p, int d0, int d1, int d2, int d3, bool decay, bool ones = false) {
   Tensor t;
   t.dims[0] = d0; t.dims[1] = d1; t.dims[2] = d2; t.dims[3] = d3;
   t.count = 1;
   for (int i = 0; i < 4; ++i)
     if (t.dims[i] > 0) t.count *= t.dims[i];
+  t.fan_in = decay ? static_cast<int>(t.count / d0) : (ones ? 0 : -1);
   t.offset = p->arena_elems;
   t.decay = decay;
   p->arena_elems += (t.count + 63) / 64 * 64;
@@ -95,7 +97,7 @@ int add_unit(rn50_plan* p, int N, int H, int W, int Cin, int Cout, int R, int st
   u.Q = (W + 2 * pad - R) / stride + 1;
   u.bn = rn50_bn_desc{N, u.P, u.Q, Cout, p->cfg.bn_eps, p->cfg.dtype, mode};
   u.iw = add_tensor(p, Cout, R, R, Cin, true);
-  u.ig = add_tensor(p, Cout, 0, 0, 0, false);
+  u.ig = add_tensor(p, Cout, 0, 0, 0, false, true);
   u.ib = add_tensor(p, Cout, 0, 0, 0, false);
   u.bn_off = p->bn_channels;
   p->bn_channels += (Cout + 63) / 64 * 64;
@@ -565,6 +567,158 @@ extern "C" int resnet_step(rn50_plan* plan, const void* images, const int32_t* l
   clear_error();
   return run_step("resnet_step", plan, images, labels, master, velocity, grads, model, lr, nullptr, update, loss_out,
                   logits_out, workspace, workspace_bytes, stream);
+}
+
+// ------------------------------------------------------------------ seeded parallel initialization
+namespace {
+constexpr int kInitMaxTensors = 192;
+struct InitArgs {
+  float* master;
+  float* velocity;  // or null
+  uint16_t* lowp;   // or null
+  int num;
+  uint32_t seed_lo, seed_hi;
+  double cdf_lo, cdf_span;  // Phi(-2), Phi(2) - Phi(-2)
+  int64_t total;            // arena elements
+  uint32_t offset[kInitMaxTensors];
+  uint32_t count[kInitMaxTensors];
+  int fan_in[kInitMaxTensors];
+  int tensor0;              // index of the first tensor of this launch
+};
+
+// Philox4x32-10 (Salmon et al., SC'11): first output word for counter (c0, c1, c2, 0) and key (k0, k1).
+__device__ __forceinline__ uint32_t philox4x32_10_x0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t k0, uint32_t k1) {
+  uint32_t c3 = 0;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+// One thread per arena element: every value is a function of (seed, tensor, element) alone, so any
+// worker produces the same arena with no exchange.
+__global__ __launch_bounds__(256) void init_params_kernel(const InitArgs a) {
+  const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= a.total) return;
+  int lo = 0, hi = a.num;  // last tensor whose offset <= e
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.offset[mid] <= e) lo = mid; else hi = mid;
+  }
+  const int64_t i = e - a.offset[lo];
+  float w = 0.f;
+  if (i < a.count[lo]) {
+    const int fan = a.fan_in[lo];
+    if (fan == 0) {
+      w = 1.f;
+    } else if (fan > 0) {
+      const uint32_t x0 = philox4x32_10_x0(static_cast<uint32_t>(i), static_cast<uint32_t>(i >> 32),
+                                           static_cast<uint32_t>(a.tensor0 + lo), a.seed_lo, a.seed_hi);
+      const double u = (static_cast<double>(x0) + 0.5) * (1.0 / 4294967296.0);
+      const double z = normcdfinv(a.cdf_lo + u * a.cdf_span);
+      w = static_cast<float>(sqrt(2.0 / static_cast<double>(fan)) * z);
+    }
+  }
+  a.master[e] = w;
+  if (a.velocity) a.velocity[e] = 0.f;
+  if (a.lowp) a.lowp[e] = float_to_bf16_bits(w);
+}
+}  // namespace
+
+extern "C" int resnet_init_params(const rn50_plan* plan, uint64_t seed, float* master, float* velocity, void* model,
+                                  void* stream) {
+  clear_error();
+  RN50_REQUIRE(plan && master, RN50_ERR_INVALID, "resnet_init_params: null pointer");
+  RN50_REQUIRE(aligned16(master) && aligned16(velocity) && aligned16(model), RN50_ERR_ALIGN,
+               "resnet_init_params: pointer not 16-byte aligned");
+  RN50_REQUIRE(plan->tensors.size() <= kInitMaxTensors, RN50_ERR_UNSUPPORTED, "resnet_init_params: %zu tensors",
+               plan->tensors.size());
+  InitArgs a{};
+  a.master = master;
+  a.velocity = velocity;
+  a.lowp = (plan->cfg.dtype == RN50_BF16 && model && model != static_cast<void*>(master)) ? static_cast<uint16_t*>(model)
+                                                                                          : nullptr;
+  a.num = static_cast<int>(plan->tensors.size());
+  a.seed_lo = static_cast<uint32_t>(seed);
+  a.seed_hi = static_cast<uint32_t>(seed >> 32);
+  a.cdf_lo = 0.5 * erfc(2.0 / sqrt(2.0));
+  a.cdf_span = (1.0 - a.cdf_lo) - a.cdf_lo;
+  a.total = plan->arena_elems;
+  a.tensor0 = 0;
+  for (int t = 0; t < a.num; ++t) {
+    a.offset[t] = static_cast<uint32_t>(plan->tensors[t].offset);
+    a.count[t] = static_cast<uint32_t>(plan->tensors[t].count);
+    a.fan_in[t] = plan->tensors[t].fan_in;
+  }
+  hipLaunchKernelGGL(init_params_kernel, dim3(static_cast<unsigned>(ceil_div(a.total, 256))), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), a);
+  return launch_status("resnet_init_params");
+}
+
+// ------------------------------------------------------------------ evaluation
+extern "C" int resnet_eval(rn50_plan* plan, const void* state, const void* images, const int32_t* labels,
+                           const float* master, const void* model, float* logits_out, int32_t* pred_out,
+                           int32_t* correct_out, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  RN50_REQUIRE(plan && state && images && labels && master && model && pred_out && correct_out && workspace,
+               RN50_ERR_INVALID, "resnet_eval: null pointer");
+  RN50_REQUIRE(aligned16(state) && aligned16(images) && aligned16(master) && aligned16(model) && aligned16(workspace) &&
+                   aligned16(logits_out),
+               RN50_ERR_ALIGN, "resnet_eval: pointer not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= plan->ws_bytes, RN50_ERR_WORKSPACE, "resnet_eval: workspace %zu < %zu bytes",
+               workspace_bytes, plan->ws_bytes);
+  const rn50_step_config& cfg = plan->cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const size_t es = plan->es;
+  const int dt = cfg.dtype;
+  const float* run_mean = reinterpret_cast<const float*>(static_cast<const unsigned char*>(state) + kStateHeader);
+  const float* run_var = run_mean + plan->bn_channels;
+  auto W = [&](int ti) -> const void* { return static_cast<const unsigned char*>(model) + plan->tensors[ti].offset * es; };
+  auto MP = [&](int ti) -> const float* { return master + plan->tensors[ti].offset; };
+  auto F = [&](size_t off) -> float* { return reinterpret_cast<float*>(ws + off); };
+  auto bn = [&](Unit& u, const void* residual) {
+    bn_infer_run(&u.bn, ws + u.y, MP(u.ig), MP(u.ib), run_mean + u.bn_off, run_var + u.bn_off, residual, ws + u.z,
+                 F(u.rstd), s);
+  };
+  Unit& u0 = plan->units[0];
+  stem_pad_input(&u0.conv, images, ws + plan->xp, s);
+  stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, nullptr, s);
+  bn(u0, nullptr);
+  STEP_TRY(maxpool_fwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool, ws + plan->pool_argmax, s));
+  const unsigned char* cur = ws + plan->pool;
+  for (const Block& b : plan->blocks) {
+    Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
+    const void* shortcut = cur;
+    if (b.up >= 0) {
+      Unit& up = plan->units[b.up];
+      fwd_run(&up.conv, cur, W(up.iw), ws + up.y, nullptr, s);
+      bn(up, nullptr);
+      shortcut = ws + up.z;
+    }
+    fwd_run(&u1.conv, cur, W(u1.iw), ws + u1.y, nullptr, s);
+    bn(u1, nullptr);
+    fwd_run(&u2.conv, ws + u1.z, W(u2.iw), ws + u2.y, nullptr, s);
+    bn(u2, nullptr);
+    fwd_run(&u3.conv, ws + u2.z, W(u3.iw), ws + u3.y, nullptr, s);
+    bn(u3, shortcut);
+    cur = ws + u3.z;
+  }
+  const int HW = plan->final_hw * plan->final_hw;
+  const int fcw = static_cast<int>(plan->tensors.size()) - 2, fcb = fcw + 1;
+  float* logits = logits_out ? logits_out : F(plan->logits);
+  STEP_TRY(avgpool_fwd(cfg.N, HW, plan->fc_in, dt, cur, ws + plan->avg, s));
+  STEP_TRY(fc_fwd(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, W(fcw), MP(fcb), logits, s));
+  STEP_TRY(top1_accuracy(cfg.N, cfg.classes, logits, labels, pred_out, correct_out, s));
+  return launch_status("resnet_eval");
 }
 
 extern "C" int resnet_plan_num_bn(const rn50_plan* plan) { return plan ? static_cast<int>(plan->units.size()) : 0; }

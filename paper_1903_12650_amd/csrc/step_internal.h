@@ -62,6 +62,11 @@ void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, 
                           const float* partial, int nrows, void* dx, void* dres, float* dgamma, float* dbeta,
                           hipStream_t s);
 
+// evaluation mode (moving averages instead of batch statistics); rstd_scratch: float[C]
+void bn_infer_run(const rn50_bn_desc* d, const void* x, const float* gamma, const float* beta,
+                  const float* running_mean, const float* running_var, const void* residual, void* y,
+                  float* rstd_scratch, hipStream_t s);
+
 // lars.hip
 struct LarsArenaSpec {
   int num = 0;

@@ -224,3 +224,133 @@ def test_loop_lowers_the_loss_resnet50_batch40_bf16(rn):
     assert all(np.isfinite(losses)) and torch.isfinite(S["M"]).all() and torch.isfinite(st.buf[256:].view(torch.float32)).all()
     assert losses[-1] < losses[0] - 0.05, losses
     assert st.step == 12
+
+
+# ------------------------------------------------------------------ seeded initialization, evaluation
+def test_init_params_matches_the_oracle_streams(rn):
+    """resnet_init_params on the full ResNet-50 arena: every tensor equals the oracle's counter-based
+    truncated-normal stream (same Philox words, so only the rounding of Phi^-1 may differ), the vectors are
+    ones / zeros, the gaps zero, velocity zero, the bf16 copy the rounded master."""
+    plan = rn.ResnetPlan(40, rn.BF16)
+    table = net.param_table()
+    M = torch.full((plan.arena_elems,), float("nan"), device="cuda")
+    V = torch.full_like(M, float("nan"))
+    Mod = torch.zeros(plan.arena_elems, dtype=torch.bfloat16, device="cuda")
+    rn.resnet_init_params(plan, 100000, M, V, Mod)
+    torch.cuda.synchronize()
+    Mh = host(M)
+    assert np.all(host(V) == 0) and np.isfinite(Mh).all()
+    assert np.array_equal(host(Mod), synth.round_bf16(Mh))
+    covered = np.zeros(plan.arena_elems, bool)
+    check = list(range(0, 12)) + [len(table) - 2, len(table) - 1] + [t for t, (_, s, _) in enumerate(table) if s == (512, 3, 3, 512)][:1]
+    for t, (name, shape, kind) in enumerate(table):
+        got = Mh[plan.offsets[t]:plan.offsets[t] + plan.sizes[t]]
+        covered[plan.offsets[t]:plan.offsets[t] + plan.sizes[t]] = True
+        if kind == "gamma":
+            assert np.all(got == 1), name
+        elif kind in ("beta", "fcb"):
+            assert np.all(got == 0), name
+        else:
+            fan_in = int(np.prod(shape[1:]))
+            assert np.abs(got).max() <= 2 * np.sqrt(2.0 / fan_in) * (1 + 1e-6), name
+            if t in check:
+                want = (np.sqrt(2.0 / fan_in) * net.truncated_normal(100000, t, got.size)).astype(np.float32)
+                assert orc.rel_l2(got, want) <= 1e-7, name
+                assert np.mean(got == want) > 0.999, (name, np.mean(got == want))   # at most a last-bit difference
+    assert np.all(Mh[~covered] == 0)
+    # another seed, another arena; the same seed again, the same bits; float mode fills the master arena only
+    M2 = torch.empty_like(M)
+    rn.resnet_init_params(plan, 100001, M2)
+    M3 = torch.empty_like(M)
+    rn.resnet_init_params(rn.ResnetPlan(8, rn.F32), 100000, M3)
+    torch.cuda.synchronize()
+    assert not torch.equal(M2, M) and torch.equal(M3, M)
+
+
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_bn_relu_infer_vs_oracle(rn, mode_name, mode):
+    bf = mode_name == "bf16"
+    for (N, H, C) in [(3, 7, 24), (2, 28, 256), (5, 9, 2048)]:
+        x = synth.activation_nhwc(SEED, "x", N, C, H, H, 2.0) + 0.5
+        res = synth.activation_nhwc(SEED, "r", N, C, H, H) if mode == 2 else None
+        if bf:
+            x = synth.round_bf16(x); res = None if res is None else synth.round_bf16(res)
+        g = (1 + 0.3 * synth.normal(SEED, "g", (C,))).astype(np.float32)
+        b = (0.2 * synth.normal(SEED, "b", (C,))).astype(np.float32)
+        rm = (0.5 * synth.normal(SEED, "rm", (C,))).astype(np.float32)
+        rv = (0.5 + np.abs(synth.normal(SEED, "rv", (C,)))).astype(np.float32)
+        want = orc.bn_infer(x, g, b, rm, rv, res, 1e-5, mode)
+        got = rn.bn_relu_infer(dev(x, bf), dev(g), dev(b), dev(rm), dev(rv), None if res is None else dev(res, bf), 1e-5, mode)
+        assert_close(got, want, TOL[mode_name], f"bn_relu_infer {mode_name} mode {mode} {(N, H, C)}")
+
+
+def test_top1_accuracy_vs_oracle(rn):
+    rng = np.random.default_rng(5)
+    for N, K in [(1, 1), (7, 10), (40, 1000), (300, 1000), (3, 70000)]:
+        logits = rng.standard_normal((N, K)).astype(np.float32)
+        logits[0, K // 2:] = logits[0].max() + 1.0          # a run of equal maxima: the first one wins
+        labels = rng.integers(0, K, N).astype(np.int32)
+        labels[::2] = np.argmax(logits[::2], 1)
+        pred, correct = rn.top1_accuracy(dev(logits), dev(labels))
+        p_o, c_o = orc.top1(logits, labels)
+        assert np.array_equal(host(pred), p_o) and int(correct.item()) == c_o
+
+
+@pytest.mark.parametrize("mode_name,cfg", [("f32", SMALL), ("bf16", SMALL_BF)])
+def test_resnet_eval_vs_oracle_after_training_steps(rn, mode_name, cfg):
+    """Two loop steps (so the moving averages are not trivial), then the evaluation pass on another batch:
+    logits and predictions against the oracle's evaluation of the GPU's own weights and moving averages."""
+    S = setup_step(rn, mode_name, *cfg)
+    plan, table, bf = S["plan"], S["table"], S["bf"]
+    N, hw, widths, blocks, stem, classes = cfg
+    st = rn.TrainState(plan)
+    img, lab = dev(S["images"], bf), dev(S["labels"])
+    for _ in range(2):
+        rn.resnet_train_step(plan, rn.LrSchedule(1.0), st, img, lab, S["M"], S["V"], S["G"], S["Mod"], S["ws"], bn_momentum=0.5)
+    images2 = synth.activation_nhwc(SEED + 1, "img", N, 3, hw, hw)
+    labels2 = synth.labels(SEED + 1, "lab", N, classes)
+    if bf:
+        images2 = synth.round_bf16(images2)
+    logits = torch.empty((N, classes), device="cuda")
+    pred, correct = rn.resnet_eval(plan, st, dev(images2, bf), dev(labels2), S["M"], S["Mod"], S["ws"], logits_out=logits)
+    torch.cuda.synchronize()
+    # the oracle evaluates the network the GPU holds: model weights for the convolutions and the FC weight,
+    # master values for the per-channel vectors
+    params = []
+    for i, (name, shape, kind) in enumerate(table):
+        src = S["Mod"] if (bf and kind in ("conv", "fcw")) else S["M"]
+        params.append(host(plan.view(src, i)).astype(np.float32))
+    rm = [host(a) for a in st.running_mean]; rv = [host(a) for a in st.running_var]
+    o = net.eval_forward(images2, labels2, params, rm, rv, widths, blocks)
+    assert_close(logits, o["logits"], TOL[mode_name], "evaluation logits")
+    lg = host(logits)
+    p_o, c_o = orc.top1(lg, labels2)                      # decisions from the GPU's own logits: exact
+    assert np.array_equal(host(pred), p_o) and int(correct.item()) == c_o
+    margin = np.sort(o["logits"], 1)[:, -1] - np.sort(o["logits"], 1)[:, -2]
+    clear = margin > 4 * TOL[mode_name] * np.abs(o["logits"]).max()
+    assert np.array_equal(host(pred)[clear], o["pred"][clear])   # and the oracle's wherever its margin is clear
+
+
+def test_init_train_eval_round_trip_resnet50_batch40(rn):
+    """The pieces together at the measured configuration: parameters from the seed on the device, twenty
+    loop steps on one fixed synthetic batch, then the evaluation pass on that batch with the moving
+    averages: the loss falls, and the evaluation pass (chance level before training) runs on the trained
+    state and recognizes at least as many of the batch's images as before."""
+    plan = rn.ResnetPlan(40, rn.BF16, label_smoothing=0.1)
+    M = torch.empty(plan.arena_elems, device="cuda"); V = torch.empty_like(M); G = torch.zeros_like(M)
+    Mod = torch.empty(plan.arena_elems, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    rn.resnet_init_params(plan, 100000, M, V, Mod)
+    img = dev(synth.round_bf16(synth.activation_nhwc(SEED, "img", 40, 3, 224, 224)), True)
+    lab = dev(synth.labels(SEED, "lab", 40, 1000))
+    st = rn.TrainState(plan)
+    _, before = rn.resnet_eval(plan, st, img, lab, M, Mod, ws)
+    sc = rn.LrSchedule(base_lr=10.0, warmup_steps=4, warmup_start_lr=2.0)
+    losses = []
+    for t in range(20):
+        losses.append(float(rn.resnet_train_step(plan, sc, st, img, lab, M, V, G, Mod, ws, bn_momentum=0.5).item()))
+    _, after = rn.resnet_eval(plan, st, img, lab, M, Mod, ws)
+    print("losses", [round(v, 3) for v in losses], "correct before/after", int(before.item()), int(after.item()))
+    assert np.isfinite(losses).all() and losses[-1] < losses[0] - 0.05
+    assert 0 <= int(before.item()) <= 2 and int(before.item()) <= int(after.item()) <= 40
