@@ -127,7 +127,7 @@ int bn_relu_fwd(const rn50_bn_desc* d, const void* x, const float* gamma, const 
  * from z (the forward output) when z != NULL; in mode 1 both may be NULL and the mask
  * is recomputed from x, gamma, beta (required then).  Mode 2 needs relu_mask or z.
  * g = (dz+dz2)*mask;  dbeta = sum_m g;  dgamma = sum_m g*xhat;
- * dx = gamma*rstd*(g - dbeta/m - xhat*dgamma/m);  mode 2: dresidual = g.
+ * dx = gamma*rstd*(g - dbeta/m - xhat*dgamma/m);  mode 2: dresidual = g (NULL: not stored).
  * dx, dresidual: device [m,C] dtype; dgamma, dbeta: device float[C]. */
 int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const void* x,
                 const void* z, const uint8_t* relu_mask, const float* gamma, const float* beta, const float* save_mean,
@@ -145,13 +145,14 @@ int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz2, const vo
  * convolution `producer`: conv_dgrad_bn_sums computes
  *   dz = data gradient of that convolution (+ addend, when z has a second consumer
  *        whose gradient is already known: device [N,H,W,Cin] dtype or NULL; the sum is
- *        formed in float and rounded once),
+ *        formed in float and rounded once.  With addend_mask, the ReLU bits a residual-add
+ *        BN layer recorded, the addend is that layer's unmasked output gradient and counts
+ *        only where its bit is set: the identity shortcut's gradient, taken without a copy),
  * stores it in dx, and takes the sums over g = dz*[z>0] and g*xhat of the BN layer
  * (bn_x: the BN layer's input, [N,H,W,Cin]; relu_mask: the bits its forward pass
  * recorded, or NULL in mode 1 to recompute the decision from bn_x; gamma, beta,
  * save_mean, save_rstd: the layer's, device float[Cin]).  bn_relu_bwd_from_sums then
- * gives what bn_relu_bwd(d, dz, NULL, x, ...) gives (mode 2: relu_mask and dresidual
- * required).  The sums are formed from the rounded values that are stored, in a fixed
+ * gives what bn_relu_bwd(d, dz, NULL, x, ...) gives (mode 2: relu_mask required).  The sums are formed from the rounded values that are stored, in a fixed
  * order.
  * sums: device float, conv_bn_sums_bytes(d) bytes (16-byte aligned), layout private
  * to the pair of calls; `producer` must be the descriptor the sums were made with. */
@@ -164,7 +165,7 @@ int bn_relu_fwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer,
                           float* save_rstd, float* running_mean, float* running_var, float momentum,
                           void* stream);
 int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
-                       const void* addend, const void* bn_x, const uint8_t* relu_mask,
+                       const void* addend, const uint8_t* addend_mask, const void* bn_x, const uint8_t* relu_mask,
                        const float* gamma, const float* beta, const float* save_mean,
                        const float* save_rstd, float* sums, size_t sums_bytes, void* workspace,
                        size_t workspace_bytes, void* stream);

@@ -250,8 +250,8 @@ def bn_relu_fwd_from_sums(x, handle, gamma, beta, residual=None, eps=1e-5, mode=
 
 
 def conv_dgrad_bn_sums(dy, w, x_shape, stride, pad, bn_x, gamma, beta, mean, rstd, dx=None, workspace=None,
-                       sums=None, addend=None, relu_mask=None):
-    """Returns dx (= data gradient + addend) and the handle bn_relu_bwd_from_sums takes."""
+                       sums=None, addend=None, relu_mask=None, addend_mask=None):
+    """Returns dx (= data gradient + addend [under addend_mask]) and the handle bn_relu_bwd_from_sums takes."""
     d = _conv_desc(x_shape, w.shape, stride, pad, _dt(dy))
     if dx is None:
         dx = torch.empty(tuple(x_shape), dtype=dy.dtype, device=dy.device)
@@ -259,7 +259,7 @@ def conv_dgrad_bn_sums(dy, w, x_shape, stride, pad, bn_x, gamma, beta, mean, rst
         workspace = _ws(conv_dgrad_workspace_bytes(d), dy.device)
     if sums is None:
         sums = _ws(conv_bn_sums_bytes(d), dy.device)
-    _check(raw.conv_dgrad_bn_sums(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(addend), _ptr(bn_x),
+    _check(raw.conv_dgrad_bn_sums(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(addend), _ptr(addend_mask), _ptr(bn_x),
                                   _ptr(relu_mask), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(rstd), _ptr(sums),
                                   ctypes.c_size_t(sums.numel()), _ptr(workspace), ctypes.c_size_t(workspace.numel()),
                                   _stream()))

@@ -531,7 +531,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
         Vec16 ov;
         Elem<T>::pack(o, ov);
         store16(dx + b.off[u], ov);
-        if (mode == 2) {
+        if (mode == 2 && dres) {
           Vec16 gv;
           Elem<T>::pack(g, gv);
           store16(dres + b.off[u], gv);
@@ -722,8 +722,7 @@ extern "C" int bn_relu_bwd(const rn50_bn_desc* d, const void* dz, const void* dz
   if (int rc = check_desc(d, "bn_relu_bwd")) return rc;
   RN50_REQUIRE(dz && x && gamma && save_mean && save_rstd && dx && dgamma && dbeta && workspace,
                RN50_ERR_INVALID, "bn_relu_bwd: null pointer");
-  RN50_REQUIRE(d->mode != 2 || ((z || relu_mask) && dresidual), RN50_ERR_INVALID,
-               "bn_relu_bwd: mode 2 needs z or relu_mask, and dresidual");
+  RN50_REQUIRE(d->mode != 2 || z || relu_mask, RN50_ERR_INVALID, "bn_relu_bwd: mode 2 needs z or relu_mask");
   RN50_REQUIRE(d->mode != 1 || z || relu_mask || beta, RN50_ERR_INVALID,
                "bn_relu_bwd: mode 1 needs z, relu_mask, or beta to recompute the ReLU mask");
   RN50_REQUIRE(aligned16(dz) && aligned16(dz2) && aligned16(x) && aligned16(z) && aligned16(dx) &&
@@ -781,8 +780,7 @@ extern "C" int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc
   if (int rc = check_desc(d, "bn_relu_bwd_from_sums")) return rc;
   RN50_REQUIRE(d->mode == 1 || d->mode == 2, RN50_ERR_UNSUPPORTED, "bn_relu_bwd_from_sums: mode %d (needs a ReLU)",
                d->mode);
-  RN50_REQUIRE(d->mode != 2 || (relu_mask && dresidual), RN50_ERR_INVALID,
-               "bn_relu_bwd_from_sums: mode 2 needs relu_mask and dresidual");
+  RN50_REQUIRE(d->mode != 2 || relu_mask, RN50_ERR_INVALID, "bn_relu_bwd_from_sums: mode 2 needs relu_mask");
   RN50_REQUIRE(producer && conv_bn_sums_bytes(producer) > 0, RN50_ERR_INVALID,
                "bn_relu_bwd_from_sums: bad producer descriptor");
   RN50_REQUIRE(dz && x && gamma && beta && save_mean && save_rstd && sums && dx && dgamma && dbeta,

@@ -106,8 +106,11 @@ struct IgemmArgs {
   // product in float before the one rounding to the storage type (the stored output is the sum).
   // bn_zmask (or null): the BN layer's recorded ReLU decision bits, one byte per 16-byte vector of its
   // output; without them the decision is recomputed from bn_x.
+  // addend_mask (or null): the addend is the output gradient of a residual-add layer that is still
+  // unmasked; it counts only where that layer's recorded ReLU bit is set (same byte layout as bn_zmask).
   const void* addend;
   const uint8_t* bn_zmask;
+  const uint8_t* addend_mask;
 };
 
 constexpr int kPitch = 144;  // LDS row pitch of a 128-byte K chunk (conflict-free 16-byte reads)
@@ -385,7 +388,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const int nc = col_ok ? n : 0;
     const T* add = static_cast<const T*>(a.addend);
     Vec16 xv[NPASS], av[NPASS];
-    uint32_t zb[NPASS];
+    uint32_t zb[NPASS], ab[NPASS];
     int pix[NPASS];
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
@@ -395,6 +398,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       xv[pass] = load16(bx + at);
       if (add) av[pass] = load16(add + at);
       if (a.bn_zmask) zb[pass] = a.bn_zmask[at / V];
+      ab[pass] = a.addend_mask ? a.addend_mask[at / V] : 0xffu;
     }
     float scale[V], bias[V], rs[V], nmr[V], cg[V], cb[V], cm[V];
     load_floats<V>(a.bn_gamma + nc, cg);
@@ -415,6 +419,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         if (add) {
           float ad[V];
           Elem<T>::unpack(av[pass], ad);
+#pragma unroll
+          for (int j = 0; j < V; ++j) ad[j] = ((ab[pass] >> j) & 1u) ? ad[j] : 0.f;
           if (wide) {
             const float4 lo = *reinterpret_cast<const float4*>(smem + row * CPW + op * 32);
             const float4 hi = *reinterpret_cast<const float4*>(smem + row * CPW + op * 32 + 16);
@@ -1159,7 +1165,7 @@ void dgrad_run(const rn50_conv_desc* d, const void* dy, const void* wT, void* dx
   if (bn) {
     a.partial = bn->partial; a.bn_x = bn->x;
     a.bn_gamma = bn->gamma; a.bn_beta = bn->beta; a.bn_mean = bn->mean; a.bn_rstd = bn->rstd;
-    a.addend = bn->addend; a.bn_zmask = bn->relu_mask;
+    a.addend = bn->addend; a.bn_zmask = bn->relu_mask; a.addend_mask = bn->addend ? bn->addend_mask : nullptr;
   }
   a.P = d->H; a.Q = d->W;
   a.H = out_dim(d->H, d->pad, d->R, d->stride); a.W = out_dim(d->W, d->pad, d->S, d->stride);
@@ -1283,8 +1289,8 @@ extern "C" int conv_fwd_bn_sums(const rn50_conv_desc* d, const void* x, const vo
 }
 
 extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const void* w, void* dx,
-                                  const void* addend, const void* bn_x, const uint8_t* relu_mask,
-                                  const float* gamma, const float* beta,
+                                  const void* addend, const uint8_t* addend_mask, const void* bn_x,
+                                  const uint8_t* relu_mask, const float* gamma, const float* beta,
                                   const float* save_mean, const float* save_rstd, float* sums,
                                   size_t sums_bytes, void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
@@ -1304,7 +1310,8 @@ extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const
                sums_bytes, conv_bn_sums_bytes(d));
   hipStream_t s = static_cast<hipStream_t>(stream);
   dgrad_transpose_weights(d, w, workspace, s);
-  const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums, addend, relu_mask};
+  RN50_REQUIRE(!addend_mask || addend, RN50_ERR_INVALID, "conv_dgrad_bn_sums: addend_mask without addend");
+  const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums, addend, relu_mask, addend_mask};
   dgrad_run(d, dy, workspace, dx, &bn, s);
   return launch_status("conv_dgrad_bn_sums");
 }

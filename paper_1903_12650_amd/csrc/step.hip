@@ -60,8 +60,8 @@ struct rn50_plan {
   // Second stream for the work that is off the step's critical path (weight gradients, the weight
   // transposition), with the events that order it against the caller's stream.  Created at the first
   // step (default priority), destroyed with the plan.
-  static constexpr int kDyRing = 8;  // two blocks of at most four units
-  size_t dy_ring[kDyRing] = {0, 0, 0, 0, 0, 0, 0, 0};
+  int ring_blocks = 4;            // blocks the backward pass may run ahead of the weight gradients
+  std::vector<size_t> dy_ring;    // 4 * ring_blocks slots (a block has at most four units)
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_wt = nullptr;
   // Third stream: the projection shortcut of a stage's first block, forward and backward, runs beside the
@@ -188,7 +188,11 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->dlogits = bump(&top, static_cast<size_t>(N) * cfg->classes * sizeof(float));
   p->row_loss = bump(&top, static_cast<size_t>(N) * sizeof(float));
   for (int i = 0; i < 5; ++i) p->g[i] = bump(&top, max_act * es);
-  for (int i = 0; i < rn50_plan::kDyRing; ++i) p->dy_ring[i] = bump(&top, max_act * es);
+  if (const char* e = getenv("RN50_DY_RING_BLOCKS")) {  // tuning aid
+    const int v = atoi(e);
+    if (v >= 1 && v <= 16) p->ring_blocks = v;
+  }
+  for (int i = 0; i < 4 * p->ring_blocks; ++i) p->dy_ring.push_back(bump(&top, max_act * es));
   (void)max_wT;
   p->wT = bump(&top, static_cast<size_t>(p->arena_elems) * es);  // transposed copy of every conv weight
   for (const Unit& u : p->units)
@@ -452,7 +456,7 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   PendingWgrad pending[4];
   int npending = 0, seq = 0, blk = 0;  // units / blocks processed so far in this backward pass
   auto block_begin = [&]() {
-    if (blk >= 2) (void)hipStreamWaitEvent(s, plan->ev_wg[blk - 2], 0);
+    if (blk >= plan->ring_blocks) (void)hipStreamWaitEvent(s, plan->ev_wg[blk - plan->ring_blocks], 0);
   };
   auto block_end = [&]() {
     (void)hipEventRecord(plan->ev_dy[blk], s);
@@ -466,7 +470,7 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   // Phase 1 of a unit: BN backward, dz (+dz2) -> dy (a ring slot; returned), on stream st with BN scratch wsx.
   auto unit_bn_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, bool sums_ready,
                          hipStream_t st, void* wsx, void** dy_out) -> int {
-    void* dy = ws + plan->dy_ring[seq % rn50_plan::kDyRing];
+    void* dy = ws + plan->dy_ring[seq % plan->dy_ring.size()];
     // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
     const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
     if (sums_ready) {
@@ -485,11 +489,12 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   // Phase 2: the data gradient of dy into dx.  `below`: the unit whose BN output is this unit's input,
   // when dx (+ addend, the gradient of that output's other consumer) is its complete dz: the data gradient
   // then stores the sum and leaves that layer's sums in bn_ws.
-  auto unit_dgrad = [&](Unit& u, const void* dy, void* dx, Unit* below, const void* addend, hipStream_t st) {
+  auto unit_dgrad = [&](Unit& u, const void* dy, void* dx, Unit* below, const void* addend, hipStream_t st,
+                        const uint8_t* addend_mask = nullptr) {
     BnBwdSums fuse{};
     if (below) {
       fuse = BnBwdSums{ws + below->y, MP(below->ig), MP(below->ib), F(below->mean), F(below->rstd), sums, addend,
-                       below->bn.mode == 2 ? ws + below->relu_mask : nullptr};
+                       below->bn.mode == 2 ? ws + below->relu_mask : nullptr, addend_mask};
       dgrad_sums_rows = dgrad_partial_rows(&u.conv).num;
     }
     dgrad_run(&u.conv, dy, ws + plan->wT + plan->tensors[u.iw].offset * es, dx, below ? &fuse : nullptr, st);
@@ -501,8 +506,11 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     if (dx) unit_dgrad(u, dy, dx, below, addend, s);
     return RN50_OK;
   };
-  // dzo (+ dzo2): the gradient w.r.t. the current block's output; top_sums: its BN sums are in bn_ws
+  // dzo (+ dzo2): the gradient w.r.t. the current block's output; top_sums: its BN sums are in bn_ws.
+  // It alternates between two buffers: a block's conv1 data gradient reads the old one (as the shortcut's
+  // gradient) while it writes the new one.
   const void *dzo = g[0], *dzo2 = nullptr;
+  unsigned char* dz_next = g[2];
   bool top_sums = false;
   for (int bi = static_cast<int>(plan->blocks.size()) - 1; bi >= 0; --bi) {
     const Block& b = plan->blocks[bi];
@@ -512,9 +520,13 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     block_begin();
     // The block input has two consumers (conv1 and the shortcut).  conv1's data gradient comes last: it
     // adds the shortcut's gradient and takes the sums of the previous block's last BN layer.
+    // The shortcut's gradient is dzo under the block output's ReLU mask.  An identity shortcut needs no copy
+    // of it: conv1's data gradient below reads dzo with the recorded bits.  A projection shortcut's BN
+    // backward takes it as a tensor (g[3]).
     void* dy3 = nullptr;
-    STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, g[3], top_sums, s, bn_ws, &dy3));   // g[3]: gradient of the shortcut
-    const void* shortcut_grad = g[3];
+    STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, b.up >= 0 ? g[3] : nullptr, top_sums, s, bn_ws, &dy3));
+    const void* shortcut_grad = dzo;
+    const uint8_t* shortcut_mask = ws + u3.relu_mask;
     if (b.up >= 0) {  // the projection's backward pass runs beside the main branch, on its own stream
       Unit& up = plan->units[b.up];
       (void)hipEventRecord(plan->ev_bfork, s);
@@ -524,24 +536,27 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
       unit_dgrad(up, dyp, g[1], nullptr, nullptr, branch);
       (void)hipEventRecord(plan->ev_bjoin, branch);
       shortcut_grad = g[1];
+      shortcut_mask = nullptr;
     }
     unit_dgrad(u3, dy3, g[4], &u2, nullptr, s);
     STEP_TRY(unit_bwd(u2, ws + u1.z, g[4], nullptr, nullptr, g[4], true, &u1, nullptr));
     void* dy1 = nullptr;
     STEP_TRY(unit_bn_bwd(u1, block_in, g[4], nullptr, nullptr, true, s, bn_ws, &dy1));
     if (b.up >= 0) (void)hipStreamWaitEvent(s, plan->ev_bjoin, 0);
+    unsigned char* const dz_new = dz_next;
+    dz_next = const_cast<unsigned char*>(static_cast<const unsigned char*>(dzo));
     if (prev) {
-      unit_dgrad(u1, dy1, g[0], prev, shortcut_grad, s);
-      dzo = g[0]; dzo2 = nullptr; top_sums = true;
-    } else {  // the first block: the max-pool's backward pass adds the two branches
-      unit_dgrad(u1, dy1, g[0], nullptr, nullptr, s);
-      dzo = g[0]; dzo2 = shortcut_grad; top_sums = false;
+      unit_dgrad(u1, dy1, dz_new, prev, shortcut_grad, s, shortcut_mask);
+      dzo = dz_new; dzo2 = nullptr; top_sums = true;
+    } else {  // the first block (it has a projection): the max-pool's backward pass adds the two branches
+      unit_dgrad(u1, dy1, dz_new, nullptr, nullptr, s);
+      dzo = dz_new; dzo2 = shortcut_grad; top_sums = false;
     }
     block_end();
   }
-  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, dzo, dzo2, g[2], s));
+  STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, dzo, dzo2, dz_next, s));
   block_begin();
-  STEP_TRY(unit_bwd(u0, ws + plan->xp, g[2], nullptr, nullptr, nullptr, false, nullptr, nullptr));
+  STEP_TRY(unit_bwd(u0, ws + plan->xp, dz_next, nullptr, nullptr, nullptr, false, nullptr, nullptr));
   block_end();
   // ------------------------------------------------------------------ LARS
   // The side stream runs in order: the event of the last block but one covers every weight gradient

@@ -30,13 +30,16 @@ void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, flo
 // The BN layer (with ReLU) whose output gradient a data gradient produces: x is that
 // layer's input [N*H*W][Cin]; partial receives float[2][Cin][num] = sum(g), sum(g * xhat) per tile.
 // addend (or null): a second branch of the gradient, [N*H*W][Cin], added to the data gradient before it
-// is stored; relu_mask (or null): the BN layer's recorded ReLU decisions (else recomputed from x).
+// is stored; relu_mask (or null): the BN layer's recorded ReLU decisions (else recomputed from x);
+// addend_mask (or null): ReLU bits under which the addend counts (the addend is then the still unmasked
+// output gradient of the residual-add layer that recorded them).
 struct BnBwdSums {
   const void* x;
   const float *gamma, *beta, *mean, *rstd;
   float* partial;
   const void* addend = nullptr;
   const uint8_t* relu_mask = nullptr;
+  const uint8_t* addend_mask = nullptr;
 };
 size_t dgrad_wt_bytes(const rn50_conv_desc* d);
 void dgrad_transpose_weights(const rn50_conv_desc* d, const void* w, void* wT, hipStream_t s);

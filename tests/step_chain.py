@@ -59,7 +59,10 @@ class Chain:
     # backward of conv + BN; returns dx (or None), dres, (dw, dgamma, dbeta), sums handle for `below`.
     # sums: handle left by the data gradient that produced dz (then dz2 is None and the mode is 1);
     # below: tape of the unit whose BN output is this unit's input and has no other use.
-    def cbn_bwd(self, t, dz, dz2=None, need_dx=True, sums=None, below=None, addend=None):
+    # addend_mask: the addend is an unmasked gradient that counts under these recorded ReLU bits (the step's
+    # identity shortcut); addend_ref then is the masked tensor the oracle check adds.
+    def cbn_bwd(self, t, dz, dz2=None, need_dx=True, sums=None, below=None, addend=None, addend_mask=None,
+                addend_ref=None):
         rn = self.rn
         z = t["z"] if t["mode"] == 2 else None                      # mode 1: mask recomputed, as the step does
         if sums is not None:
@@ -86,14 +89,14 @@ class Chain:
             if below is not None:
                 dx, out_sums = rn.conv_dgrad_bn_sums(dy, t["w"], t["x"].shape, t["stride"], t["pad"], below["y"],
                                                      below["gamma"], below["beta"], below["mean"], below["rstd"],
-                                                     addend=addend, relu_mask=below["bits"])
+                                                     addend=addend, relu_mask=below["bits"], addend_mask=addend_mask)
             else:
                 assert addend is None
                 dx = rn.conv_dgrad(dy, t["w"], t["x"].shape, t["stride"], t["pad"])
             if self.check:
                 want = orc.conv_dgrad(_h(dy), _h(t["w"]), tuple(t["x"].shape), t["stride"], t["pad"])
                 if addend is not None:
-                    want = want + _h(addend)
+                    want = want + _h(addend_ref if addend_ref is not None else addend)
                 self.cmp(t["name"] + ".dx", dx, want)
         return dx, dres, [dw, dg, db], out_sums
 
@@ -160,8 +163,11 @@ def run_chain(rn, images, labels, model, vecs, blocks, ls, tol, check=True):
         dz1_, _, g2, s1 = ch.cbn_bwd(t2, dz2_, sums=s2, below=t1)
         gl = None
         if tp is None:
-            # identity shortcut: conv1's data gradient adds the shortcut's gradient and takes the previous block's sums
-            d, _, g1, top_sums = ch.cbn_bwd(t1, dz1_, sums=s1, below=prev, addend=dres)
+            # identity shortcut: conv1's data gradient adds the shortcut's gradient (the block output's gradient
+            # under its recorded ReLU bits, no copy) and takes the previous block's sums
+            assert d2 is None
+            d, _, g1, top_sums = ch.cbn_bwd(t1, dz1_, sums=s1, below=prev, addend=d, addend_mask=t3["bits"],
+                                            addend_ref=dres)
             d2 = None
             gl = g1 + g2 + g3
         else:

@@ -156,6 +156,19 @@ def test_conv_dgrad_bn_sums_residual_layer_with_addend(rn, mode_name, shape):
         assert_close(dres, dres_o, tol, "dresidual")
         assert_close(dg, dg_o, max(tol, 1e-3), "dgamma")
         assert_close(db, db_o, max(tol, 1e-3), "dbeta")
+    # an addend that counts only under recorded ReLU bits (the identity shortcut's gradient, taken without
+    # a masked copy) gives the bits of the call with the masked tensor
+    V = 8 if bf else 4
+    rng = np.random.default_rng(11)
+    abits = rng.integers(0, 1 << V, size=add.size // V).astype(np.uint8)
+    keep = ((abits[:, None] >> np.arange(V)[None, :]) & 1).astype(add.dtype).reshape(add.shape)
+    nbytes = rn.conv_bn_sums_bytes(rn.ConvDesc(N, H, W, C, K, R, R, stride, pad, rn.BF16 if bf else rn.F32))
+    zeros = lambda: torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    dz_m, sums_m = rn.conv_dgrad_bn_sums(dev(dy, bf), dev(w, bf), (N, H, W, C), stride, pad, bxd, gd, bd, md, rd,
+                                         addend=dev(add, bf), relu_mask=bits, addend_mask=dev(abits), sums=zeros())
+    dz_p, sums_p = rn.conv_dgrad_bn_sums(dev(dy, bf), dev(w, bf), (N, H, W, C), stride, pad, bxd, gd, bd, md, rd,
+                                         addend=dev(add * keep, bf), relu_mask=bits, sums=zeros())
+    assert torch.equal(dz_m, dz_p) and torch.equal(sums_m[1], sums_p[1])
     # the separate-pass kernels agree to rounding of the float sums
     dx_u, dres_u, dg_u, db_u = rn.bn_relu_bwd(dz, bxd, z, gd, md, rd, 2, beta=bd)
     assert torch.equal(dres, dres_u)
