@@ -468,12 +468,20 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     ++blk;
   };
   // Phase 1 of a unit: BN backward, dz (+dz2) -> dy (a ring slot; returned), on stream st with BN scratch wsx.
+  // outer_bits: dz is still to be masked by the ReLU bits another layer recorded (the projection shortcut's
+  // BN, whose output gradient is the block output's gradient under the block's ReLU): for the backward
+  // arithmetic that is a BN+ReLU layer with recorded bits.
   auto unit_bn_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, bool sums_ready,
-                         hipStream_t st, void* wsx, void** dy_out) -> int {
+                         hipStream_t st, void* wsx, void** dy_out, const uint8_t* outer_bits = nullptr) -> int {
     void* dy = ws + plan->dy_ring[seq % plan->dy_ring.size()];
     // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
     const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
-    if (sums_ready) {
+    if (outer_bits) {
+      rn50_bn_desc masked = u.bn;
+      masked.mode = 1;
+      STEP_TRY(bn_relu_bwd(&masked, dz, dz2, ws + u.y, nullptr, outer_bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy,
+                           nullptr, G(u.ig), G(u.ib), wsx, bn_ws_bytes, st));
+    } else if (sums_ready) {
       bn_bwd_from_partials(&u.bn, dz, ws + u.y, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd),
                            static_cast<const float*>(wsx), dgrad_sums_rows, dy, u.bn.mode == 2 ? dres : nullptr,
                            G(u.ig), G(u.ib), st);
@@ -520,11 +528,11 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     block_begin();
     // The block input has two consumers (conv1 and the shortcut).  conv1's data gradient comes last: it
     // adds the shortcut's gradient and takes the sums of the previous block's last BN layer.
-    // The shortcut's gradient is dzo under the block output's ReLU mask.  An identity shortcut needs no copy
-    // of it: conv1's data gradient below reads dzo with the recorded bits.  A projection shortcut's BN
-    // backward takes it as a tensor (g[3]).
+    // The shortcut's gradient is dzo under the block output's ReLU mask.  No copy of it is made: an identity
+    // shortcut's share is added by conv1's data gradient below, which reads dzo with the recorded bits, and
+    // a projection shortcut's BN backward reads dzo with the same bits.
     void* dy3 = nullptr;
-    STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, b.up >= 0 ? g[3] : nullptr, top_sums, s, bn_ws, &dy3));
+    STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, nullptr, top_sums, s, bn_ws, &dy3));
     const void* shortcut_grad = dzo;
     const uint8_t* shortcut_mask = ws + u3.relu_mask;
     if (b.up >= 0) {  // the projection's backward pass runs beside the main branch, on its own stream
@@ -532,7 +540,7 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
       (void)hipEventRecord(plan->ev_bfork, s);
       (void)hipStreamWaitEvent(branch, plan->ev_bfork, 0);
       void* dyp = nullptr;
-      STEP_TRY(unit_bn_bwd(up, block_in, g[3], nullptr, nullptr, false, branch, bn_ws2, &dyp));
+      STEP_TRY(unit_bn_bwd(up, block_in, dzo, dzo2, nullptr, false, branch, bn_ws2, &dyp, ws + u3.relu_mask));
       unit_dgrad(up, dyp, g[1], nullptr, nullptr, branch);
       (void)hipEventRecord(plan->ev_bjoin, branch);
       shortcut_grad = g[1];
