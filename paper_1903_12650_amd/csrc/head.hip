@@ -66,8 +66,12 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ 
   }
 }
 
-// Backward from the stored window positions: one thread per input pixel vector; it collects dy of the
-// (at most four) windows that contain it and whose recorded maximum is this pixel.
+// Backward from the stored window positions: one thread per 2x2 block of input pixel vectors
+// (rows 2a, 2a+1; columns 2b, 2b+1).  The block lies in exactly the four windows (a..a+1, b..b+1), each
+// of which is loaded once and dealt to the pixel its recorded position names: pixel (2a,2b) can only be
+// the centre of window (a,b); (2a,2b+1) position 5 of (a,b) or 3 of (a,b+1); (2a+1,2b) position 7 of
+// (a,b) or 1 of (a+1,b); (2a+1,2b+1) position 8, 6, 2, 0 of the four.  The summands of a pixel are
+// added in window order (p, then q).
 template <typename T>
 __global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const uint8_t* __restrict__ argmax,
                                                               const T* __restrict__ dy,
@@ -76,22 +80,26 @@ __global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const uint8_t* __r
                                                               int C, int P, int Q) {
   constexpr int V = Elem<T>::VEC;
   const int cv = C / V;
-  const int64_t total = static_cast<int64_t>(N) * H * W * cv;
+  const int Ha = (H + 1) / 2, Wb = (W + 1) / 2;
+  const int64_t total = static_cast<int64_t>(N) * Ha * Wb * cv;
   const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (i >= total) return;
   const int c = static_cast<int>(i % cv);
   int64_t t = i / cv;
-  const int w = static_cast<int>(t % W); t /= W;
-  const int h = static_cast<int>(t % H);
-  const int n = static_cast<int>(t / H);
-  float acc[V];
+  const int b = static_cast<int>(t % Wb); t /= Wb;
+  const int a = static_cast<int>(t % Ha);
+  const int n = static_cast<int>(t / Ha);
+  float acc[2][2][V];
 #pragma unroll
-  for (int j = 0; j < V; ++j) acc[j] = 0.f;
-  const int p_lo = h / 2, p_hi = min((h + 1) / 2, P - 1);
-  const int q_lo = w / 2, q_hi = min((w + 1) / 2, Q - 1);
-  for (int p = p_lo; p <= p_hi; ++p)
-    for (int q = q_lo; q <= q_hi; ++q) {
-      const int my_pos = (h - (p * 2 - 1)) * 3 + (w - (q * 2 - 1));
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[k >> 1][k & 1][j] = 0.f;
+#pragma unroll
+  for (int dp = 0; dp < 2; ++dp)
+#pragma unroll
+    for (int dq = 0; dq < 2; ++dq) {
+      const int p = a + dp, q = b + dq;
+      if (p >= P || q >= Q) continue;
       const int64_t o = ((static_cast<int64_t>(n) * P + p) * Q + q) * C + c * V;
       uint8_t idx[V];
       if (V == 8) *reinterpret_cast<uint2*>(idx) = *reinterpret_cast<const uint2*>(argmax + o);
@@ -104,12 +112,27 @@ __global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const uint8_t* __r
 #pragma unroll
         for (int j = 0; j < V; ++j) g[j] += g2[j];
       }
+      // pixel (2a+i, 2b+jj) sits at window position (2a+i - (2p-1))*3 + (2b+jj - (2q-1))
 #pragma unroll
-      for (int j = 0; j < V; ++j) acc[j] += idx[j] == my_pos ? g[j] : 0.f;
+      for (int ii = dp; ii < 2; ++ii)      // window row a+1 starts at pixel row 2a+1
+#pragma unroll
+        for (int jj = dq; jj < 2; ++jj) {
+          const int pos = (ii + 1 - 2 * dp) * 3 + (jj + 1 - 2 * dq);
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[ii][jj][j] += idx[j] == pos ? g[j] : 0.f;
+        }
     }
-  Vec16 ov;
-  Elem<T>::pack(acc, ov);
-  store16(dx + i * V, ov);
+#pragma unroll
+  for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+      const int h = 2 * a + ii, w = 2 * b + jj;
+      if (h < H && w < W) {
+        Vec16 ov;
+        Elem<T>::pack(acc[ii][jj], ov);
+        store16(dx + ((static_cast<int64_t>(n) * H + h) * W + w) * C + c * V, ov);
+      }
+    }
 }
 
 // One thread per input pixel vector.  The pixel receives dy of window (p,q) iff
@@ -534,8 +557,9 @@ extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x,
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int64_t total = static_cast<int64_t>(N) * H * W * (C / Elem<T>::VEC);
+    const int64_t quads = static_cast<int64_t>(N) * ((H + 1) / 2) * ((W + 1) / 2) * (C / Elem<T>::VEC);
     if (argmax)
-      hipLaunchKernelGGL(maxpool_bwd_idx_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s, argmax,
+      hipLaunchKernelGGL(maxpool_bwd_idx_kernel<T>, dim3(ceil_div(quads, 256)), dim3(256), 0, s, argmax,
                          static_cast<const T*>(dy), static_cast<const T*>(dy2), static_cast<T*>(dx), N,
                          H, W, C, P, Q);
     else
