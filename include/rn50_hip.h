@@ -49,8 +49,8 @@ const char* rn50_last_error(void);
 int rn50_version(void);
 
 /* Measurement aid (not part of the method): while enabled, every launch whose kernel
- * tag begins with `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad" (which also
- * covers "conv_wgrad_reduce"), "bn_stats", "bn_finalize", "bn_apply", "bn_bwd_reduce",
+ * tag begins with `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad", "splitk_reduce"
+ * (the second pass of a split weight gradient), "bn_stats", "bn_finalize", "bn_apply", "bn_bwd_reduce",
  * "bn_bwd_finalize", "bn_bwd_apply", "lars_norms", "lars_apply", "fc_bwd_da") is
  * given a HIP event pair that receives the begin and end timestamps of that dispatch
  * on the launch stream, up to max_records launches.  rn50_profile_end waits for the

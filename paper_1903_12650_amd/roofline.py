@@ -6,13 +6,18 @@ Per unit of work (elements are activation elements of the BN's tensor, bf16 = 2 
                          needs (and is only charged) every other row and column of its input.
                          A data gradient that also takes the backward sums of the BN layer below reads
                          that layer's input (es*|dx| more), and, when it closes a block, the other
-                         gradient branch (es*|dx|) and the recorded ReLU bits (|dx|/8 bytes)
+                         gradient branch (es*|dx|) and the recorded ReLU bits of the layer below
+                         (|dx|/8 bytes; as many again for an identity shortcut, whose gradient is the
+                         block output's gradient under the block's own recorded bits)
   conv_wgrad             2*M*N*K flop;  bytes = es*(|x| + |dy|) + 4*|dw|
   bn_apply               2*es bytes/element (read x, write y) + es for the residual read (mode 2)
   bn_bwd_reduce          2*es bytes/element (read dz, x); launched only for the layers whose sums are not
                          taken in the output stage of the data gradient that produces dz (the stem, the
                          last block's residual-add layer and the projection shortcuts)
-  bn_bwd_apply           3*es bytes/element (read dz, x, write dx) + es for dresidual (mode 2)
+  bn_bwd_apply           3*es bytes/element (read dz, x, write dx) + 1/8 byte where the ReLU decision is
+                         read from recorded bits (the residual-add layers and the projection shortcuts'
+                         BN, whose incoming gradient is masked by the block's bits); no masked copy of the
+                         shortcut's gradient is written
   lars_norms             8 bytes/parameter (read w, g)
   lars_apply             20 bytes/parameter (read w, g, v; write w, v) + 2 for the bf16 copy
 The forward BN statistics and the other backward sums are part of conv_fwd / conv_dgrad (no bytes of
@@ -30,8 +35,8 @@ DOMINANT_KERNEL = "conv_dgrad"  # largest share of the step's kernel time (rocpr
 # copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
 # dirty in L2 are written back during later kernels.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "conv_fwd": 40.34e6, "conv_dgrad": 63.59e6, "conv_wgrad": 52.14e6, "bn_apply": 42.58e6,
-    "bn_bwd_reduce": 73.40e6, "bn_bwd_apply": 59.97e6, "lars_norms": 102.30e6, "lars_apply": 281.25e6,
+    "conv_fwd": 40.39e6, "conv_dgrad": 64.03e6, "conv_wgrad": 52.16e6, "bn_apply": 42.58e6,
+    "bn_bwd_reduce": 75.68e6, "bn_bwd_apply": 51.91e6, "lars_norms": 102.30e6, "lars_apply": 281.25e6,
 }
 
 
@@ -95,18 +100,21 @@ def per_launch_cost(tag, plan):
                     by += es * dx
                 elif j == 0 and bi > 0:    # conv1 closes the block: + the shortcut's gradient, the previous
                     by += 2 * es * dx + dx / 8   # block's BN input and its ReLU bits
+                    if len(b) == 3:        # identity shortcut: its gradient is read under the block's bits
+                        by += dx / 8
                 out.append((f, by))
         return out
     if tag == "conv_wgrad":
         return [conv_cost(l, True) for l in _bwd_order(L)]
-    per_elem = {"bn_apply": (2 * es, es), "bn_bwd_reduce": (2 * es, 0), "bn_bwd_apply": (3 * es, es)}
+    per_elem = {"bn_apply": (2 * es, es), "bn_bwd_reduce": (2 * es, 0), "bn_bwd_apply": (3 * es, 0.125)}
     if tag in per_elem:
         base, extra = per_elem[tag]
         seq = _fwd_order(L, L) if tag == "bn_apply" else _bwd_order(L)
         if tag == "bn_bwd_reduce":  # every other layer gets its sums from the data gradient that produces its dz
             last_add = [l for l in L if l["mode"] == 2][-1]
             seq = [l for l in seq if l["mode"] == 0 or l["Cin"] == 3 or l is last_add]
-        return [(0.0, elems(l) * (base + (extra if l["mode"] == 2 else 0))) for l in seq]
+        bits = (2, 0) if tag == "bn_bwd_apply" else (2,)   # layers that read recorded ReLU bits / a residual
+        return [(0.0, elems(l) * (base + (extra if l["mode"] in bits else 0))) for l in seq]
     # two launches each: every tensor but the stem's weight, then the stem's weight (whose gradient comes last)
     n_params, n_stem = sum(plan.sizes), plan.sizes[0]
     if tag == "lars_norms":

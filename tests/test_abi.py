@@ -76,6 +76,11 @@ def test_roofline_cost_model_totals():
     assert len(apply) == 53
     red = rl.per_launch_cost("bn_bwd_reduce", plan)       # the stem, the last residual-add layer, 4 projections
     assert len(red) == 6
-    bwd = rl.per_launch_cost("bn_bwd_apply", plan)        # 3 tensors per element + dresidual of the add layers
-    assert abs((sum(b for _, b in bwd) - sum(b for _, b in apply)) / 2 / 1e6 - 444.6) < 0.5   # one more tensor pass
+    bwd = rl.per_launch_cost("bn_bwd_apply", plan)        # 3 tensors per element + recorded bits where they are read
+    L = rl.layers(plan)
+    E = sum(l["N"] * l["P"] * l["P"] * l["Cout"] for l in L)
+    E_add = sum(l["N"] * l["P"] * l["P"] * l["Cout"] for l in L if l["mode"] == 2)
+    E_proj = sum(l["N"] * l["P"] * l["P"] * l["Cout"] for l in L if l["mode"] == 0)
+    assert abs(E / 1e6 - 444.6) < 0.5
+    assert sum(b for _, b in apply) == 4 * E + 2 * E_add and sum(b for _, b in bwd) == 6 * E + (E_add + E_proj) / 8
     assert sum(b for _, b in rl.per_launch_cost("lars_apply", plan)) == 22 * 25_557_032

@@ -263,7 +263,7 @@ def test_profile_hooks_and_plan_lifecycle(rn):
         step()
         torch.cuda.synchronize()
         ms = rn.profile_end()
-        assert len(ms) >= 2 * n_units and len(ms) % 2 == 0      # two timed steps; split-K reduces share the tag prefix
+        assert len(ms) == 2 * n_units                           # two timed steps, one weight gradient per unit
         assert all(0.0 < t < 50.0 for t in ms), ms
         loss = step()
         torch.cuda.synchronize()
