@@ -27,8 +27,8 @@ def lib_path():
 
 
 if not os.path.exists(lib_path()):
-    raise ImportError("librn50_hip.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
-                      "(or python paper_1903_12650_amd/build.py) first; there is no fallback path")
+    raise ImportError("librn50_hip.so is not built: run `python paper_1903_12650_amd/build.py` (or "
+                      "`python -c 'import __graft_entry__ as g; g.build()'`) first; there is no fallback path")
 raw = ctypes.CDLL(lib_path())
 
 

@@ -18,7 +18,10 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     lib_path = os.path.join(ROOT, "paper_1903_12650_amd", "librn50_hip.so")
     if not os.path.exists(lib_path):
-        from paper_1903_12650_amd import build
+        import importlib.util
+        spec = importlib.util.spec_from_file_location("rn50_hip_build", os.path.join(ROOT, "paper_1903_12650_amd", "build.py"))
+        build = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(build)
         build.build()
     lib = ctypes.CDLL(lib_path)
     names = _declared()
