@@ -300,3 +300,27 @@ def test_step_on_a_caller_stream_matches_the_default_stream(rn):
     for a, b in zip(*outs):
         assert torch.equal(a, b)
     assert torch.isfinite(outs[0][2][: plan.sizes[0]]).all()
+
+
+def test_step_resnet50_batch256_bf16_equals_the_chain(rn):
+    """The large-batch configuration (batch 256, 6.4 times the measured one: tensors of up to 411 MB, tens
+    of thousands of output tiles): resnet_step is bit for bit the operation-by-operation chain, whose
+    operations are held to the oracle at batch 40 and below; the loss of the untrained network is near
+    ln(1000) and every gradient is finite and non-zero."""
+    from step_chain import run_chain
+    cfg = (256, 224, (64, 128, 256, 512), (3, 4, 6, 3), 64, 1000)
+    S = setup_step(rn, "bf16", *cfg)
+    plan, table = S["plan"], S["table"]
+    img, lab = dev(S["images"], True), dev(S["labels"])
+    logits = torch.empty((S["N"], S["classes"]), device="cuda")
+    loss = rn.resnet_step(plan, img, lab, S["M"], S["V"], S["G"], S["Mod"], 1.0, S["ws"], update=False, logits_out=logits)
+    torch.cuda.synchronize()
+    assert abs(float(loss.item()) - np.log(1000.0)) < 1.0, float(loss.item())
+    model = [dev(p, True) for p in S["model"]]
+    vecs = [dev(p) for p in S["master"]]
+    c_loss, c_logits, c_grads, _ = run_chain(rn, img, lab, model, vecs, S["blocks"], 0.0, TOL["bf16"], check=False)
+    assert torch.equal(loss, c_loss) and torch.equal(logits, c_logits)
+    for i, (name, _, _) in enumerate(table):
+        g = plan.view(S["G"], i)
+        assert torch.equal(g, c_grads[i]), f"grad {name} differs from the op-by-op chain"
+        assert torch.isfinite(g).all() and float(g.abs().max()) > 0, name
