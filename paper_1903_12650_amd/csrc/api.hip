@@ -69,4 +69,4 @@ extern "C" int rn50_profile_end(float* ms_out, int capacity) {
 }
 
 extern "C" const char* rn50_last_error(void) { return rn50::g_err; }
-extern "C" int rn50_version(void) { return 1; }
+extern "C" int rn50_version(void) { return 2; }

@@ -53,6 +53,37 @@ def test_host_side_argument_checks_need_no_gpu():
     assert raw.xent_fwd_bwd(0, 10, one, one, ctypes.c_float(0), ctypes.c_float(1), one, one, one, None) == -1
 
 
+def test_loop_entry_points_check_their_arguments_without_a_gpu():
+    import paper_1903_12650_amd as rn
+    raw = rn.raw
+    plan = rn.ResnetPlan(8, rn.BF16, 64, 10, (8, 8, 8, 8), (1, 1, 1, 1), 8, 4)
+    one = ctypes.c_void_p(256)
+    sched = rn.LrSchedule(1.0)
+    f = ctypes.c_float
+    assert raw.resnet_train_step(plan.handle, None, one, f(0.9), one, one, one, one, one, one, one, None, one,
+                                 ctypes.c_size_t(1 << 40), None) == -1                      # no schedule
+    assert raw.resnet_train_step(plan.handle, ctypes.byref(rn.LrSchedule(1.0, decay="step", step_every=0)), one, f(0.9), one,
+                                 one, one, one, one, one, one, None, one, ctypes.c_size_t(1 << 40), None) == -1
+    assert b"step_every" in raw.rn50_last_error()
+    assert raw.resnet_train_step(plan.handle, ctypes.byref(sched), ctypes.c_void_p(8), f(0.9), one, one, one, one, one, one,
+                                 one, None, one, ctypes.c_size_t(1 << 40), None) == -4            # misaligned state
+    assert raw.resnet_train_step(plan.handle, ctypes.byref(sched), one, f(0.9), one, one, one, one, one, one, one, None,
+                                 one, ctypes.c_size_t(16), None) == -3                             # workspace too small
+    assert raw.resnet_train_state_init(plan.handle, one, ctypes.c_size_t(8), ctypes.c_int64(0), None) == -3
+    assert raw.resnet_train_state_init(plan.handle, one, ctypes.c_size_t(1 << 30), ctypes.c_int64(-1), None) == -1
+    assert raw.resnet_init_params(plan.handle, ctypes.c_uint64(1), None, None, None, None) == -1
+    assert raw.resnet_eval(plan.handle, one, one, None, one, one, None, one, one, one, ctypes.c_size_t(1 << 40), None) == -1
+    assert raw.top1_accuracy(0, 10, one, one, one, one, None) == -1
+    b = rn.BnDesc(2, 4, 4, 16, 1e-5, rn.BF16, 2)
+    assert raw.bn_relu_infer(ctypes.byref(b), one, one, one, one, one, None, one, one, ctypes.c_size_t(256), None) == -1
+    n_bn = raw.resnet_plan_num_bn(plan.handle)
+    assert n_bn == 1 + 3 * 4 + 4 and int(raw.resnet_plan_bn_channels(plan.handle)) % 64 == 0
+    c = ctypes.c_int()
+    assert int(raw.resnet_plan_bn_offset(plan.handle, 0, ctypes.byref(c))) == 0 and c.value == 8
+    assert int(raw.resnet_plan_bn_offset(plan.handle, n_bn, None)) == -1
+    assert int(raw.resnet_train_state_bytes(plan.handle)) == 256 + 8 * int(raw.resnet_plan_bn_channels(plan.handle))
+
+
 def test_plan_matches_the_oracles_parameter_table():
     import paper_1903_12650_amd as rn
     from oracle import net
