@@ -355,7 +355,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   }
 
   // Output stage with batch-norm sums: every thread owns V channels and NPASS rows of the tile.
-  __shared__ float red[4][2][BN];
   const bool col_ok = n < a.Ncols;
   float s1[V], s2[V];
 #pragma unroll
@@ -450,38 +449,30 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       }
     }
   }
-  // rows of one wave (lanes with equal op), then the four waves in order
+  // The per-thread sums of a column meet through LDS: [row group][plane][column], over the tile buffer
+  // (every thread is done with its rows of the tile), then one thread per plane and column adds the RPP row
+  // groups in order.  (Wave shuffles here -- 6 * V of them per thread -- cost more than the whole loop above.)
+  float kshift = 0.f;
+  if (MODE == 0 && tid < BN) kshift = Elem<T>::load(reinterpret_cast<const T*>(smem) + tid);  // row m0 of the tile
+  __syncthreads();
+  float* cs = reinterpret_cast<float*>(smem);
+  static_assert(RPP * 2 * BN * 4 <= 2 * STAGE, "column sums must fit in the pipeline buffers");
 #pragma unroll
-  for (int off = PPR; off < 64; off <<= 1) {
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-      s1[j] += __shfl_xor(s1[j], off, 64);
-      s2[j] += __shfl_xor(s2[j], off, 64);
-    }
-  }
-  if (lane < PPR) {
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-      red[wave][0][op * V + j] = s1[j];
-      red[wave][1][op * V + j] = s2[j];
-    }
+  for (int j = 0; j < V; j += 4) {
+    *reinterpret_cast<float4*>(cs + (orow * 2 + 0) * BN + op * V + j) = make_float4(s1[j], s1[j + 1], s1[j + 2], s1[j + 3]);
+    *reinterpret_cast<float4*>(cs + (orow * 2 + 1) * BN + op * V + j) = make_float4(s2[j], s2[j + 1], s2[j + 2], s2[j + 3]);
   }
   __syncthreads();
-  if (tid < BN && n0 + tid < a.Ncols) {
-    const float t1 = ((red[0][0][tid] + red[1][0][tid]) + red[2][0][tid]) + red[3][0][tid];
-    const float t2 = ((red[0][1][tid] + red[1][1][tid]) + red[2][1][tid]) + red[3][1][tid];
-    // partial[plane][channel][tile row]: the rows of one channel are contiguous for the finalize pass
-    const int64_t nrows = gridDim.x / a.ntn, plane = static_cast<int64_t>(a.Ncols) * nrows;
-    float* o = a.partial + static_cast<int64_t>(n0 + tid) * nrows + mt;
-    if (MODE == 0) {
-      o[0] = Elem<T>::load(reinterpret_cast<const T*>(smem) + tid);
-      o[plane] = t1;
-      o[2 * plane] = t2;
-    } else {
-      o[0] = t1;
-      o[plane] = t2;
-    }
+  // partial[plane][channel][tile row]: the rows of one channel are contiguous for the finalize pass
+  const int64_t nrows = gridDim.x / a.ntn, plane = static_cast<int64_t>(a.Ncols) * nrows;
+  if (tid < 2 * BN) {
+    const int pl = tid / BN, ch = tid % BN;
+    float t = 0.f;
+#pragma unroll 8
+    for (int r = 0; r < RPP; ++r) t += cs[(r * 2 + pl) * BN + ch];
+    if (n0 + ch < a.Ncols) a.partial[(MODE == 0 ? pl + 1 : pl) * plane + static_cast<int64_t>(n0 + ch) * nrows + mt] = t;
   }
+  if (MODE == 0 && tid < BN && n0 + tid < a.Ncols) a.partial[static_cast<int64_t>(n0 + tid) * nrows + mt] = kshift;
 }
 
 // ------------------------------------------------------------ weight gradient
