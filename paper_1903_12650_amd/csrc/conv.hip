@@ -815,10 +815,16 @@ static void allow_big_lds(K kernel, int bytes) {
 
 template <typename T, int BM, int BN, int WM, int WN, int MODE>
 static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid, hipStream_t s) {
-  constexpr int lds = 2 * (BM + BN) * kPitch;
+  constexpr int stage = (BM + BN) * kPitch;
+  constexpr int lds = 2 * stage;
   static std::once_flag once;
   std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE>, lds); });
-  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, s, a);
+  // A reduction of a single chunk (the 1x1 layers with 64 channels, the largest pixel counts of the net)
+  // never touches the second pipeline buffer; without it more workgroups fit a CU.  The output stage's
+  // uses of the buffer (tile in float: BM*(4*BN+16) bytes; column sums: at most 16 KB) fit one 64x64 stage.
+  const bool one_chunk = BM == 64 && BN == 64 && a.R * a.S * a.cpt == 1;
+  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE>), dim3(static_cast<unsigned>(grid)), dim3(256),
+              one_chunk ? stage : lds, s, a);
 }
 template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
