@@ -206,18 +206,34 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ 
 
 // -------------------------------------------------------------- average pool
 template <typename T>
-__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const T* __restrict__ x,
-                                                          T* __restrict__ y, int N, int HW, int C) {
+__global__ __launch_bounds__(64) void avgpool_fwd_kernel(const T* __restrict__ x,
+                                                         T* __restrict__ y, int N, int HW, int C) {
   constexpr int V = Elem<T>::VEC;
   const int cv = C / V;
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int i = blockIdx.x * 64 + threadIdx.x;
   if (i >= N * cv) return;
   const int n = i / cv, c = i % cv;
   float acc[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) acc[j] = 0.f;
   const T* p = x + static_cast<int64_t>(n) * HW * C + c * V;
-  for (int r = 0; r < HW; ++r) {
+  // the rows are requested sixteen at a time (a thread's loads are what this kernel waits for) and added in
+  // row order
+  constexpr int U = 16;
+  int r = 0;
+  for (; r + U <= HW; r += U) {
+    Vec16 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = load16(p + static_cast<int64_t>(r + u) * C);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float f[V];
+      Elem<T>::unpack(v[u], f);
+#pragma unroll
+      for (int j = 0; j < V; ++j) acc[j] += f[j];
+    }
+  }
+  for (; r < HW; ++r) {
     float f[V];
     Elem<T>::unpack(load16(p + static_cast<int64_t>(r) * C), f);
 #pragma unroll
@@ -342,7 +358,7 @@ __global__ __launch_bounds__(256) void fc_fwd_mfma_kernel(const uint16_t* __rest
   f32x16 acc0, acc1;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
-  constexpr int U = 4;
+  constexpr int U = 8;  // loads in flight per operand: the kernel runs at the latency of its batches of loads
   int c = wave * 16;
   for (; c + (U - 1) * 64 < Cin; c += U * 64) {
     Vec16 fw[U], f0[U], f1[U];
@@ -580,7 +596,7 @@ extern "C" int avgpool_fwd(int N, int HW, int C, int dtype, const void* x, void*
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int total = N * (C / Elem<T>::VEC);
-    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, dim3(ceil_div(total, 64)), dim3(64), 0, s,
                        static_cast<const T*>(x), static_cast<T*>(y), N, HW, C);
   });
   return launch_status("avgpool_fwd");
