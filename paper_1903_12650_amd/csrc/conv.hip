@@ -157,6 +157,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   // Rows of this tile: pixels m0.. of the whole output grid, or of one parity class of it.
   const bool classes = MODE == 1 && a.stride == 2;
   __shared__ int pix_s[BM];  // classes only: output pixel index of every tile row
+  // Data gradient with batch-norm sums: the per-channel coefficients of this tile's columns, fetched by one
+  // thread per column while the main loop runs (every thread loading its own copies costs the texture path
+  // as much as two chunks of the main loop).
+  __shared__ float prm_s[MODE == 1 ? 4 * BN : 4];
+  float pg = 0.f, pb = 0.f, pm = 0.f, pr = 0.f;
+  if (MODE == 1 && a.partial != nullptr && tid < BN) {
+    const int c = min(n0 + tid, a.Ncols - 1);
+    pg = a.bn_gamma[c]; pb = a.bn_beta[c]; pm = a.bn_mean[c]; pr = a.bn_rstd[c];
+  }
   int ph = 0, pw = 0, Hc = a.P, Wc = a.Q, Mc = a.M, m0 = mt * BM;
   int r0 = 0, s0 = 0, tstep = 1;
   if (classes) {
@@ -333,6 +342,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         }
       }
     }
+  if (MODE == 1 && a.partial != nullptr && tid < BN) {
+    float sc, bi;
+    bn_coeffs(pg, pb, pm, pr, &sc, &bi);
+    prm_s[tid] = sc; prm_s[BN + tid] = bi; prm_s[2 * BN + tid] = pr; prm_s[3 * BN + tid] = -pm * pr;
+  }
   __syncthreads();
   constexpr int PPR = BN * sizeof(T) / 16;  // 16-byte pieces per output row
   constexpr int RPP = 256 / PPR;            // rows per pass
@@ -399,15 +413,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       if (a.bn_zmask) zb[pass] = a.bn_zmask[at / V];
       ab[pass] = a.addend_mask ? a.addend_mask[at / V] : 0xffu;
     }
-    float scale[V], bias[V], rs[V], nmr[V], cg[V], cb[V], cm[V];
-    load_floats<V>(a.bn_gamma + nc, cg);
-    load_floats<V>(a.bn_beta + nc, cb);
-    load_floats<V>(a.bn_mean + nc, cm);
-    load_floats<V>(a.bn_rstd + nc, rs);
+    float scale[V], bias[V], rs[V], nmr[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-      nmr[j] = -cm[j] * rs[j];
-      bn_coeffs(cg[j], cb[j], cm[j], rs[j], &scale[j], &bias[j]);
+      scale[j] = prm_s[op * V + j]; bias[j] = prm_s[BN + op * V + j];
+      rs[j] = prm_s[2 * BN + op * V + j]; nmr[j] = prm_s[3 * BN + op * V + j];
     }
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
