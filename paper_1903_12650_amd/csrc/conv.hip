@@ -42,6 +42,7 @@ struct FastDiv {  // exact unsigned division by a runtime constant (Granlund-Mon
   uint32_t mul, sh1, sh2;
 };
 static FastDiv make_fastdiv(uint32_t d) {
+  if (d == 0) d = 1;  // (an empty dimension: nothing is divided by it)
   uint32_t l = 0;
   while ((1ull << l) < d) ++l;
   FastDiv f;
@@ -93,6 +94,12 @@ struct IgemmArgs {
   int ntn;          // number of column tiles
   int pair;         // stem in bf16: a 128-byte chunk holds two filter rows (pieces 0-3: row 2r, 4-7: row 2r+1)
   int nimg;         // images (M = nimg*P*Q)
+  // Divisions of the tile / pixel decode by exact multiply-shift (an integer division costs a wave some 40
+  // instructions, and every workgroup starts with several of them).  div_w / div_h: by the width / height of
+  // the row tiles' pixel grid -- [1] for the odd parity class of a stride-2 data gradient.
+  int mtiles;       // row tiles (grid = mtiles * ntn)
+  int linear;       // 1x1 filter, stride 1, no padding: row m of the output is pixel m of the gathered tensor
+  FastDiv div_ntn, div_w[2], div_h[2];
   int mode;         // host side only: selects the MODE template argument
   // Optional batch-norm sums over the rows of each output tile, taken from the rounded values that are
   // stored (null: none).  Forward: partial[3][Ncols][tiles] = shift (the tile's first row), sum(y - shift),
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   const int wave = tid >> 6, lane = tid & 63;
   const int wm = wave % WM, wn = wave / WM;
   const int bid = xcd_remap(blockIdx.x, gridDim.x);
-  const int nt = bid % a.ntn, mt = bid / a.ntn;
+  const int mt = static_cast<int>(fdiv(static_cast<uint32_t>(bid), a.div_ntn)), nt = bid - mt * a.ntn;
   const int n0 = nt * BN;
   const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a.act, a.act_bytes), rsB = make_rsrc(a.wgt, a.wgt_bytes);
 
@@ -178,7 +185,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     Mc = a.nimg * Hc * Wc;
     r0 = (ph + a.pad) & 1; s0 = (pw + a.pad) & 1; tstep = 2;
   }
-  const int nr = r0 < a.R ? (a.R - r0 + tstep - 1) / tstep : 0, ns = s0 < a.S ? (a.S - s0 + tstep - 1) / tstep : 0;
+  const int nr = r0 < a.R ? (a.R - r0 + tstep - 1) >> (tstep - 1) : 0, ns = s0 < a.S ? (a.S - s0 + tstep - 1) >> (tstep - 1) : 0;
+  FastDiv dvw, dvh;  // selected field by field, by value
+  dvw.mul = pw ? +a.div_w[1].mul : +a.div_w[0].mul; dvw.sh1 = pw ? +a.div_w[1].sh1 : +a.div_w[0].sh1; dvw.sh2 = pw ? +a.div_w[1].sh2 : +a.div_w[0].sh2;
+  dvh.mul = ph ? +a.div_h[1].mul : +a.div_h[0].mul; dvh.sh1 = ph ? +a.div_h[1].sh1 : +a.div_h[0].sh1; dvh.sh2 = ph ? +a.div_h[1].sh2 : +a.div_h[0].sh2;
 
   // per-thread rows of the A tile: decode the output pixel once
   int a_h0[RA], a_w0[RA], a_base[RA];
@@ -187,10 +197,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const int m = m0 + lrow + 32 * i;
     const bool ok = m < Mc;
     const int mm = ok ? m : 0;
-    int q = mm % Wc;
-    const int t = mm / Wc;
-    int p = t % Hc;
-    const int n = t / Hc;
+    if (a.linear) {  // no pixel decode: "image" base mm, coordinates (0, 0)
+      a_base[i] = mm;
+      a_h0[i] = ok ? 0 : -(1 << 20);
+      a_w0[i] = 0;
+      continue;
+    }
+    const int t = static_cast<int>(fdiv(static_cast<uint32_t>(mm), dvw));
+    int q = mm - t * Wc;
+    const int n = static_cast<int>(fdiv(static_cast<uint32_t>(t), dvh));
+    int p = t - n * Hc;
     if (classes) {
       p = 2 * p + ph; q = 2 * q + pw;
       if (piece == 0) pix_s[lrow + 32 * i] = ok ? (n * a.P + p) * a.Q + q : 0;
@@ -256,7 +272,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         cur_r += tstep;
       }
       b_tap = static_cast<uint32_t>((cur_r * a.S + cur_s) * a.Cg) * sizeof(T);
-      tap_setup();
+      if (cur < nchunks) tap_setup();  // (nothing is loaded past the last chunk)
     }
   };
   auto store_chunk = [&](int stage, const Staged& st) __attribute__((always_inline)) {
@@ -474,7 +490,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   }
   __syncthreads();
   // partial[plane][channel][tile row]: the rows of one channel are contiguous for the finalize pass
-  const int64_t nrows = gridDim.x / a.ntn, plane = static_cast<int64_t>(a.Ncols) * nrows;
+  const int64_t nrows = a.mtiles, plane = static_cast<int64_t>(a.Ncols) * nrows;
   if (tid < 2 * BN) {
     const int pl = tid / BN, ch = tid % BN;
     float t = 0.f;
@@ -500,6 +516,7 @@ struct WgradArgs {
   int pair;            // stem in bf16: a tap is two filter rows (column pieces 0-3: row 2r, 4-7: row 2r+1)
   int64_t split_stride;
   FastDiv divQ, divP;
+  FastDiv div_tps, div_tiles_x, div_ctiles, div_S;  // the tile decode's divisors
 };
 
 template <typename T> struct WgradCfg;
@@ -556,11 +573,11 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   // Logical id = (split, output-channel tile, tap, column tile), the last fastest.  All tiles of one
   // split read the same rows of x and dy, so the renumbering keeps them on one XCD and in its L2.
   const int lid = xcd_remap(blockIdx.x, gridDim.x);
-  const int split = lid / a.tiles_per_split, tile = lid - split * a.tiles_per_split;
+  const int split = static_cast<int>(fdiv(static_cast<uint32_t>(lid), a.div_tps)), tile = lid - split * a.tiles_per_split;
   const int tiles_x = a.R * a.S * a.ctiles;
-  const int ko_tile = tile / tiles_x, tx = tile - ko_tile * tiles_x;
-  const int tap = tx / a.ctiles, c0 = (tx - tap * a.ctiles) * BC;
-  const int r = tap / a.S, s = tap - r * a.S;
+  const int ko_tile = static_cast<int>(fdiv(static_cast<uint32_t>(tile), a.div_tiles_x)), tx = tile - ko_tile * tiles_x;
+  const int tap = static_cast<int>(fdiv(static_cast<uint32_t>(tx), a.div_ctiles)), c0 = (tx - tap * a.ctiles) * BC;
+  const int r = static_cast<int>(fdiv(static_cast<uint32_t>(tap), a.div_S)), s = tap - r * a.S;
   const int ko0 = ko_tile * BMO;
   const int row_begin = split * a.rows_per_split;
   const int row_end = min(row_begin + a.rows_per_split, a.M);
@@ -843,7 +860,14 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   // stride-2 data gradient: four parity classes of the output pixels, each with its own row tiles
   const int64_t tiles_per_class = ceil_div(static_cast<int64_t>(a.nimg) * ((a.P + 1) / 2) * ((a.Q + 1) / 2), BM);
   const bool classes = a.mode == 1 && a.stride == 2;
-  const int64_t grid = (classes ? 4 * tiles_per_class : ceil_div(a.M, BM)) * a.ntn;
+  a.mtiles = static_cast<int>(classes ? 4 * tiles_per_class : ceil_div(a.M, BM));
+  const int64_t grid = static_cast<int64_t>(a.mtiles) * a.ntn;
+  a.div_ntn = make_fastdiv(a.ntn);
+  a.linear = a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0 && !a.pair && a.H == a.P && a.W == a.Q;
+  for (int c = 0; c < 2; ++c) {
+    a.div_w[c] = make_fastdiv(classes ? (a.Q - c + 1) >> 1 : a.Q);
+    a.div_h[c] = make_fastdiv(classes ? (a.P - c + 1) >> 1 : a.P);
+  }
   if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0>(a, tag, grid, s);
   else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
 }
@@ -920,6 +944,10 @@ static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC>, lds); });
   WgradArgs b = a;
   b.tiles_per_split = a.R * a.S * a.ctiles * static_cast<int>(ceil_div(a.Cout, BMO));
+  b.div_tps = make_fastdiv(b.tiles_per_split);
+  b.div_tiles_x = make_fastdiv(a.R * a.S * a.ctiles);
+  b.div_ctiles = make_fastdiv(a.ctiles);
+  b.div_S = make_fastdiv(a.S);
   const dim3 grid(static_cast<unsigned>(b.tiles_per_split) * splits);
   RN50_LAUNCH("conv_wgrad", (wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, b);
 }
