@@ -140,7 +140,10 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
 // are processed in four parity classes (p mod 2, q mod 2): a row tile holds pixels of one class and loops
 // over that class's taps only (a quarter of the taps on average, none for three classes of a 1x1 filter,
 // whose tiles just store zeros).
-template <typename T, int BM, int BN, int WM, int WN, int MODE>
+// LIN: compiled for a 1x1 filter with stride 1 and no padding (output row m is pixel m of the gathered
+// tensor): no pixel decode, no tap cursor, no bounds checks -- these layers have the shortest reductions
+// of the network, and a workgroup's instruction count outside the main loop is what bounds them.
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false>
 __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   constexpr int V = 16 / sizeof(T);
   constexpr int BK = 128 / sizeof(T);
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a.act, a.act_bytes), rsB = make_rsrc(a.wgt, a.wgt_bytes);
 
   // Rows of this tile: pixels m0.. of the whole output grid, or of one parity class of it.
-  const bool classes = MODE == 1 && a.stride == 2;
+  const bool classes = !LIN && MODE == 1 && a.stride == 2;
   __shared__ int pix_s[BM];  // classes only: output pixel index of every tile row
   // Data gradient with batch-norm sums: the per-channel coefficients of this tile's columns, fetched by one
   // thread per column while the main loop runs (every thread loading its own copies costs the texture path
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const int m = m0 + lrow + 32 * i;
     const bool ok = m < Mc;
     const int mm = ok ? m : 0;
-    if (a.linear) {  // no pixel decode: "image" base mm, coordinates (0, 0)
+    if (LIN || a.linear) {  // no pixel decode: "image" base mm, coordinates (0, 0)
       a_base[i] = mm;
       a_h0[i] = ok ? 0 : -(1 << 20);
       a_w0[i] = 0;
@@ -230,6 +233,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   uint32_t a_off[RA], b_tap = static_cast<uint32_t>((r0 * a.S + s0) * a.Cg) * sizeof(T);
   const bool ragged = (a.Cg % BK) != 0;
   auto tap_setup = [&]() __attribute__((always_inline)) {
+    if constexpr (LIN) {
+#pragma unroll
+      for (int i = 0; i < RA; ++i)
+        a_off[i] = a_h0[i] < 0 ? kOob : static_cast<uint32_t>(a_base[i] * a.PS + piece * V) * sizeof(T);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
       int ih, iw;
@@ -264,7 +273,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
     for (int i = 0; i < RB; ++i) st.b[i] = buffer_load16(rsB, cval ? b_row[i] : kOob, b_tap + so);
     // advance the cursor
-    if (++cur_cc == a.cpt) {
+    if constexpr (LIN) {
+      ++cur_cc;
+    } else if (++cur_cc == a.cpt) {
       cur_cc = 0;
       cur_s += tstep;
       if (cur_s >= a.S) {
@@ -840,17 +851,17 @@ static void allow_big_lds(K kernel, int bytes) {
   if (bytes > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int MODE>
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false>
 static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid, hipStream_t s) {
   constexpr int stage = (BM + BN) * kPitch;
   constexpr int lds = 2 * stage;
   static std::once_flag once;
-  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE>, lds); });
+  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>, lds); });
   // A reduction of a single chunk (the 1x1 layers with 64 channels, the largest pixel counts of the net)
   // never touches the second pipeline buffer; without it more workgroups fit a CU.  The output stage's
   // uses of the buffer (tile in float: BM*(4*BN+16) bytes; column sums: at most 16 KB) fit one 64x64 stage.
   const bool one_chunk = BM == 64 && BN == 64 && a.R * a.S * a.cpt == 1;
-  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE>), dim3(static_cast<unsigned>(grid)), dim3(256),
+  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>), dim3(static_cast<unsigned>(grid)), dim3(256),
               one_chunk ? stage : lds, s, a);
 }
 template <typename T, int BM, int BN, int WM, int WN>
@@ -867,6 +878,13 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   for (int c = 0; c < 2; ++c) {
     a.div_w[c] = make_fastdiv(classes ? (a.Q - c + 1) >> 1 : a.Q);
     a.div_h[c] = make_fastdiv(classes ? (a.P - c + 1) >> 1 : a.P);
+  }
+  if constexpr (BM == 64 && BN == 64) {
+    if (a.linear) {
+      if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, true>(a, tag, grid, s);
+      else launch_igemm_mode<T, BM, BN, WM, WN, 1, true>(a, tag, grid, s);
+      return;
+    }
   }
   if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0>(a, tag, grid, s);
   else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
