@@ -65,12 +65,18 @@ union alignas(16) Vec16 {
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t h) {
   return __uint_as_float(static_cast<uint32_t>(h) << 16);
 }
-// Round to nearest even; NaN stays NaN.
+// Round to nearest even; NaN stays NaN.  The conversion is gfx950's own instruction (v_cvt_pk_bf16_f32,
+// two values at a time): written out with integer arithmetic and a NaN test it costs 13 instructions and
+// a branch per element, which was most of the convolutions' output stage.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(u >> 16);
+  return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
+}
+__device__ __forceinline__ uint32_t float2_to_bf16x2_bits(float lo, float hi) {
+  f32x2 v;
+  v.x = lo; v.y = hi;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Element traits: VEC elements per 16-byte vector.
@@ -95,8 +101,8 @@ template <> struct Elem<uint16_t> {  // bf16 storage
     for (int i = 0; i < 8; ++i) out[i] = bf16_bits_to_float(v.h[i]);
   }
   static __device__ __forceinline__ void pack(const float* in, Vec16& v) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v.h[i] = float_to_bf16_bits(in[i]);
+    v.u = make_uint4(float2_to_bf16x2_bits(in[0], in[1]), float2_to_bf16x2_bits(in[2], in[3]),
+                     float2_to_bf16x2_bits(in[4], in[5]), float2_to_bf16x2_bits(in[6], in[7]));
   }
   static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
   static __device__ __forceinline__ void store(uint16_t* p, float x) { *p = float_to_bf16_bits(x); }

@@ -361,8 +361,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
               make_float4(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
         } else if (sizeof(T) == 2) {
           uint2 p;
-          p.x = float_to_bf16_bits(acc[i][j][g * 4 + 0]) | (static_cast<uint32_t>(float_to_bf16_bits(acc[i][j][g * 4 + 1])) << 16);
-          p.y = float_to_bf16_bits(acc[i][j][g * 4 + 2]) | (static_cast<uint32_t>(float_to_bf16_bits(acc[i][j][g * 4 + 3])) << 16);
+          p.x = float2_to_bf16x2_bits(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1]);
+          p.y = float2_to_bf16x2_bits(acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
           *reinterpret_cast<uint2*>(dst) = p;
         } else {
           *reinterpret_cast<float4*>(dst) = make_float4(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);

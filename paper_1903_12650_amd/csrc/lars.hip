@@ -162,8 +162,8 @@ __global__ __launch_bounds__(256) void lars_apply_kernel(const Args a) {
     *reinterpret_cast<float4*>(T.w + i) = w4;
     if (lowp) {
       uint2 p;
-      p.x = float_to_bf16_bits(w4.x) | (static_cast<uint32_t>(float_to_bf16_bits(w4.y)) << 16);
-      p.y = float_to_bf16_bits(w4.z) | (static_cast<uint32_t>(float_to_bf16_bits(w4.w)) << 16);
+      p.x = float2_to_bf16x2_bits(w4.x, w4.y);
+      p.y = float2_to_bf16x2_bits(w4.z, w4.w);
       *reinterpret_cast<uint2*>(lowp + i) = p;
     }
   }
