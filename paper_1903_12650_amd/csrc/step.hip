@@ -20,6 +20,7 @@ struct Unit {  // convolution + BN (+ReLU / +add+ReLU)
   rn50_bn_desc bn;
   int iw, ig, ib;        // parameter tensor indices: weight, gamma, beta
   size_t y, z;           // workspace offsets of the conv output and the BN output
+  size_t dy;             // workspace offset of the gradient with respect to the conv output
   size_t mean, rstd;     // workspace offsets (float[C])
   size_t relu_mask;      // residual-add layers: the ReLU decision bits (1 byte per 16-byte vector of z)
   int64_t bn_off;        // first entry of this BN layer in the moving-average arrays of a training state
@@ -60,8 +61,6 @@ struct rn50_plan {
   // Second stream for the work that is off the step's critical path (weight gradients, the weight
   // transposition), with the events that order it against the caller's stream.  Created at the first
   // step (default priority), destroyed with the plan.
-  int ring_blocks = 4;            // blocks the backward pass may run ahead of the weight gradients
-  std::vector<size_t> dy_ring;    // 4 * ring_blocks slots (a block has at most four units)
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_wt = nullptr;
   // Third stream: the projection shortcut of a stage's first block, forward and backward, runs beside the
@@ -168,6 +167,10 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
     u.y = bump(&top, out_elems * es);
     u.z = bump(&top, out_elems * es);
     u.relu_mask = u.bn.mode == 2 ? bump(&top, out_elems * es / 16) : 0;
+    // Every unit keeps its own dy: the weight gradients read them on the side stream as late as they like,
+    // and the backward pass never waits for a buffer (all of them together are smaller than a ring of 16
+    // buffers of the largest activation, the depth at which a ring stops making the main stream wait).
+    u.dy = bump(&top, out_elems * es);
     u.mean = bump(&top, u.conv.Cout * sizeof(float));
     u.rstd = bump(&top, u.conv.Cout * sizeof(float));
     if (out_elems > max_act) max_act = out_elems;
@@ -188,11 +191,6 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->dlogits = bump(&top, static_cast<size_t>(N) * cfg->classes * sizeof(float));
   p->row_loss = bump(&top, static_cast<size_t>(N) * sizeof(float));
   for (int i = 0; i < 5; ++i) p->g[i] = bump(&top, max_act * es);
-  if (const char* e = getenv("RN50_DY_RING_BLOCKS")) {  // tuning aid
-    const int v = atoi(e);
-    if (v >= 1 && v <= 16) p->ring_blocks = v;
-  }
-  for (int i = 0; i < 4 * p->ring_blocks; ++i) p->dy_ring.push_back(bump(&top, max_act * es));
   (void)max_wT;
   p->wT = bump(&top, static_cast<size_t>(p->arena_elems) * es);  // transposed copy of every conv weight
   for (const Unit& u : p->units)
@@ -446,18 +444,15 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   // layer's sums in bn_ws.
   // The weight gradients are off the critical path (nothing in the backward pass reads them): they run
   // on the side stream, a block's worth at a time (one event each way per block: an event is a packet
-  // the stream has to drain for).  dy lives in a ring of buffers, two blocks deep, so the next block's BN
-  // backward need not wait; a slot is rewritten only after the weight gradient that read it.
+  // the stream has to drain for).  Every unit has a dy buffer of its own, so the backward pass never waits
+  // for the weight gradients.
   struct PendingWgrad {
     Unit* u;
     const void* in;
     void* dy;
   };
   PendingWgrad pending[4];
-  int npending = 0, seq = 0, blk = 0;  // units / blocks processed so far in this backward pass
-  auto block_begin = [&]() {
-    if (blk >= plan->ring_blocks) (void)hipStreamWaitEvent(s, plan->ev_wg[blk - plan->ring_blocks], 0);
-  };
+  int npending = 0, blk = 0;  // blocks processed so far in this backward pass
   auto block_end = [&]() {
     (void)hipEventRecord(plan->ev_dy[blk], s);
     (void)hipStreamWaitEvent(side, plan->ev_dy[blk], 0);
@@ -467,13 +462,13 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     npending = 0;
     ++blk;
   };
-  // Phase 1 of a unit: BN backward, dz (+dz2) -> dy (a ring slot; returned), on stream st with BN scratch wsx.
+  // Phase 1 of a unit: BN backward, dz (+dz2) -> dy (the unit's buffer; returned), on stream st with BN scratch wsx.
   // outer_bits: dz is still to be masked by the ReLU bits another layer recorded (the projection shortcut's
   // BN, whose output gradient is the block output's gradient under the block's ReLU): for the backward
   // arithmetic that is a BN+ReLU layer with recorded bits.
   auto unit_bn_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, bool sums_ready,
                          hipStream_t st, void* wsx, void** dy_out, const uint8_t* outer_bits = nullptr) -> int {
-    void* dy = ws + plan->dy_ring[seq % plan->dy_ring.size()];
+    void* dy = ws + u.dy;
     // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
     const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
     if (outer_bits) {
@@ -490,7 +485,6 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
                            G(u.ig), G(u.ib), wsx, bn_ws_bytes, st));
     }
     pending[npending++] = PendingWgrad{&u, in, dy};
-    ++seq;
     *dy_out = dy;
     return RN50_OK;
   };
@@ -525,7 +519,6 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     Unit &u1 = plan->units[b.u1], &u2 = plan->units[b.u2], &u3 = plan->units[b.u3];
     Unit* prev = bi > 0 ? &plan->units[plan->blocks[bi - 1].u3] : nullptr;  // its BN output is this block's input
     const void* block_in = prev ? static_cast<const void*>(ws + prev->z) : static_cast<const void*>(ws + plan->pool);
-    block_begin();
     // The block input has two consumers (conv1 and the shortcut).  conv1's data gradient comes last: it
     // adds the shortcut's gradient and takes the sums of the previous block's last BN layer.
     // The shortcut's gradient is dzo under the block output's ReLU mask.  No copy of it is made: an identity
@@ -563,7 +556,6 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     block_end();
   }
   STEP_TRY(maxpool_bwd(cfg.N, u0.P, u0.Q, cfg.stem, dt, ws + u0.z, ws + plan->pool_argmax, dzo, dzo2, dz_next, s));
-  block_begin();
   STEP_TRY(unit_bwd(u0, ws + plan->xp, dz_next, nullptr, nullptr, nullptr, false, nullptr, nullptr));
   block_end();
   // ------------------------------------------------------------------ LARS
