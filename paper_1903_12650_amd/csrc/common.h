@@ -49,6 +49,25 @@ class KernelTimer {
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 
+// ------------------------------------------- division by a launch constant
+struct FastDiv {  // exact unsigned division by a runtime constant (Granlund-Montgomery)
+  uint32_t mul, sh1, sh2;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  if (d == 0) d = 1;  // (an empty dimension: nothing is divided by it)
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  FastDiv f;
+  f.mul = static_cast<uint32_t>(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
+  const uint32_t t = __umulhi(f.mul, n);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 // -------------------------------------------------------------- device: types
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

@@ -38,24 +38,6 @@
 namespace rn50 {
 
 // ----------------------------------------------------------- small utilities
-struct FastDiv {  // exact unsigned division by a runtime constant (Granlund-Montgomery)
-  uint32_t mul, sh1, sh2;
-};
-static FastDiv make_fastdiv(uint32_t d) {
-  if (d == 0) d = 1;  // (an empty dimension: nothing is divided by it)
-  uint32_t l = 0;
-  while ((1ull << l) < d) ++l;
-  FastDiv f;
-  f.mul = static_cast<uint32_t>(((1ull << 32) * ((1ull << l) - d)) / d + 1);
-  f.sh1 = l < 1 ? l : 1;
-  f.sh2 = l > 0 ? l - 1 : 0;
-  return f;
-}
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
-  const uint32_t t = __umulhi(f.mul, n);
-  return (t + ((n - t) >> f.sh1)) >> f.sh2;
-}
-
 template <typename T> struct Mma;
 template <> struct Mma<uint16_t> {  // bf16: one 32x32x16 MFMA per 16-byte fragment pair
   static __device__ __forceinline__ void run(const Vec16& a, const Vec16& b, f32x16& acc) {
@@ -814,11 +796,11 @@ __global__ __launch_bounds__(256) void transpose_batch_kernel(const TransposeBat
 template <typename T>
 __global__ __launch_bounds__(256) void stem_pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp,
                                                              int N, int H, int W, int Hp, int Wp) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (i >= static_cast<int64_t>(N) * Hp * Wp) return;
-  const int wq = static_cast<int>(i % Wp);
-  const int64_t t = i / Wp;
-  const int hq = static_cast<int>(t % Hp), n = static_cast<int>(t / Hp);
+  // grid: (padded row, padded rows, images)
+  const int wq = blockIdx.x * 256 + threadIdx.x;
+  if (wq >= Wp) return;
+  const int hq = blockIdx.y, n = blockIdx.z;
+  const int64_t i = (static_cast<int64_t>(n) * Hp + hq) * Wp + wq;
   const int h = hq - 3, w = wq - 3;
   T v[4] = {0, 0, 0, 0};
   if (h >= 0 && h < H && w >= 0 && w < W) {
@@ -1006,6 +988,8 @@ static int check_conv(const rn50_conv_desc* d, const char* who) {
   RN50_REQUIRE(d->Cin % V == 0 || is_stem(d), RN50_ERR_UNSUPPORTED,
                "%s: Cin=%d is neither a multiple of %d nor the 7x7/2 pad-3 stem", who, d->Cin, V);
   RN50_REQUIRE(d->pad < d->R && d->pad < d->S, RN50_ERR_UNSUPPORTED, "%s: pad >= filter size", who);
+  RN50_REQUIRE(!is_stem(d) || (d->N <= 65535 && d->H + 6 <= 65535), RN50_ERR_UNSUPPORTED,
+               "%s: stem with N=%d, H=%d is beyond the padding kernel's launch grid", who, d->N, d->H);
   const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
   const int64_t lim = ((1ll << 31) - 1) / esize(d->dtype);  // byte offsets are 31-bit
   RN50_REQUIRE(static_cast<int64_t>(d->N) * (d->H + 6) * (d->W + 16) * (d->Cin < 4 ? 4 : d->Cin) < lim &&
@@ -1038,12 +1022,12 @@ namespace rn50 {
 
 void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_t s) {
   const StemGeom g = stem_geom(d);
-  const int64_t n = static_cast<int64_t>(d->N) * g.Hp * g.Wp;
+  const dim3 grid(static_cast<unsigned>(ceil_div(g.Wp, 256)), g.Hp, d->N);
   if (d->dtype == RN50_BF16)
-    hipLaunchKernelGGL(stem_pad_input_kernel<uint16_t>, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s,
+    hipLaunchKernelGGL(stem_pad_input_kernel<uint16_t>, grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(x), static_cast<uint16_t*>(xp), d->N, d->H, d->W, g.Hp, g.Wp);
   else
-    hipLaunchKernelGGL(stem_pad_input_kernel<float>, dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, s,
+    hipLaunchKernelGGL(stem_pad_input_kernel<float>, grid, dim3(256), 0, s,
                        static_cast<const float*>(x), static_cast<float*>(xp), d->N, d->H, d->W, g.Hp, g.Wp);
 }
 

@@ -12,17 +12,15 @@ template <typename T>
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ x,
                                                           T* __restrict__ y,
                                                           uint8_t* __restrict__ argmax, int N,
-                                                          int H, int W, int C, int P, int Q) {
+                                                          int H, int W, int C, int P, int Q, FastDiv div_cv) {
+  // grid: (vectors of one output row, output rows, images) -- no index arithmetic beyond one division
   constexpr int V = Elem<T>::VEC;
   const int cv = C / V;
-  const int64_t total = static_cast<int64_t>(N) * P * Q * cv;
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int c = static_cast<int>(i % cv);
-  int64_t t = i / cv;
-  const int q = static_cast<int>(t % Q); t /= Q;
-  const int p = static_cast<int>(t % P);
-  const int n = static_cast<int>(t / P);
+  const int xi = blockIdx.x * 256 + threadIdx.x;
+  if (xi >= Q * cv) return;
+  const int q = static_cast<int>(fdiv(static_cast<uint32_t>(xi), div_cv)), c = xi - q * cv;
+  const int p = blockIdx.y, n = blockIdx.z;
+  const int64_t i = (static_cast<int64_t>(n) * P + p) * Q * cv + xi;
   float best[V];
   int at[V];  // window position r*3+s of the first maximum
   bool have = false;
@@ -77,18 +75,15 @@ __global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const uint8_t* __r
                                                               const T* __restrict__ dy,
                                                               const T* __restrict__ dy2,
                                                               T* __restrict__ dx, int N, int H, int W,
-                                                              int C, int P, int Q) {
+                                                              int C, int P, int Q, FastDiv div_cv) {
+  // grid: (vectors of one row of 2x2 pixel blocks, rows of blocks, images)
   constexpr int V = Elem<T>::VEC;
   const int cv = C / V;
-  const int Ha = (H + 1) / 2, Wb = (W + 1) / 2;
-  const int64_t total = static_cast<int64_t>(N) * Ha * Wb * cv;
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int c = static_cast<int>(i % cv);
-  int64_t t = i / cv;
-  const int b = static_cast<int>(t % Wb); t /= Wb;
-  const int a = static_cast<int>(t % Ha);
-  const int n = static_cast<int>(t / Ha);
+  const int Wb = (W + 1) / 2;
+  const int xi = blockIdx.x * 256 + threadIdx.x;
+  if (xi >= Wb * cv) return;
+  const int b = static_cast<int>(fdiv(static_cast<uint32_t>(xi), div_cv)), c = xi - b * cv;
+  const int a = blockIdx.y, n = blockIdx.z;
   float acc[2][2][V];
 #pragma unroll
   for (int k = 0; k < 4; ++k)
@@ -546,15 +541,16 @@ extern "C" int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x,
   clear_error();
   if (int rc = check_dtype(dtype, "maxpool_fwd")) return rc;
   RN50_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, RN50_ERR_INVALID, "maxpool_fwd: non-positive size");
+  RN50_REQUIRE(N <= 65535 && H <= 131070, RN50_ERR_UNSUPPORTED, "maxpool_fwd: N=%d or H=%d beyond the launch grid", N, H);
   RN50_REQUIRE(x && y, RN50_ERR_INVALID, "maxpool_fwd: null pointer");
   RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "maxpool_fwd: C=%d", C);
   RN50_REQUIRE(aligned16(x) && aligned16(y), RN50_ERR_ALIGN, "maxpool_fwd: pointer not 16-byte aligned");
   const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
-    const int64_t total = static_cast<int64_t>(N) * P * Q * (C / Elem<T>::VEC);
-    hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
-                       static_cast<const T*>(x), static_cast<T*>(y), argmax, N, H, W, C, P, Q);
+    const int cv = C / Elem<T>::VEC;
+    hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(ceil_div(Q * cv, 256), P, N), dim3(256), 0, s,
+                       static_cast<const T*>(x), static_cast<T*>(y), argmax, N, H, W, C, P, Q, make_fastdiv(cv));
   });
   return launch_status("maxpool_fwd");
 }
@@ -565,6 +561,7 @@ extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x,
   clear_error();
   if (int rc = check_dtype(dtype, "maxpool_bwd")) return rc;
   RN50_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0, RN50_ERR_INVALID, "maxpool_bwd: non-positive size");
+  RN50_REQUIRE(N <= 65535 && H <= 131070, RN50_ERR_UNSUPPORTED, "maxpool_bwd: N=%d or H=%d beyond the launch grid", N, H);
   RN50_REQUIRE((x || argmax) && dy && dx, RN50_ERR_INVALID, "maxpool_bwd: null pointer");
   RN50_REQUIRE(C % (dtype == RN50_BF16 ? 8 : 4) == 0, RN50_ERR_UNSUPPORTED, "maxpool_bwd: C=%d", C);
   RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2) && aligned16(dx) && aligned16(argmax),
@@ -573,11 +570,10 @@ extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x,
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int64_t total = static_cast<int64_t>(N) * H * W * (C / Elem<T>::VEC);
-    const int64_t quads = static_cast<int64_t>(N) * ((H + 1) / 2) * ((W + 1) / 2) * (C / Elem<T>::VEC);
     if (argmax)
-      hipLaunchKernelGGL(maxpool_bwd_idx_kernel<T>, dim3(ceil_div(quads, 256)), dim3(256), 0, s, argmax,
-                         static_cast<const T*>(dy), static_cast<const T*>(dy2), static_cast<T*>(dx), N,
-                         H, W, C, P, Q);
+      hipLaunchKernelGGL(maxpool_bwd_idx_kernel<T>, dim3(ceil_div(((W + 1) / 2) * (C / Elem<T>::VEC), 256), (H + 1) / 2, N),
+                         dim3(256), 0, s, argmax, static_cast<const T*>(dy), static_cast<const T*>(dy2),
+                         static_cast<T*>(dx), N, H, W, C, P, Q, make_fastdiv(C / Elem<T>::VEC));
     else
       hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
                          static_cast<const T*>(x), static_cast<const T*>(dy),
