@@ -35,8 +35,8 @@ DOMINANT_KERNEL = "conv_dgrad"  # largest share of the step's kernel time (rocpr
 # copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
 # dirty in L2 are written back during later kernels.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "conv_fwd": 40.43e6, "conv_dgrad": 64.00e6, "conv_wgrad": 52.16e6, "bn_apply": 42.58e6,
-    "bn_bwd_reduce": 75.68e6, "bn_bwd_apply": 51.91e6, "lars_norms": 102.30e6, "lars_apply": 281.25e6,
+    "conv_fwd": 40.45e6, "conv_dgrad": 63.87e6, "conv_wgrad": 52.14e6, "bn_apply": 42.55e6,
+    "bn_bwd_reduce": 75.67e6, "bn_bwd_apply": 51.85e6, "lars_norms": 102.30e6, "lars_apply": 281.25e6,
 }
 
 
