@@ -51,6 +51,12 @@ def test_host_side_argument_checks_need_no_gpu():
     assert raw.bn_relu_fwd(ctypes.byref(b), one, one, one, None, one, None, one, one, None, None, ctypes.c_float(0.9), one,
                            ctypes.c_size_t(1 << 20), None) == -1                                # mode 2 without residual
     assert raw.xent_fwd_bwd(0, 10, one, one, ctypes.c_float(0), ctypes.c_float(1), one, one, one, None) == -1
+    # the pooling kernels and the stem's padding kernel launch one grid plane per image and per row
+    assert raw.maxpool_fwd(70000, 4, 4, 8, rn.BF16, one, one, None, None) == -2
+    assert b"launch grid" in raw.rn50_last_error()
+    assert raw.maxpool_bwd(70000, 4, 4, 8, rn.BF16, one, None, one, None, one, None) == -2
+    stem = rn.ConvDesc(70000, 8, 8, 3, 64, 7, 7, 2, 3, rn.BF16)
+    assert raw.conv_fwd(ctypes.byref(stem), one, one, one, one, ctypes.c_size_t(1 << 40), None) == -2
 
 
 def test_loop_entry_points_check_their_arguments_without_a_gpu():
