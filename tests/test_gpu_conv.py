@@ -55,13 +55,13 @@ SMALL = [  # N,H,W,C,K,R,stride,pad : ragged tiles, tails, every stride/pad/filt
     (2, 9, 7, 16, 16, 1, 2, 0),      # stride 2, odd sizes: the four pixel parity classes differ in size
     (1, 1, 5, 8, 8, 3, 2, 1),        # a single row: two parity classes are empty
     (2, 5, 4, 8, 16, 2, 2, 0),       # even filter, stride 2
-    # 3x3 stride 1 pad 1 with whole 128-byte channel chunks: the halo kernel's pixel windows
-    (3, 9, 9, 64, 64, 3, 1, 1),      # full-width windows of 7 rows that span two images, short last window
-    (2, 5, 12, 128, 72, 3, 1, 1),    # two windows side by side, two channel chunks, ragged column tile
+    # 3x3 stride 1 pad 1 with whole 128-byte channel chunks, several tiles and images per case
+    (3, 9, 9, 64, 64, 3, 1, 1),      # tiles that span two images, short last tile
+    (2, 5, 12, 128, 72, 3, 1, 1),    # two channel chunks, ragged column tile
     (5, 7, 21, 192, 64, 3, 1, 1),    # three channel chunks (odd number of pipeline steps)
-    (7, 4, 48, 64, 128, 3, 1, 1),    # three windows side by side
+    (7, 4, 48, 64, 128, 3, 1, 1),    # wide, low images
     (2, 1, 56, 64, 64, 3, 1, 1),     # one-row images: every tap row but the middle one is padding
-    (3, 8, 8, 128, 128, 3, 1, 1),    # one full 8x8 window per image
+    (3, 8, 8, 128, 128, 3, 1, 1),    # one 64-pixel tile per image
 ]
 
 

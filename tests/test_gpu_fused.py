@@ -25,7 +25,7 @@ FUSED_SHAPES = [(2, 14, 14, 64, 64, 1, 1, 0), (3, 13, 9, 24, 40, 3, 1, 1), (2, 2
                 (5, 28, 28, 128, 128, 1, 1, 0), (2, 30, 30, 64, 256, 1, 2, 0), (1, 5, 5, 8, 8, 3, 1, 1),
                 (2, 64, 64, 3, 64, 7, 2, 3), (40, 7, 7, 256, 64, 1, 1, 0), (3, 11, 13, 24, 40, 3, 2, 1),
                 (2, 9, 7, 16, 16, 1, 2, 0),
-                # 3x3 stride 1 pad 1, whole channel chunks: tiles are pixel windows (halo kernel)
+                # 3x3 stride 1 pad 1, whole channel chunks, tiles spanning images
                 (3, 9, 9, 64, 64, 3, 1, 1), (2, 5, 12, 128, 72, 3, 1, 1), (5, 7, 21, 192, 64, 3, 1, 1),
                 (7, 4, 48, 64, 128, 3, 1, 1), (40, 14, 14, 64, 64, 3, 1, 1)]
 
