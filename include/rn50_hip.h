@@ -245,7 +245,6 @@ size_t lars_update_workspace_bytes(const rn50_lars_desc* d, const rn50_lars_tens
 int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
                 const rn50_lars_tensor* table_dev, float* norms_out, void* workspace,
                 size_t workspace_bytes, void* stream);
-
 /* ----------------------------------------------------------------- whole step
  * One training step of ResNet-50 v1.5 on the local batch: forward, softmax
  * cross-entropy, backward, LARS update of every parameter tensor (the gradient
@@ -271,8 +270,14 @@ typedef struct {
 
 typedef struct rn50_plan rn50_plan; /* host-side object (layout, two streams, events); holds no device memory */
 
+/* Checks every layer's shape against what the kernels cover (so that a step cannot fail on a
+ * shape half-way through) and lays out the workspace.  On error no plan is returned. */
 int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_out);
 void resnet_plan_destroy(rn50_plan* plan);
+/* Creates the plan's two streams and their events now instead of at the first step (needs the
+ * GPU; all or nothing; a second call is a no-op).  Call it before capturing a step into a graph
+ * when no step has run outside the capture yet. */
+int resnet_plan_prepare(rn50_plan* plan);
 int resnet_plan_num_tensors(const rn50_plan* plan);
 /* Shape of parameter tensor i: dims_out[4] = {K,R,S,C} for convolution weights,
  * {K,C,0,0} for the FC weight, {C,0,0,0} for vectors.  Returns the element count. */
@@ -294,6 +299,9 @@ size_t resnet_plan_workspace_bytes(const rn50_plan* plan);
  * loss_out: device float[1]; logits_out: device float[N,classes] or NULL.
  * lr: the learning rate of this step (schedules live with the caller).
  * If update == 0 the step stops after backward (gradients only).
+ * Errors: every argument is checked before the first launch (the shapes at plan creation, the
+ * pointers, alignment and workspace here); after that only a launch failure reported by the HIP
+ * runtime (RN50_ERR_HIP) can end a step early, with the kernels enqueued so far left to run.
  * Stream semantics: everything is ordered after the work `stream` holds at the call and
  * is complete when the work this call enqueues on `stream` is.  Inside, independent parts
  * (weight gradients, the projection shortcuts, the weight transposition) run on two

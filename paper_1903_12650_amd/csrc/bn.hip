@@ -65,7 +65,6 @@ static BnGeom bn_apply_geom(int64_t m, int C, int dtype, int target) {
   BnGeom g = bn_geom(m, C, dtype);
   const int TY = 256 >> g.tx_log2;
   int64_t rpt = ceil_div(m * g.gy, static_cast<int64_t>(TY) * target);
-  if (const char* e = getenv("RN50_BN_APPLY_RPT")) rpt = atoi(e) > 0 ? atoi(e) : rpt;  // tuning aid
   rpt = ceil_div(rpt, kBnRows) * kBnRows;
   if (rpt > 32) rpt = 32;
   g.rpb = static_cast<int>(rpt) * TY;
@@ -552,6 +551,8 @@ static int check_desc(const rn50_bn_desc* d, const char* who) {
   RN50_REQUIRE(d->eps >= 0.f, RN50_ERR_INVALID, "%s: eps < 0", who);
   return RN50_OK;
 }
+
+int bn_desc_check(const rn50_bn_desc* d, const char* who) { return check_desc(d, who); }
 
 static size_t bn_ws_bytes(const rn50_bn_desc* d) {
   const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;

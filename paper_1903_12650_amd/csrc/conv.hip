@@ -1020,6 +1020,8 @@ using namespace rn50;
 // Internal entry points shared with the whole-step driver (declared in step_internal.h).
 namespace rn50 {
 
+int conv_desc_check(const rn50_conv_desc* d, const char* who) { return check_conv(d, who); }
+
 void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_t s) {
   const StemGeom g = stem_geom(d);
   const dim3 grid(static_cast<unsigned>(ceil_div(g.Wp, 256)), g.Hp, d->N);
@@ -1345,9 +1347,9 @@ extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const
                "conv_dgrad_bn_sums: workspace %zu < %zu bytes", workspace_bytes, dgrad_wt_bytes(d));
   RN50_REQUIRE(sums_bytes >= conv_bn_sums_bytes(d), RN50_ERR_WORKSPACE, "conv_dgrad_bn_sums: sums %zu < %zu bytes",
                sums_bytes, conv_bn_sums_bytes(d));
+  RN50_REQUIRE(!addend_mask || addend, RN50_ERR_INVALID, "conv_dgrad_bn_sums: addend_mask without addend");
   hipStream_t s = static_cast<hipStream_t>(stream);
   dgrad_transpose_weights(d, w, workspace, s);
-  RN50_REQUIRE(!addend_mask || addend, RN50_ERR_INVALID, "conv_dgrad_bn_sums: addend_mask without addend");
   const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums, addend, relu_mask, addend_mask};
   dgrad_run(d, dy, workspace, dx, &bn, s);
   return launch_status("conv_dgrad_bn_sums");

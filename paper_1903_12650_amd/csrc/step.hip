@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <memory>
 #include <vector>
 
 #include "common.h"
@@ -69,6 +70,7 @@ struct rn50_plan {
   hipEvent_t ev_bfork = nullptr, ev_bjoin = nullptr;
   size_t bn_scratch2 = 0;
   std::vector<hipEvent_t> ev_dy, ev_wg;  // per block: its dy tensors are ready / its weight gradients are done
+  bool streams_ready = false;            // all of the above exist
 };
 
 using namespace rn50;
@@ -123,7 +125,8 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   for (int i = 0; i < 4; ++i)
     RN50_REQUIRE(cfg->widths[i] > 0 && cfg->widths[i] % V == 0 && cfg->blocks[i] > 0, RN50_ERR_UNSUPPORTED,
                  "resnet_plan_create: stage %d width/blocks", i);
-  rn50_plan* p = new rn50_plan();
+  std::unique_ptr<rn50_plan> owner(new rn50_plan());  // freed on every error path below
+  rn50_plan* p = owner.get();
   p->cfg = *cfg;
   p->es = cfg->dtype == RN50_BF16 ? 2 : 4;
   const int N = cfg->N;
@@ -153,6 +156,18 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   add_tensor(p, cfg->classes, cin, 0, 0, true);
   add_tensor(p, cfg->classes, 0, 0, 0, false);
   RN50_REQUIRE(p->arena_elems < (1ll << 31), RN50_ERR_UNSUPPORTED, "resnet_plan_create: too many parameters");
+  // Every shape-dependent condition that the operations of a step check is checked here, once, so that a
+  // step, after its own pointer / alignment / workspace checks, cannot fail on an argument half-way through.
+  for (const Unit& u : p->units) {
+    if (int rc = conv_desc_check(&u.conv, "resnet_plan_create")) return rc;
+    if (int rc = bn_desc_check(&u.bn, "resnet_plan_create")) return rc;
+  }
+  RN50_REQUIRE(N <= 65535 && p->units[0].P <= 131070, RN50_ERR_UNSUPPORTED,
+               "resnet_plan_create: N=%d or image size beyond the pooling kernels' launch grid", N);
+  RN50_REQUIRE(cfg->classes <= 65536, RN50_ERR_UNSUPPORTED, "resnet_plan_create: more than 65536 classes");
+  RN50_REQUIRE(cin % V == 0, RN50_ERR_UNSUPPORTED, "resnet_plan_create: classifier input width %d", cin);
+  RN50_REQUIRE(cfg->label_smoothing >= 0.f && cfg->label_smoothing <= 1.f, RN50_ERR_INVALID,
+               "resnet_plan_create: label_smoothing %g", static_cast<double>(cfg->label_smoothing));
 
   // ---- workspace layout
   size_t top = 0;
@@ -216,33 +231,45 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
   p->lars_scratch = bump(&top, lars_arena_partial_bytes(p->lars_rest));
   p->lars_stem_scratch = bump(&top, lars_arena_partial_bytes(p->lars_stem));
   p->ws_bytes = top;
-  *plan_out = p;
+  *plan_out = owner.release();
   return RN50_OK;
 }
 
+namespace {
+void destroy_streams(rn50_plan* p);
+}
 extern "C" void resnet_plan_destroy(rn50_plan* plan) {
   if (!plan) return;
-  if (plan->side) {
-    (void)hipStreamSynchronize(plan->side);
-    (void)hipStreamDestroy(plan->side);
-  }
-  if (plan->branch) {
-    (void)hipStreamSynchronize(plan->branch);
-    (void)hipStreamDestroy(plan->branch);
-  }
-  if (plan->ev_bfork) (void)hipEventDestroy(plan->ev_bfork);
-  if (plan->ev_bjoin) (void)hipEventDestroy(plan->ev_bjoin);
-  if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
-  if (plan->ev_wt) (void)hipEventDestroy(plan->ev_wt);
-  for (hipEvent_t e : plan->ev_dy) (void)hipEventDestroy(e);
-  for (hipEvent_t e : plan->ev_wg) (void)hipEventDestroy(e);
+  destroy_streams(plan);
   delete plan;
 }
 
 namespace {
-// The side stream and its events (host-side handles only; no device memory).
+// The side streams and their events (host-side handles only; no device memory).  All or nothing: after a
+// failure every handle made so far is destroyed again, so a later call starts from scratch.
+void destroy_streams(rn50_plan* p) {
+  if (p->side) {
+    (void)hipStreamSynchronize(p->side);
+    (void)hipStreamDestroy(p->side);
+  }
+  if (p->branch) {
+    (void)hipStreamSynchronize(p->branch);
+    (void)hipStreamDestroy(p->branch);
+  }
+  for (hipEvent_t* e : {&p->ev_bfork, &p->ev_bjoin, &p->ev_fork, &p->ev_wt})
+    if (*e) {
+      (void)hipEventDestroy(*e);
+      *e = nullptr;
+    }
+  for (hipEvent_t e : p->ev_dy) (void)hipEventDestroy(e);
+  for (hipEvent_t e : p->ev_wg) (void)hipEventDestroy(e);
+  p->ev_dy.clear();
+  p->ev_wg.clear();
+  p->side = p->branch = nullptr;
+  p->streams_ready = false;
+}
 int ensure_side_stream(rn50_plan* p) {
-  if (p->side) return RN50_OK;
+  if (p->streams_ready) return RN50_OK;
   auto ok = [](hipError_t e) { return e == hipSuccess; };
   bool good = ok(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking)) &&
               ok(hipStreamCreateWithFlags(&p->branch, hipStreamNonBlocking)) &&
@@ -256,10 +283,20 @@ int ensure_side_stream(rn50_plan* p) {
     if (a) p->ev_dy.push_back(a);
     if (b) p->ev_wg.push_back(b);
   }
-  if (!good) return fail(RN50_ERR_HIP, "resnet_step: could not create the side stream or its events");
+  if (!good) {
+    (void)hipGetLastError();
+    destroy_streams(p);
+    return fail(RN50_ERR_HIP, "resnet_step: could not create the side streams or their events");
+  }
+  p->streams_ready = true;
   return RN50_OK;
 }
 }  // namespace
+extern "C" int resnet_plan_prepare(rn50_plan* plan) {
+  clear_error();
+  RN50_REQUIRE(plan, RN50_ERR_INVALID, "resnet_plan_prepare: null plan");
+  return ensure_side_stream(plan);
+}
 extern "C" int resnet_plan_num_tensors(const rn50_plan* plan) {
   return plan ? static_cast<int>(plan->tensors.size()) : 0;
 }

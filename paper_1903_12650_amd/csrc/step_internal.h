@@ -10,6 +10,10 @@
 
 namespace rn50 {
 
+// The descriptor checks of the C ABI's own entry points (0, or the error code with the text set).
+int conv_desc_check(const rn50_conv_desc* d, const char* who);
+int bn_desc_check(const rn50_bn_desc* d, const char* who);
+
 // conv.hip
 size_t stem_padded_input_bytes(const rn50_conv_desc* d);
 size_t stem_padded_weight_bytes(const rn50_conv_desc* d);

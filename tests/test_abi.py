@@ -59,6 +59,30 @@ def test_host_side_argument_checks_need_no_gpu():
     assert raw.conv_fwd(ctypes.byref(stem), one, one, one, one, ctypes.c_size_t(1 << 40), None) == -2
 
 
+def test_dgrad_bn_sums_rejects_a_mask_without_addend_before_any_launch():
+    """Every argument check of conv_dgrad_bn_sums precedes its first launch (the weight transposition): with no
+    GPU here a launch attempt would surface as a HIP error (-5), an argument error comes back as -1."""
+    import paper_1903_12650_amd as rn
+    raw = rn.raw
+    d = rn.ConvDesc(1, 8, 8, 16, 16, 3, 3, 1, 1, rn.BF16)
+    one = ctypes.c_void_p(256)
+    big = ctypes.c_size_t(1 << 30)
+    rc = raw.conv_dgrad_bn_sums(ctypes.byref(d), one, one, one, None, one, one, None, one, one, one, one, one, big, one,
+                                big, None)
+    assert rc == -1 and b"addend_mask without addend" in raw.rn50_last_error()
+
+
+def test_plan_creation_checks_shapes_and_frees_the_plan_on_error():
+    import paper_1903_12650_amd as rn
+    with __import__("pytest").raises(rn.Rn50Error) as e:
+        rn.ResnetPlan(8, rn.BF16, 64, 70000, (8, 8, 8, 8), (1, 1, 1, 1), 8, 4)     # more classes than xent covers
+    assert e.value.code == -2
+    with __import__("pytest").raises(rn.Rn50Error) as e:
+        rn.ResnetPlan(8, rn.BF16, 64, 10, (8, 8, 8, 12), (1, 1, 1, 1), 8, 4)       # width not a multiple of 8
+    assert e.value.code == -2
+    assert rn.raw.resnet_plan_prepare(None) == -1
+
+
 def test_loop_entry_points_check_their_arguments_without_a_gpu():
     import paper_1903_12650_amd as rn
     raw = rn.raw

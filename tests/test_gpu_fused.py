@@ -212,3 +212,17 @@ def test_fused_abi_errors(rn):
     with pytest.raises(rn.Rn50Error) as e:
         rn.bn_relu_fwd_from_sums(y, h, g, b, None, 1e-5, 2)     # mode 2 without residual
     assert e.value.code == -1
+    # addend_mask without addend: rejected before the first launch, so workspace, dx and sums stay as they were
+    dy = dev(synth.activation_nhwc(SEED, "dy", N, K, H, W), True)
+    mask = torch.full((N * H * W * C // 8,), 0xff, dtype=torch.uint8, device="cuda")
+    d = rn.ConvDesc(N, H, W, C, K, 1, 1, 1, 0, rn.BF16)
+    wsb = torch.full((rn.conv_dgrad_workspace_bytes(d),), 0x5a, dtype=torch.uint8, device="cuda")
+    sums = torch.full((rn.conv_bn_sums_bytes(d),), 0x5a, dtype=torch.uint8, device="cuda")
+    dx = torch.full((N, H, W, C), 3.0, dtype=torch.bfloat16, device="cuda")
+    gc, bc = dev(np.ones(C, np.float32)), dev(np.zeros(C, np.float32))
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv_dgrad_bn_sums(dy, w, (N, H, W, C), 1, 0, x, gc, bc, bc, gc, dx=dx, workspace=wsb, sums=sums,
+                              addend=None, addend_mask=mask)
+    assert e.value.code == -1
+    torch.cuda.synchronize()
+    assert bool((wsb == 0x5a).all()) and bool((sums == 0x5a).all()) and bool((dx == 3.0).all())
