@@ -245,6 +245,21 @@ size_t lars_update_workspace_bytes(const rn50_lars_desc* d, const rn50_lars_tens
 int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
                 const rn50_lars_tensor* table_dev, float* norms_out, void* workspace,
                 size_t workspace_bytes, void* stream);
+/* lars_update for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, arithmetic and
+ * results as lars_update, but the partial norms live in a device array built into the library
+ * (256 KB, held on every GPU the library runs on until the process ends) instead of a caller
+ * workspace, and the call allocates nothing.  Limit: the table's tensors may need at most
+ * lars_update_noalloc_max_chunks() chunks of 8192 elements in all (one chunk per started 8192
+ * elements of each tensor; 32768 chunks, i.e. up to 268 M parameters); a larger table
+ * is rejected with RN50_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share that
+ * array: calls that overlap in time on one GPU (different streams or threads) race; calls on
+ * one stream, or otherwise ordered, are safe.  Nothing in the array has to survive between
+ * calls. */
+int64_t lars_update_noalloc_max_chunks(void);
+int lars_update_noalloc(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
+                        const rn50_lars_tensor* table_dev, float* norms_out, void* stream);
+
 /* ----------------------------------------------------------------- whole step
  * One training step of ResNet-50 v1.5 on the local batch: forward, softmax
  * cross-entropy, backward, LARS update of every parameter tensor (the gradient

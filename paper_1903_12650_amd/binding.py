@@ -11,7 +11,7 @@ import torch
 
 __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd",
            "bn_relu_bwd", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "fc_fwd", "fc_bwd",
-           "xent_fwd_bwd", "lars_update", "LarsTable", "profile_begin", "profile_pause", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
+           "xent_fwd_bwd", "lars_update", "lars_update_noalloc", "LarsTable", "profile_begin", "profile_pause", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
            "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
@@ -73,7 +73,7 @@ for _n in ("conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad
     if hasattr(raw, _n):
         getattr(raw, _n).restype = ctypes.c_size_t
 for _n in ("resnet_plan_tensor_shape", "resnet_plan_tensor_offset", "resnet_plan_arena_elems", "resnet_plan_bn_channels",
-           "resnet_plan_bn_offset"):
+           "resnet_plan_bn_offset", "lars_update_noalloc_max_chunks"):
     if hasattr(raw, _n):
         getattr(raw, _n).restype = ctypes.c_int64
 
@@ -373,6 +373,13 @@ def lars_update(table, eta, momentum, lr, eps=0.0, norms_out=None, workspace=Non
         workspace = _ws(raw.lars_update_workspace_bytes(ctypes.byref(d), table.host), table.device)
     _check(raw.lars_update(ctypes.byref(d), table.host, _ptr(table.dev), _ptr(norms_out), _ptr(workspace),
                            ctypes.c_size_t(workspace.numel()), _stream()))
+    return norms_out
+
+
+def lars_update_noalloc(table, eta, momentum, lr, eps=0.0, norms_out=None):
+    """lars_update without a workspace: the library's built-in scratch array holds the partial norms."""
+    d = LarsDesc(table.T, eta, momentum, lr, eps, table.grad_dtype)
+    _check(raw.lars_update_noalloc(ctypes.byref(d), table.host, _ptr(table.dev), _ptr(norms_out), _stream()))
     return norms_out
 
 

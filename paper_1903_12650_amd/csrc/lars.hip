@@ -9,6 +9,8 @@
 // HBM traffic per parameter: 8 B (norm pass: w, g) + 20 B (update: w, g, v read,
 // w, v written) + 2 B for the bf16 model copy.  The second read of w and g can
 // be served by the 256 MB last-level cache when the model fits.
+#include <mutex>
+
 #include "common.h"
 #include "step_internal.h"
 
@@ -241,21 +243,9 @@ extern "C" size_t lars_update_workspace_bytes(const rn50_lars_desc* d,
   return align_up(static_cast<size_t>(total_chunks(d, table_host)) * 2 * sizeof(float), 256);
 }
 
-extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
-                           const rn50_lars_tensor* table_dev, float* norms_out, void* workspace,
-                           size_t workspace_bytes, void* stream) {
-  clear_error();
-  if (int rc = check_table(d, table_host)) return rc;
-  RN50_REQUIRE(table_dev && workspace, RN50_ERR_INVALID, "lars_update: null device table or workspace");
-  RN50_REQUIRE(aligned16(table_dev) && aligned16(workspace), RN50_ERR_ALIGN,
-               "lars_update: table_dev / workspace not 16-byte aligned");
-  RN50_REQUIRE(workspace_bytes >= lars_update_workspace_bytes(d, table_host), RN50_ERR_WORKSPACE,
-               "lars_update: workspace %zu < %zu bytes", workspace_bytes,
-               lars_update_workspace_bytes(d, table_host));
-  RN50_REQUIRE(total_chunks(d, table_host) < (1ll << 30), RN50_ERR_UNSUPPORTED,
-               "lars_update: too many elements");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  float* partial = static_cast<float*>(workspace);
+// Both entry points below: the two launches per group of at most kLarsMaxTensors tensors.
+static void run_table(const rn50_lars_desc* d, const rn50_lars_tensor* table_host, const rn50_lars_tensor* table_dev,
+                      float* norms_out, float* partial, hipStream_t s) {
   for (int t0 = 0; t0 < d->num_tensors; t0 += kLarsMaxTensors) {
     LarsArgs a;
     a.num = d->num_tensors - t0 < kLarsMaxTensors ? d->num_tensors - t0 : kLarsMaxTensors;
@@ -278,5 +268,72 @@ extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* tabl
     }
     partial += 2 * static_cast<size_t>(grid);
   }
+}
+
+extern "C" int lars_update(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
+                           const rn50_lars_tensor* table_dev, float* norms_out, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_table(d, table_host)) return rc;
+  RN50_REQUIRE(table_dev && workspace, RN50_ERR_INVALID, "lars_update: null device table or workspace");
+  RN50_REQUIRE(aligned16(table_dev) && aligned16(workspace), RN50_ERR_ALIGN,
+               "lars_update: table_dev / workspace not 16-byte aligned");
+  RN50_REQUIRE(workspace_bytes >= lars_update_workspace_bytes(d, table_host), RN50_ERR_WORKSPACE,
+               "lars_update: workspace %zu < %zu bytes", workspace_bytes,
+               lars_update_workspace_bytes(d, table_host));
+  RN50_REQUIRE(total_chunks(d, table_host) < (1ll << 30), RN50_ERR_UNSUPPORTED,
+               "lars_update: too many elements");
+  run_table(d, table_host, table_dev, norms_out, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
   return launch_status("lars_update");
+}
+
+// ---- lars_update for callers that cannot allocate: the partial norms live in a device array of the
+// library itself.  Every GPU holds its own copy of the array at its own address; the address is looked
+// up once per device (with that device current) and kept.
+constexpr int kLarsStaticChunks = 32768;  // 8192-element chunks: 268 M elements, 256 KB of partial sums
+static __device__ __align__(256) float lars_static_scratch[2 * kLarsStaticChunks];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_lock;
+static float* scratch_ptr[kMaxDevices];  // device address of lars_static_scratch on device i, once known
+
+// Device address of the scratch array on the current device (null + error text on failure).
+static float* static_scratch_for_current_device() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(RN50_ERR_HIP, "lars_update_noalloc: hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> hold(scratch_lock);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(lars_static_scratch));
+    if (e != hipSuccess || !p) {
+      fail(RN50_ERR_HIP, "lars_update_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  return scratch_ptr[dev];
+}
+
+extern "C" int64_t lars_update_noalloc_max_chunks(void) { return kLarsStaticChunks; }
+
+extern "C" int lars_update_noalloc(const rn50_lars_desc* d, const rn50_lars_tensor* table_host,
+                                   const rn50_lars_tensor* table_dev, float* norms_out, void* stream) {
+  clear_error();
+  if (int rc = check_table(d, table_host)) return rc;
+  RN50_REQUIRE(table_dev, RN50_ERR_INVALID, "lars_update_noalloc: null device table");
+  RN50_REQUIRE(aligned16(table_dev), RN50_ERR_ALIGN, "lars_update_noalloc: table_dev not 16-byte aligned");
+  const int64_t chunks = total_chunks(d, table_host);
+  RN50_REQUIRE(chunks <= kLarsStaticChunks, RN50_ERR_WORKSPACE,
+               "lars_update_noalloc: the table needs %lld chunks of %d elements, the built-in scratch holds %d "
+               "(use lars_update with a workspace)", (long long)chunks, kLarsChunk, kLarsStaticChunks);
+  float* partial = static_scratch_for_current_device();
+  if (!partial) return RN50_ERR_HIP;
+  // Every partial sum the second launch reads is written by the first launch of the same call, so
+  // nothing of an earlier call's contents is ever read and nothing needs clearing.
+  run_table(d, table_host, table_dev, norms_out, partial, static_cast<hipStream_t>(stream));
+  return launch_status("lars_update_noalloc");
 }
