@@ -21,6 +21,12 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp")))
 
 
+# Tuning builds (RN50_TUNING=1 in the environment of this script) compile in the environment-variable overrides of
+# tile shapes that the sweeps use; the product build has none.
+if os.environ.get("RN50_TUNING") == "1":
+    FLAGS.append("-DRN50_TUNING")
+
+
 def _compile(src, force):
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
     deps = [src] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]

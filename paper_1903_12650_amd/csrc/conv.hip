@@ -102,7 +102,6 @@ struct IgemmArgs {
   const uint8_t* addend_mask;
 };
 
-constexpr int kPitch = 144;  // LDS row pitch of a 128-byte K chunk (conflict-free 16-byte reads)
 constexpr uint32_t kOob = 0x80000000u;  // buffer offset beyond every tensor: the load returns zeros
 
 // Raw buffer descriptor over a tensor: loads whose offset is >= bytes return 0, which is how padding,
@@ -115,6 +114,39 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
   const v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, static_cast<int>(voffset), static_cast<int>(soffset), 0);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+// The same load with LDS as its destination (buffer_load_dwordx4 ... lds): lane l of the wave writes its 16
+// bytes to LDS address lds_addr + 16*l (lds_addr uniform, taken from M0), so one instruction fills 1 KB; lanes
+// whose offset is out of range write zeros.  Nothing passes through registers; the transfer is counted by
+// vmcnt like any other vector-memory load.  Written as assembly on purpose: the compiler would make every
+// later LDS read wait for ALL outstanding loads of this kind (it cannot tell the ring buffers apart), which
+// is the prefetch distance this kernel lives on; the waits are placed by hand (wait_loads_then_barrier).
+typedef int rsrc_words __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_words make_rsrc_words(const void* p, uint32_t bytes) {
+  const uint64_t addr = reinterpret_cast<uint64_t>(p);
+  rsrc_words r;
+  r.x = static_cast<int>(addr);
+  r.y = static_cast<int>((addr >> 32) & 0xffffu);  // stride 0: a raw buffer
+  r.z = static_cast<int>(bytes);
+  r.w = 0x00020000;
+  return r;
+}
+__device__ __forceinline__ void buffer_load16_to_lds(rsrc_words r, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(r), "s"(soffset)
+               : "memory");  // (m0 is reserved: the compiler keeps nothing in it across statements)
+}
+// Wait until at most N of this wave's vector-memory loads are outstanding, then the workgroup barrier, without
+// the full memory fence of __syncthreads() (which would also wait for the loads of the chunks still in flight).
+template <int N>
+__device__ __forceinline__ void wait_loads_then_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; 7 / 15 = no wait
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 // MODE 0: forward gather  ih = p*stride - pad + r.
 // MODE 1: data-gradient gather  ih = (p + pad - r)/stride when divisible (stride 1 or 2).  With stride 2
@@ -125,26 +157,50 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
 // LIN: compiled for a 1x1 filter with stride 1 and no padding (output row m is pixel m of the gathered
 // tensor): no pixel decode, no tap cursor, no bounds checks -- these layers have the shortest reductions
 // of the network, and a workgroup's instruction count outside the main loop is what bounds them.
+//
+// Tile BM x BN, WM x WN waves (4 or 8), each wave a (BM/WM) x (BN/WN) tile of 32x32 MFMA blocks.  A 128-byte
+// K chunk of the tile is (BM + BN) rows of 128 bytes in LDS, filled by buffer loads that write LDS directly
+// (8 lanes per row, 8 rows per wave instruction) into a ring of three chunk buffers: the loads of chunk k+2 are
+// issued when chunk k starts, one barrier per chunk.  Within a row the eight 16-byte pieces are stored
+// permuted, piece p of row r in slot p ^ ((r >> 1) & 7): the MFMA fragment reads (lane = row, 16 bytes of one
+// piece) then touch every bank once per 16 lanes.  What bounds the main loop per compute unit, measured:
+// 16-byte vector loads deliver ~60 B/clk, 16-byte LDS reads ~220 B/clk, one 32x32x16 MFMA per SIMD every 32
+// clocks.  A 32x32 wave tile reads 2 KB of fragments per MFMA (LDS-bound at half the MFMA rate), a 64x64
+// wave tile 1 KB; a 64x64 workgroup tile loads 16 KB per 128 MFMA-clocks (load-bound at half the MFMA rate),
+// a 128x128 tile 32 KB per 512.  Hence the largest tile that still gives every compute unit work is chosen
+// per layer shape (igemm_tile below).
+// Chunk buffers in the ring: three (loads two chunks ahead), or two where three would leave room for only one
+// four-wave workgroup per compute unit (160 KB of LDS): two workgroups hide each other's barriers and latencies.
+template <int BM, int BN, int NW>
+constexpr int igemm_ring() {
+  return (NW == 4 && 3 * (BM + BN) * 128 > 80 * 1024) ? 2 : 3;
+}
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false>
-__global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
+__global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) {
+  constexpr int NW = WM * WN, NT = 64 * NW;
   constexpr int V = 16 / sizeof(T);
   constexpr int BK = 128 / sizeof(T);
-  constexpr int RA = BM / 32, RB = BN / 32;
+  constexpr int RPL = NT / 8;                   // tile rows covered by one load pass of the workgroup
+  constexpr int RA = BM / RPL, RB = BN / RPL;  // load passes (= load instructions per thread and chunk)
+  constexpr int NL = RA + RB;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int STAGE = (BM + BN) * kPitch;
+  constexpr int STAGE = (BM + BN) * 128;
+  constexpr int NSTAGE = igemm_ring<BM, BN, WM * WN>();
   constexpr int CP = BN * sizeof(T) + 16;  // epilogue pitch
-  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+  static_assert((NW == 4 || NW == 8) && TM >= 1 && TN >= 1 && RA >= 1 && RB >= 1, "tile shape");
+  static_assert(BM % RPL == 0 && BN % RPL == 0, "every load pass covers whole rows of the tile");
   constexpr int CPW = BN * 4 + 16;         // pitch of a float output tile (bf16 data gradient with an addend)
-  static_assert(BM * CP <= 2 * STAGE && BM * CPW <= 2 * STAGE, "epilogue tile must fit in the pipeline buffers");
+  // (the launch sizes the dynamic LDS as the larger of the ring and what the output stage stores in it)
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const int tid = threadIdx.x, piece = tid & 7, lrow = tid >> 3;
+  const int tid = threadIdx.x, slot = tid & 7, lrow = tid >> 3;
+  const int piece = slot ^ ((lrow >> 1) & 7);  // the 16-byte piece of its rows' chunk this thread fetches
   const int wave = tid >> 6, lane = tid & 63;
   const int wm = wave % WM, wn = wave / WM;
   const int bid = xcd_remap(blockIdx.x, gridDim.x);
   const int mt = static_cast<int>(fdiv(static_cast<uint32_t>(bid), a.div_ntn)), nt = bid - mt * a.ntn;
   const int n0 = nt * BN;
-  const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a.act, a.act_bytes), rsB = make_rsrc(a.wgt, a.wgt_bytes);
+  const rsrc_words rsA = make_rsrc_words(a.act, a.act_bytes), rsB = make_rsrc_words(a.wgt, a.wgt_bytes);
 
   // Rows of this tile: pixels m0.. of the whole output grid, or of one parity class of it.
   const bool classes = !LIN && MODE == 1 && a.stride == 2;
@@ -179,7 +235,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   int a_h0[RA], a_w0[RA], a_base[RA];
 #pragma unroll
   for (int i = 0; i < RA; ++i) {
-    const int m = m0 + lrow + 32 * i;
+    const int m = m0 + lrow + RPL * i;
     const bool ok = m < Mc;
     const int mm = ok ? m : 0;
     if (LIN || a.linear) {  // no pixel decode: "image" base mm, coordinates (0, 0)
@@ -194,7 +250,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     int p = t - n * Hc;
     if (classes) {
       p = 2 * p + ph; q = 2 * q + pw;
-      if (piece == 0) pix_s[lrow + 32 * i] = ok ? (n * a.P + p) * a.Q + q : 0;
+      if (slot == 0) pix_s[lrow + RPL * i] = ok ? (n * a.P + p) * a.Q + q : 0;
     }
     a_base[i] = n * a.H * a.W;
     // a row beyond the last gets coordinates that fail every bounds check below
@@ -204,7 +260,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   uint32_t b_row[RB];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
-    const int n = n0 + lrow + 32 * i;
+    const int n = n0 + lrow + RPL * i;
     b_row[i] = n < a.Ncols ? static_cast<uint32_t>(n * a.Ktot + piece * V) * sizeof(T) : kOob;
   }
 
@@ -241,19 +297,21 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       a_off[i] = ok ? static_cast<uint32_t>((a_base[i] + ih * a.W + iw) * a.PS + pc * V) * sizeof(T) : kOob;
     }
   };
-  struct Staged {
-    uint4 a[RA], b[RB];
-  };
-  // Chunks past the last one load zeros (no memory access), so the main loop below needs no conditions:
-  // a branch around a load makes the compiler wait for every outstanding load at the join.
-  auto load_chunk = [&](Staged& st) __attribute__((always_inline)) {
-    const uint32_t so = static_cast<uint32_t>(cur_cc) * 128u;
-    const bool cval = (!ragged || (cur_cc * BK + piece * V < a.Cg)) && cur < nchunks;
+  // One chunk into one ring buffer: every wave fills its 8 rows of each load pass (1 KB per instruction).
+  typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+  const uint32_t wave_dst = __builtin_amdgcn_readfirstlane(
+      static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_ptr)smem)) + static_cast<uint32_t>(wave) * 1024u);
+  auto load_chunk = [&](int stage) __attribute__((always_inline)) {
+    const uint32_t so = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cur_cc) * 128u);
+    const bool cval = !ragged || (cur_cc * BK + piece * V < a.Cg);
     ++cur;
+    const uint32_t sa = wave_dst + static_cast<uint32_t>(stage) * STAGE;
+    const uint32_t sb = sa + BM * 128;
+    const uint32_t sob = __builtin_amdgcn_readfirstlane(b_tap + so);
 #pragma unroll
-    for (int i = 0; i < RA; ++i) st.a[i] = buffer_load16(rsA, cval ? a_off[i] : kOob, so);
+    for (int i = 0; i < RA; ++i) buffer_load16_to_lds(rsA, sa + i * (RPL * 128), cval ? a_off[i] : kOob, so);
 #pragma unroll
-    for (int i = 0; i < RB; ++i) st.b[i] = buffer_load16(rsB, cval ? b_row[i] : kOob, b_tap + so);
+    for (int i = 0; i < RB; ++i) buffer_load16_to_lds(rsB, sb + i * (RPL * 128), cval ? b_row[i] : kOob, sob);
     // advance the cursor
     if constexpr (LIN) {
       ++cur_cc;
@@ -268,14 +326,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
       if (cur < nchunks) tap_setup();  // (nothing is loaded past the last chunk)
     }
   };
-  auto store_chunk = [&](int stage, const Staged& st) __attribute__((always_inline)) {
-    unsigned char* sa = smem + stage * STAGE;
-    unsigned char* sb = sa + BM * kPitch;
-#pragma unroll
-    for (int i = 0; i < RA; ++i) *reinterpret_cast<uint4*>(sa + (lrow + 32 * i) * kPitch + piece * 16) = st.a[i];
-#pragma unroll
-    for (int i = 0; i < RB; ++i) *reinterpret_cast<uint4*>(sb + (lrow + 32 * i) * kPitch + piece * 16) = st.b[i];
-  };
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -285,46 +335,59 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int frag_off = (lane & 31) * kPitch + (lane >> 5) * 16;
+  // Fragment of a 32-row block for k step kk: row = lane % 32, piece 2*kk + lane/32, in its permuted slot
+  // (the block starts at a multiple of 32 rows, so the permutation depends on the lane alone).
+  int frag_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    frag_off[kk] = (lane & 31) * 128 + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+  // The fragment reads run ahead of the MFMAs that use them -- a whole chunk ahead for the small wave tiles
+  // (one MFMA per k step is far shorter than an LDS read's latency), one k step ahead for 64x64 wave tiles --
+  // so a wave pays the LDS latency once per chunk, not once per k step.
+  constexpr int AHEAD = (TM + TN <= 3) ? 4 : 1;  // k steps whose fragments are in registers before the first MFMA
   auto compute = [&](int stage) __attribute__((always_inline)) {
-    const unsigned char* sa = smem + stage * STAGE + wm * (BM / WM) * kPitch + frag_off;
-    const unsigned char* sb = smem + stage * STAGE + BM * kPitch + wn * (BN / WN) * kPitch + frag_off;
+    const unsigned char* sa = smem + stage * STAGE + wm * (BM / WM) * 128;
+    const unsigned char* sb = smem + stage * STAGE + BM * 128 + wn * (BN / WN) * 128;
+    Vec16 fa[4][TM], fb[4][TN];
+    auto read_frags = [&](int kk) __attribute__((always_inline)) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[kk][i].u = *reinterpret_cast<const uint4*>(sa + i * 32 * 128 + frag_off[kk]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[kk][j].u = *reinterpret_cast<const uint4*>(sb + j * 32 * 128 + frag_off[kk]);
+    };
+#pragma unroll
+    for (int kk = 0; kk < AHEAD; ++kk) read_frags(kk);
+    __builtin_amdgcn_sched_barrier(0);  // (the instruction scheduler would sink every read to its first use)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      Vec16 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i].u = *reinterpret_cast<const uint4*>(sa + i * 32 * kPitch + kk * 32);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j].u = *reinterpret_cast<const uint4*>(sb + j * 32 * kPitch + kk * 32);
+      if (kk + AHEAD < 4) {
+        read_frags(kk + AHEAD);
+        __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) Mma<T>::run(fb[j], fa[i], acc[i][j]);  // D'[n][m]
+        for (int j = 0; j < TN; ++j) Mma<T>::run(fb[kk][j], fa[kk][i], acc[i][j]);  // D'[n][m]
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // Two register sets: the loads of chunk k+2 are issued before chunk k is multiplied, so every global
-  // load has a full chunk of MFMA work (plus the other resident workgroups) to land.
-  Staged st0, st1;
+  // Ring of NSTAGE chunk buffers, loads NSTAGE-1 chunks ahead.  At the top of iteration kc this wave waits for
+  // its own loads of chunk kc (those of the later chunks may still be in flight), then the barrier: behind it
+  // every wave's part of chunk kc is in LDS and every wave is done reading chunk kc-1, whose buffer the loads
+  // of chunk kc+NSTAGE-1 issued next will overwrite.
   tap_setup();
-  load_chunk(st0);
-  load_chunk(st1);
-  store_chunk(0, st0);
-  __syncthreads();
-  int kc = 0;
-  for (; kc + 2 <= nchunks; kc += 2) {
-    load_chunk(st0);      // chunk kc+2
-    compute(0);           // chunk kc
-    store_chunk(1, st1);  // chunk kc+1
-    __syncthreads();
-    load_chunk(st1);      // chunk kc+3
-    compute(1);           // chunk kc+1
-    store_chunk(0, st0);  // chunk kc+2
-    __syncthreads();
+#pragma unroll
+  for (int c = 0; c < NSTAGE - 1; ++c)
+    if (c < nchunks) load_chunk(c);
+  int stage = 0;
+  for (int kc = 0; kc < nchunks; ++kc) {
+    if (NSTAGE == 3 && kc + 1 < nchunks) wait_loads_then_barrier<NL>(); else wait_loads_then_barrier<0>();
+    if (kc + NSTAGE - 1 < nchunks) load_chunk(stage >= 1 ? stage - 1 : NSTAGE - 1);  // buffer (kc - 1) mod NSTAGE
+    compute(stage);
+    stage = stage == NSTAGE - 1 ? 0 : stage + 1;
   }
-  if (kc < nchunks) {  // odd count: the last chunk is already in stage 0
-    compute(0);
-    __syncthreads();   // the output tile below reuses the pipeline buffers
-  }
+  __builtin_amdgcn_s_barrier();  // the output tile below reuses the pipeline buffers
+  asm volatile("" ::: "memory");
 
   // Epilogue.  acc[i][j][v]: output channel n = j*32 + (v/4)*8 + (lane/32)*4 + v%4, pixel m = i*32 + lane%32.
   // The tile goes to LDS in the storage type, or in float when a bf16 data gradient has an addend.
@@ -358,7 +421,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   }
   __syncthreads();
   constexpr int PPR = BN * sizeof(T) / 16;  // 16-byte pieces per output row
-  constexpr int RPP = 256 / PPR;            // rows per pass
+  constexpr int RPP = NT / PPR;             // rows per pass
   constexpr int NPASS = BM / RPP;
   T* out = static_cast<T*>(a.out);
   const int op = tid % PPR, orow = tid / PPR;
@@ -475,7 +538,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
   if (MODE == 0 && tid < BN) kshift = Elem<T>::load(reinterpret_cast<const T*>(smem) + tid);  // row m0 of the tile
   __syncthreads();
   float* cs = reinterpret_cast<float*>(smem);
-  static_assert(RPP * 2 * BN * 4 <= 2 * STAGE, "column sums must fit in the pipeline buffers");
+  static_assert(RPP * 2 * BN * 4 <= BM * CPW, "the column sums fit where the output tile was");
+  static_assert(2 * BN <= NT && NPASS >= 1, "one thread per plane and column");
 #pragma unroll
   for (int j = 0; j < V; j += 4) {
     *reinterpret_cast<float4*>(cs + (orow * 2 + 0) * BN + op * V + j) = make_float4(s1[j], s1[j + 1], s1[j + 2], s1[j + 3]);
@@ -833,18 +897,25 @@ static void allow_big_lds(K kernel, int bytes) {
   if (bytes > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false>
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN>
 static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid, hipStream_t s) {
-  constexpr int stage = (BM + BN) * kPitch;
-  constexpr int lds = 2 * stage;
+  constexpr int NT = 64 * WM * WN;
+  constexpr int stage = (BM + BN) * 128;
+  constexpr int es = static_cast<int>(sizeof(T));
+  // the output stage reuses the ring: the tile (in float when a bf16 data gradient adds a second branch) and
+  // the column sums of the fused batch norm
+  constexpr int out_tile = BM * (BN * 4 + 16);
+  constexpr int col_sums = (NT / (BN * es / 16)) * 2 * BN * 4;
+  constexpr int out_need = out_tile > col_sums ? out_tile : col_sums;
   static std::once_flag once;
-  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>, lds); });
-  // A reduction of a single chunk (the 1x1 layers with 64 channels, the largest pixel counts of the net)
-  // never touches the second pipeline buffer; without it more workgroups fit a CU.  The output stage's
-  // uses of the buffer (tile in float: BM*(4*BN+16) bytes; column sums: at most 16 KB) fit one 64x64 stage.
-  const bool one_chunk = BM == 64 && BN == 64 && a.R * a.S * a.cpt == 1;
-  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>), dim3(static_cast<unsigned>(grid)), dim3(256),
-              one_chunk ? stage : lds, s, a);
+  constexpr int nring = igemm_ring<BM, BN, WM * WN>();
+  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>, nring * stage > out_need ? nring * stage : out_need); });
+  // A short reduction never touches the later ring buffers; without them more workgroups fit a CU (the 1x1
+  // layers with 64 channels, the largest pixel counts of the net, have a single chunk).
+  const int chunks = a.R * a.S * a.cpt;
+  const int ring = (chunks < nring ? (chunks < 1 ? 1 : chunks) : nring) * stage;
+  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>), dim3(static_cast<unsigned>(grid)), dim3(NT),
+              ring > out_need ? ring : out_need, s, a);
 }
 template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
@@ -861,37 +932,60 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
     a.div_w[c] = make_fastdiv(classes ? (a.Q - c + 1) >> 1 : a.Q);
     a.div_h[c] = make_fastdiv(classes ? (a.P - c + 1) >> 1 : a.P);
   }
-  if constexpr (BM == 64 && BN == 64) {
-    if (a.linear) {
-      if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, true>(a, tag, grid, s);
-      else launch_igemm_mode<T, BM, BN, WM, WN, 1, true>(a, tag, grid, s);
-      return;
-    }
+  if (a.linear) {
+    if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, true>(a, tag, grid, s);
+    else launch_igemm_mode<T, BM, BN, WM, WN, 1, true>(a, tag, grid, s);
+    return;
   }
-  if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0>(a, tag, grid, s);
-  else launch_igemm_mode<T, BM, BN, WM, WN, 1>(a, tag, grid, s);
+  if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, false>(a, tag, grid, s);
+  else launch_igemm_mode<T, BM, BN, WM, WN, 1, false>(a, tag, grid, s);
 }
 
-// Tile choice, from per-layer timings of ResNet-50's shapes at batch 40: these kernels are bound by the
-// latency of a workgroup's load -> LDS -> MFMA chain, not by L2 bandwidth, so many small workgroups beat
-// fewer large ones on every layer; the larger tiles stay available through RN50_IGEMM_TILE.
+// Tile per layer shape.  The compiled shapes: rows x columns of the workgroup tile, waves along rows x columns.
 struct TileShape {
-  int bm, bn;
+  int bm, bn, wm, wn;
 };
-static TileShape igemm_tile(int64_t M, int Ncols, bool strided_dgrad) {
-  int fbm = 0, fbn = 0;  // tuning aid: RN50_IGEMM_TILE=bm,bn forces a tile shape
-  if (const char* e = getenv("RN50_IGEMM_TILE")) sscanf(e, "%d,%d", &fbm, &fbn);
-  if ((fbm == 128 || fbm == 64) && (fbn == 128 || fbn == 64)) return TileShape{fbm, fbn};
-  (void)M; (void)Ncols; (void)strided_dgrad;
-  return TileShape{64, 64};
+#define RN50_IGEMM_SHAPES(X) X(64, 64, 2, 2) X(128, 64, 2, 2) X(128, 128, 2, 2) X(256, 128, 4, 2)
+static bool igemm_shape_compiled(const TileShape& t) {
+#define X(BM, BN, WM, WN) if (t.bm == BM && t.bn == BN && t.wm == WM && t.wn == WN) return true;
+  RN50_IGEMM_SHAPES(X)
+#undef X
+  return false;
+}
+// The tile of a layer shape: M rows (output pixels; of one parity class for a stride-2 data gradient, `live` of
+// whose four classes have any taps), Ncols output channels, `chunks` 128-byte steps of the reduction.  The rule
+// is fitted to per-layer sweeps of all compiled shapes over ResNet-50's 23 convolution shapes at batch 40 and at
+// batch 256 (profiles/conv_tile_sweep_*.txt): the largest tile that still leaves about two workgroups per
+// compute unit wins -- larger tiles load fewer operand bytes per flop (the main loop's bound) but a grid that
+// does not give every compute unit at least one and a half workgroups leaves the latencies of a workgroup's load -> LDS -> MFMA chain exposed; a
+// reduction of one or two chunks has nothing to reuse and takes the smallest tile.
+static TileShape igemm_tile(int64_t M, int Ncols, int chunks, bool dgrad, bool strided_dgrad, int live = 4) {
+#ifdef RN50_TUNING  // tuning builds only: RN50_IGEMM_TILE=bm,bn,wm,wn forces a compiled tile shape
+  if (const char* e = getenv("RN50_IGEMM_TILE")) {
+    TileShape f{0, 0, 0, 0};
+    if (sscanf(e, "%d,%d,%d,%d", &f.bm, &f.bn, &f.wm, &f.wn) == 4 && igemm_shape_compiled(f)) return f;
+  }
+#endif
+  const int64_t classes = strided_dgrad ? live : 1;
+  auto groups = [&](int bm, int bn) { return ceil_div(M, bm) * ceil_div(Ncols, bn) * classes; };
+  constexpr int64_t kCover = 384;  // workgroups: one and a half per compute unit (two four-wave workgroups fit each)
+  if (chunks <= 1) return TileShape{64, 64, 2, 2};
+  if (Ncols > 64) {
+    // (the eight-wave tile pays off in the data gradients of the largest layers only)
+    if (dgrad && chunks >= 2 && groups(256, 128) >= 4 * kCover) return TileShape{256, 128, 4, 2};
+    if (groups(128, 128) >= kCover) return TileShape{128, 128, 2, 2};
+  }
+  if (chunks >= 8 && groups(128, 64) >= kCover) return TileShape{128, 64, 2, 2};
+  return TileShape{64, 64, 2, 2};
 }
 template <typename T>
 static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
-  const TileShape t = igemm_tile(a.M, a.Ncols, a.mode == 1 && a.stride == 2);
-  if (t.bm == 128 && t.bn == 128) return launch_igemm_cfg<T, 128, 128, 2, 2>(a, tag, s);
-  if (t.bm == 128) return launch_igemm_cfg<T, 128, 64, 2, 2>(a, tag, s);
-  if (t.bn == 128) return launch_igemm_cfg<T, 64, 128, 2, 2>(a, tag, s);
-  return launch_igemm_cfg<T, 64, 64, 2, 2>(a, tag, s);
+  const bool classes = a.mode == 1 && a.stride == 2;
+  const int64_t rows = classes ? static_cast<int64_t>(a.M / (a.P * a.Q)) * ((a.P + 1) / 2) * ((a.Q + 1) / 2) : a.M;
+  const TileShape t = igemm_tile(rows, a.Ncols, a.R * a.S * a.cpt, a.mode == 1, classes, a.R * a.S > 1 ? 4 : 1);
+#define X(BM, BN, WM, WN) if (t.bm == BM && t.bn == BN && t.wm == WM && t.wn == WN) return launch_igemm_cfg<T, BM, BN, WM, WN>(a, tag, s);
+  RN50_IGEMM_SHAPES(X)
+#undef X
 }
 
 struct WgradPlan {
@@ -1036,19 +1130,19 @@ void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_
 size_t stem_padded_input_bytes(const rn50_conv_desc* d) { return stem_geom(d).xp_bytes; }
 size_t stem_padded_weight_bytes(const rn50_conv_desc* d) { return stem_geom(d).wp_bytes; }
 
-static PartialRows tile_rows(int64_t M, int Ncols, bool strided_dgrad) {
-  const int bm = igemm_tile(M, Ncols, strided_dgrad).bm;
-  return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
-}
+static int chunks_per_tap(int channels, int dtype) { return static_cast<int>(ceil_div(channels * esize(dtype), 128)); }
 // stride-2 data gradient: four parity classes of ceil(N * ceil(H/2) * ceil(W/2) / bm) row tiles each
 static PartialRows class_tile_rows(const rn50_conv_desc* d) {
-  const int bm = igemm_tile(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin, true).bm;
-  const int64_t per_class = ceil_div(static_cast<int64_t>(d->N) * ((d->H + 1) / 2) * ((d->W + 1) / 2), bm);
-  return PartialRows{bm, static_cast<int>(4 * per_class)};
+  const int64_t rows = static_cast<int64_t>(d->N) * ((d->H + 1) / 2) * ((d->W + 1) / 2);
+  const int bm = igemm_tile(rows, d->Cin, d->R * d->S * chunks_per_tap(d->Cout, d->dtype), true, true, d->R * d->S > 1 ? 4 : 1).bm;
+  return PartialRows{bm, static_cast<int>(4 * ceil_div(rows, bm))};
 }
 PartialRows fwd_partial_rows(const rn50_conv_desc* d) {
   const int64_t M = static_cast<int64_t>(d->N) * out_dim(d->H, d->pad, d->R, d->stride) * out_dim(d->W, d->pad, d->S, d->stride);
-  return tile_rows(M, d->Cout, false);
+  // the chunk count as the launch computes it (the bf16 stem runs as 4 taps of one chunk, the float stem as 7)
+  const int chunks = is_stem(d) ? (d->dtype == RN50_BF16 ? 4 : 7) : d->R * d->S * chunks_per_tap(d->Cin, d->dtype);
+  const int bm = igemm_tile(M, d->Cout, chunks, false, false).bm;
+  return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
 }
 int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d) {
   const int64_t plain = ceil_div(static_cast<int64_t>(d->N) * d->H * d->W, 64);
@@ -1057,7 +1151,9 @@ int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d) {
 }
 PartialRows dgrad_partial_rows(const rn50_conv_desc* d) {
   if (d->stride == 2) return class_tile_rows(d);
-  return tile_rows(static_cast<int64_t>(d->N) * d->H * d->W, d->Cin, false);
+  const int64_t M = static_cast<int64_t>(d->N) * d->H * d->W;
+  const int bm = igemm_tile(M, d->Cin, d->R * d->S * chunks_per_tap(d->Cout, d->dtype), true, false).bm;
+  return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
 }
 
 static IgemmArgs stem_igemm_args(const rn50_conv_desc* d, const void* xp, const void* wp, void* y) {

@@ -1,11 +1,15 @@
 """Per-shape timing of the convolution entry points on the 23 distinct convolution shapes of ResNet-50
 v1.5 (forward, data gradient, weight gradient), each against its own roofline.
 
-  python -m paper_1903_12650_amd.layer_bench [--batch 40] [--dtype bf16|f32] [--iters 6]
+  python -m paper_1903_12650_amd.layer_bench [--batch 40] [--dtype bf16|f32] [--iters 6] [--passes fwd,dgrad,wgrad]
+                                             [--cold]
 
 For every shape: the bound max(flops / MFMA peak, algorithmic bytes / HBM peak) in microseconds, then per
-pass the launch duration (the library's dispatch timestamps, warm caches, buffers reused) and bound /
-duration.  Bytes are the minimum traffic of the pass (x, y, w once; a 1x1 stride-2 convolution is only
+pass the launch duration (the library's dispatch timestamps) and bound / duration.  By default the buffers are
+reused from iteration to iteration (warm caches: at batch 40 most operands stay in the 256 MB last-level cache);
+with --cold every iteration works on its own copy of the tensors, enough copies that a pass has written and read
+more than 512 MB before a copy comes round again, so every operand comes from HBM: the figure to hold against
+the HBM bound.  Bytes are the minimum traffic of the pass (x, y, w once; a 1x1 stride-2 convolution is only
 charged the quarter of x it needs); the weight gradient is timed with its split-K reduction.  Needs a GPU
 and the built library; reads nothing but its arguments.
 """
@@ -26,7 +30,10 @@ def main():
     ap.add_argument("--batch", type=int, default=40)
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--iters", type=int, default=6)
+    ap.add_argument("--passes", default="fwd,dgrad,wgrad")
+    ap.add_argument("--cold", action="store_true")
     args = ap.parse_args()
+    passes = set(args.passes.split(","))
     import torch
     import paper_1903_12650_amd as rn
 
@@ -36,32 +43,37 @@ def main():
     peak = MFMA_BF16_PEAK if bf else MFMA_F32_PEAK
     N = args.batch
 
-    def timed(tags, f):
-        """Sum of the durations (us) of the launches with these tags in one call of f."""
-        for _ in range(2):
-            f()
+    def timed(tags, f, copies):
+        """Sum of the durations (us) of the launches with these tags in one call of f(copy index)."""
+        for i in range(2):
+            f(i % copies)
         torch.cuda.synchronize()
         total = 0.0
         for tag in tags:
             rn.profile_begin(tag, 64 * args.iters)
-            for _ in range(args.iters):
-                f()
+            for i in range(args.iters):
+                f((i + 2) % copies)
             torch.cuda.synchronize()
             total += sum(rn.profile_end()) / args.iters * 1e3
         return total
 
-    print("batch %d, %s; microseconds; %% = roofline bound / measured" % (N, args.dtype))
+    print("batch %d, %s, %s; microseconds; %% = roofline bound / measured"
+          % (N, args.dtype, "cold (rotating tensor copies, > 512 MB between reuses)" if args.cold else "warm caches"))
     print("%-26s %3s %9s | %8s %5s | %8s %5s | %8s %5s" % ("shape", "x", "bound", "fwd", "%", "dgrad", "%", "wgrad", "%"))
     tot = dict(bound=0.0, fwd=0.0, dgrad=0.0, wgrad=0.0, flops=0.0)
     for (C, K, R, st, H, cnt) in SHAPES:
         pad = R // 2
         P = (H + 2 * pad - R) // st + 1
-        x = torch.randn(N, H, H, C, device="cuda").to(tdt)
-        w = (torch.randn(K, R, R, C, device="cuda") * 0.05).to(tdt)
-        dy = torch.randn(N, P, P, K, device="cuda").to(tdt)
-        y = torch.empty_like(dy)
-        dx = torch.empty_like(x)
-        dw = torch.empty(K, R, R, C, device="cuda")
+        per_copy = es * (N * H * H * C + N * P * P * K + K * R * R * C)
+        copies = max(2, -(-(512 << 20) // per_copy)) if args.cold else 1
+        copies = min(copies, args.iters + 2)
+        xs = [torch.randn(N, H, H, C, device="cuda").to(tdt) for _ in range(copies)]
+        ws_ = [(torch.randn(K, R, R, C, device="cuda") * 0.05).to(tdt) for _ in range(copies)]
+        dys = [torch.randn(N, P, P, K, device="cuda").to(tdt) for _ in range(copies)]
+        ys = [torch.empty_like(t) for t in dys]
+        dxs = [torch.empty_like(t) for t in xs]
+        dws = [torch.empty(K, R, R, C, device="cuda") for _ in range(copies)]
+        x, w, dy = xs[0], ws_[0], dys[0]
         d = rn.ConvDesc(N, H, H, C, K, R, R, st, pad, rn.BF16 if bf else rn.F32)
         need = max(rn.conv_fwd_workspace_bytes(d), rn.conv_dgrad_workspace_bytes(d) if C != 3 else 0,
                    rn.conv_wgrad_workspace_bytes(d), 256)
@@ -69,16 +81,23 @@ def main():
         flops = 2.0 * N * P * P * K * R * R * C
         x_bytes = x.numel() / (4 if (R == 1 and st == 2) else 1)
         bound = max(flops / peak, es * (x_bytes + dy.numel() + w.numel()) / HBM_PEAK) * 1e6
-        t_f = timed(["conv_fwd"], lambda: rn.conv_fwd(x, w, st, pad, y=y, workspace=ws))
-        t_d = timed(["conv_dgrad"], lambda: rn.conv_dgrad(dy, w, x.shape, st, pad, dx=dx, workspace=ws)) if C != 3 else 0.0
-        t_w = timed(["conv_wgrad", "splitk_reduce"], lambda: rn.conv_wgrad(x, dy, w.shape, st, pad, dw=dw, workspace=ws))
+        t_f = t_d = t_w = 0.0
+        if "fwd" in passes:
+            t_f = timed(["conv_fwd"], lambda i: rn.conv_fwd(xs[i], ws_[i], st, pad, y=ys[i], workspace=ws), copies)
+        if "dgrad" in passes and C != 3:
+            t_d = timed(["conv_dgrad"], lambda i: rn.conv_dgrad(dys[i], ws_[i], x.shape, st, pad, dx=dxs[i], workspace=ws),
+                        copies)
+        if "wgrad" in passes:
+            t_w = timed(["conv_wgrad", "splitk_reduce"],
+                        lambda i: rn.conv_wgrad(xs[i], dys[i], w.shape, st, pad, dw=dws[i], workspace=ws), copies)
         pct = lambda t: 100.0 * bound / t if t else 0.0
         print("%4d->%4d %dx%d/%d @%3d      x%d %9.1f | %8.1f %4.0f%% | %8.1f %4.0f%% | %8.1f %4.0f%%"
               % (C, K, R, R, st, H, cnt, bound, t_f, pct(t_f), t_d, pct(t_d), t_w, pct(t_w)))
         tot["bound"] += bound * cnt; tot["fwd"] += t_f * cnt; tot["dgrad"] += t_d * cnt; tot["wgrad"] += t_w * cnt
         tot["flops"] += flops * cnt
     print("whole network, one pass each: bound %.0f us; forward %.0f us (%.0f TFLOP/s), data gradient %.0f us, "
-          "weight gradient %.0f us" % (tot["bound"], tot["fwd"], tot["flops"] / tot["fwd"] / 1e6, tot["dgrad"], tot["wgrad"]))
+          "weight gradient %.0f us" % (tot["bound"], tot["fwd"], tot["flops"] / max(tot["fwd"], 1e-9) / 1e6, tot["dgrad"],
+                                       tot["wgrad"]))
 
 
 if __name__ == "__main__":
