@@ -580,49 +580,78 @@ template <typename T> struct WgradCfg;
 template <> struct WgradCfg<uint16_t> { static constexpr int BKM = 64; };
 template <> struct WgradCfg<float> { static constexpr int BKM = 32; };
 
-// Fragment of a [k][col] LDS tile for the MFMA operand "32 columns x 16 (8 for float) k".
-template <typename T>
-__device__ __forceinline__ Vec16 load_frag_kmajor(const unsigned char* tile, int pitch, int col0, int k0, int lane);
-template <>
-__device__ __forceinline__ Vec16 load_frag_kmajor<uint16_t>(const unsigned char* tile, int pitch, int col0, int k0, int lane) {
-  // ds_read_b64_tr_b16: within 16 lanes, lane t supplies the address of row t/4, columns 4*(t%4)..+3 and
-  // receives column t of rows 0..3.  Two reads give 8 k values of column lane%32.
-  const int g = lane >> 4, t = lane & 15;
-  const int krow = k0 + 8 * (g >> 1) + (t >> 2);
-  const int col = col0 + 16 * (g & 1) + 4 * (t & 3);
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-  const unsigned char* p0 = tile + krow * pitch + col * 2;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * pitch));
+// LDS tiles of the weight gradient are [k row][column] with rows of RBY = 16 * (columns per 16 bytes ...) bytes,
+// filled by LDS-destination loads (RBY/16 lanes per row).  The 16-byte slots of a row are stored permuted,
+// slot s of row r at s ^ wgrad_swz(r), so that the fragment reads below touch every bank once:
+//   bf16, 128-byte rows: a transposing read's 32 lanes take 64 bytes of 4 consecutive rows -- rows two apart
+//                        share their banks, so they swap halves;
+//   bf16, 256-byte rows: the same 4 rows all start at bank 0 -- each is rotated by a different 64 bytes;
+//   float:               lanes 32-63 read the row 4 below lanes 0-31 -- it is shifted by 128 bytes.
+template <typename T, int RBY>
+__device__ __forceinline__ int wgrad_swz(int row) {
+  if (sizeof(T) == 4) return ((row >> 2) & 1) << 3;
+  return RBY == 128 ? ((row >> 1) & 1) << 2 : (row & 3) << 2;
+}
+// Byte offset, inside a tile, of this lane's first read for the MFMA operand "32 columns from col0 x one k step"
+// at k step 0; step kk is KSTEP * kk rows further down.
+template <typename T, int RBY>
+__device__ __forceinline__ int wgrad_frag_base(int lane, int col0) {
+  if (sizeof(T) == 2) {
+    // ds_read_b64_tr_b16: within 16 lanes, lane t supplies the address of row t/4, columns 4*(t%4)..+3 and
+    // receives column t of rows 0..3.  Two reads (rows +0 and +4) give 8 k values of column lane%32.
+    const int g = lane >> 4, t = lane & 15;
+    const int krow = 8 * (g >> 1) + (t >> 2);
+    const int cb = 2 * (col0 + 16 * (g & 1) + 4 * (t & 3));
+    return krow * RBY + (((cb >> 4) ^ wgrad_swz<T, RBY>(krow)) << 4) + (cb & 15);
+  }
+  const int krow = (lane >> 5) * 4;  // + j, j = 0..3: the permutation only looks at bit 2
+  const int cb = 4 * (col0 + (lane & 31));
+  return krow * RBY + (((cb >> 4) ^ wgrad_swz<T, RBY>(krow)) << 4) + (cb & 15);
+}
+template <typename T, int RBY>
+__device__ __forceinline__ Vec16 wgrad_read_frag(const unsigned char* tile, int base, int kk) {
   Vec16 v;
+  if constexpr (sizeof(T) == 2) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const unsigned char* p0 = tile + base + kk * 16 * RBY;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * RBY));
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    v.h[j] = static_cast<uint16_t>(lo[j]);
-    v.h[4 + j] = static_cast<uint16_t>(hi[j]);
+    for (int j = 0; j < 4; ++j) {
+      v.h[j] = static_cast<uint16_t>(lo[j]);
+      v.h[4 + j] = static_cast<uint16_t>(hi[j]);
+    }
+  } else {
+    const unsigned char* p = tile + base + kk * 8 * RBY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v.f[j] = *reinterpret_cast<const float*>(p + j * RBY);
   }
   return v;
 }
-template <>
-__device__ __forceinline__ Vec16 load_frag_kmajor<float>(const unsigned char* tile, int pitch, int col0, int k0, int lane) {
-  Vec16 v;
-  const unsigned char* p = tile + (k0 + (lane >> 5) * 4) * pitch + (col0 + (lane & 31)) * 4;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) v.f[j] = *reinterpret_cast<const float*>(p + j * pitch);
-  return v;
+
+// Ring depth as in the forward kernel: three chunk buffers, two where three would leave one workgroup per CU.
+template <int STAGE>
+constexpr int wgrad_ring() {
+  return 3 * STAGE > 80 * 1024 ? 2 : 3;
 }
 
+// One workgroup: the BMO x BC tile (output channels x input channels of one tap) of one split of the pixel
+// range.  2 x 2 waves; per 64-row (32 in float) chunk of pixels the dy and x rows go straight into LDS
+// (a ring of chunk buffers, one barrier per chunk, as in igemm_kernel) and are read back transposed.
 template <typename T, int BMO, int BC>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   constexpr int V = 16 / sizeof(T);
   constexpr int BKM = WgradCfg<T>::BKM;
   constexpr int KSTEP = sizeof(T) == 2 ? 16 : 8;
-  constexpr int PA = BMO * sizeof(T) + 64, PB = BC * sizeof(T) + 64;  // LDS pitches
-  constexpr int PPRA = BMO / V, PPRB = BC / V;                        // 16-byte pieces per row
-  constexpr int NA = BKM * PPRA / 256, NB = BKM * PPRB / 256;         // pieces per thread
-  constexpr int STAGE = BKM * (PA + PB);
+  constexpr int RA = BMO * sizeof(T), RB = BC * sizeof(T);  // row bytes of the two tiles
+  constexpr int LA = RA / 16, LB = RB / 16;                  // lanes (16-byte pieces) per row
+  constexpr int NA = BKM * LA / 256, NB = BKM * LB / 256;    // load instructions per thread and chunk
+  constexpr int NL = NA + NB;
+  constexpr int STAGE = BKM * (RA + RB);
+  constexpr int NSTAGE = wgrad_ring<STAGE>();
   constexpr int TM = BMO / 64, TN = BC / 64;  // 2x2 waves
-  static_assert(NA >= 1 && NB >= 1, "tile too small");
+  static_assert(NA >= 1 && NB >= 1 && 256 % LA == 0 && 256 % LB == 0, "tile shape");
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -638,41 +667,44 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   const int ko0 = ko_tile * BMO;
   const int row_begin = split * a.rows_per_split;
   const int row_end = min(row_begin + a.rows_per_split, a.M);
-  const __amdgpu_buffer_rsrc_t rsX = make_rsrc(a.x, a.x_bytes), rsD = make_rsrc(a.dy, a.dy_bytes);
+  const rsrc_words rsX = make_rsrc_words(a.x, a.x_bytes), rsD = make_rsrc_words(a.dy, a.dy_bytes);
 
-  const int pa = tid % PPRA, rowa = tid / PPRA;
-  const int pb = tid % PPRB, rowb = tid / PPRB;
+  // this thread's rows of a chunk and the 16-byte piece of them it fetches (the slot's permuted partner)
+  const int rowa = tid / LA, rowb = tid / LB;
+  const int pa = (tid % LA) ^ wgrad_swz<T, RA>(rowa), pb = (tid % LB) ^ wgrad_swz<T, RB>(rowb);
   const bool a_col_ok = ko0 + pa * V < a.Cout;
   const bool b_col_ok = c0 + pb * V < a.Cg;
   // byte offsets of this thread's first rows at m = row_begin; later chunks add a scalar offset
   uint32_t a_off[NA], b_off[NB];
 #pragma unroll
   for (int i = 0; i < NA; ++i)
-    a_off[i] = a_col_ok ? static_cast<uint32_t>((row_begin + rowa + i * (256 / PPRA)) * a.Cout + ko0 + pa * V) * sizeof(T) : kOob;
+    a_off[i] = a_col_ok ? static_cast<uint32_t>((row_begin + rowa + i * (256 / LA)) * a.Cout + ko0 + pa * V) * sizeof(T) : kOob;
 #pragma unroll
   for (int i = 0; i < NB; ++i)
-    b_off[i] = b_col_ok ? static_cast<uint32_t>((row_begin + rowb + i * (256 / PPRB)) * a.PS + c0 + pb * V) * sizeof(T) : kOob;
+    b_off[i] = b_col_ok ? static_cast<uint32_t>((row_begin + rowb + i * (256 / LB)) * a.PS + c0 + pb * V) * sizeof(T) : kOob;
 
-  struct Staged {  // two register sets, unconditional zero-filling buffer loads (see igemm_kernel)
-    uint4 a[NA], b[NB];
-  };
+  typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+  const uint32_t wave_dst = __builtin_amdgcn_readfirstlane(
+      static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_ptr)smem)) + static_cast<uint32_t>(wave) * 1024u);
   int cur = 0;  // chunk index of the load cursor
-  auto load_chunk = [&](Staged& st) __attribute__((always_inline)) {
+  // Rows past row_end load zeros (no memory access): the last chunk of a split needs no special case.
+  auto load_chunk = [&](int stage) __attribute__((always_inline)) {
     const int m_base = row_begin + cur * BKM;
     const int left = row_end - m_base;  // rows of this chunk that belong to the split
-    const uint32_t soA = static_cast<uint32_t>(cur) * static_cast<uint32_t>(BKM * a.Cout) * sizeof(T);
+    const uint32_t sa = wave_dst + static_cast<uint32_t>(stage) * STAGE, sb = sa + BKM * RA;
+    const uint32_t soA = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cur) * static_cast<uint32_t>(BKM * a.Cout) * sizeof(T));
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-      st.a[i] = buffer_load16(rsD, (rowa + i * (256 / PPRA) < left) ? a_off[i] : kOob, soA);
+      buffer_load16_to_lds(rsD, sa + i * 4096, (rowa + i * (256 / LA) < left) ? a_off[i] : kOob, soA);
     if (a.linear) {
-      const uint32_t soB = static_cast<uint32_t>(cur) * static_cast<uint32_t>(BKM * a.PS) * sizeof(T);
+      const uint32_t soB = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cur) * static_cast<uint32_t>(BKM * a.PS) * sizeof(T));
 #pragma unroll
       for (int i = 0; i < NB; ++i)
-        st.b[i] = buffer_load16(rsX, (rowb + i * (256 / PPRB) < left) ? b_off[i] : kOob, soB);
+        buffer_load16_to_lds(rsX, sb + i * 4096, (rowb + i * (256 / LB) < left) ? b_off[i] : kOob, soB);
     } else {
 #pragma unroll
       for (int i = 0; i < NB; ++i) {
-        const int lr = rowb + i * (256 / PPRB);
+        const int lr = rowb + i * (256 / LB);
         bool ok = b_col_ok && lr < left;
         const uint32_t mm = ok ? static_cast<uint32_t>(m_base + lr) : 0u;
         const uint32_t t = fdiv(mm, a.divQ);
@@ -684,18 +716,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
              static_cast<unsigned>(iw) < static_cast<unsigned>(a.W);
         const int pcol = a.pair ? (pb & 3) * V : c0 + pb * V;
         const uint32_t off = static_cast<uint32_t>(((static_cast<int>(n) * a.H + ih) * a.W + iw) * a.PS + pcol) * sizeof(T);
-        st.b[i] = buffer_load16(rsX, ok ? off : kOob, 0);
+        buffer_load16_to_lds(rsX, sb + i * 4096, ok ? off : kOob, 0u);
       }
     }
     ++cur;
-  };
-  auto store_chunk = [&](int stage, const Staged& st) __attribute__((always_inline)) {
-    unsigned char* sa = smem + stage * STAGE;
-    unsigned char* sb = sa + BKM * PA;
-#pragma unroll
-    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(sa + (rowa + i * (256 / PPRA)) * PA + pa * 16) = st.a[i];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(sb + (rowb + i * (256 / PPRB)) * PB + pb * 16) = st.b[i];
   };
 
   f32x16 acc[TM][TN];
@@ -706,41 +730,50 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  int fa_base[TM], fb_base[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) fa_base[i] = wgrad_frag_base<T, RA>(lane, wm * (BMO / 2) + i * 32);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) fb_base[j] = BKM * RA + wgrad_frag_base<T, RB>(lane, wn * (BC / 2) + j * 32);
   const int nchunks = (row_end - row_begin + BKM - 1) / BKM;
+  constexpr int KK = BKM / KSTEP;
+  constexpr int AHEAD = (TM + TN <= 3) ? KK : 1;  // k steps whose fragments are read before the first MFMA
   auto compute = [&](int stage) __attribute__((always_inline)) {
-    const unsigned char* sa = smem + stage * STAGE;
-    const unsigned char* sb = sa + BKM * PA;
+    const unsigned char* st = smem + stage * STAGE;
+    Vec16 fa[KK][TM], fb[KK][TN];
+    auto read_frags = [&](int kk) __attribute__((always_inline)) {
 #pragma unroll
-    for (int kk = 0; kk < BKM / KSTEP; ++kk) {
-      Vec16 fa[TM], fb[TN];
+      for (int i = 0; i < TM; ++i) fa[kk][i] = wgrad_read_frag<T, RA>(st, fa_base[i], kk);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = load_frag_kmajor<T>(sa, PA, wm * (BMO / 2) + i * 32, kk * KSTEP, lane);
+      for (int j = 0; j < TN; ++j) fb[kk][j] = wgrad_read_frag<T, RB>(st, fb_base[j], kk);
+    };
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = load_frag_kmajor<T>(sb, PB, wn * (BC / 2) + j * 32, kk * KSTEP, lane);
+    for (int kk = 0; kk < AHEAD; ++kk) read_frags(kk);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + AHEAD < KK) {
+        read_frags(kk + AHEAD);
+        __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) Mma<T>::run(fa[i], fb[j], acc[i][j]);  // D[ko][c]
+        for (int j = 0; j < TN; ++j) Mma<T>::run(fa[kk][i], fb[kk][j], acc[i][j]);  // D[ko][c]
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // Rows past row_end load zeros (no memory access), so the loop needs no conditions (see igemm_kernel).
-  Staged st0, st1;
-  load_chunk(st0);
-  load_chunk(st1);
-  store_chunk(0, st0);
-  __syncthreads();
-  int kc = 0;
-  for (; kc + 2 <= nchunks; kc += 2) {
-    load_chunk(st0);      // chunk kc+2
-    compute(0);           // chunk kc
-    store_chunk(1, st1);  // chunk kc+1
-    __syncthreads();
-    load_chunk(st1);      // chunk kc+3
-    compute(1);           // chunk kc+1
-    store_chunk(0, st0);  // chunk kc+2
-    __syncthreads();
+  // the ring of igemm_kernel: loads NSTAGE-1 chunks ahead, one barrier per chunk
+#pragma unroll
+  for (int c = 0; c < NSTAGE - 1; ++c)
+    if (c < nchunks) load_chunk(c);
+  int stage = 0;
+  for (int kc = 0; kc < nchunks; ++kc) {
+    if (NSTAGE == 3 && kc + 1 < nchunks) wait_loads_then_barrier<NL>(); else wait_loads_then_barrier<0>();
+    if (kc + NSTAGE - 1 < nchunks) load_chunk(stage >= 1 ? stage - 1 : NSTAGE - 1);
+    compute(stage);
+    stage = stage == NSTAGE - 1 ? 0 : stage + 1;
   }
-  if (kc < nchunks) compute(0);  // odd count: the last chunk is already in stage 0
 
   // acc[i][j][v]: ko = i*32 + (v/4)*8 + (lane/32)*4 + v%4, c = j*32 + lane%32
   float* out = a.out + static_cast<int64_t>(split) * a.split_stride;
@@ -991,49 +1024,50 @@ static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
 struct WgradPlan {
   int bmo, bc, ctiles, splits, rows_per_split;
 };
-// Tile shape and number of reduction splits, a rule fitted to per-layer sweeps of ResNet-50's shapes at
-// batch 40.  The kernel is latency-bound per workgroup, so the aim is 2-3 workgroups per CU with at least
-// 8 chunks each; the split partials cost a second launch, which is only worth it while the output tiles
-// alone cannot occupy every CU.  3x3 layers with wide channels take 128x128 tiles (half the operand
-// traffic per flop), everything else 64x64.
+// Tile shape and number of reduction splits.  Inside a training step the weight gradients run beside the
+// backward pass on a stream of their own (nothing waits for them until the update), so what counts is the
+// compute-unit time and the memory traffic they take from the kernels next to them, not their latency alone:
+// the largest tile the channel counts allow (a 64x64 wave tile reads half the LDS bytes per MFMA of a 32x32
+// one, a 128x128 workgroup tile loads half the operand bytes per flop of a 64x64 one), and only as many splits
+// of the pixel range as give about 192 workgroups (384 for very long reductions), each at least 8 chunks
+// long -- every split costs a full-size partial result written and read again by the reduction pass.
+// Measured on the whole step at batch 40 (profiles/wgrad_plan_step_time_batch40.txt): 128 to 256 workgroups
+// are within 1 % of each other, 64 and 576 lose 13 % and 3 %.
 static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype, bool tunable = true) {
   const int bkm = dtype == RN50_BF16 ? 64 : 32;
   WgradPlan best{};
-  auto fill = [&](int bmo, int bc, int64_t want_splits) {
-    const int64_t cap = M / (8 * bkm) > 1 ? M / (8 * bkm) : 1;
+  auto fill = [&](int bmo, int bc, int64_t want_splits, int min_chunks) {
+    const int64_t cap = M / (min_chunks * bkm) > 1 ? M / (min_chunks * bkm) : 1;
     int64_t sp = want_splits < 1 ? 1 : (want_splits > cap ? cap : want_splits);
     const int64_t rps = ceil_div(ceil_div(M, sp), bkm) * bkm;
     best.bmo = bmo; best.bc = bc; best.ctiles = static_cast<int>(ceil_div(Cg, bc));
     best.splits = static_cast<int>(ceil_div(M, rps));
     best.rows_per_split = static_cast<int>(rps);
   };
-  const char* e = tunable ? getenv("RN50_WGRAD_PLAN") : nullptr;
-  if (e) {  // tuning aid: bmo,bc,splits
-    int bmo = 0, bc = 0, sp = 0;
-    if (sscanf(e, "%d,%d,%d", &bmo, &bc, &sp) == 3 && (bmo == 64 || bmo == 128) && (bc == 64 || bc == 128) && sp >= 1) {
-      const int64_t rps = ceil_div(ceil_div(M, sp), bkm) * bkm;
-      best.bmo = bmo; best.bc = bc; best.ctiles = static_cast<int>(ceil_div(Cg, bc));
-      best.splits = static_cast<int>(ceil_div(M, rps));
-      best.rows_per_split = static_cast<int>(rps);
+  int target = M > 200000 ? 384 : 192, min_chunks = 8;
+  int bmo = Cout >= 128 ? 128 : 64, bc = Cg >= 128 ? 128 : 64;
+#ifdef RN50_TUNING  // tuning builds only: RN50_WGRAD_PLAN=bmo,bc,splits or RN50_WGRAD_TARGET=workgroups[,min chunks]
+  if (const char* e = tunable ? getenv("RN50_WGRAD_PLAN") : nullptr) {
+    int fbmo = 0, fbc = 0, sp = 0;
+    if (sscanf(e, "%d,%d,%d", &fbmo, &fbc, &sp) == 3 && (fbmo == 64 || fbmo == 128) && (fbc == 64 || fbc == 128) && sp >= 1) {
+      fill(fbmo, fbc, sp, 1);
       return best;
     }
   }
-  const int64_t tiles64 = static_cast<int64_t>(taps) * ceil_div(Cg, 64) * ceil_div(Cout, 64);
-  if (tiles64 >= 256) {
-    fill(64, 64, 1);
-  } else if (taps >= 9 && Cout >= 128 && Cg >= 128) {
-    const int64_t tiles = static_cast<int64_t>(taps) * ceil_div(Cg, 128) * ceil_div(Cout, 128);
-    fill(128, 128, (432 + tiles / 2) / tiles);
-  } else {
-    fill(64, 64, (576 + tiles64 / 2) / tiles64);
-  }
+  if (const char* e2 = tunable ? getenv("RN50_WGRAD_TARGET") : nullptr) sscanf(e2, "%d,%d", &target, &min_chunks);
+#else
+  (void)tunable;
+#endif
+  const int64_t tiles = static_cast<int64_t>(taps) * ceil_div(Cg, bc) * ceil_div(Cout, bmo);
+  fill(bmo, bc, (target + tiles / 2) / tiles, min_chunks);
   return best;
 }
 
 template <typename T, int BMO, int BC>
 static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   constexpr int BKM = WgradCfg<T>::BKM;
-  constexpr int lds = 2 * BKM * ((BMO + BC) * static_cast<int>(sizeof(T)) + 128);
+  constexpr int stage = BKM * (BMO + BC) * static_cast<int>(sizeof(T));
+  constexpr int lds = wgrad_ring<stage>() * stage;
   static std::once_flag once;
   std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC>, lds); });
   WgradArgs b = a;

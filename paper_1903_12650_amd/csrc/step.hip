@@ -5,6 +5,7 @@
 // appendix log (stem convolution stride 2 / 64 filters / no bias -> BN -> ReLU
 // -> max-pool 112 -> 56, bottleneck blocks) and He et al.; the gradient exchange
 // between workers (Sec. III-C) would sit between backward and the LARS call.
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -493,6 +494,10 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   auto block_end = [&]() {
     (void)hipEventRecord(plan->ev_dy[blk], s);
     (void)hipStreamWaitEvent(side, plan->ev_dy[blk], 0);
+#ifdef RN50_TUNING  // what-if measurement: the step without its weight gradients
+    static const bool skip_wgrad = getenv("RN50_SKIP_WGRAD") != nullptr;
+    if (skip_wgrad) npending = 0;
+#endif
     for (int i = 0; i < npending; ++i)
       wgrad_run(&pending[i].u->conv, pending[i].in, pending[i].dy, G(pending[i].u->iw), ws + plan->wgrad_scratch, side);
     (void)hipEventRecord(plan->ev_wg[blk], side);
