@@ -5,8 +5,9 @@
 Prints ONE JSON line: images/s for whole training steps at batch 40 (one worker's share of the
 paper's 81,920-image minibatch), with inputs, parameters and workspace resident in HBM before
 the timed region, plus
-  "roofline":     achieved vs peak for the step's dominant kernel, from HIP events recorded by the
-                  library around every launch of that kernel inside the timed steps, and
+  "roofline":     achieved vs peak for the step's dominant kernel class (the one with the largest kernel
+                  time, chosen from this run's timings) and for every other class, from HIP events the
+                  library hands to every tagged launch in a sample of the timed steps, and
   "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload,
   "train_loop":   the same step inside the training loop (device-side learning-rate schedule and step
                   counter, BN moving averages, label smoothing), launched eagerly and as replays of one
@@ -33,7 +34,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-train-loop", action="store_true")
-    ap.add_argument("--roofline-kernel", default=None, help="kernel tag to time (default: the dominant one)")
+    ap.add_argument("--sample-every", type=int, default=50,
+                    help="per-launch timing in every n-th timed step (a timed launch costs a few microseconds more)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of known size (the float master arena) before the steps: "
                          "the reference dispatch that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -64,6 +66,49 @@ def build_state(rn, N, dtype):
     return S
 
 
+def cpu_one_thread():
+    """The oracle on one thread for the three small configurations (one bottleneck block in float at batch 2,
+    forward + backward; the LARS update over ResNet-50's 161 tensors; one convolution shape of the sweep, forward,
+    at batch 4): seconds each."""
+    import ctypes
+    import numpy as np
+    import oracle as orc
+    import synth
+    from oracle import net
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        before = gomp.omp_get_max_threads()
+        gomp.omp_set_num_threads(1)
+    except OSError:
+        return {"note": "libgomp not found: no one-thread figure"}
+    try:
+        rec = {"threads": 1}
+        x = synth.activation_nhwc(synth.DEFAULT_SEED, "x", 2, 64, 56, 56)
+        ws = [synth.conv_weight_krsc(synth.DEFAULT_SEED, "w%d" % i, k, c, r, r)
+              for i, (k, c, r) in enumerate(((64, 64, 1), (64, 64, 3), (256, 64, 1), (256, 64, 1)))]
+        t0 = time.perf_counter()
+        y1 = orc.conv_fwd(x, ws[0], 1, 0); y2 = orc.conv_fwd(y1, ws[1], 1, 1); y3 = orc.conv_fwd(y2, ws[2], 1, 0)
+        ys = orc.conv_fwd(x, ws[3], 1, 0)
+        for (a, w, yy, pad) in ((y2, ws[2], y3, 0), (y1, ws[1], y2, 1), (x, ws[0], y1, 0), (x, ws[3], ys, 0)):
+            orc.conv_dgrad(yy, w, a.shape, 1, pad); orc.conv_wgrad(a, yy, w.shape, 1, pad)
+        rec["config1_block_convs_fwd_bwd_batch2_s"] = time.perf_counter() - t0
+        table = net.param_table()
+        params = synth.params_from_table(synth.DEFAULT_SEED, table)
+        grads = synth.grads_from_table(synth.DEFAULT_SEED, table, 1e-3)
+        vel = [np.zeros_like(p) for p in params]
+        t0 = time.perf_counter()
+        orc.lars_update(params, grads, vel, 0.001, 0.9, 1.0, net.lars_hyper(table, 5e-5))
+        rec["config2_lars_161_tensors_s"] = time.perf_counter() - t0
+        x = synth.round_bf16(synth.activation_nhwc(synth.DEFAULT_SEED, "x3", 4, 256, 14, 14))
+        w = synth.round_bf16(synth.conv_weight_krsc(synth.DEFAULT_SEED, "w3", 256, 256, 3, 3))
+        t0 = time.perf_counter()
+        orc.conv_fwd(x, w, 1, 1)
+        rec["config3_conv3x3_256_14x14_fwd_batch4_s"] = time.perf_counter() - t0
+        return rec
+    finally:
+        gomp.omp_set_num_threads(before)
+
+
 def cpu_baseline(batch_sample=40):
     """The oracle's training step (forward, backward, LARS) on a bounded sample: `batch_sample`
     images of the same 224x224 workload, all host cores OpenMP gives it."""
@@ -86,7 +131,8 @@ def cpu_baseline(batch_sample=40):
         cores = min(cores, int(omp))
     return {"value": batch_sample / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
             "sample": f"one full training step (fwd+bwd+LARS) of ResNet-50 on {batch_sample} of the 40 images, "
-                      f"{dt:.1f} s wall"}
+                      f"{dt:.1f} s wall",
+            "one_thread": cpu_one_thread()}
 
 
 def train_loop_record(rn, torch, S, steps, warmup, batch):
@@ -156,32 +202,42 @@ def main():
         torch.cuda.synchronize()
         print("calibration copy: %d bytes read, %d bytes written" % (4 * plan.arena_elems, 4 * plan.arena_elems),
               file=sys.stderr)
-    tag = None
-    if not args.no_roofline:
-        tag = args.roofline_kernel or rl.DOMINANT_KERNEL
-        rn.profile_begin(tag, args.steps * 256)
-    # the dominant kernel's launches are timed in every fifth step of the timed region (a timed launch
-    # costs a few microseconds more than a plain one)
+    sampling = not args.no_roofline
+    if sampling:
+        rn.profile_begin("", (args.steps // args.sample_every + 2) * 1024)   # every tagged launch of the sampled steps
+        rn.profile_pause(True)
+    # Every step is bracketed by a pair of events on the stream the step is launched on (its side streams
+    # fork from and join back into it); the kernels' own durations are timed in every n-th step only.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     sampled = 0
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        if tag is not None:
-            rn.profile_pause(i % 5 != 0)
-            sampled += i % 5 == 0
+        if sampling:
+            rn.profile_pause(i % args.sample_every != 0)
+            sampled += i % args.sample_every == 0
+        ev[i][0].record()
         step()
+        ev[i][1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = dt / args.steps * 1e3
-    out = {"metric": "ResNet-50 train images/sec on 1 MI355X, batch 40 bf16", "value": args.batch / (ms * 1e-3),
+    step_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    plain = sorted(a.elapsed_time(b) for i, (a, b) in enumerate(ev) if not sampling or i % args.sample_every != 0) or step_ms
+    out = {"metric": f"ResNet-50 train images/sec on 1 MI355X, batch {args.batch} {args.dtype}",
+           "value": args.batch / (ms * 1e-3),
            "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype,
            "data": "synthetic",
            "config": {"workload": f"full ResNet-50 v1.5 training step (fwd+bwd+LARS), batch {args.batch}, 224x224, "
                                   f"1000 classes, {args.dtype} activations with fp32 master weights",
-                      "global_batch": args.batch, "loss": float(S["loss"].item())}}
-    if tag is not None:
+                      "global_batch": args.batch, "loss": float(S["loss"].item())},
+           "step_ms_events": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1],
+                              "median_of_steps_without_launch_timing": plain[len(plain) // 2],
+                              "note": "hipEvent pairs around every timed step on the launch stream"}}
+    if sampling:
         durations_ms = rn.profile_end()
-        out["roofline"] = rl.roofline(tag, plan, durations_ms, sampled)
+        out["roofline"] = rl.roofline(plan, list(zip(rn.profile_tags(), durations_ms)), sampled)
         out["roofline"]["timed_steps"] = sampled
     if not args.no_train_loop:
         out["train_loop"] = train_loop_record(rn, torch, S, args.steps, args.warmup, args.batch)

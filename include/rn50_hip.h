@@ -51,18 +51,20 @@ int rn50_version(void);
 /* Measurement aid (not part of the method): while enabled, every launch whose kernel
  * tag begins with `kernel_tag` ("conv_fwd", "conv_dgrad", "conv_wgrad", "splitk_reduce"
  * (the second pass of a split weight gradient), "bn_stats", "bn_finalize", "bn_apply", "bn_bwd_reduce",
- * "bn_bwd_finalize", "bn_bwd_apply", "lars_norms", "lars_apply", "fc_bwd_da") is
- * given a HIP event pair that receives the begin and end timestamps of that dispatch
+ * "bn_bwd_finalize", "bn_bwd_apply", "lars_norms", "lars_apply", "fc_bwd_da"; the empty
+ * string matches every tagged launch) is given a HIP event pair that receives the begin and end timestamps of that dispatch
  * on the launch stream, up to max_records launches.  rn50_profile_end waits for the
  * last recorded launch, writes the milliseconds each recorded kernel ran, in launch
  * order, to ms_out (host, capacity floats), disables recording and returns the number
- * of records.  A timed launch costs a few microseconds more than a plain one, so a caller
+ * of records; rn50_profile_tag(i) then names the kernel tag of record i (until the next
+ * rn50_profile_begin).  A timed launch costs a few microseconds more than a plain one, so a caller
  * timing whole steps can sample: rn50_profile_pause(1) suspends recording (launches are
  * plain again), rn50_profile_pause(0) resumes it.  Events are the only resource created;
  * all three calls are host-side and not thread-safe. */
 int rn50_profile_begin(const char* kernel_tag, int max_records);
 void rn50_profile_pause(int paused);
 int rn50_profile_end(float* ms_out, int capacity);
+const char* rn50_profile_tag(int record);
 
 /* ------------------------------------------------------------------ convolution
  * y[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]

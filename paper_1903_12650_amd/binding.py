@@ -11,7 +11,7 @@ import torch
 
 __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd",
            "bn_relu_bwd", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "fc_fwd", "fc_bwd",
-           "xent_fwd_bwd", "lars_update", "lars_update_noalloc", "LarsTable", "profile_begin", "profile_pause", "profile_end", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
+           "xent_fwd_bwd", "lars_update", "lars_update_noalloc", "LarsTable", "profile_begin", "profile_pause", "profile_end", "profile_tags", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
            "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
@@ -66,6 +66,7 @@ class StepConfig(ctypes.Structure):
 
 
 raw.rn50_last_error.restype = ctypes.c_char_p
+raw.rn50_profile_tag.restype = ctypes.c_char_p
 for _n in ("conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "lars_update_workspace_bytes",
            "resnet_plan_workspace_bytes", "conv_bn_sums_bytes", "resnet_train_state_bytes",
@@ -549,4 +550,10 @@ def profile_end():
     n = raw.rn50_profile_end(buf, cap)
     if n < 0:
         _check(n)
+    profile_end._n = min(n, cap)
     return [float(buf[i]) for i in range(min(n, cap))]
+
+
+def profile_tags():
+    """The kernel tag of every record the last profile_end returned, in the same order."""
+    return [raw.rn50_profile_tag(i).decode() for i in range(getattr(profile_end, "_n", 0))]

@@ -24,7 +24,9 @@ static bool g_prof_on = false;
 static char g_prof_tag[64] = "";
 static size_t g_prof_max = 0, g_prof_used = 0;
 static bool g_prof_paused = false;
+static size_t g_prof_ended = 0;  // records of the last rn50_profile_end
 static std::vector<hipEvent_t> g_prof_events;  // start/stop pairs, grown on demand, reused
+static std::vector<const char*> g_prof_tags;   // the tag (a string literal of the library) of every record
 
 KernelTimer::KernelTimer(const char* tag) {
   if (!g_prof_on || g_prof_paused || g_prof_used >= g_prof_max || strncmp(tag, g_prof_tag, strlen(g_prof_tag)) != 0) return;
@@ -35,6 +37,8 @@ KernelTimer::KernelTimer(const char* tag) {
   }
   start_ = g_prof_events[2 * g_prof_used];
   stop_ = g_prof_events[2 * g_prof_used + 1];
+  if (g_prof_tags.size() <= g_prof_used) g_prof_tags.resize(g_prof_used + 1);
+  g_prof_tags[g_prof_used] = tag;
   ++g_prof_used;
 }
 }  // namespace rn50
@@ -65,7 +69,13 @@ extern "C" int rn50_profile_end(float* ms_out, int capacity) {
     ms_out[w++] = ms;
   }
   g_prof_used = 0;
+  g_prof_ended = n;
   return static_cast<int>(n);
+}
+extern "C" const char* rn50_profile_tag(int record) {
+  using namespace rn50;
+  if (record < 0 || static_cast<size_t>(record) >= g_prof_ended || static_cast<size_t>(record) >= g_prof_tags.size()) return "";
+  return g_prof_tags[record];
 }
 
 extern "C" const char* rn50_last_error(void) { return rn50::g_err; }

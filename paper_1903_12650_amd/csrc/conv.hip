@@ -1154,10 +1154,10 @@ void stem_pad_input(const rn50_conv_desc* d, const void* x, void* xp, hipStream_
   const StemGeom g = stem_geom(d);
   const dim3 grid(static_cast<unsigned>(ceil_div(g.Wp, 256)), g.Hp, d->N);
   if (d->dtype == RN50_BF16)
-    hipLaunchKernelGGL(stem_pad_input_kernel<uint16_t>, grid, dim3(256), 0, s,
+    RN50_LAUNCH("stem_pad", stem_pad_input_kernel<uint16_t>, grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(x), static_cast<uint16_t*>(xp), d->N, d->H, d->W, g.Hp, g.Wp);
   else
-    hipLaunchKernelGGL(stem_pad_input_kernel<float>, grid, dim3(256), 0, s,
+    RN50_LAUNCH("stem_pad", stem_pad_input_kernel<float>, grid, dim3(256), 0, s,
                        static_cast<const float*>(x), static_cast<float*>(xp), d->N, d->H, d->W, g.Hp, g.Wp);
 }
 
@@ -1215,11 +1215,11 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
   IgemmArgs a = stem_igemm_args(d, xp, wp, y);
   a.partial = bn_partial;
   if (d->dtype == RN50_BF16) {
-    hipLaunchKernelGGL(stem_pad_weight_kernel<uint16_t>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
+    RN50_LAUNCH("stem_pad", stem_pad_weight_kernel<uint16_t>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
                        static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wp), d->Cout);
     launch_igemm<uint16_t>(a, "conv_fwd", s);
   } else {
-    hipLaunchKernelGGL(stem_pad_weight_kernel<float>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
+    RN50_LAUNCH("stem_pad", stem_pad_weight_kernel<float>, dim3(ceil_div(nw, 256)), dim3(256), 0, s,
                        static_cast<const float*>(w), static_cast<float*>(wp), d->Cout);
     launch_igemm<float>(a, "conv_fwd", s);
   }
@@ -1279,7 +1279,7 @@ void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, flo
   if (d->dtype == RN50_BF16) launch_wgrad<uint16_t>(a, p, target, partial, s);
   else launch_wgrad<float>(a, p, target, partial, s);
   if (stem)
-    hipLaunchKernelGGL(stem_unpad_dw_kernel, dim3(ceil_div(d->Cout * 147, 256)), dim3(256), 0, s, target, dw, d->Cout);
+    RN50_LAUNCH("stem_unpad", stem_unpad_dw_kernel, dim3(ceil_div(d->Cout * 147, 256)), dim3(256), 0, s, target, dw, d->Cout);
 }
 
 void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s,
@@ -1322,8 +1322,8 @@ void transpose_batch_run(const std::vector<TransposeEntry>& list, int dtype, con
       a.tile_prefix[i + 1] = a.tile_prefix[i] + static_cast<int>(ceil_div(e.K, 32) * ceil_div(e.C, 32) * e.taps);
     }
     const int grid = a.tile_prefix[a.num];
-    if (dtype == RN50_BF16) hipLaunchKernelGGL(transpose_batch_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(transpose_batch_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+    if (dtype == RN50_BF16) RN50_LAUNCH("weight_transpose", transpose_batch_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, a);
+    else RN50_LAUNCH("weight_transpose", transpose_batch_kernel<float>, dim3(grid), dim3(256), 0, s, a);
   }
 }
 

@@ -461,7 +461,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ d
 template <typename TA, typename TB, typename TC>
 static void small_gemm(const TA* a, int64_t as_i, int64_t as_k, const TB* b, int64_t bs_k,
                        int64_t bs_j, const float* bias, TC* c, int M, int Nn, int K, hipStream_t s) {
-  hipLaunchKernelGGL((small_gemm_kernel<TA, TB, TC>), dim3(ceil_div(Nn, 64), ceil_div(M, 64)),
+  RN50_LAUNCH("fc_gemm", (small_gemm_kernel<TA, TB, TC>), dim3(ceil_div(Nn, 64), ceil_div(M, 64)),
                      dim3(256), 0, s, a, as_i, as_k, b, bs_k, bs_j, bias, c, M, Nn, K);
 }
 
@@ -549,7 +549,7 @@ extern "C" int maxpool_fwd(int N, int H, int W, int C, int dtype, const void* x,
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int cv = C / Elem<T>::VEC;
-    hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(ceil_div(Q * cv, 256), P, N), dim3(256), 0, s,
+    RN50_LAUNCH("maxpool_fwd", maxpool_fwd_kernel<T>, dim3(ceil_div(Q * cv, 256), P, N), dim3(256), 0, s,
                        static_cast<const T*>(x), static_cast<T*>(y), argmax, N, H, W, C, P, Q, make_fastdiv(cv));
   });
   return launch_status("maxpool_fwd");
@@ -571,11 +571,11 @@ extern "C" int maxpool_bwd(int N, int H, int W, int C, int dtype, const void* x,
   DISPATCH_T(dtype, {
     const int64_t total = static_cast<int64_t>(N) * H * W * (C / Elem<T>::VEC);
     if (argmax)
-      hipLaunchKernelGGL(maxpool_bwd_idx_kernel<T>, dim3(ceil_div(((W + 1) / 2) * (C / Elem<T>::VEC), 256), (H + 1) / 2, N),
+      RN50_LAUNCH("maxpool_bwd", maxpool_bwd_idx_kernel<T>, dim3(ceil_div(((W + 1) / 2) * (C / Elem<T>::VEC), 256), (H + 1) / 2, N),
                          dim3(256), 0, s, argmax, static_cast<const T*>(dy), static_cast<const T*>(dy2),
                          static_cast<T*>(dx), N, H, W, C, P, Q, make_fastdiv(C / Elem<T>::VEC));
     else
-      hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+      RN50_LAUNCH("maxpool_bwd", maxpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
                          static_cast<const T*>(x), static_cast<const T*>(dy),
                          static_cast<const T*>(dy2), static_cast<T*>(dx), N, H, W, C, P, Q);
   });
@@ -592,7 +592,7 @@ extern "C" int avgpool_fwd(int N, int HW, int C, int dtype, const void* x, void*
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int total = N * (C / Elem<T>::VEC);
-    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, dim3(ceil_div(total, 64)), dim3(64), 0, s,
+    RN50_LAUNCH("avgpool_fwd", avgpool_fwd_kernel<T>, dim3(ceil_div(total, 64)), dim3(64), 0, s,
                        static_cast<const T*>(x), static_cast<T*>(y), N, HW, C);
   });
   return launch_status("avgpool_fwd");
@@ -608,7 +608,7 @@ extern "C" int avgpool_bwd(int N, int HW, int C, int dtype, const void* dy, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   DISPATCH_T(dtype, {
     const int64_t total = static_cast<int64_t>(N) * HW * (C / Elem<T>::VEC);
-    hipLaunchKernelGGL(avgpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
+    RN50_LAUNCH("avgpool_bwd", avgpool_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, s,
                        static_cast<const T*>(dy), static_cast<T*>(dx), N, HW, C);
   });
   return launch_status("avgpool_bwd");
@@ -629,7 +629,7 @@ extern "C" int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const voi
     return launch_status("fc_fwd");
   }
   DISPATCH_T(dtype, {
-    hipLaunchKernelGGL(fc_fwd_kernel<T>, dim3(ceil_div(K, 4)), dim3(256), 0, s, static_cast<const T*>(a),
+    RN50_LAUNCH("fc_fwd", fc_fwd_kernel<T>, dim3(ceil_div(K, 4)), dim3(256), 0, s, static_cast<const T*>(a),
                        static_cast<const T*>(W), b, logits, N, Cin, K);
   });
   return launch_status("fc_fwd");
@@ -671,7 +671,7 @@ extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const voi
     const void* dl_t = dlogits;
     if (dtype == RN50_BF16) {
       const int64_t n = static_cast<int64_t>(N) * K;
-      hipLaunchKernelGGL(cast_from_float_kernel<uint16_t>, dim3(ceil_div(n, 256)), dim3(256), 0, s, dlogits,
+      RN50_LAUNCH("fc_bwd_cast", cast_from_float_kernel<uint16_t>, dim3(ceil_div(n, 256)), dim3(256), 0, s, dlogits,
                          reinterpret_cast<uint16_t*>(ws), n);
       dl_t = ws;
     }
@@ -691,7 +691,7 @@ extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const voi
     small_gemm<float, T, float>(dlogits, 1, K, static_cast<const T*>(a), Cin, 1, nullptr, dW, K,
                                 Cin, N, s);
   });
-  hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(K, 256)), dim3(256), 0, s, dlogits, db, N, K);
+  RN50_LAUNCH("fc_bwd_bias", colsum_kernel, dim3(ceil_div(K, 256)), dim3(256), 0, s, dlogits, db, N, K);
   return launch_status("fc_bwd");
 }
 
@@ -705,9 +705,9 @@ extern "C" int xent_fwd_bwd(int N, int K, const float* logits, const int32_t* la
   RN50_REQUIRE(label_smoothing >= 0.f && label_smoothing <= 1.f, RN50_ERR_INVALID,
                "xent_fwd_bwd: label_smoothing %g", label_smoothing);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL(xent_rows_kernel, dim3(N), dim3(256), 0, s, logits, labels, N, K,
+  RN50_LAUNCH("xent", xent_rows_kernel, dim3(N), dim3(256), 0, s, logits, labels, N, K,
                      label_smoothing, grad_scale, row_loss_out, dlogits);
-  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, s, row_loss_out, N, loss_out);
+  RN50_LAUNCH("xent", mean_kernel, dim3(1), dim3(256), 0, s, row_loss_out, N, loss_out);
   return launch_status("xent_fwd_bwd");
 }
 

@@ -2,7 +2,7 @@
 v1.5 (forward, data gradient, weight gradient), each against its own roofline.
 
   python -m paper_1903_12650_amd.layer_bench [--batch 40] [--dtype bf16|f32] [--iters 6] [--passes fwd,dgrad,wgrad]
-                                             [--cold]
+                                             [--cold] [--only "<shape>,<shape>"]
 
 For every shape: the bound max(flops / MFMA peak, algorithmic bytes / HBM peak) in microseconds, then per
 pass the launch duration (the library's dispatch timestamps) and bound / duration.  By default the buffers are
@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--iters", type=int, default=6)
     ap.add_argument("--passes", default="fwd,dgrad,wgrad")
     ap.add_argument("--cold", action="store_true")
+    ap.add_argument("--only", default=None,
+                    help="comma-separated shape labels to run, e.g. '128->128 3x3/1 @28,256->256 3x3/1 @14' (default: all)")
     args = ap.parse_args()
     passes = set(args.passes.split(","))
     import torch
@@ -61,7 +63,10 @@ def main():
           % (N, args.dtype, "cold (rotating tensor copies, > 512 MB between reuses)" if args.cold else "warm caches"))
     print("%-26s %3s %9s | %8s %5s | %8s %5s | %8s %5s" % ("shape", "x", "bound", "fwd", "%", "dgrad", "%", "wgrad", "%"))
     tot = dict(bound=0.0, fwd=0.0, dgrad=0.0, wgrad=0.0, flops=0.0)
+    only = [o.strip() for o in args.only.split(",")] if args.only else None
     for (C, K, R, st, H, cnt) in SHAPES:
+        if only is not None and ("%d->%d %dx%d/%d @%d" % (C, K, R, R, st, H)) not in only:
+            continue
         pad = R // 2
         P = (H + 2 * pad - R) // st + 1
         per_copy = es * (N * H * H * C + N * P * P * K + K * R * R * C)

@@ -28,16 +28,25 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
-DOMINANT_KERNEL = "conv_dgrad"  # largest share of the step's kernel time (rocprofv3 summary under profiles/)
-
 # HBM bytes per launch (fetch + write) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs summarized in
 # profiles/resnet50_step_batch40_bf16_hbm_traffic.txt (batch 40, bf16), already scaled by the calibration
 # copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
-# dirty in L2 are written back during later kernels.
+# dirty in L2 are written back during later kernels.  conv_wgrad includes its reduction pass.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "conv_fwd": 40.45e6, "conv_dgrad": 63.87e6, "conv_wgrad": 52.14e6, "bn_apply": 42.55e6,
-    "bn_bwd_reduce": 75.67e6, "bn_bwd_apply": 51.85e6, "lars_norms": 102.30e6, "lars_apply": 281.25e6,
+    "conv_fwd": 40.45e6, "conv_dgrad": 63.87e6, "conv_wgrad": 63.98e6, "bn_apply": 42.55e6,
+    "bn_bwd_reduce": 75.67e6, "bn_bwd_apply": 51.85e6, "lars_update": 383.55e6,
 }
+
+# Kernel classes of the step: (class, launch tags whose durations it sums, tag whose launches it is counted in).
+# bn_finalize / bn_bwd_finalize (the passes from per-tile sums to per-channel statistics) and "other" (stem
+# padding, weight transposition, pooling, classifier, cross-entropy) move next to nothing: they are listed with
+# their time and no bound, so that the classes add up to all of the step's tagged kernel time.
+CLASSES = [
+    ("conv_fwd", ("conv_fwd",)), ("conv_dgrad", ("conv_dgrad",)), ("conv_wgrad", ("conv_wgrad", "splitk_reduce", "stem_unpad")),
+    ("bn_apply", ("bn_apply",)), ("bn_bwd_reduce", ("bn_bwd_reduce",)), ("bn_bwd_apply", ("bn_bwd_apply",)),
+    ("lars_update", ("lars_norms", "lars_apply")),
+    ("bn_finalize", ("bn_finalize",)), ("bn_bwd_finalize", ("bn_bwd_finalize",)),
+]
 
 
 def layers(plan):
@@ -88,7 +97,9 @@ def per_launch_cost(tag, plan):
 
     if tag == "conv_fwd":
         return _fwd_order(L, [conv_cost(l) for l in L])
-    if tag == "conv_dgrad":
+    if tag in ("conv_dgrad", "conv_dgrad_fused_reads"):
+        # conv_dgrad: the convolution's own bytes.  conv_dgrad_fused_reads: what its output stage reads on top
+        # of that for the batch-norm backward sums it takes (bytes a separate reduce pass would otherwise read).
         out = []
         blocks = _blocks(L)[1:]
         for bi in range(len(blocks) - 1, -1, -1):
@@ -96,13 +107,14 @@ def per_launch_cost(tag, plan):
             for j, l in enumerate(b):
                 f, by = conv_cost(l)
                 dx = l["N"] * l["H"] * l["H"] * l["Cin"]
+                extra = 0.0
                 if j in (1, 2):            # conv2, conv3: sums of the BN+ReLU layer below (its input is read)
-                    by += es * dx
+                    extra = es * dx
                 elif j == 0 and bi > 0:    # conv1 closes the block: + the shortcut's gradient, the previous
-                    by += 2 * es * dx + dx / 8   # block's BN input and its ReLU bits
+                    extra = 2 * es * dx + dx / 8   # block's BN input and its ReLU bits
                     if len(b) == 3:        # identity shortcut: its gradient is read under the block's bits
-                        by += dx / 8
-                out.append((f, by))
+                        extra += dx / 8
+                out.append((f, by) if tag == "conv_dgrad" else (0.0, extra))
         return out
     if tag == "conv_wgrad":
         return [conv_cost(l, True) for l in _bwd_order(L)]
@@ -120,6 +132,9 @@ def per_launch_cost(tag, plan):
     if tag == "lars_norms":
         return [(0.0, 8.0 * (n_params - n_stem)), (0.0, 8.0 * n_stem)]
     if tag == "lars_apply":
+        per = 20.0 + (2.0 if plan.dtype == 1 else 0.0)
+        return [(0.0, per * (n_params - n_stem)), (0.0, per * n_stem)]
+    if tag == "lars_update":  # the whole update against the single-pass figure: w, g, v read, w, v written (+ bf16 copy)
         per = 20.0 + (2.0 if plan.dtype == 1 else 0.0)
         return [(0.0, per * (n_params - n_stem)), (0.0, per * n_stem)]
     raise KeyError(tag)
@@ -155,31 +170,60 @@ def _bwd_order(L):
     return seq
 
 
-def roofline(tag, plan, durations_ms, steps):
-    """Roofline record for the kernel `tag` from per-launch event durations of `steps` steps."""
-    cost = per_launch_cost(tag, plan)
-    n = len(cost)
-    rec = {"kernel": tag, "launches_per_step": n}
-    if not durations_ms or len(durations_ms) % n != 0:
-        rec.update(bound=None, achieved=None, note=f"{len(durations_ms or [])} event records, expected a multiple of {n}")
+def class_record(name, tags, plan, tagged_ms, steps):
+    """One kernel class: time per step summed over its tags' launches in `steps` sampled steps, against its bound."""
+    ms = [t for tag, t in tagged_ms if tag in tags]
+    rec = {"class": name, "tags": list(tags), "launches_per_step": len(ms) / steps, "time_per_step_ms": sum(ms) / steps}
+    try:
+        cost = per_launch_cost(name, plan)
+    except KeyError:
+        rec.update(bound=None, note="no algorithmic traffic of its own")
         return rec
-    total_ms = sum(durations_ms)
-    reps = len(durations_ms) // n
-    flops = sum(c[0] for c in cost) * reps
-    nbytes = sum(c[1] for c in cost) * reps
+    flops, nbytes = sum(c[0] for c in cost), sum(c[1] for c in cost)   # per step
+    n = len(cost)
+    main = [t for tag, t in tagged_ms if tag == tags[0]]
+    if not ms or len(main) != n * steps:
+        rec.update(bound=None, note=f"{len(main)} records of {tags[0]}, expected {n * steps}")
+        return rec
+    t = rec["time_per_step_ms"] * 1e-3
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if plan.dtype == 1 else MFMA_F32_PEAK_TFLOPS
-    t_flop = flops / (mfma_peak * 1e12)
-    t_byte = nbytes / (HBM_PEAK_GBS * 1e9)
-    rec["avg_launch_us"] = total_ms * 1e3 / len(durations_ms)
-    rec["time_per_step_ms"] = total_ms / reps
+    t_flop, t_byte = flops / (mfma_peak * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    rec["launches_per_step"] = n
+    rec["avg_launch_us"] = t * 1e6 / n
     if t_flop > t_byte:
-        a = flops / (total_ms * 1e-3) / 1e12
+        a = flops / t / 1e12
         rec.update(bound="mfma", achieved=a, peak=mfma_peak, unit="TFLOP/s", frac=a / mfma_peak)
     else:
-        a = nbytes / (total_ms * 1e-3) / 1e9
+        a = nbytes / t / 1e9
         rec.update(bound="hbm", achieved=a, peak=HBM_PEAK_GBS, unit="GB/s", frac=a / HBM_PEAK_GBS)
-    rec["algorithmic_bytes_per_launch"] = nbytes / len(durations_ms)
-    rec["algorithmic_flops_per_launch"] = flops / len(durations_ms)
-    t = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(tag) if (plan.dtype == 1 and plan.cfg.N == 40) else None
-    rec["traffic"] = t
+    rec["algorithmic_bytes_per_launch"] = nbytes / n
+    rec["algorithmic_flops_per_launch"] = flops / n
+    if name == "conv_dgrad":   # credited separately: the reads its output stage makes for the fused BN sums
+        extra = sum(c[1] for c in per_launch_cost("conv_dgrad_fused_reads", plan))
+        rec["fused_bn_read_bytes_per_launch"] = extra / n
+        rec["frac_with_fused_reads"] = (nbytes + extra) / t / 1e9 / HBM_PEAK_GBS if rec["bound"] == "hbm" else None
+    rec["traffic"] = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(name) if (plan.dtype == 1 and plan.cfg.N == 40) else None
+    return rec
+
+
+def roofline(plan, tagged_ms, steps):
+    """The bench line's roofline object from (tag, ms) records of every tagged launch in `steps` sampled steps:
+    the class with the largest time per step (chosen from these measurements), with every class listed."""
+    classes = [class_record(name, tags, plan, tagged_ms, steps) for name, tags in CLASSES]
+    known = {t for _, tags in CLASSES for t in tags}
+    other = [t for tag, t in tagged_ms if tag not in known]
+    classes.append({"class": "other", "tags": sorted({tag for tag, _ in tagged_ms if tag not in known}),
+                    "launches_per_step": len(other) / steps, "time_per_step_ms": sum(other) / steps, "bound": None})
+    bounded = [c for c in classes if c.get("bound")]
+    if not bounded:
+        return {"kernel": None, "bound": None, "classes": classes}
+    dom = max(bounded, key=lambda c: c["time_per_step_ms"])
+    rec = {"kernel": dom["class"]}
+    rec.update({k: v for k, v in dom.items() if k not in ("class",)})
+    rec["chosen_by"] = "largest kernel time per step among the classes, from this run's own timings"
+    rec["timing"] = ("dispatch begin/end timestamps of every tagged launch (events handed to hipExtLaunchKernel) in "
+                     f"{steps} of the timed steps; kernels of the step's three streams overlap, so class times add up "
+                     "to more than the step")
+    rec["kernel_time_per_step_ms"] = sum(c["time_per_step_ms"] for c in classes)
+    rec["classes"] = classes
     return rec
