@@ -21,6 +21,8 @@
 //   mean = K + S1/m, var = S2/m - (S1/m)^2,
 // which removes the cancellation of the plain E[x^2]-E[x]^2 form whenever K lies
 // within a few standard deviations of the mean.
+#include <stdlib.h>
+
 #include "common.h"
 #include "step_internal.h"
 
@@ -58,11 +60,20 @@ static BnGeom bn_geom(int64_t m, int C, int dtype) {
   return g;
 }
 
-// The elementwise passes have no sums to combine, so their geometry is free.  Measured on the layer
-// shapes of ResNet-50: best is about `target` workgroups in all (1-3 per CU), each thread streaming
-// 4 to 32 rows; small tensors then still give every CU a workgroup and need one round of loads.
+// The elementwise passes have no sums to combine, so their geometry is free: at most `target` workgroups,
+// each thread streaming 4 to 32 rows.  Measured inside the training step (profiles/bn_apply_grid_step_time_batch40.txt)
+// and on a plain copy kernel: many small workgroups that make one round of loads each stream faster than few
+// long-running ones (a 16-byte-per-thread copy of 1 GiB runs at 6.2 TB/s, the same copy by 2,048 looping workgroups
+// at 4.9), so the target is high enough that every thread of ResNet-50's layers takes its minimum of 4 rows.
+constexpr int kBnApplyGroups = 16384, kBnBwdApplyGroups = 16383;  // (distinct values: the tuning override tells them apart)
 static BnGeom bn_apply_geom(int64_t m, int C, int dtype, int target) {
   BnGeom g = bn_geom(m, C, dtype);
+#ifdef RN50_TUNING  // tuning builds only: RN50_BN_TARGET=forward,backward workgroup targets of the apply passes
+  if (const char* e = getenv("RN50_BN_TARGET")) {
+    int tf = 0, tb = 0;
+    if (sscanf(e, "%d,%d", &tf, &tb) == 2) target = target == kBnApplyGroups ? tf : tb;
+  }
+#endif
   const int TY = 256 >> g.tx_log2;
   int64_t rpt = ceil_div(m * g.gy, static_cast<int64_t>(TY) * target);
   rpt = ceil_div(rpt, kBnRows) * kBnRows;
@@ -567,7 +578,7 @@ static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
                             float momentum, const float* partial, int nrows, int rpp, hipStream_t s) {
   RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), d->eps, save_mean, save_rstd, rm, rv, momentum);
-  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 768);
+  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnApplyGroups);
   RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, ga.tx_log2, ga.rpb, d->mode);
 }
 
@@ -590,7 +601,7 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             void* dx, void* dres, float* dgamma, float* dbeta, const float* partial,
                             int nrows, hipStream_t s) {
   RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
-  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 384);
+  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnBwdApplyGroups);
 #define RN50_BWD_APPLY(DZ2, ZK)                                                                                  \
   RN50_LAUNCH("bn_bwd_apply", (bn_bwd_apply_kernel<T, DZ2, ZK>), dim3(ga.nblk, ga.gy), dim3(256), 0, s,            \
               static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x),                     \
@@ -654,7 +665,7 @@ void bn_infer_run(const rn50_bn_desc* d, const void* x, const float* gamma, cons
   const int64_t m = static_cast<int64_t>(d->N) * d->H * d->W;
   hipLaunchKernelGGL(bn_infer_rstd_kernel, dim3(static_cast<unsigned>(ceil_div(d->C, 256))), dim3(256), 0, s,
                      running_var, d->eps, d->C, rstd_scratch);
-  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, 768);
+  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnApplyGroups);
   if (d->dtype == RN50_BF16)
     RN50_LAUNCH("bn_apply", bn_apply_kernel<uint16_t>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const uint16_t*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const uint16_t*>(residual), static_cast<uint16_t*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode);
   else
