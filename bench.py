@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-train-loop", action="store_true")
+    ap.add_argument("--fuse-conv3-input", action="store_true",
+                    help="conv3 of every block applies conv2's BN+ReLU in its operand load (same results; for timing)")
     ap.add_argument("--sample-every", type=int, default=50,
                     help="per-launch timing in every n-th timed step (a timed launch costs a few microseconds more)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -188,6 +190,8 @@ def main():
 
     S = build_state(rn, args.batch, args.dtype)
     plan = S["plan"]
+    if args.fuse_conv3_input:
+        plan.fuse_conv3_input(True)
 
     def step():
         rn.resnet_step(plan, S["images"], S["labels"], S["M"], S["V"], S["G"], S["Mod"], 1.0, S["ws"], update=True,

@@ -177,6 +177,24 @@ int bn_relu_bwd_from_sums(const rn50_bn_desc* d, const rn50_conv_desc* producer,
                           const float* sums, void* dx, void* dresidual, float* dgamma, float* dbeta,
                           void* stream);
 
+/* ----------------------- convolution whose input is a BN+ReLU layer's output, applied on the fly
+ * The other half of the convolution <-> batch-norm fusion: a 1x1, stride-1, unpadded convolution
+ * (conv3 of a bottleneck block) reads the INPUT x of the BN+ReLU layer in front of it and applies
+ *   z = max(gamma*(x-mean)*rstd + beta, 0)     (mode 1 of bn_relu_fwd, rounded once to dtype)
+ * to every operand vector after it has been loaded, so that z is never stored and the stand-alone
+ * BN pass over it disappears.  The results are bit for bit those of conv_fwd / conv_wgrad on the z
+ * that bn_relu_fwd stores (same arithmetic, same rounding).
+ * in_gamma, in_beta, in_mean, in_rstd: device float[Cin], the BN layer's parameters and the
+ * statistics its forward pass saved.  x [N,H,W,Cin]: that layer's input.  conv_fwd_bn_in: sums
+ * (or NULL) as in conv_fwd_bn_sums, for the BN layer BEHIND this convolution.  Unsupported
+ * (RN50_ERR_UNSUPPORTED): any filter other than 1x1 / stride 1 / pad 0, Cin > 4096. */
+int conv_fwd_bn_in(const rn50_conv_desc* d, const void* x, const float* in_gamma, const float* in_beta,
+                   const float* in_mean, const float* in_rstd, const void* w, void* y, float* sums,
+                   size_t sums_bytes, void* stream);
+int conv_wgrad_bn_in(const rn50_conv_desc* d, const void* x, const float* in_gamma, const float* in_beta,
+                     const float* in_mean, const float* in_rstd, const void* dy, float* dw, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
 /* --------------------------------------------------------------------- pooling
  * Max pooling, window 3x3, stride 2, pad 1 (the appendix's 112 -> 56 step);
  * padding never wins; among equal maxima the first in row-major window order
@@ -295,6 +313,12 @@ void resnet_plan_destroy(rn50_plan* plan);
  * GPU; all or nothing; a second call is a no-op).  Call it before capturing a step into a graph
  * when no step has run outside the capture yet. */
 int resnet_plan_prepare(rn50_plan* plan);
+/* on != 0: in every bottleneck block, conv3 applies conv2's BN+ReLU while it loads its operand
+ * (conv_fwd_bn_in in the forward pass, conv_wgrad_bn_in for conv3's weight gradient): conv2's BN
+ * pass only finalises its statistics and its normalised output is never stored.  Results of the
+ * step are bit for bit the same either way; only the time differs.  Off when the plan is created.
+ * Applies to resnet_step / resnet_train_step (resnet_infer always stores every layer's output). */
+int resnet_plan_fuse_conv3_input(rn50_plan* plan, int on);
 int resnet_plan_num_tensors(const rn50_plan* plan);
 /* Shape of parameter tensor i: dims_out[4] = {K,R,S,C} for convolution weights,
  * {K,C,0,0} for the FC weight, {C,0,0,0} for vectors.  Returns the element count. */

@@ -14,7 +14,7 @@ __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "co
            "xent_fwd_bwd", "lars_update", "lars_update_noalloc", "LarsTable", "profile_begin", "profile_pause", "profile_end", "profile_tags", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
-           "conv_fwd_bn_sums", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
+           "conv_fwd_bn_sums", "conv_fwd_bn_in", "conv_wgrad_bn_in", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
            "LrSchedule", "TrainState", "resnet_train_step", "DECAY_NONE", "DECAY_STEP", "DECAY_POLY", "DECAY_LINEAR",
            "DECAY_TABLE", "resnet_init_params", "bn_relu_infer", "top1_accuracy", "resnet_eval"]
 
@@ -267,6 +267,28 @@ def conv_dgrad_bn_sums(dy, w, x_shape, stride, pad, bn_x, gamma, beta, mean, rst
     return dx, (d, sums)
 
 
+def conv_fwd_bn_in(x, in_gamma, in_beta, in_mean, in_rstd, w, with_sums=False):
+    """1x1 convolution of relu(bn(x)) without storing it.  Returns y (and the sums handle with with_sums)."""
+    d = _conv_desc(x.shape, w.shape, 1, 0, _dt(x))
+    N, H, W_, _ = x.shape
+    y = torch.empty((N, H, W_, w.shape[0]), dtype=x.dtype, device=x.device)
+    sums = _ws(conv_bn_sums_bytes(d), x.device) if with_sums else None
+    _check(raw.conv_fwd_bn_in(ctypes.byref(d), _ptr(x), _ptr(in_gamma), _ptr(in_beta), _ptr(in_mean), _ptr(in_rstd),
+                              _ptr(w), _ptr(y), _ptr(sums), ctypes.c_size_t(sums.numel() if with_sums else 0), _stream()))
+    return (y, (d, sums)) if with_sums else y
+
+
+def conv_wgrad_bn_in(x, in_gamma, in_beta, in_mean, in_rstd, dy, w_shape, workspace=None):
+    """Weight gradient of a 1x1 convolution whose input is relu(bn(x)), without storing that input."""
+    d = _conv_desc(x.shape, w_shape, 1, 0, _dt(x))
+    dw = torch.empty(tuple(w_shape), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = _ws(conv_wgrad_workspace_bytes(d), x.device)
+    _check(raw.conv_wgrad_bn_in(ctypes.byref(d), _ptr(x), _ptr(in_gamma), _ptr(in_beta), _ptr(in_mean), _ptr(in_rstd),
+                                _ptr(dy), _ptr(dw), _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    return dw
+
+
 def bn_relu_bwd_from_sums(dz, x, handle, gamma, beta, mean, rstd, eps=1e-5, mode=1, relu_mask=None):
     """Returns dx, dresidual (None unless mode 2), dgamma, dbeta."""
     producer, sums = handle
@@ -415,6 +437,10 @@ class ResnetPlan:
 
     def view(self, arena, i):
         return arena[self.offsets[i]:self.offsets[i] + self.sizes[i]].view(self.shapes[i])
+
+    def fuse_conv3_input(self, on=True):
+        """conv3 of every block applies conv2's BN+ReLU in its operand load (same results, other timing)."""
+        _check(raw.resnet_plan_fuse_conv3_input(self.handle, int(bool(on))))
 
 
 def resnet_step(plan, images, labels, master, velocity, grads, model, lr, workspace, update=True, loss_out=None,

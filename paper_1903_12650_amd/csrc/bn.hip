@@ -578,6 +578,7 @@ static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
                             float momentum, const float* partial, int nrows, int rpp, hipStream_t s) {
   RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), d->eps, save_mean, save_rstd, rm, rv, momentum);
+  if (!y) return;  // statistics only: the consumer applies the layer while it loads its operand
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnApplyGroups);
   RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, ga.tx_log2, ga.rpb, d->mode);
 }

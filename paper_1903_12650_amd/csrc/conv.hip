@@ -100,7 +100,33 @@ struct IgemmArgs {
   const void* addend;
   const uint8_t* bn_zmask;
   const uint8_t* addend_mask;
+  // Forward, 1x1 / stride 1 only (BNIN kernels): the gathered tensor is the INPUT of a BN+ReLU layer, whose
+  // relu(x*scale + bias) is applied to every operand vector once it sits in LDS (null: the tensor is used as is).
+  // in_lds: byte offset of the per-channel coefficient table behind the ring (host side: lds bytes without it).
+  const float *in_gamma, *in_beta, *in_mean, *in_rstd;
+  int in_lds;
 };
+
+// relu(bn(x)) of one 16-byte vector with the arithmetic of the stand-alone BN pass (bn_affine, one rounding to
+// the storage type), so that a convolution reading it sees bit for bit the tensor that pass would have stored.
+template <typename T>
+__device__ __forceinline__ Vec16 bn_relu_vector(const Vec16& v, const float* scale, const float* bias) {
+  constexpr int V = 16 / sizeof(T);
+  float f[V];
+  Elem<T>::unpack(v, f);
+#pragma unroll
+  for (int j = 0; j < V; ++j) f[j] = fmaxf(bn_affine(f[j], scale[j], bias[j]), 0.f);
+  Vec16 o;
+  Elem<T>::pack(f, o);
+  return o;
+}
+// Barrier behind LDS writes of this wave (s_barrier alone does not wait for them), leaving vector-memory loads in flight.
+__device__ __forceinline__ void lds_writes_then_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0); vmcnt, expcnt: no wait
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 constexpr uint32_t kOob = 0x80000000u;  // buffer offset beyond every tensor: the load returns zeros
 
@@ -148,6 +174,20 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// Top of iteration kc of a ring of NSTAGE chunk buffers (loads NSTAGE-1 chunks ahead, NL load instructions per
+// thread and chunk): wait until this wave's loads of chunk kc have landed -- those of the chunks behind it that
+// have been issued, at most NSTAGE-2 of them and none past the last chunk, may stay in flight -- then the barrier.
+template <int NSTAGE, int NL>
+__device__ __forceinline__ void ring_wait(int chunks_after) {
+  static_assert(NSTAGE >= 2 && NSTAGE <= 6 && NL * (NSTAGE - 2) < 64, "ring depth");
+  const int ahead = chunks_after < NSTAGE - 2 ? chunks_after : NSTAGE - 2;
+  if (NSTAGE >= 6 && ahead == 4) wait_loads_then_barrier<(NSTAGE >= 6 ? 4 : 0) * NL>();
+  else if (NSTAGE >= 5 && ahead == 3) wait_loads_then_barrier<(NSTAGE >= 5 ? 3 : 0) * NL>();
+  else if (NSTAGE >= 4 && ahead == 2) wait_loads_then_barrier<(NSTAGE >= 4 ? 2 : 0) * NL>();
+  else if (NSTAGE >= 3 && ahead == 1) wait_loads_then_barrier<(NSTAGE >= 3 ? 1 : 0) * NL>();
+  else wait_loads_then_barrier<0>();
+}
+
 // MODE 0: forward gather  ih = p*stride - pad + r.
 // MODE 1: data-gradient gather  ih = (p + pad - r)/stride when divisible (stride 1 or 2).  With stride 2
 // an output pixel only receives the taps r = (p + pad) mod 2, s = (q + pad) mod 2 (mod 2), so the pixels
@@ -175,8 +215,9 @@ template <int BM, int BN, int NW>
 constexpr int igemm_ring() {
   return (NW == 4 && 3 * (BM + BN) * 128 > 80 * 1024) ? 2 : 3;
 }
-template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false>
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false, bool BNIN = false>
 __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) {
+  static_assert(!BNIN || (LIN && MODE == 0), "the input-side BN is compiled for the linear forward kernel only");
   constexpr int NW = WM * WN, NT = 64 * NW;
   constexpr int V = 16 / sizeof(T);
   constexpr int BK = 128 / sizeof(T);
@@ -376,13 +417,40 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) 
   // every wave's part of chunk kc is in LDS and every wave is done reading chunk kc-1, whose buffer the loads
   // of chunk kc+NSTAGE-1 issued next will overwrite.
   tap_setup();
+  float* const in_tab = reinterpret_cast<float*>(smem + (BNIN ? a.in_lds : 0));  // [2][nchunks * BK]: scale, bias
+  if constexpr (BNIN) {
+    const int kpad = nchunks * BK;
+    for (int c = tid; c < kpad; c += NT) {
+      float sc = 0.f, bi = 0.f;
+      if (c < a.Cg) bn_coeffs(a.in_gamma[c], a.in_beta[c], a.in_mean[c], a.in_rstd[c], &sc, &bi);
+      in_tab[c] = sc;
+      in_tab[kpad + c] = bi;
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int c = 0; c < NSTAGE - 1; ++c)
     if (c < nchunks) load_chunk(c);
   int stage = 0;
   for (int kc = 0; kc < nchunks; ++kc) {
-    if (NSTAGE == 3 && kc + 1 < nchunks) wait_loads_then_barrier<NL>(); else wait_loads_then_barrier<0>();
+    ring_wait<NSTAGE, NL>(nchunks - 1 - kc);
     if (kc + NSTAGE - 1 < nchunks) load_chunk(stage >= 1 ? stage - 1 : NSTAGE - 1);  // buffer (kc - 1) mod NSTAGE
+    if constexpr (BNIN) {
+      // every thread transforms, in place, the vectors of chunk kc that its own loads brought (its slot of its
+      // rows holds piece `piece`, i.e. channels kc*BK + piece*V ..), then a second barrier
+      float scale[V], bias[V];
+      const int kpad = nchunks * BK;
+      load_floats<V>(in_tab + kc * BK + piece * V, scale);
+      load_floats<V>(in_tab + kpad + kc * BK + piece * V, bias);
+#pragma unroll
+      for (int i = 0; i < RA; ++i) {
+        uint4* p = reinterpret_cast<uint4*>(smem + stage * STAGE + (lrow + RPL * i) * 128 + slot * 16);
+        Vec16 v;
+        v.u = *p;
+        *p = bn_relu_vector<T>(v, scale, bias).u;
+      }
+      lds_writes_then_barrier();
+    }
     compute(stage);
     stage = stage == NSTAGE - 1 ? 0 : stage + 1;
   }
@@ -574,6 +642,9 @@ struct WgradArgs {
   int64_t split_stride;
   FastDiv divQ, divP;
   FastDiv div_tps, div_tiles_x, div_ctiles, div_S;  // the tile decode's divisors
+  // BNIN kernels (1x1, stride 1): x is the INPUT of a BN+ReLU layer whose output is the convolution's input;
+  // relu(x*scale + bias) is applied to the x tile in LDS (as in igemm_kernel).  Null: x is used as is.
+  const float *in_gamma, *in_beta, *in_mean, *in_rstd;
 };
 
 template <typename T> struct WgradCfg;
@@ -630,16 +701,14 @@ __device__ __forceinline__ Vec16 wgrad_read_frag(const unsigned char* tile, int 
   return v;
 }
 
-// Ring depth as in the forward kernel: three chunk buffers, two where three would leave one workgroup per CU.
-template <int STAGE>
-constexpr int wgrad_ring() {
-  return 3 * STAGE > 80 * 1024 ? 2 : 3;
-}
 
 // One workgroup: the BMO x BC tile (output channels x input channels of one tap) of one split of the pixel
 // range.  2 x 2 waves; per 64-row (32 in float) chunk of pixels the dy and x rows go straight into LDS
 // (a ring of chunk buffers, one barrier per chunk, as in igemm_kernel) and are read back transposed.
-template <typename T, int BMO, int BC>
+// NSTAGE: chunk buffers in the ring.  Both operands stream past a workgroup exactly once, from memory that is cold
+// inside a training step, so a workgroup's rate is (bytes in flight) / (memory latency): the launch picks the
+// deepest ring that the workgroups sharing a compute unit have LDS for (wgrad_stages).
+template <typename T, int BMO, int BC, int NSTAGE, bool BNIN = false>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   constexpr int V = 16 / sizeof(T);
   constexpr int BKM = WgradCfg<T>::BKM;
@@ -649,7 +718,6 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
   constexpr int NA = BKM * LA / 256, NB = BKM * LB / 256;    // load instructions per thread and chunk
   constexpr int NL = NA + NB;
   constexpr int STAGE = BKM * (RA + RB);
-  constexpr int NSTAGE = wgrad_ring<STAGE>();
   constexpr int TM = BMO / 64, TN = BC / 64;  // 2x2 waves
   static_assert(NA >= 1 && NB >= 1 && 256 % LA == 0 && 256 % LB == 0, "tile shape");
   extern __shared__ __align__(16) unsigned char smem[];
@@ -763,14 +831,35 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  // BNIN: this thread's piece of every x row is the same 16 bytes of channels for the whole launch
+  float in_scale[V], in_bias[V];
+  if constexpr (BNIN) {
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const int c = min(c0 + pb * V + j, a.Cg - 1);
+      bn_coeffs(a.in_gamma[c], a.in_beta[c], a.in_mean[c], a.in_rstd[c], &in_scale[j], &in_bias[j]);
+    }
+  }
   // the ring of igemm_kernel: loads NSTAGE-1 chunks ahead, one barrier per chunk
 #pragma unroll
   for (int c = 0; c < NSTAGE - 1; ++c)
     if (c < nchunks) load_chunk(c);
   int stage = 0;
   for (int kc = 0; kc < nchunks; ++kc) {
-    if (NSTAGE == 3 && kc + 1 < nchunks) wait_loads_then_barrier<NL>(); else wait_loads_then_barrier<0>();
+    ring_wait<NSTAGE, NL>(nchunks - 1 - kc);
     if (kc + NSTAGE - 1 < nchunks) load_chunk(stage >= 1 ? stage - 1 : NSTAGE - 1);
+    if constexpr (BNIN) {
+      // every thread transforms, in place, the x vectors of chunk kc that its own loads brought.  Rows past the
+      // split's end (loaded as zeros) become relu(bias); their dy rows are zeros, so they add nothing.
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        uint4* p = reinterpret_cast<uint4*>(smem + stage * STAGE + BKM * RA + i * 4096 + tid * 16);
+        Vec16 v;
+        v.u = *p;
+        *p = bn_relu_vector<T>(v, in_scale, in_bias).u;
+      }
+      lds_writes_then_barrier();
+    }
     compute(stage);
     stage = stage == NSTAGE - 1 ? 0 : stage + 1;
   }
@@ -930,8 +1019,8 @@ static void allow_big_lds(K kernel, int bytes) {
   if (bytes > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN>
-static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid, hipStream_t s) {
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN, bool BNIN = false>
+static void launch_igemm_mode(IgemmArgs a, const char* tag, int64_t grid, hipStream_t s) {
   constexpr int NT = 64 * WM * WN;
   constexpr int stage = (BM + BN) * 128;
   constexpr int es = static_cast<int>(sizeof(T));
@@ -942,13 +1031,21 @@ static void launch_igemm_mode(const IgemmArgs& a, const char* tag, int64_t grid,
   constexpr int out_need = out_tile > col_sums ? out_tile : col_sums;
   static std::once_flag once;
   constexpr int nring = igemm_ring<BM, BN, WM * WN>();
-  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>, nring * stage > out_need ? nring * stage : out_need); });
+  constexpr int kInTabMax = 8 * 4096;  // input-side BN coefficients: two floats per channel, at most 4096 channels
+  std::call_once(once, [] {
+    allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE, LIN, BNIN>,
+                  (nring * stage > out_need ? nring * stage : out_need) + (BNIN ? kInTabMax : 0));
+  });
   // A short reduction never touches the later ring buffers; without them more workgroups fit a CU (the 1x1
   // layers with 64 channels, the largest pixel counts of the net, have a single chunk).
   const int chunks = a.R * a.S * a.cpt;
   const int ring = (chunks < nring ? (chunks < 1 ? 1 : chunks) : nring) * stage;
-  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, LIN>), dim3(static_cast<unsigned>(grid)), dim3(NT),
-              ring > out_need ? ring : out_need, s, a);
+  int lds = ring > out_need ? ring : out_need;
+  if (BNIN) {
+    a.in_lds = lds;
+    lds += 8 * chunks * (128 / es);
+  }
+  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, LIN, BNIN>), dim3(static_cast<unsigned>(grid)), dim3(NT), lds, s, a);
 }
 template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
@@ -966,7 +1063,8 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
     a.div_h[c] = make_fastdiv(classes ? (a.P - c + 1) >> 1 : a.P);
   }
   if (a.linear) {
-    if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, true>(a, tag, grid, s);
+    if (a.mode == 0 && a.in_gamma) launch_igemm_mode<T, BM, BN, WM, WN, 0, true, true>(a, tag, grid, s);
+    else if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, true>(a, tag, grid, s);
     else launch_igemm_mode<T, BM, BN, WM, WN, 1, true>(a, tag, grid, s);
     return;
   }
@@ -1063,13 +1161,40 @@ static WgradPlan plan_wgrad(int M, int Cout, int Cg, int taps, int dtype, bool t
   return best;
 }
 
+// Ring depth of a weight-gradient launch: as many chunk buffers as fit when the compute unit's 160 KB of LDS
+// are shared by the workgroups it will hold (grid / 256 compute units, rounded up, at most 3), between 2 and 6.
+static int wgrad_stages(int stage_bytes, int64_t grid) {
+#ifdef RN50_TUNING  // tuning builds only: RN50_WGRAD_STAGES=n forces the depth
+  if (const char* e = getenv("RN50_WGRAD_STAGES")) {
+    const int n = atoi(e);
+    if (n >= 2 && n <= 6 && n * stage_bytes <= 160 * 1024) return n;
+  }
+#endif
+  int64_t per_cu = ceil_div(grid, 256);
+  if (per_cu > 3) per_cu = 3;
+  int n = static_cast<int>((156 * 1024 / per_cu) / stage_bytes);
+  return n < 2 ? 2 : (n > 6 ? 6 : n);
+}
+template <typename T, int BMO, int BC, int NSTAGE>
+static void launch_wgrad_ring(const WgradArgs& b, dim3 grid, hipStream_t s) {
+  constexpr int BKM = WgradCfg<T>::BKM;
+  constexpr int lds = NSTAGE * BKM * (BMO + BC) * static_cast<int>(sizeof(T));
+  if (b.in_gamma) {  // the input-side BN variant is compiled for the two deepest rings only
+    if constexpr (NSTAGE == 2 || NSTAGE == 3) {
+      static std::once_flag once_in;
+      std::call_once(once_in, [] { allow_big_lds(wgrad_kernel<T, BMO, BC, NSTAGE, true>, lds); });
+      RN50_LAUNCH("conv_wgrad", (wgrad_kernel<T, BMO, BC, NSTAGE, true>), grid, dim3(256), lds, s, b);
+      return;
+    }
+  }
+  static std::once_flag once;
+  std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC, NSTAGE>, lds); });
+  RN50_LAUNCH("conv_wgrad", (wgrad_kernel<T, BMO, BC, NSTAGE>), grid, dim3(256), lds, s, b);
+}
 template <typename T, int BMO, int BC>
 static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   constexpr int BKM = WgradCfg<T>::BKM;
   constexpr int stage = BKM * (BMO + BC) * static_cast<int>(sizeof(T));
-  constexpr int lds = wgrad_ring<stage>() * stage;
-  static std::once_flag once;
-  std::call_once(once, [] { allow_big_lds(wgrad_kernel<T, BMO, BC>, lds); });
   WgradArgs b = a;
   b.tiles_per_split = a.R * a.S * a.ctiles * static_cast<int>(ceil_div(a.Cout, BMO));
   b.div_tps = make_fastdiv(b.tiles_per_split);
@@ -1077,7 +1202,15 @@ static void launch_wgrad_cfg(const WgradArgs& a, int splits, hipStream_t s) {
   b.div_ctiles = make_fastdiv(a.ctiles);
   b.div_S = make_fastdiv(a.S);
   const dim3 grid(static_cast<unsigned>(b.tiles_per_split) * splits);
-  RN50_LAUNCH("conv_wgrad", (wgrad_kernel<T, BMO, BC>), grid, dim3(256), lds, s, b);
+  int stages = wgrad_stages(stage, grid.x);
+  if (b.in_gamma) stages = (stages >= 3 && 3 * stage <= 160 * 1024) ? 3 : 2;
+  switch (stages) {
+    case 2: return launch_wgrad_ring<T, BMO, BC, 2>(b, grid, s);
+    case 3: return launch_wgrad_ring<T, BMO, BC, 3>(b, grid, s);
+    case 4: return launch_wgrad_ring<T, BMO, BC, 4>(b, grid, s);
+    case 5: return launch_wgrad_ring<T, BMO, BC, (stage * 5 <= 160 * 1024 ? 5 : 4)>(b, grid, s);
+    default: return launch_wgrad_ring<T, BMO, BC, (stage * 6 <= 160 * 1024 ? 6 : 4)>(b, grid, s);
+  }
 }
 
 template <typename T>
@@ -1266,9 +1399,11 @@ size_t wgrad_partial_bytes(const rn50_conv_desc* d) {
 }
 
 // Weight gradient; for the stem x must be the padded input.  scratch: wgrad_partial_bytes(d).
-void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s) {
+void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s,
+               const BnIn* in) {
   const bool stem = is_stem(d);
   WgradArgs a = stem ? stem_wgrad_args(d, x_or_xp, dy) : wgrad_args(d, x_or_xp, dy);
+  if (in) { a.in_gamma = in->gamma; a.in_beta = in->beta; a.in_mean = in->mean; a.in_rstd = in->rstd; }
   const WgradPlan p = plan_wgrad(a.M, a.Cout, a.Cg, a.R * a.S, d->dtype, !stem);  // the stem's tile is fixed (64x64)
   float* partial = static_cast<float*>(scratch);
   float* target = dw;
@@ -1283,9 +1418,10 @@ void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, flo
 }
 
 void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s,
-             const char* tag) {
+             const char* tag, const BnIn* in) {
   IgemmArgs a{};
   a.act = x; a.wgt = w; a.out = y; a.partial = bn_partial;
+  if (in) { a.in_gamma = in->gamma; a.in_beta = in->beta; a.in_mean = in->mean; a.in_rstd = in->rstd; }
   a.P = out_dim(d->H, d->pad, d->R, d->stride); a.Q = out_dim(d->W, d->pad, d->S, d->stride);
   a.M = d->N * a.P * a.Q; a.Ncols = d->Cout; a.Ktot = d->R * d->S * d->Cin;
   a.H = d->H; a.W = d->W; a.PS = d->Cin; a.Cg = d->Cin; a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
@@ -1483,4 +1619,43 @@ extern "C" int conv_dgrad_bn_sums(const rn50_conv_desc* d, const void* dy, const
   const BnBwdSums bn{bn_x, gamma, beta, save_mean, save_rstd, sums, addend, relu_mask, addend_mask};
   dgrad_run(d, dy, workspace, dx, &bn, s);
   return launch_status("conv_dgrad_bn_sums");
+}
+
+// ---- convolution whose input is the output of a BN+ReLU layer that is applied on the fly
+static int check_bn_in(const rn50_conv_desc* d, const char* who) {
+  RN50_REQUIRE(d->R == 1 && d->S == 1 && d->stride == 1 && d->pad == 0, RN50_ERR_UNSUPPORTED,
+               "%s: only 1x1 convolutions with stride 1 and no padding take their input through a BN layer", who);
+  RN50_REQUIRE(d->Cin <= 4096, RN50_ERR_UNSUPPORTED, "%s: Cin=%d > 4096", who, d->Cin);
+  return RN50_OK;
+}
+extern "C" int conv_fwd_bn_in(const rn50_conv_desc* d, const void* x, const float* in_gamma, const float* in_beta,
+                              const float* in_mean, const float* in_rstd, const void* w, void* y, float* sums,
+                              size_t sums_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_fwd_bn_in")) return rc;
+  if (int rc = check_bn_in(d, "conv_fwd_bn_in")) return rc;
+  RN50_REQUIRE(x && w && y && in_gamma && in_beta && in_mean && in_rstd, RN50_ERR_INVALID, "conv_fwd_bn_in: null pointer");
+  RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(sums), RN50_ERR_ALIGN,
+               "conv_fwd_bn_in: pointer not 16-byte aligned");
+  RN50_REQUIRE(!sums || sums_bytes >= conv_bn_sums_bytes(d), RN50_ERR_WORKSPACE, "conv_fwd_bn_in: sums %zu < %zu bytes",
+               sums_bytes, conv_bn_sums_bytes(d));
+  const BnIn in{in_gamma, in_beta, in_mean, in_rstd};
+  fwd_run(d, x, w, y, sums, static_cast<hipStream_t>(stream), "conv_fwd", &in);
+  return launch_status("conv_fwd_bn_in");
+}
+extern "C" int conv_wgrad_bn_in(const rn50_conv_desc* d, const void* x, const float* in_gamma, const float* in_beta,
+                                const float* in_mean, const float* in_rstd, const void* dy, float* dw, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_conv(d, "conv_wgrad_bn_in")) return rc;
+  if (int rc = check_bn_in(d, "conv_wgrad_bn_in")) return rc;
+  RN50_REQUIRE(x && dy && dw && in_gamma && in_beta && in_mean && in_rstd, RN50_ERR_INVALID, "conv_wgrad_bn_in: null pointer");
+  RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dw) && aligned16(workspace), RN50_ERR_ALIGN,
+               "conv_wgrad_bn_in: pointer not 16-byte aligned");
+  const size_t need = conv_wgrad_workspace_bytes(d);
+  RN50_REQUIRE(workspace_bytes >= need && (need == 0 || workspace), RN50_ERR_WORKSPACE,
+               "conv_wgrad_bn_in: workspace %zu < %zu bytes", workspace_bytes, need);
+  const BnIn in{in_gamma, in_beta, in_mean, in_rstd};
+  wgrad_run(d, x, dy, dw, workspace, static_cast<hipStream_t>(stream), &in);
+  return launch_status("conv_wgrad_bn_in");
 }

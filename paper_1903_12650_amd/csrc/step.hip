@@ -72,6 +72,9 @@ struct rn50_plan {
   size_t bn_scratch2 = 0;
   std::vector<hipEvent_t> ev_dy, ev_wg;  // per block: its dy tensors are ready / its weight gradients are done
   bool streams_ready = false;            // all of the above exist
+  // conv3 of every block applies conv2's BN+ReLU while it loads its operand (forward and weight gradient):
+  // conv2's normalised output is then never stored.
+  bool fuse_conv3_input = false;
 };
 
 using namespace rn50;
@@ -298,6 +301,15 @@ extern "C" int resnet_plan_prepare(rn50_plan* plan) {
   RN50_REQUIRE(plan, RN50_ERR_INVALID, "resnet_plan_prepare: null plan");
   return ensure_side_stream(plan);
 }
+extern "C" int resnet_plan_fuse_conv3_input(rn50_plan* plan, int on) {
+  clear_error();
+  RN50_REQUIRE(plan, RN50_ERR_INVALID, "resnet_plan_fuse_conv3_input: null plan");
+  for (const rn50::Block& b : plan->blocks)
+    RN50_REQUIRE(!on || plan->units[b.u3].conv.Cin <= 4096, RN50_ERR_UNSUPPORTED,
+                 "resnet_plan_fuse_conv3_input: a conv3 with more than 4096 input channels");
+  plan->fuse_conv3_input = on != 0;
+  return RN50_OK;
+}
 extern "C" int resnet_plan_num_tensors(const rn50_plan* plan) {
   return plan ? static_cast<int>(plan->tensors.size()) : 0;
 }
@@ -425,12 +437,13 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   hipStream_t branch = plan->branch;
   void* bn_ws2 = ws + plan->bn_scratch2;  // the projection branch's own BN scratch
   float* sums2 = static_cast<float*>(bn_ws2);
-  auto bn_after_conv = [&](Unit& u, const void* residual, float* sm, hipStream_t st) {
+  // stats_only: the layer's output is not stored (its consumer applies it on the fly).
+  auto bn_after_conv = [&](Unit& u, const void* residual, float* sm, hipStream_t st, bool stats_only = false) {
     const PartialRows pr = fwd_partial_rows(&u.conv);
     // the residual-add layers record their ReLU decisions: their backward pass then reads one byte per
     // vector instead of z
-    bn_fwd_from_partials(&u.bn, ws + u.y, sm, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual, ws + u.z,
-                         u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd),
+    bn_fwd_from_partials(&u.bn, ws + u.y, sm, pr.num, pr.rows, MP(u.ig), MP(u.ib), residual,
+                         stats_only ? nullptr : ws + u.z, u.bn.mode == 2 ? ws + u.relu_mask : nullptr, F(u.mean), F(u.rstd),
                          run_mean ? run_mean + u.bn_off : nullptr, run_var ? run_var + u.bn_off : nullptr, bn_momentum, st);
   };
   stem_fwd_padded(&u0.conv, ws + plan->xp, W(u0.iw), ws + plan->wp, ws + u0.y, sums, s);
@@ -453,9 +466,18 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
       shortcut = ws + up.z;
     }
     conv_bn(u1, cur, nullptr, sums, s);
-    conv_bn(u2, ws + u1.z, nullptr, sums, s);
-    if (b.up >= 0) (void)hipStreamWaitEvent(s, plan->ev_bjoin, 0);
-    conv_bn(u3, ws + u2.z, shortcut, sums, s);
+    if (plan->fuse_conv3_input) {  // conv3 reads conv2's raw output and applies BN+ReLU in its operand load
+      fwd_run(&u2.conv, ws + u1.z, W(u2.iw), ws + u2.y, sums, s);
+      bn_after_conv(u2, nullptr, sums, s, true);
+      if (b.up >= 0) (void)hipStreamWaitEvent(s, plan->ev_bjoin, 0);
+      const BnIn in{MP(u2.ig), MP(u2.ib), F(u2.mean), F(u2.rstd)};
+      fwd_run(&u3.conv, ws + u2.y, W(u3.iw), ws + u3.y, sums, s, "conv_fwd", &in);
+      bn_after_conv(u3, shortcut, sums, s);
+    } else {
+      conv_bn(u2, ws + u1.z, nullptr, sums, s);
+      if (b.up >= 0) (void)hipStreamWaitEvent(s, plan->ev_bjoin, 0);
+      conv_bn(u3, ws + u2.z, shortcut, sums, s);
+    }
     cur = ws + u3.z;
   }
   const int HW = plan->final_hw * plan->final_hw;
@@ -488,6 +510,8 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     Unit* u;
     const void* in;
     void* dy;
+    bool bn_in;  // `in` is the input of the BN+ReLU layer in front of the convolution, applied on the fly
+    BnIn bn;
   };
   PendingWgrad pending[4];
   int npending = 0, blk = 0;  // blocks processed so far in this backward pass
@@ -499,7 +523,8 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     if (skip_wgrad) npending = 0;
 #endif
     for (int i = 0; i < npending; ++i)
-      wgrad_run(&pending[i].u->conv, pending[i].in, pending[i].dy, G(pending[i].u->iw), ws + plan->wgrad_scratch, side);
+      wgrad_run(&pending[i].u->conv, pending[i].in, pending[i].dy, G(pending[i].u->iw), ws + plan->wgrad_scratch, side,
+                pending[i].bn_in ? &pending[i].bn : nullptr);
     (void)hipEventRecord(plan->ev_wg[blk], side);
     npending = 0;
     ++blk;
@@ -509,7 +534,8 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   // BN, whose output gradient is the block output's gradient under the block's ReLU): for the backward
   // arithmetic that is a BN+ReLU layer with recorded bits.
   auto unit_bn_bwd = [&](Unit& u, const void* in, const void* dz, const void* dz2, void* dres, bool sums_ready,
-                         hipStream_t st, void* wsx, void** dy_out, const uint8_t* outer_bits = nullptr) -> int {
+                         hipStream_t st, void* wsx, void** dy_out, const uint8_t* outer_bits = nullptr,
+                         const BnIn* bn_in = nullptr) -> int {
     void* dy = ws + u.dy;
     // the ReLU mask: recorded bits (residual-add layers) or recomputed from x (BN+ReLU layers)
     const uint8_t* bits = u.bn.mode == 2 ? ws + u.relu_mask : nullptr;
@@ -526,7 +552,7 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
       STEP_TRY(bn_relu_bwd(&u.bn, dz, dz2, ws + u.y, nullptr, bits, MP(u.ig), MP(u.ib), F(u.mean), F(u.rstd), dy, dres,
                            G(u.ig), G(u.ib), wsx, bn_ws_bytes, st));
     }
-    pending[npending++] = PendingWgrad{&u, in, dy};
+    pending[npending++] = PendingWgrad{&u, in, dy, bn_in != nullptr, bn_in ? *bn_in : BnIn{}};
     *dy_out = dy;
     return RN50_OK;
   };
@@ -567,7 +593,12 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
     // shortcut's share is added by conv1's data gradient below, which reads dzo with the recorded bits, and
     // a projection shortcut's BN backward reads dzo with the same bits.
     void* dy3 = nullptr;
-    STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, nullptr, top_sums, s, bn_ws, &dy3));
+    if (plan->fuse_conv3_input) {
+      const BnIn in{MP(u2.ig), MP(u2.ib), F(u2.mean), F(u2.rstd)};
+      STEP_TRY(unit_bn_bwd(u3, ws + u2.y, dzo, dzo2, nullptr, top_sums, s, bn_ws, &dy3, nullptr, &in));
+    } else {
+      STEP_TRY(unit_bn_bwd(u3, ws + u2.z, dzo, dzo2, nullptr, top_sums, s, bn_ws, &dy3));
+    }
     const void* shortcut_grad = dzo;
     const uint8_t* shortcut_mask = ws + u3.relu_mask;
     if (b.up >= 0) {  // the projection's backward pass runs beside the main branch, on its own stream

@@ -29,8 +29,13 @@ int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d);  // most rows any til
 // bn_partial (null: none): float[3][Cout][num] = shift, sum(y - shift), sum((y - shift)^2) per tile.
 void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, void* wp, void* y, float* bn_partial,
                      hipStream_t s);
+// A BN+ReLU layer applied to a convolution's input on the fly (1x1, stride 1 convolutions only): its parameters
+// and saved statistics, float[Cin] each.
+struct BnIn {
+  const float *gamma, *beta, *mean, *rstd;
+};
 void fwd_run(const rn50_conv_desc* d, const void* x, const void* w, void* y, float* bn_partial, hipStream_t s,
-             const char* tag = "conv_fwd");
+             const char* tag = "conv_fwd", const BnIn* in = nullptr);
 // The BN layer (with ReLU) whose output gradient a data gradient produces: x is that
 // layer's input [N*H*W][Cin]; partial receives float[2][Cin][num] = sum(g), sum(g * xhat) per tile.
 // addend (or null): a second branch of the gradient, [N*H*W][Cin], added to the data gradient before it
@@ -55,7 +60,8 @@ struct TransposeEntry {
 void transpose_batch_run(const std::vector<TransposeEntry>& list, int dtype, const void* src_arena, void* dst_arena,
                          hipStream_t s);
 size_t wgrad_partial_bytes(const rn50_conv_desc* d);
-void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s);
+void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, float* dw, void* scratch, hipStream_t s,
+               const BnIn* in = nullptr);
 
 // bn.hip: the part of the forward / backward pass that follows the sums
 void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* partial, int nrows, int rpp,

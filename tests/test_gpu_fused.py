@@ -226,3 +226,53 @@ def test_fused_abi_errors(rn):
     assert e.value.code == -1
     torch.cuda.synchronize()
     assert bool((wsb == 0x5a).all()) and bool((sums == 0x5a).all()) and bool((dx == 3.0).all())
+
+
+# ------------------------------------------------- BN+ReLU applied in the consumer convolution's operand load
+BN_IN_SHAPES = [(2, 9, 7, 24, 40), (3, 14, 14, 64, 256), (40, 14, 14, 256, 1024), (2, 8, 8, 72, 136), (40, 7, 7, 512, 2048),
+                (1, 5, 5, 8, 8)]
+
+
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", BN_IN_SHAPES)
+def test_conv_bn_in_equals_the_unfused_pair_and_the_oracle(rn, mode_name, shape):
+    """conv_fwd_bn_in / conv_wgrad_bn_in read the BN layer's INPUT and apply BN+ReLU on the fly: bit for bit the
+    convolution of the tensor bn_relu_fwd stores, and that tensor's convolution by the oracle at the mode's bar."""
+    N, H, W, C, K = shape
+    bf = mode_name == "bf16"
+    if not bf and (C % 4 or K % 4):
+        pytest.skip("channel counts must be multiples of the 16-byte vector")
+    if bf and (C % 8 or K % 8):
+        pytest.skip("channel counts must be multiples of the 16-byte vector")
+    x, w, dy = inputs(mode_name, synth.activation_nhwc(SEED, "x", N, C, H, W) * 1.5 + 0.3,
+                      synth.conv_weight_krsc(SEED, "w", K, C, 1, 1), synth.activation_nhwc(SEED, "dy", N, K, H, W))
+    gamma = (1.0 + 0.2 * synth.normal(SEED, "g", (C,))).astype(np.float32)
+    beta = (0.1 * synth.normal(SEED, "b", (C,))).astype(np.float32)
+    xd, wd, dyd, gd, bd = dev(x, bf), dev(w, bf), dev(dy, bf), dev(gamma), dev(beta)
+    z, mean, rstd = rn.bn_relu_fwd(xd, gd, bd, None, 1e-5, 1)
+    y_ref = rn.conv_fwd(z, wd, 1, 0)
+    dw_ref = rn.conv_wgrad(z, dyd, wd.shape, 1, 0)
+    y, handle = rn.conv_fwd_bn_in(xd, gd, bd, mean, rstd, wd, with_sums=True)
+    dw = rn.conv_wgrad_bn_in(xd, gd, bd, mean, rstd, dyd, wd.shape)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_ref), "forward differs from the convolution of the stored BN output"
+    assert torch.equal(dw, dw_ref), "weight gradient differs from that of the stored BN output"
+    assert_close(y, orc.conv_fwd(host(z), host(wd), 1, 0), TOL[mode_name], "y")
+    assert_close(dw, orc.conv_wgrad(host(z), host(dyd), tuple(wd.shape), 1, 0), TOL[mode_name], "dw")
+    # the sums it leaves for the BN layer behind it are those of conv_fwd_bn_sums on the stored tensor
+    g2, b2 = dev(np.ones(K, np.float32)), dev(np.zeros(K, np.float32))
+    z2, m2, r2 = rn.bn_relu_fwd_from_sums(y, handle, g2, b2)
+    y3, h3 = rn.conv_fwd_bn_sums(z, wd, 1, 0)
+    z3, m3, r3 = rn.bn_relu_fwd_from_sums(y3, h3, g2, b2)
+    assert torch.equal(z2, z3) and torch.equal(m2, m3) and torch.equal(r2, r3)
+
+
+def test_conv_bn_in_rejects_other_filters(rn):
+    x = torch.zeros((1, 8, 8, 16), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((16, 3, 3, 16), dtype=torch.bfloat16, device="cuda")
+    v = torch.ones(16, device="cuda")
+    d = rn.ConvDesc(1, 8, 8, 16, 16, 3, 3, 1, 1, rn.BF16)
+    import ctypes
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = rn.raw.conv_fwd_bn_in(ctypes.byref(d), p(x), p(v), p(v), p(v), p(v), p(w), p(x), None, ctypes.c_size_t(0), None)
+    assert rc == -2 and b"1x1" in rn.raw.rn50_last_error()

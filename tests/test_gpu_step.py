@@ -352,6 +352,35 @@ def test_step_on_a_caller_stream_matches_the_default_stream(rn):
     assert torch.isfinite(outs[0][2][: plan.sizes[0]]).all()
 
 
+@pytest.mark.parametrize("mode", ["bf16", "f32"])
+def test_step_with_conv3_input_fusion_gives_the_same_bits(rn, mode):
+    """With conv3 applying conv2's BN+ReLU in its operand load (forward and weight gradient) the step's
+    weights, momenta, gradients, loss and logits are bit for bit those of the step that stores conv2's
+    normalised output: two blocks per stage, ragged widths, two steps in a row."""
+    bf = mode == "bf16"
+    N, hw, widths, blocks, stem, classes = 4, 64, (8, 16, 24, 40), (2, 1, 2, 1), 8, 10
+    outs = []
+    for fused in (False, True):
+        plan = rn.ResnetPlan(N, rn.BF16 if bf else rn.F32, hw, classes, widths, blocks, stem, 4)
+        plan.fuse_conv3_input(fused)
+        table = net.param_table(widths, blocks, stem, classes, 3, 4)
+        M = torch.zeros(plan.arena_elems)
+        for off, p in zip(plan.offsets, synth.params_from_table(SEED, table)):
+            M[off:off + p.size] = torch.from_numpy(p.ravel())
+        M = M.cuda(); V = torch.zeros_like(M); G = torch.zeros_like(M); Mod = M.to(torch.bfloat16) if bf else M
+        img = dev(synth.activation_nhwc(SEED, "img", N, 3, hw, hw), bf)
+        lab = dev(synth.labels(SEED, "lab", N, classes))
+        ws = torch.full((plan.workspace_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+        loss = torch.zeros(1, device="cuda"); logits = torch.zeros(N, classes, device="cuda")
+        for _ in range(2):
+            rn.resnet_step(plan, img, lab, M, V, G, Mod, 0.5, ws, loss_out=loss, logits_out=logits)
+        torch.cuda.synchronize()
+        outs.append((M.clone(), V.clone(), G.clone(), Mod.clone(), loss.clone(), logits.clone()))
+    for name, a, b in zip(("master", "velocity", "grads", "model", "loss", "logits"), *outs):
+        assert torch.equal(a, b), name
+    assert torch.isfinite(outs[0][2]).all()
+
+
 def test_step_resnet50_batch256_bf16_equals_the_chain(rn):
     """The large-batch configuration (batch 256, 6.4 times the measured one: tensors of up to 411 MB, tens
     of thousands of output tiles): resnet_step is bit for bit the operation-by-operation chain, whose
