@@ -577,6 +577,10 @@ static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             const float* gamma, const float* beta, const void* residual, void* y,
                             uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
                             float momentum, const float* partial, int nrows, int rpp, hipStream_t s) {
+#ifdef RN50_TUNING  // what-if measurement: the step without its finalize launches (results are then wrong)
+  static const bool skip_fin = getenv("RN50_SKIP_BN_FINALIZE") != nullptr;
+  if (!skip_fin)
+#endif
   RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), d->eps, save_mean, save_rstd, rm, rv, momentum);
   if (!y) return;  // statistics only: the consumer applies the layer while it loads its operand
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnApplyGroups);
@@ -601,6 +605,10 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             const float* gamma, const float* beta, const float* mean, const float* rstd,
                             void* dx, void* dres, float* dgamma, float* dbeta, const float* partial,
                             int nrows, hipStream_t s) {
+#ifdef RN50_TUNING
+  static const bool skip_fin = getenv("RN50_SKIP_BN_FINALIZE") != nullptr;
+  if (!skip_fin)
+#endif
   RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnBwdApplyGroups);
 #define RN50_BWD_APPLY(DZ2, ZK)                                                                                  \

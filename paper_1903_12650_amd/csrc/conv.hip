@@ -1227,6 +1227,10 @@ static void launch_wgrad(WgradArgs a, const WgradPlan& p, float* dw, float* part
   else launch_wgrad_cfg<T, 64, 64>(a, p.splits, s);
   if (p.splits > 1) {
     const int64_t n = a.split_stride;
+#ifdef RN50_TUNING  // what-if measurement: the weight gradients without their reduction launches (results wrong)
+    static const bool skip_red = getenv("RN50_SKIP_SPLITK_REDUCE") != nullptr;
+    if (!skip_red)
+#endif
     RN50_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 64))), dim3(256), 0, s, partial, p.splits, n, dw);
   }
 }

@@ -33,8 +33,8 @@ MFMA_F32_PEAK_TFLOPS = 157.3
 # copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
 # dirty in L2 are written back during later kernels.  conv_wgrad includes its reduction pass.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "conv_fwd": 40.45e6, "conv_dgrad": 63.87e6, "conv_wgrad": 63.98e6, "bn_apply": 42.55e6,
-    "bn_bwd_reduce": 75.67e6, "bn_bwd_apply": 51.85e6, "lars_update": 383.55e6,
+    "conv_fwd": 39.89e6, "conv_dgrad": 63.52e6, "conv_wgrad": 59.75e6, "bn_apply": 42.55e6,
+    "bn_bwd_reduce": 75.71e6, "bn_bwd_apply": 51.85e6, "lars_update": 383.53e6,
 }
 
 # Kernel classes of the step: (class, launch tags whose durations it sums, tag whose launches it is counted in).
@@ -227,3 +227,30 @@ def roofline(plan, tagged_ms, steps):
     rec["kernel_time_per_step_ms"] = sum(c["time_per_step_ms"] for c in classes)
     rec["classes"] = classes
     return rec
+
+
+def main():
+    """python -m paper_1903_12650_amd.roofline <file with bench.py's JSON line> ...   prints the class table of each."""
+    import json
+    import sys
+    print("%-26s %-16s %8s %8s %9s %6s %14s %8s %12s %8s" % ("workload", "class", "launches", "avg us", "ms/step", "bound",
+                                                             "achieved", "of peak", "traffic MB", "x alg."))
+    for path in sys.argv[1:]:
+        line = [l for l in open(path).read().splitlines() if l.startswith("{")][-1]
+        r = json.loads(line)
+        wl = "step, batch %d, %s" % (r["config"]["global_batch"], r["dtype"])
+        for c in r["roofline"]["classes"]:
+            if c.get("bound"):
+                tr = c.get("traffic")
+                print("%-26s %-16s %8d %8.1f %9.3f %6s %9.0f %-4s %7.1f%% %12s %8s"
+                      % (wl, c["class"], c["launches_per_step"], c["avg_launch_us"], c["time_per_step_ms"], c["bound"],
+                         c["achieved"], c["unit"], 100 * c["frac"], "%.1f" % (tr / 1e6) if tr else "-",
+                         "%.2f" % (tr / c["algorithmic_bytes_per_launch"]) if tr else "-"))
+            else:
+                print("%-26s %-16s %8d %8s %9.3f" % (wl, c["class"], c["launches_per_step"], "", c["time_per_step_ms"]))
+        print("%-26s %-16s %8s %8s %9.3f   (step: %.3f ms; streams overlap)"
+              % (wl, "all classes", "", "", r["roofline"]["kernel_time_per_step_ms"], r["ms_per_step"]))
+
+
+if __name__ == "__main__":
+    main()
