@@ -64,6 +64,10 @@ int rn50_version(void);
 int rn50_profile_begin(const char* kernel_tag, int max_records);
 void rn50_profile_pause(int paused);
 int rn50_profile_end(float* ms_out, int capacity);
+/* As rn50_profile_end; also writes to start_ms_out (host, capacity floats; may be NULL) when each
+ * recorded dispatch began, in milliseconds after the begin of the first recorded one: with the
+ * durations, the timeline of the step's launches on all of its streams. */
+int rn50_profile_end_timeline(float* ms_out, float* start_ms_out, int capacity);
 const char* rn50_profile_tag(int record);
 
 /* ------------------------------------------------------------------ convolution

@@ -11,7 +11,7 @@ import torch
 
 __all__ = ["F32", "BF16", "Rn50Error", "lib_path", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd",
            "bn_relu_bwd", "maxpool_fwd", "maxpool_bwd", "avgpool_fwd", "avgpool_bwd", "fc_fwd", "fc_bwd",
-           "xent_fwd_bwd", "lars_update", "lars_update_noalloc", "LarsTable", "profile_begin", "profile_pause", "profile_end", "profile_tags", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
+           "xent_fwd_bwd", "lars_update", "lars_update_noalloc", "LarsTable", "profile_begin", "profile_pause", "profile_end", "profile_end_timeline", "profile_tags", "ResnetPlan", "resnet_step", "ConvDesc", "BnDesc",
            "conv_fwd_workspace_bytes", "conv_dgrad_workspace_bytes", "conv_wgrad_workspace_bytes",
            "bn_relu_fwd_workspace_bytes", "bn_relu_bwd_workspace_bytes", "raw", "conv_bn_sums_bytes",
            "conv_fwd_bn_sums", "conv_fwd_bn_in", "conv_wgrad_bn_in", "bn_relu_fwd_from_sums", "relu_mask_like", "conv_dgrad_bn_sums", "bn_relu_bwd_from_sums",
@@ -578,6 +578,17 @@ def profile_end():
         _check(n)
     profile_end._n = min(n, cap)
     return [float(buf[i]) for i in range(min(n, cap))]
+
+
+def profile_end_timeline():
+    """(start ms after the first recorded launch began, duration ms) of every recorded launch, in launch order."""
+    cap = getattr(profile_begin, "_cap", 0)
+    buf, at = (ctypes.c_float * max(cap, 1))(), (ctypes.c_float * max(cap, 1))()
+    n = raw.rn50_profile_end_timeline(buf, at, cap)
+    if n < 0:
+        _check(n)
+    profile_end._n = min(n, cap)
+    return [(float(at[i]), float(buf[i])) for i in range(min(n, cap))]
 
 
 def profile_tags():

@@ -55,7 +55,12 @@ extern "C" int rn50_profile_begin(const char* kernel_tag, int max_records) {
   return RN50_OK;
 }
 extern "C" void rn50_profile_pause(int paused) { rn50::g_prof_paused = paused != 0; }
-extern "C" int rn50_profile_end(float* ms_out, int capacity) {
+static int profile_end_impl(float* ms_out, float* start_ms_out, int capacity);
+extern "C" int rn50_profile_end(float* ms_out, int capacity) { return profile_end_impl(ms_out, nullptr, capacity); }
+extern "C" int rn50_profile_end_timeline(float* ms_out, float* start_ms_out, int capacity) {
+  return profile_end_impl(ms_out, start_ms_out, capacity);
+}
+static int profile_end_impl(float* ms_out, float* start_ms_out, int capacity) {
   using namespace rn50;
   g_prof_on = false;
   const size_t n = g_prof_used;
@@ -66,6 +71,11 @@ extern "C" int rn50_profile_end(float* ms_out, int capacity) {
   for (size_t i = 0; i < n && ms_out && w < static_cast<size_t>(capacity); ++i) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]) != hipSuccess) ms = -1.f;
+    if (start_ms_out) {  // begin of this launch after the begin of the first recorded one
+      float at = 0.f;
+      if (hipEventElapsedTime(&at, g_prof_events[0], g_prof_events[2 * i]) != hipSuccess) at = -1.f;
+      start_ms_out[w] = at;
+    }
     ms_out[w++] = ms;
   }
   g_prof_used = 0;

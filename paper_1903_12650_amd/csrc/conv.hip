@@ -215,9 +215,19 @@ template <int BM, int BN, int NW>
 constexpr int igemm_ring() {
   return (NW == 4 && 3 * (BM + BN) * 128 > 80 * 1024) ? 2 : 3;
 }
-template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false, bool BNIN = false>
+//
+// HALO: compiled for a 3x3 filter with stride 1 and padding 1 (output pixel m reads input pixels m + dy*W + dx,
+// dy, dx in -1..1, of the same flat pixel index space).  The nine taps of a tile then read one contiguous run of
+// BM + 2W + 2 input pixels: that run is brought into LDS once per 128-byte channel chunk (instead of a gathered
+// BM-row tile per tap: nine times the operand traffic), and the fragment reads of tap (dy, dx) start dy*W + dx rows
+// further down in it.  Taps that fall off the image (or into the neighbouring image of the run) are zeroed in
+// the fragment registers, by a per-lane bit mask computed once.  The weights go through a ring of three
+// BN-row tiles, two taps ahead; the next chunk's run is loaded one pass per tap while the
+// current one is in use, so that every step issues the same number of loads (the load waits count them).
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool LIN = false, bool BNIN = false, bool HALO = false>
 __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) {
   static_assert(!BNIN || (LIN && MODE == 0), "the input-side BN is compiled for the linear forward kernel only");
+  static_assert(!HALO || (!LIN && !BNIN), "the halo main loop is a kernel of its own");
   constexpr int NW = WM * WN, NT = 64 * NW;
   constexpr int V = 16 / sizeof(T);
   constexpr int BK = 128 / sizeof(T);
@@ -416,6 +426,115 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) 
   // its own loads of chunk kc (those of the later chunks may still be in flight), then the barrier: behind it
   // every wave's part of chunk kc is in LDS and every wave is done reading chunk kc-1, whose buffer the loads
   // of chunk kc+NSTAGE-1 issued next will overwrite.
+  if constexpr (HALO) {
+    constexpr int NSB = 3;                       // weight tiles in the ring
+    const int Wd = a.W;
+    const int NA = (BM + 2 * Wd + 2 + RPL - 1) / RPL;  // load passes of one run (the host checked NA <= 8)
+    const uint32_t run_bytes = static_cast<uint32_t>(NA) * (RPL * 128);
+    const int cpt = a.cpt;
+    const uint32_t b_base = (cpt > 1 ? 2u : 1u) * run_bytes;  // two runs when there is a next chunk to prefetch
+    const uint32_t dump = b_base + NSB * BN * 128;          // where the loads that only keep the count go (zeros)
+    const uint32_t lds0 = wave_dst;                           // LDS address of smem + this wave's 1 KB share of a pass
+    const int q0 = m0 - Wd - 1 + lrow;                        // input pixel of this thread's row in pass 0 of a run
+    auto load_run_pass = [&](int j, int cc, int buf) __attribute__((always_inline)) {
+      const int q = q0 + RPL * j;
+      const bool ok = static_cast<unsigned>(q) < static_cast<unsigned>(a.M) && (!ragged || cc * BK + piece * V < a.Cg);
+      const uint32_t off = ok ? static_cast<uint32_t>(q * a.PS + piece * V) * sizeof(T) : kOob;
+      buffer_load16_to_lds(rsA, lds0 + static_cast<uint32_t>(buf) * run_bytes + static_cast<uint32_t>(j) * (RPL * 128), off,
+                           __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cc) * 128u));
+    };
+    auto load_b_tile = [&](int stage, int cc, int tap, bool live) __attribute__((always_inline)) {
+      const bool cval = live && (!ragged || cc * BK + piece * V < a.Cg);
+      const uint32_t sob = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(tap * a.Cg) * static_cast<uint32_t>(sizeof(T)) +
+                                                          static_cast<uint32_t>(cc) * 128u);
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+        buffer_load16_to_lds(rsB, lds0 + b_base + static_cast<uint32_t>(stage) * (BN * 128) + i * (RPL * 128),
+                             cval ? b_row[i] : kOob, sob);
+    };
+    auto load_nothing = [&]() __attribute__((always_inline)) { buffer_load16_to_lds(rsA, lds0 + dump, kOob, 0); };
+    // Which taps of which rows exist: bit `tap` of vmask[i] for this lane's row of the wave's row block i.
+    uint32_t vmask[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
+      const bool ok = m < a.M;
+      const int mm = ok ? m : 0;
+      const int t = static_cast<int>(fdiv(static_cast<uint32_t>(mm), a.div_w[0]));
+      const int x = mm - t * a.Q;
+      const int y = t - static_cast<int>(fdiv(static_cast<uint32_t>(t), a.div_h[0])) * a.P;
+      uint32_t bits = 0;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int dyo = MODE == 0 ? tap / 3 - 1 : 1 - tap / 3, dxo = MODE == 0 ? tap % 3 - 1 : 1 - tap % 3;
+        const bool v = ok && static_cast<unsigned>(y + dyo) < static_cast<unsigned>(a.H) &&
+                       static_cast<unsigned>(x + dxo) < static_cast<unsigned>(a.W);
+        bits |= v ? (1u << tap) : 0u;
+      }
+      vmask[i] = bits;
+    }
+    auto compute_tap = [&](int buf, int bstage, int tap, int dyo, int dxo) __attribute__((always_inline)) {
+      const int rl = (lane & 31) + (dyo + 1) * Wd + (dxo + 1);  // row of the run this lane's row 0 reads
+      const int swz = (rl >> 1) & 7;
+      int aoff[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) aoff[kk] = rl * 128 + (((2 * kk + (lane >> 5)) ^ swz) << 4);
+      uint32_t mk[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) mk[i] = ((vmask[i] >> tap) & 1u) ? 0xffffffffu : 0u;
+      const unsigned char* sa = smem + static_cast<uint32_t>(buf) * run_bytes + wm * (BM / WM) * 128;
+      const unsigned char* sb = smem + b_base + bstage * (BN * 128) + wn * (BN / WN) * 128;
+      Vec16 fa[4][TM], fb[4][TN];
+      auto read_frags = [&](int kk) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[kk][i].u = *reinterpret_cast<const uint4*>(sa + i * 32 * 128 + aoff[kk]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[kk][j].u = *reinterpret_cast<const uint4*>(sb + j * 32 * 128 + frag_off[kk]);
+      };
+      constexpr int AH = (TM + TN <= 3) ? 4 : 1;
+#pragma unroll
+      for (int kk = 0; kk < AH; ++kk) read_frags(kk);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk + AH < 4) {
+          read_frags(kk + AH);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          fa[kk][i].u.x &= mk[i]; fa[kk][i].u.y &= mk[i]; fa[kk][i].u.z &= mk[i]; fa[kk][i].u.w &= mk[i];
+#pragma unroll
+          for (int j = 0; j < TN; ++j) Mma<T>::run(fb[kk][j], fa[kk][i], acc[i][j]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // Prologue: the first run, the weight tiles of steps 0 and 1.  Every step of the loop then issues RB + 1
+    // loads (the weight tile two steps ahead; one pass of the next chunk's run, or a load of nothing), so at its
+    // top "at most RB + 1 outstanding" means: everything up to the step before the previous one has landed.
+    for (int j = 0; j < NA; ++j) load_run_pass(j, 0, 0);
+    load_b_tile(0, 0, 0, true);
+    load_b_tile(1, 0, 1, true);
+    load_nothing();
+    int bstage = 0;
+    for (int cc = 0; cc < cpt; ++cc) {
+      const int buf = cpt > 1 ? (cc & 1) : 0;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        wait_loads_then_barrier<RB + 1>();
+        const int tap2 = (tap + 2) % 9, cc2 = cc + (tap + 2 >= 9 ? 1 : 0);
+        load_b_tile(bstage >= 1 ? bstage - 1 : NSB - 1, cc2, tap2, cc2 < cpt);  // the tile of step - 1: free again
+        if (tap < NA && cc + 1 < cpt) load_run_pass(tap, cc + 1, buf ^ 1);
+        else load_nothing();
+        compute_tap(buf, bstage, tap, MODE == 0 ? tap / 3 - 1 : 1 - tap / 3, MODE == 0 ? tap % 3 - 1 : 1 - tap % 3);
+        bstage = bstage == NSB - 1 ? 0 : bstage + 1;
+      }
+    }
+    // (the loads still in flight carry nothing and land in the dump area or in weight tiles nobody reads again;
+    // they are waited for before the output stage reuses LDS)
+    wait_loads_then_barrier<0>();
+  } else {
   tap_setup();
   float* const in_tab = reinterpret_cast<float*>(smem + (BNIN ? a.in_lds : 0));  // [2][nchunks * BK]: scale, bias
   if constexpr (BNIN) {
@@ -453,6 +572,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) 
     }
     compute(stage);
     stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+  }
   }
   __builtin_amdgcn_s_barrier();  // the output tile below reuses the pipeline buffers
   asm volatile("" ::: "memory");
@@ -1047,6 +1167,30 @@ static void launch_igemm_mode(IgemmArgs a, const char* tag, int64_t grid, hipStr
   }
   RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, LIN, BNIN>), dim3(static_cast<unsigned>(grid)), dim3(NT), lds, s, a);
 }
+// The halo kernel (3x3, stride 1, padding 1): LDS bytes of its main loop for an image width, or 0 when the shape
+// does not fit it (a run of more than 8 load passes, more LDS than a compute unit has).
+static bool igemm_halo_shape(const IgemmArgs& a);
+constexpr int kHaloLdsMax = 152 * 1024;  // (the kernel's static arrays come on top; a compute unit has 160 KB)
+template <int BM, int BN, int WM, int WN>
+static int halo_lds_bytes(int W, int cpt) {
+  constexpr int NW = WM * WN, RPL = NW * 8;
+  const int passes = (BM + 2 * W + 2 + RPL - 1) / RPL;
+  if (passes > 8) return 0;
+  const int bytes = (cpt > 1 ? 2 : 1) * passes * RPL * 128 + 3 * BN * 128 + NW * 1024;
+  return bytes <= kHaloLdsMax ? bytes : 0;
+}
+template <typename T, int BM, int BN, int WM, int WN, int MODE>
+static void launch_igemm_halo(IgemmArgs a, const char* tag, int64_t grid, int main_lds, hipStream_t s) {
+  constexpr int NT = 64 * WM * WN;
+  constexpr int es = static_cast<int>(sizeof(T));
+  constexpr int out_tile = BM * (BN * 4 + 16);
+  constexpr int col_sums = (NT / (BN * es / 16)) * 2 * BN * 4;
+  constexpr int out_need = out_tile > col_sums ? out_tile : col_sums;
+  static std::once_flag once;
+  std::call_once(once, [] { allow_big_lds(igemm_kernel<T, BM, BN, WM, WN, MODE, false, false, true>, kHaloLdsMax); });
+  const int lds = main_lds > out_need ? main_lds : out_need;
+  RN50_LAUNCH(tag, (igemm_kernel<T, BM, BN, WM, WN, MODE, false, false, true>), dim3(static_cast<unsigned>(grid)), dim3(NT), lds, s, a);
+}
 template <typename T, int BM, int BN, int WM, int WN>
 static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   a.ntn = static_cast<int>(ceil_div(a.Ncols, BN));
@@ -1066,6 +1210,12 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
     if (a.mode == 0 && a.in_gamma) launch_igemm_mode<T, BM, BN, WM, WN, 0, true, true>(a, tag, grid, s);
     else if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, true>(a, tag, grid, s);
     else launch_igemm_mode<T, BM, BN, WM, WN, 1, true>(a, tag, grid, s);
+    return;
+  }
+  const bool halo_shape = igemm_halo_shape(a);
+  if (const int halo_lds = halo_shape ? halo_lds_bytes<BM, BN, WM, WN>(a.W, a.cpt) : 0) {
+    if (a.mode == 0) launch_igemm_halo<T, BM, BN, WM, WN, 0>(a, tag, grid, halo_lds, s);
+    else launch_igemm_halo<T, BM, BN, WM, WN, 1>(a, tag, grid, halo_lds, s);
     return;
   }
   if (a.mode == 0) launch_igemm_mode<T, BM, BN, WM, WN, 0, false>(a, tag, grid, s);
@@ -1109,11 +1259,36 @@ static TileShape igemm_tile(int64_t M, int Ncols, int chunks, bool dgrad, bool s
   if (chunks >= 8 && groups(128, 64) >= kCover) return TileShape{128, 64, 2, 2};
   return TileShape{64, 64, 2, 2};
 }
+// The tile of a 3x3 / stride 1 / padding 1 layer, which runs the halo main loop (forward and data gradient
+// alike): fitted to sweeps of the compiled shapes over ResNet-50's four such layers at batch 40 and 256.  The
+// eight-wave 256x128 tile once it gives three quarters of the compute units a workgroup, else 128x64 while that
+// leaves one and a half workgroups per compute unit, else 64x64 (the 128x128 tile never won: its two runs and
+// three weight tiles leave room for one workgroup per compute unit only).
+static TileShape igemm_halo_tile(int64_t M, int Ncols) {
+  auto groups = [&](int bm, int bn) { return ceil_div(M, bm) * ceil_div(Ncols, bn); };
+  if (Ncols > 64 && groups(256, 128) >= 192) return TileShape{256, 128, 4, 2};
+  if (groups(128, 64) >= 384) return TileShape{128, 64, 2, 2};
+  return TileShape{64, 64, 2, 2};
+}
+// A 3x3 filter with stride 1 and padding 1 (the gathered tensor and the output have the same pixel grid): the
+// layers of the halo main loop.  The launch and the callers that size the batch-norm sums (one row per row tile)
+// both go through halo_filter / igemm_halo_tile, so they agree on the tile.
+static bool halo_filter(int R, int S, int stride, int pad) {
+#ifdef RN50_TUNING  // tuning builds only: a forced tile shape, or RN50_NO_HALO, send these layers down the general path
+  static const bool off = getenv("RN50_IGEMM_TILE") != nullptr || getenv("RN50_NO_HALO") != nullptr;
+  if (off) return false;
+#endif
+  return R == 3 && S == 3 && stride == 1 && pad == 1;
+}
+static bool igemm_halo_shape(const IgemmArgs& a) {
+  return halo_filter(a.R, a.S, a.stride, a.pad) && !a.pair && a.H == a.P && a.W == a.Q;
+}
 template <typename T>
 static void launch_igemm(const IgemmArgs& a, const char* tag, hipStream_t s) {
   const bool classes = a.mode == 1 && a.stride == 2;
   const int64_t rows = classes ? static_cast<int64_t>(a.M / (a.P * a.Q)) * ((a.P + 1) / 2) * ((a.Q + 1) / 2) : a.M;
-  const TileShape t = igemm_tile(rows, a.Ncols, a.R * a.S * a.cpt, a.mode == 1, classes, a.R * a.S > 1 ? 4 : 1);
+  TileShape t = igemm_tile(rows, a.Ncols, a.R * a.S * a.cpt, a.mode == 1, classes, a.R * a.S > 1 ? 4 : 1);
+  if (igemm_halo_shape(a)) t = igemm_halo_tile(a.M, a.Ncols);
 #define X(BM, BN, WM, WN) if (t.bm == BM && t.bn == BN && t.wm == WM && t.wn == WN) return launch_igemm_cfg<T, BM, BN, WM, WN>(a, tag, s);
   RN50_IGEMM_SHAPES(X)
 #undef X
@@ -1312,7 +1487,8 @@ PartialRows fwd_partial_rows(const rn50_conv_desc* d) {
   const int64_t M = static_cast<int64_t>(d->N) * out_dim(d->H, d->pad, d->R, d->stride) * out_dim(d->W, d->pad, d->S, d->stride);
   // the chunk count as the launch computes it (the bf16 stem runs as 4 taps of one chunk, the float stem as 7)
   const int chunks = is_stem(d) ? (d->dtype == RN50_BF16 ? 4 : 7) : d->R * d->S * chunks_per_tap(d->Cin, d->dtype);
-  const int bm = igemm_tile(M, d->Cout, chunks, false, false).bm;
+  const int bm = halo_filter(d->R, d->S, d->stride, d->pad) ? igemm_halo_tile(M, d->Cout).bm
+                                                            : igemm_tile(M, d->Cout, chunks, false, false).bm;
   return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
 }
 int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d) {
@@ -1323,7 +1499,9 @@ int64_t dgrad_partial_rows_bound(const rn50_conv_desc* d) {
 PartialRows dgrad_partial_rows(const rn50_conv_desc* d) {
   if (d->stride == 2) return class_tile_rows(d);
   const int64_t M = static_cast<int64_t>(d->N) * d->H * d->W;
-  const int bm = igemm_tile(M, d->Cin, d->R * d->S * chunks_per_tap(d->Cout, d->dtype), true, false).bm;
+  const int bm = halo_filter(d->R, d->S, d->stride, d->pad)
+                     ? igemm_halo_tile(M, d->Cin).bm
+                     : igemm_tile(M, d->Cin, d->R * d->S * chunks_per_tap(d->Cout, d->dtype), true, false).bm;
   return PartialRows{bm, static_cast<int>(ceil_div(M, bm))};
 }
 

@@ -138,3 +138,24 @@ def test_conv_error_codes(rn):
     with pytest.raises(rn.Rn50Error) as e:
         rn.conv_dgrad(torch.zeros((1, 8, 8, 64), dtype=torch.bfloat16, device="cuda"), w3, x3.shape, 2, 3)
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("mode_name", ["f32", "bf16"])
+def test_3x3_taps_never_reach_into_the_neighbouring_image(rn, mode_name):
+    """The 3x3 / stride 1 kernels read one contiguous run of pixels per tile, which spans image borders: with one
+    image of the batch all NaN (forward: of x; data gradient: of dy), the other images' outputs are bit for bit
+    those of the batch where that image is zero."""
+    bf = mode_name == "bf16"
+    N, H, W, C, K = 3, 6, 10, (64 if bf else 32), (64 if bf else 32)
+    x, w, dy = inputs(mode_name, synth.activation_nhwc(SEED, "x", N, C, H, W), synth.conv_weight_krsc(SEED, "w", K, C, 3, 3),
+                      synth.activation_nhwc(SEED, "dy", N, K, H, W))
+    wd = dev(w, bf)
+    outs = []
+    for poison in (0.0, float("nan")):
+        xd, dyd = dev(x, bf).clone(), dev(dy, bf).clone()
+        xd[1] = poison
+        dyd[1] = poison
+        outs.append((rn.conv_fwd(xd, wd, 1, 1), rn.conv_dgrad(dyd, wd, xd.shape, 1, 1)))
+    for a, b in zip(*outs):
+        assert torch.equal(a[0], b[0]) and torch.equal(a[2], b[2])
+        assert torch.isnan(b[1]).any()

@@ -27,7 +27,9 @@ FUSED_SHAPES = [(2, 14, 14, 64, 64, 1, 1, 0), (3, 13, 9, 24, 40, 3, 1, 1), (2, 2
                 (2, 9, 7, 16, 16, 1, 2, 0),
                 # 3x3 stride 1 pad 1, whole channel chunks, tiles spanning images
                 (3, 9, 9, 64, 64, 3, 1, 1), (2, 5, 12, 128, 72, 3, 1, 1), (5, 7, 21, 192, 64, 3, 1, 1),
-                (7, 4, 48, 64, 128, 3, 1, 1), (40, 14, 14, 64, 64, 3, 1, 1)]
+                (7, 4, 48, 64, 128, 3, 1, 1), (40, 14, 14, 64, 64, 3, 1, 1),
+                # ... large enough for the eight-wave 256x128 tile (forward / data gradient): the sums' row count follows
+                (16, 28, 28, 64, 512, 3, 1, 1), (16, 28, 28, 512, 64, 3, 1, 1)]
 
 
 def _vec(tag, C, scale, shift):

@@ -32,10 +32,6 @@ def test_config1_bottleneck_block_f32(rn):
                    np.zeros(s[0], np.float32)]
     T = synth.activation_nhwc(SEED, "T", N, 4 * Wd, H, H)
     out_o, tape = net.bottleneck_fwd(x, params, 1, True)
-    dx_o, grads_o = net.bottleneck_bwd(T, tape)
-    wds = net.lars_hyper(table, 5e-5)
-    vel = [np.zeros_like(p) for p in params]
-    w_o, v_o, _ = orc.lars_update(params, grads_o, vel, 0.001, 0.9, 1.0, wds)
 
     P = [dev(p) for p in params]
     xd, Td = dev(x), dev(T)
@@ -56,6 +52,21 @@ def test_config1_bottleneck_block_f32(rn):
     t1 = cbn(xd, 0, 1, 0, 1); t2 = cbn(t1["z"], 1, 1, 1, 1); tp = cbn(xd, 3, 1, 0, 0)
     t3 = cbn(t2["z"], 2, 1, 0, 2, res=tp["z"])
     assert_close(t3["z"], out_o, TOL["f32"], "block output")
+    # A pre-activation within float rounding of zero may land on either side of the ReLU (a handful of the
+    # block's 1.2 million do, depending on the summation order of the convolution in front), and one differing
+    # decision moves the gradients by more than the float bar.  Both outcomes are valid: the decisions are
+    # checked to differ only where the value is within rounding of zero, then the oracle's backward pass runs
+    # with the decisions of the forward pass under test.
+    for t_g, t_o in ((t1, tape[0]), (t2, tape[1]), (t3, tape[2])):
+        zg, zo = host(t_g["z"]), t_o["z"]
+        differ = (zg > 0) != (zo > 0)
+        assert differ.sum() <= 8 and (not differ.any() or
+                                      max(np.abs(zg[differ]).max(), np.abs(zo[differ]).max()) <= 1e-5 * np.sqrt(np.mean(zo * zo)))
+        t_o["z"] = np.where(zg > 0, np.maximum(zo, np.float32(1e-30)), np.float32(0)).astype(zo.dtype)
+    dx_o, grads_o = net.bottleneck_bwd(T, tape)
+    wds = net.lars_hyper(table, 5e-5)
+    vel = [np.zeros_like(p) for p in params]
+    w_o, v_o, _ = orc.lars_update(params, grads_o, vel, 0.001, 0.9, 1.0, wds)
     d2, dsc, g3 = cbn_bwd(Td, t3)
     d1, _, g2 = cbn_bwd(d2, t2)
     dxa, _, g1 = cbn_bwd(d1, t1)

@@ -211,11 +211,14 @@ def test_train_step_graph_replays_equal_eager_steps(rn):
 
 def test_loop_lowers_the_loss_resnet50_batch40_bf16(rn):
     """The full network at the measured configuration: twelve steps of the loop on one fixed synthetic
-    batch (warm-up, then constant rate; label smoothing 0.1) lower the loss and keep everything finite."""
+    batch (warm-up, then constant rate; label smoothing 0.1) lower the loss and keep everything finite.
+    The rate is one at which the descent is steady (7.6 -> about 3.0; at base rate 10 the loss of this one-batch
+    problem bounces between 4.5 and 7.6 from step 4 on, and where it stands after twelve steps depends on the
+    last bit of the convolutions' summation order)."""
     S = setup_step(rn, "bf16", 40, 224, (64, 128, 256, 512), (3, 4, 6, 3), 64, 1000, ls=0.1)
     plan = S["plan"]
     st = rn.TrainState(plan)
-    sc = rn.LrSchedule(base_lr=10.0, warmup_steps=4, warmup_start_lr=2.0)
+    sc = rn.LrSchedule(base_lr=4.0, warmup_steps=4, warmup_start_lr=1.0)
     img, lab = dev(S["images"], True), dev(S["labels"])
     losses = []
     for t in range(12):
@@ -223,7 +226,7 @@ def test_loop_lowers_the_loss_resnet50_batch40_bf16(rn):
         losses.append(float(loss.item()))
     print("losses", [round(v, 4) for v in losses])
     assert all(np.isfinite(losses)) and torch.isfinite(S["M"]).all() and torch.isfinite(st.buf[256:].view(torch.float32)).all()
-    assert losses[-1] < losses[0] - 0.05, losses
+    assert losses[-1] < losses[0] - 2.0, losses
     assert st.step == 12
 
 
