@@ -765,6 +765,9 @@ struct WgradArgs {
   // BNIN kernels (1x1, stride 1): x is the INPUT of a BN+ReLU layer whose output is the convolution's input;
   // relu(x*scale + bias) is applied to the x tile in LDS (as in igemm_kernel).  Null: x is used as is.
   const float *in_gamma, *in_beta, *in_mean, *in_rstd;
+  // wgrad3x3_kernel: the padded pixel index space, Gpad = N * (H + 1) * (W + 1) positions
+  int Gpad;
+  FastDiv div_img, div_w1;  // by (H + 1) * (W + 1) and by W + 1
 };
 
 template <typename T> struct WgradCfg;
@@ -998,6 +1001,141 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
         if (ko < a.Cout) out[static_cast<int64_t>(ko) * a.Ktot + tap * a.Cg + c] = acc[i][j][v];
       }
     }
+}
+
+// Weight gradient of a 3x3 / stride 1 / padding 1 layer, bf16, all nine taps in one workgroup.
+// The reduction index is a PADDED pixel position: every image row gets one more column and every image one more
+// row, whose dy and x are zero (never stored: the loads of those positions carry an out-of-range offset and
+// write zeros).  In that index space tap (r, s) of position k reads x at k + (r-1)(W+1) + (s-1), a constant shift,
+// and every tap that falls off the image lands on a zero position -- so there is nothing to mask: per chunk of 64
+// positions the workgroup brings one dy tile [64][64 output channels] and one x run [64 + 2W + 4][64 input
+// channels] into LDS and multiplies the dy tile with nine row-shifted windows of the run (transposing reads, the
+// slot permutation follows the shifted row) into nine 64x64 accumulator tiles.  Against one gathered tile per tap
+// that is 9x fewer dy loads and 9 / (1 + (2W+4)/64) fewer x loads; the reduction grows by (1+1/H)(1+1/W).
+// NBX: load passes (32 rows each) of the run; NSTAGE: chunk buffers in the ring (as in wgrad_kernel).
+template <int NBX, int NSTAGE>
+__global__ __launch_bounds__(256) void wgrad3x3_kernel(const WgradArgs a) {
+  typedef uint16_t T;
+  constexpr int V = 8, BKM = 64, RBY = 128, KK = 4;
+  constexpr int NA = 2, NL = NA + NBX;
+  constexpr int STAGE = BKM * RBY + NBX * 4096;
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = wave & 1, wn = wave >> 1;
+  // logical id = (split, output-channel tile, input-channel tile): the tiles of a split share its rows
+  const int lid = xcd_remap(blockIdx.x, gridDim.x);
+  const int split = static_cast<int>(fdiv(static_cast<uint32_t>(lid), a.div_tps)), tile = lid - split * a.tiles_per_split;
+  const int ko_tile = static_cast<int>(fdiv(static_cast<uint32_t>(tile), a.div_ctiles));
+  const int c0 = (tile - ko_tile * a.ctiles) * 64, ko0 = ko_tile * 64;
+  const int row_begin = split * a.rows_per_split;
+  const int row_end = min(row_begin + a.rows_per_split, a.Gpad);
+  const rsrc_words rsX = make_rsrc_words(a.x, a.x_bytes), rsD = make_rsrc_words(a.dy, a.dy_bytes);
+
+  const int row = tid >> 3;                                  // this thread's row in every 32-row load pass
+  const int pc = (tid & 7) ^ wgrad_swz<T, RBY>(row);        // the 16-byte piece of its rows it fetches
+  const bool a_col_ok = ko0 + pc * V < a.Cout, b_col_ok = c0 + pc * V < a.Cg;
+  const int W1 = a.W + 1, IMG = (a.H + 1) * W1;
+  // padded position -> pixel index; ok: the position is a real pixel
+  auto pixel_of = [&](int g, bool* ok) __attribute__((always_inline)) {
+    const bool in = static_cast<unsigned>(g) < static_cast<unsigned>(a.Gpad);
+    const uint32_t gg = in ? static_cast<uint32_t>(g) : 0u;
+    const uint32_t n = fdiv(gg, a.div_img), rem = gg - n * static_cast<uint32_t>(IMG);
+    const uint32_t y = fdiv(rem, a.div_w1), x = rem - y * static_cast<uint32_t>(W1);
+    *ok = in && y < static_cast<uint32_t>(a.H) && x < static_cast<uint32_t>(a.W);
+    return static_cast<int>((n * a.H + y) * a.W + x);
+  };
+  typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+  const uint32_t wave_dst = __builtin_amdgcn_readfirstlane(
+      static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte_ptr)smem)) + static_cast<uint32_t>(wave) * 1024u);
+  int cur = 0;
+  auto load_chunk = [&](int stage) __attribute__((always_inline)) {
+    const int g0 = row_begin + cur * BKM;
+    const uint32_t sa = wave_dst + static_cast<uint32_t>(stage) * STAGE, sb = sa + BKM * RBY;
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {  // dy: positions of this split only (the others belong to other workgroups)
+      const int g = g0 + row + 32 * i;
+      bool ok;
+      const int pix = pixel_of(g, &ok);
+      ok = ok && a_col_ok && g < row_end;
+      buffer_load16_to_lds(rsD, sa + i * 4096, ok ? static_cast<uint32_t>(pix * a.Cout + ko0 + pc * V) * 2u : kOob, 0u);
+    }
+#pragma unroll
+    for (int i = 0; i < NBX; ++i) {  // x: the run starts W + 2 positions before the chunk
+      const int g = g0 - (a.W + 2) + row + 32 * i;
+      bool ok;
+      const int pix = pixel_of(g, &ok);
+      ok = ok && b_col_ok;
+      buffer_load16_to_lds(rsX, sb + i * 4096, ok ? static_cast<uint32_t>(pix * a.PS + c0 + pc * V) * 2u : kOob, 0u);
+    }
+    ++cur;
+  };
+
+  f32x16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  // Fragment addresses.  dy: as in wgrad_kernel.  x: the same transposing read r*(W+1) + s rows further down the
+  // run; the slot permutation of a row depends on bit 1 of the row, so it is taken from the shifted row (the
+  // reads' +4 and +16*kk rows leave that bit alone).
+  const int fa_base = wgrad_frag_base<T, RBY>(lane, wm * 32);
+  int fb_base[9];
+  {
+    const int g4 = lane >> 4, t = lane & 15;
+    const int krow = 8 * (g4 >> 1) + (t >> 2);
+    const int cb = 2 * (wn * 32 + 16 * (g4 & 1) + 4 * (t & 3));
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int kr = krow + (tap / 3) * W1 + (tap % 3);
+      fb_base[tap] = BKM * RBY + kr * RBY + (((cb >> 4) ^ wgrad_swz<T, RBY>(kr)) << 4) + (cb & 15);
+    }
+  }
+  const int nchunks = (row_end - row_begin + BKM - 1) / BKM;
+  auto compute = [&](int stage) __attribute__((always_inline)) {
+    const unsigned char* st = smem + stage * STAGE;
+    Vec16 fa[KK], fb[2][KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) fa[kk] = wgrad_read_frag<T, RBY>(st, fa_base, kk);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) fb[0][kk] = wgrad_read_frag<T, RBY>(st, fb_base[0], kk);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      if (tap + 1 < 9) {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) fb[(tap + 1) & 1][kk] = wgrad_read_frag<T, RBY>(st, fb_base[tap + 1], kk);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) Mma<T>::run(fa[kk], fb[tap & 1][kk], acc[tap]);  // D[ko][c]
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+#pragma unroll
+  for (int c = 0; c < NSTAGE - 1; ++c)
+    if (c < nchunks) load_chunk(c);
+  int stage = 0;
+  for (int kc = 0; kc < nchunks; ++kc) {
+    ring_wait<NSTAGE, NL>(nchunks - 1 - kc);
+    if (kc + NSTAGE - 1 < nchunks) load_chunk(stage >= 1 ? stage - 1 : NSTAGE - 1);
+    compute(stage);
+    stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+  }
+
+  // acc[tap][v]: ko = (v/4)*8 + (lane/32)*4 + v%4, c = lane%32 of this wave's 32x32 block
+  float* out = a.out + static_cast<int64_t>(split) * a.split_stride;
+  const int c = c0 + wn * 32 + (lane & 31);
+  if (c < a.Cg) {
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ko = ko0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (ko < a.Cout) out[static_cast<int64_t>(ko) * a.Ktot + tap * a.Cg + c] = acc[tap][v];
+      }
+  }
 }
 
 // dw[i] = sum_s partial[s][i].  A workgroup owns 64 float4 outputs; its four waves each sum every
@@ -1540,6 +1678,94 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
   }
 }
 
+static int esize(int dtype);
+static bool is_stem(const rn50_conv_desc* d);
+
+// The nine-tap weight gradient (wgrad3x3_kernel): bf16, 3x3, stride 1, padding 1, and an image width whose run
+// of 2W + 68 rows fits six load passes.  Plan: 64x64 tiles, the padded pixel range split to give about 192
+// workgroups (384 for the longest reductions), each at least 8 chunks long (as for wgrad_kernel).
+struct Wgrad3x3Plan {
+  int nbx;  // load passes of the x run: 3, 4 or 6; 0: the layer does not run this kernel
+  int ctiles, kotiles, splits, rows_per_split, gpad;
+};
+static Wgrad3x3Plan plan_wgrad3x3(const rn50_conv_desc* d) {
+  Wgrad3x3Plan p{};
+#ifdef RN50_TUNING  // tuning builds only: RN50_NO_WGRAD3X3 sends these layers through the per-tap kernel
+  static const bool off = getenv("RN50_NO_WGRAD3X3") != nullptr;
+  if (off) return p;
+#endif
+  if (d->dtype != RN50_BF16 || d->R != 3 || d->S != 3 || d->stride != 1 || d->pad != 1 || is_stem(d)) return p;
+  const int need = static_cast<int>(ceil_div(2 * d->W + 68, 32));
+  if (need > 6) return p;
+  const int64_t gpad = static_cast<int64_t>(d->N) * (d->H + 1) * (d->W + 1);
+  if (gpad >= (1ll << 31) - 64) return p;
+  p.nbx = need <= 3 ? 3 : (need == 4 ? 4 : 6);
+  p.ctiles = static_cast<int>(ceil_div(d->Cin, 64));
+  p.kotiles = static_cast<int>(ceil_div(d->Cout, 64));
+  p.gpad = static_cast<int>(gpad);
+  int target = 384, min_chunks = 8;
+  bool always = false;
+#ifdef RN50_TUNING  // RN50_WGRAD3X3_TARGET=workgroups,min chunks[,1: every eligible layer]
+  if (const char* e = getenv("RN50_WGRAD3X3_TARGET")) {
+    int al = 0;
+    sscanf(e, "%d,%d,%d", &target, &min_chunks, &al);
+    always = al != 0;
+  }
+#endif
+  // Where it pays (per-layer sweeps at batch 40 and 256, profiles/wgrad3x3_nine_tap_sweep_batch40_batch256_bf16.txt): where the
+  // per-tap kernel is held to 64-wide tiles by the channel counts, and where its plan leaves a workgroup a
+  // reduction of 100 chunks or more (few, long-running workgroups: the wide layers at large batch).  Elsewhere
+  // the per-tap kernel's 128x128 tiles (64x64 wave tiles: half the LDS reads per MFMA) are as fast or faster.
+  if (!always && d->Cin > 64 && d->Cout > 64 &&
+      plan_wgrad(d->N * d->H * d->W, d->Cout, d->Cin, 9, d->dtype).rows_per_split < 100 * 64) {
+    p.nbx = 0;
+    return p;
+  }
+  const int64_t tiles = static_cast<int64_t>(p.ctiles) * p.kotiles;
+  const int64_t cap = gpad / (min_chunks * 64) > 1 ? gpad / (min_chunks * 64) : 1;
+  int64_t sp = (target + tiles / 2) / tiles;
+  sp = sp < 1 ? 1 : (sp > cap ? cap : sp);
+  const int64_t rps = ceil_div(ceil_div(gpad, sp), 64) * 64;
+  p.rows_per_split = static_cast<int>(rps);
+  p.splits = static_cast<int>(ceil_div(gpad, rps));
+  return p;
+}
+template <int NBX, int NSTAGE>
+static void launch_wgrad3x3_ring(const WgradArgs& a, dim3 grid, hipStream_t s) {
+  constexpr int lds = NSTAGE * (64 * 128 + NBX * 4096);
+  static std::once_flag once;
+  std::call_once(once, [] { allow_big_lds(wgrad3x3_kernel<NBX, NSTAGE>, lds); });
+  RN50_LAUNCH("conv_wgrad", (wgrad3x3_kernel<NBX, NSTAGE>), grid, dim3(256), lds, s, a);
+}
+template <int NBX>
+static void launch_wgrad3x3_nbx(const WgradArgs& a, dim3 grid, hipStream_t s) {
+  // three chunk buffers where the workgroups sharing a compute unit have the LDS for them, else two
+  int64_t per_cu = ceil_div(grid.x, 256);
+  if (per_cu > 3) per_cu = 3;
+  const bool three = 3 * (64 * 128 + NBX * 4096) * per_cu <= 156 * 1024;
+  if (three) launch_wgrad3x3_ring<NBX, 3>(a, grid, s);
+  else launch_wgrad3x3_ring<NBX, 2>(a, grid, s);
+}
+static void launch_wgrad3x3(WgradArgs a, const Wgrad3x3Plan& p, int H, float* dw, float* partial, hipStream_t s) {
+  a.ctiles = p.ctiles;
+  a.tiles_per_split = p.ctiles * p.kotiles;
+  a.rows_per_split = p.rows_per_split;
+  a.split_stride = static_cast<int64_t>(a.Cout) * a.Ktot;
+  a.out = p.splits > 1 ? partial : dw;
+  a.Gpad = p.gpad;
+  a.div_tps = make_fastdiv(a.tiles_per_split);
+  a.div_ctiles = make_fastdiv(a.ctiles);
+  a.div_img = make_fastdiv((H + 1) * (a.W + 1));
+  a.div_w1 = make_fastdiv(a.W + 1);
+  const dim3 grid(static_cast<unsigned>(a.tiles_per_split) * p.splits);
+  if (p.nbx == 3) launch_wgrad3x3_nbx<3>(a, grid, s);
+  else if (p.nbx == 4) launch_wgrad3x3_nbx<4>(a, grid, s);
+  else launch_wgrad3x3_nbx<6>(a, grid, s);
+  if (p.splits > 1) {
+    const int64_t n = a.split_stride;
+    RN50_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3(static_cast<unsigned>(ceil_div(ceil_div(n, 4), 64))), dim3(256), 0, s, partial, p.splits, n, dw);
+  }
+}
 static WgradArgs wgrad_args(const rn50_conv_desc* d, const void* x, const void* dy) {
   WgradArgs a{};
   a.x = x; a.dy = dy;
@@ -1575,7 +1801,9 @@ size_t wgrad_partial_bytes(const rn50_conv_desc* d) {
   const WgradPlan p = stem ? plan_wgrad(M, d->Cout, pair ? 64 : 32, pair ? 4 : 7, d->dtype, false)
                            : plan_wgrad(M, d->Cout, d->Cin, d->R * d->S, d->dtype);
   const size_t dw_elems = static_cast<size_t>(d->Cout) * (stem ? kStemK : d->R * d->S * d->Cin);
-  size_t b = p.splits > 1 ? align_up(dw_elems * p.splits * sizeof(float), 256) : 0;
+  const Wgrad3x3Plan p9 = plan_wgrad3x3(d);
+  const int splits = p9.nbx ? p9.splits : p.splits;
+  size_t b = splits > 1 ? align_up(dw_elems * splits * sizeof(float), 256) : 0;
   if (stem) b += align_up(dw_elems * sizeof(float), 256);  // padded dw
   return b;
 }
@@ -1586,6 +1814,10 @@ void wgrad_run(const rn50_conv_desc* d, const void* x_or_xp, const void* dy, flo
   const bool stem = is_stem(d);
   WgradArgs a = stem ? stem_wgrad_args(d, x_or_xp, dy) : wgrad_args(d, x_or_xp, dy);
   if (in) { a.in_gamma = in->gamma; a.in_beta = in->beta; a.in_mean = in->mean; a.in_rstd = in->rstd; }
+  if (const Wgrad3x3Plan p9 = plan_wgrad3x3(d); p9.nbx && !in) {
+    launch_wgrad3x3(a, p9, d->H, dw, static_cast<float*>(scratch), s);
+    return;
+  }
   const WgradPlan p = plan_wgrad(a.M, a.Cout, a.Cg, a.R * a.S, d->dtype, !stem);  // the stem's tile is fixed (64x64)
   float* partial = static_cast<float*>(scratch);
   float* target = dw;
