@@ -33,8 +33,8 @@ MFMA_F32_PEAK_TFLOPS = 157.3
 # copy; None where not measured.  Counter attribution per kernel is approximate: lines a kernel leaves
 # dirty in L2 are written back during later kernels.  conv_wgrad includes its reduction pass.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "conv_fwd": 39.89e6, "conv_dgrad": 63.52e6, "conv_wgrad": 59.75e6, "bn_apply": 42.55e6,
-    "bn_bwd_reduce": 75.71e6, "bn_bwd_apply": 51.85e6, "lars_update": 383.53e6,
+    "conv_fwd": 39.93e6, "conv_dgrad": 63.54e6, "conv_wgrad": 62.64e6, "bn_apply": 42.55e6,
+    "bn_bwd_reduce": 75.69e6, "bn_bwd_apply": 51.85e6, "lars_update": 383.55e6,
 }
 
 # Kernel classes of the step: (class, launch tags whose durations it sums, tag whose launches it is counted in).

@@ -13,7 +13,7 @@ import csv
 import re
 import sys
 
-TAGS = [("conv_fwd", r"igemm_kernel<[^,]+(, \d+){4}, 0,"), ("conv_dgrad", r"igemm_kernel<[^,]+(, \d+){4}, 1,"), ("conv_wgrad", r"wgrad_kernel"),
+TAGS = [("conv_fwd", r"igemm_kernel<[^,]+(, \d+){4}, 0,"), ("conv_dgrad", r"igemm_kernel<[^,]+(, \d+){4}, 1,"), ("conv_wgrad", r"wgrad(3x3)?_kernel"),
         ("conv_wgrad_reduce", r"splitk_reduce"), ("bn_finalize", r"bn_finalize_kernel"), ("bn_apply", r"bn_apply_kernel"),
         ("bn_bwd_reduce", r"bn_bwd_reduce"), ("bn_bwd_finalize", r"bn_bwd_finalize"), ("bn_bwd_apply", r"bn_bwd_apply"),
         ("lars_norms", r"lars_norms"), ("lars_apply", r"lars_apply")]
