@@ -326,6 +326,16 @@ def test_profile_hooks_and_plan_lifecycle(rn):
         ms = rn.profile_end()
         assert len(ms) == 2 * n_units                           # two timed steps, one weight gradient per unit
         assert all(0.0 < t < 50.0 for t in ms), ms
+        # the timeline form: when every launch of one step began, after the first one, and how long it ran
+        rn.profile_begin("", 4000)
+        step()
+        torch.cuda.synchronize()
+        tl = rn.profile_end_timeline()
+        tags = rn.profile_tags()
+        assert len(tl) == len(tags) > 5 * n_units and tl[0][0] == 0.0
+        assert all(at >= 0.0 and 0.0 < dur < 50.0 for at, dur in tl)
+        assert {"conv_fwd", "conv_dgrad", "conv_wgrad", "bn_apply", "bn_bwd_apply", "lars_apply"} <= set(tags)
+        assert max(at for at, _ in tl) > max(dur for _, dur in tl)      # the launches are spread over the step
         loss = step()
         torch.cuda.synchronize()
         assert np.isfinite(float(loss.item()))
