@@ -223,7 +223,8 @@ def roofline(plan, tagged_ms, steps):
     rec["chosen_by"] = "largest kernel time per step among the classes, from this run's own timings"
     rec["timing"] = ("dispatch begin/end timestamps of every tagged launch (events handed to hipExtLaunchKernel) in "
                      f"{steps} of the timed steps; kernels of the step's three streams overlap, so class times add up "
-                     "to more than the step")
+                     "to more than the step; a step whose launches all carry event packets is about twice as long as a "
+                     "plain one, so its kernels overlap less than in the steps that make up ms_per_step")
     rec["kernel_time_per_step_ms"] = sum(c["time_per_step_ms"] for c in classes)
     rec["classes"] = classes
     return rec
