@@ -192,7 +192,7 @@ static int finalize_grid(int C, int nrows) { return static_cast<int>(ceil_div(C 
 // to the first row's shift K0 exactly, in double,
 //   sum(x - K0) = S1 + n e,  sum((x - K0)^2) = S2 + 2 e S1 + n e^2,  e = shift - K0.
 __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partial, int nrows, int rpp,
-                                                          int64_t m, int C, int wpc, float eps,
+                                                          int64_t m, int C, int wpc, int row_major, float eps,
                                                           float* __restrict__ mean_out,
                                                           float* __restrict__ rstd_out,
                                                           float* running_mean, float* running_var,
@@ -202,7 +202,10 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
   const int first = (wpc == 1 ? 0 : wave * 64) + lane, step = 64 * wpc;
   double s1 = 0.0, s2 = 0.0, k0 = 0.0;
   if (c < C) {
-    const float* pk = partial + static_cast<int64_t>(c) * nrows;
+    // element (c, row) of a plane: channel-major c * nrows + row, or row-major row * C + c (the layout of layers
+    // with few tile rows, whose apply pass normally finalizes by itself)
+    const int64_t rs = row_major ? C : 1;
+    const float* pk = partial + (row_major ? static_cast<int64_t>(c) : static_cast<int64_t>(c) * nrows);
     const float* p1 = pk + static_cast<int64_t>(C) * nrows;
     const float* p2 = p1 + static_cast<int64_t>(C) * nrows;
     k0 = static_cast<double>(pk[0]);
@@ -212,9 +215,9 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
       float vk[U], v1[U], v2[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        vk[u] = pk[b + u * step];
-        v1[u] = p1[b + u * step];
-        v2[u] = p2[b + u * step];
+        vk[u] = pk[(b + u * step) * rs];
+        v1[u] = p1[(b + u * step) * rs];
+        v2[u] = p2[(b + u * step) * rs];
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -228,9 +231,9 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
     for (; b < nrows; b += step) {
       const int64_t left = m - static_cast<int64_t>(b) * rpp;
       const double n = static_cast<double>(left < rpp ? left : rpp);
-      const double e = static_cast<double>(pk[b]) - k0, a1 = static_cast<double>(p1[b]);
+      const double e = static_cast<double>(pk[b * rs]) - k0, a1 = static_cast<double>(p1[b * rs]);
       s1 += a1 + n * e;
-      s2 += static_cast<double>(p2[b]) + e * (2.0 * a1 + n * e);
+      s2 += static_cast<double>(p2[b * rs]) + e * (2.0 * a1 + n * e);
     }
   }
   if (!finalize_combine(&s1, &s2, wpc, c, C)) return;
@@ -244,7 +247,81 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
   if (running_var) running_var[c] = momentum * running_var[c] + (1.f - momentum) * static_cast<float>(var);
 }
 
-template <typename T>
+// What a pass that finalizes its own statistics gets on top of the apply pass's arguments (FIN kernels below):
+// the per-tile sums in ROW-major order, partial[plane][tile row][C], and where the statistics go.
+struct BnFinArgs {
+  const float* partial;
+  int nrows, rpp;  // tile rows; pixel rows summed per tile row (the last may cover fewer)
+  float eps, momentum;
+  float *mean_out, *rstd_out, *running_mean, *running_var;
+};
+// Forward statistics of the CS channels from c0 on, by all 256 threads of a workgroup, into mean_s / rstd_s (LDS),
+// with the arithmetic of bn_finalize_kernel (every tile row's sums moved to the first row's shift, in double).
+// Thread (channel ch, part p) adds tile rows p, p + P, ... in order, the P parts are added in order: a fixed order,
+// the same in every workgroup that computes these channels.  Ends with a barrier.
+template <int CS>
+__device__ __forceinline__ void finalize_slice_fwd(const BnFinArgs& f, int64_t m, int C, int c0, bool writer,
+                                                   float* mean_s, float* rstd_s) {
+  constexpr int P = 256 / CS, U = 4;
+  __shared__ double red[2][256];
+  const int ch = threadIdx.x % CS, part = threadIdx.x / CS;
+  const int c = min(c0 + ch, C - 1);
+  const int64_t plane = static_cast<int64_t>(f.nrows) * C;
+  const float* pk = f.partial + c;
+  const double k0 = static_cast<double>(pk[0]);
+  double s1 = 0.0, s2 = 0.0;
+  for (int b = part; b < f.nrows; b += P * U) {
+    float vk[U], v1[U], v2[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t at = static_cast<int64_t>(min(b + u * P, f.nrows - 1)) * C;
+      vk[u] = pk[at];
+      v1[u] = pk[plane + at];
+      v2[u] = pk[2 * plane + at];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (b + u * P < f.nrows) {
+        const int64_t left = m - static_cast<int64_t>(b + u * P) * f.rpp;
+        const double n = static_cast<double>(left < f.rpp ? left : f.rpp);
+        const double e = static_cast<double>(vk[u]) - k0, a1 = static_cast<double>(v1[u]);
+        s1 += a1 + n * e;
+        s2 += static_cast<double>(v2[u]) + e * (2.0 * a1 + n * e);
+      }
+    }
+  }
+  red[0][threadIdx.x] = s1;
+  red[1][threadIdx.x] = s2;
+  __syncthreads();
+  if (threadIdx.x < CS) {
+    double t1 = red[0][ch], t2 = red[1][ch];
+#pragma unroll
+    for (int q = 1; q < P; ++q) {
+      t1 += red[0][q * CS + ch];
+      t2 += red[1][q * CS + ch];
+    }
+    const double d = t1 / static_cast<double>(m);
+    double var = t2 / static_cast<double>(m) - d * d;
+    if (var < 0.0) var = 0.0;
+    const double mean = k0 + d;
+    const float mf = static_cast<float>(mean), rf = static_cast<float>(1.0 / sqrt(var + static_cast<double>(f.eps)));
+    mean_s[ch] = mf;
+    rstd_s[ch] = rf;
+    if (writer && c0 + ch < C) {
+      f.mean_out[c] = mf;
+      f.rstd_out[c] = rf;
+      if (f.running_mean) f.running_mean[c] = f.momentum * f.running_mean[c] + (1.f - f.momentum) * mf;
+      if (f.running_var) f.running_var[c] = f.momentum * f.running_var[c] + (1.f - f.momentum) * static_cast<float>(var);
+    }
+  }
+  __syncthreads();
+}
+
+// FIN: the pass takes its statistics from the row-major per-tile sums itself (fin), every workgroup for the 8
+// vector columns it applies (tx_log2 = 3), and the first row block of every column slice stores them: no
+// finalize launch in front.  For layers with few tile rows the redundant reads of the sums are far cheaper than a
+// launch on the step's dependency chain (about 4 us whatever it computes).
+template <typename T, bool FIN = false>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
                                                        const float* __restrict__ gamma,
                                                        const float* __restrict__ beta,
@@ -252,12 +329,15 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
                                                        const float* __restrict__ rstd,
                                                        const T* __restrict__ residual,
                                                        T* __restrict__ y, uint8_t* __restrict__ relu_mask,
-                                                       int64_t m, int C, int tx_log2, int rpb, int mode) {
+                                                       int64_t m, int C, int tx_log2, int rpb, int mode,
+                                                       const BnFinArgs fin) {
   constexpr int V = Elem<T>::VEC;
   const int TX = 1 << tx_log2, TY = 256 >> tx_log2;
   const int tcol = threadIdx.x & (TX - 1), trow = threadIdx.x >> tx_log2;
   const int col = blockIdx.y * TX + tcol;
-  if (col >= C / V) return;
+  __shared__ float mean_s[FIN ? 8 * V : 1], rstd_s[FIN ? 8 * V : 1];
+  if (!FIN && col >= C / V) return;
+  const bool live = col < C / V;  // (FIN: every thread takes part in the statistics)
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
   const int64_t r1 = min(r0 + rpb, m);
   int64_t r = r0 + trow;
@@ -275,12 +355,24 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x,
     }
   };
   // the first rows are requested before the per-channel values, so both arrive in one round trip
-  if (r < r1) load_rows();
+  if (live && r < r1) load_rows();
   float scale[V], bias[V], cg[V], cb[V], cm[V], cr[V];
-  load_floats<V>(gamma + col * V, cg);
-  load_floats<V>(beta + col * V, cb);
-  load_floats<V>(mean + col * V, cm);
-  load_floats<V>(rstd + col * V, cr);
+  if (live) {
+    load_floats<V>(gamma + col * V, cg);
+    load_floats<V>(beta + col * V, cb);
+  }
+  if constexpr (FIN) {
+    finalize_slice_fwd<8 * V>(fin, m, C, blockIdx.y * 8 * V, blockIdx.x == 0, mean_s, rstd_s);
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      cm[j] = mean_s[tcol * V + j];
+      cr[j] = rstd_s[tcol * V + j];
+    }
+  } else {
+    load_floats<V>(mean + col * V, cm);
+    load_floats<V>(rstd + col * V, cr);
+  }
 #pragma unroll
   for (int j = 0; j < V; ++j) bn_coeffs(cg[j], cb[j], cm[j], cr[j], &scale[j], &bias[j]);
   for (; r < r1; r += kBnRows * TY) {
@@ -576,15 +668,28 @@ template <typename T>
 static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const void* x,
                             const float* gamma, const float* beta, const void* residual, void* y,
                             uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
-                            float momentum, const float* partial, int nrows, int rpp, hipStream_t s) {
+                            float momentum, const float* partial, int nrows, int rpp, bool row_major, hipStream_t s) {
+  if (row_major && y) {
+    // few tile rows: the apply pass finalizes for itself.  Column slices of 8 vectors, about 768 workgroups.
+    const int V = d->dtype == RN50_BF16 ? 8 : 4, TY = 32;
+    const int gy = static_cast<int>(ceil_div(d->C / V, 8));
+    const int64_t nblk_target = 768 / gy > 0 ? 768 / gy : 1;
+    int64_t rpt = ceil_div(m, TY * nblk_target);
+    rpt = ceil_div(rpt, kBnRows) * kBnRows;
+    const int rpb = static_cast<int>(rpt) * TY;
+    const BnFinArgs fin{partial, nrows, rpp, d->eps, momentum, save_mean, save_rstd, rm, rv};
+    RN50_LAUNCH("bn_apply", (bn_apply_kernel<T, true>), dim3(static_cast<unsigned>(ceil_div(m, rpb)), gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, nullptr, nullptr, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, 3, rpb, d->mode, fin);
+    return;
+  }
 #ifdef RN50_TUNING  // what-if measurement: the step without its finalize launches (results are then wrong)
   static const bool skip_fin = getenv("RN50_SKIP_BN_FINALIZE") != nullptr;
-  if (!skip_fin)
+  static const int skip_below = getenv("RN50_SKIP_BN_FINALIZE_ROWS") ? atoi(getenv("RN50_SKIP_BN_FINALIZE_ROWS")) : 1 << 30;
+  if (!skip_fin || nrows > skip_below)
 #endif
-  RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), d->eps, save_mean, save_rstd, rm, rv, momentum);
+  RN50_LAUNCH("bn_finalize", bn_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, rpp, m, d->C, finalize_wpc(nrows), row_major ? 1 : 0, d->eps, save_mean, save_rstd, rm, rv, momentum);
   if (!y) return;  // statistics only: the consumer applies the layer while it loads its operand
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnApplyGroups);
-  RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, ga.tx_log2, ga.rpb, d->mode);
+  RN50_LAUNCH("bn_apply", bn_apply_kernel<T>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, save_mean, save_rstd, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, ga.tx_log2, ga.rpb, d->mode, BnFinArgs{});
 }
 
 template <typename T>
@@ -595,7 +700,7 @@ static void launch_fwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
   const size_t lds = 256 * 2 * Elem<T>::VEC * sizeof(float);
   RN50_LAUNCH("bn_stats", bn_stats_kernel<T>, dim3(g.nblk, g.gy), dim3(256), lds, s, static_cast<const T*>(x), m, d->C, g.tx_log2, g.rpb, partial);
   launch_fwd_tail<T>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
-                     partial, g.nblk, g.rpb, s);
+                     partial, g.nblk, g.rpb, false, s);
 }
 
 // finalize + apply from partial sums rows [sum g, sum g*xhat]
@@ -607,7 +712,8 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             int nrows, hipStream_t s) {
 #ifdef RN50_TUNING
   static const bool skip_fin = getenv("RN50_SKIP_BN_FINALIZE") != nullptr;
-  if (!skip_fin)
+  static const int skip_below = getenv("RN50_SKIP_BN_FINALIZE_ROWS") ? atoi(getenv("RN50_SKIP_BN_FINALIZE_ROWS")) : 1 << 30;
+  if (!skip_fin || nrows > skip_below)
 #endif
   RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnBwdApplyGroups);
@@ -656,10 +762,10 @@ void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* par
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
     launch_fwd_tail<uint16_t>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv,
-                              momentum, partial, nrows, rpp, s);
+                              momentum, partial, nrows, rpp, bn_partials_row_major(nrows), s);
   else
     launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
-                           partial, nrows, rpp, s);
+                           partial, nrows, rpp, bn_partials_row_major(nrows), s);
 }
 // Evaluation mode: 1/sqrt(running_var + eps) per channel, then the training pass's apply kernel with the
 // moving averages in place of the batch statistics.
@@ -676,9 +782,9 @@ void bn_infer_run(const rn50_bn_desc* d, const void* x, const float* gamma, cons
                      running_var, d->eps, d->C, rstd_scratch);
   const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnApplyGroups);
   if (d->dtype == RN50_BF16)
-    RN50_LAUNCH("bn_apply", bn_apply_kernel<uint16_t>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const uint16_t*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const uint16_t*>(residual), static_cast<uint16_t*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+    RN50_LAUNCH("bn_apply", bn_apply_kernel<uint16_t>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const uint16_t*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const uint16_t*>(residual), static_cast<uint16_t*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode, BnFinArgs{});
   else
-    RN50_LAUNCH("bn_apply", bn_apply_kernel<float>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const float*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const float*>(residual), static_cast<float*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode);
+    RN50_LAUNCH("bn_apply", bn_apply_kernel<float>, dim3(ga.nblk, ga.gy), dim3(256), 0, s, static_cast<const float*>(x), gamma, beta, running_mean, rstd_scratch, static_cast<const float*>(residual), static_cast<float*>(y), static_cast<uint8_t*>(nullptr), m, d->C, ga.tx_log2, ga.rpb, d->mode, BnFinArgs{});
 }
 
 void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, const uint8_t* relu_mask,

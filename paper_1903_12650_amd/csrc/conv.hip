@@ -105,6 +105,7 @@ struct IgemmArgs {
   // in_lds: byte offset of the per-channel coefficient table behind the ring (host side: lds bytes without it).
   const float *in_gamma, *in_beta, *in_mean, *in_rstd;
   int in_lds;
+  int partial_rm;  // forward sums stored row-major, partial[plane][tile row][Ncols] (bn_partials_row_major)
 };
 
 // relu(bn(x)) of one 16-byte vector with the arithmetic of the stand-alone BN pass (bn_affine, one rounding to
@@ -741,9 +742,12 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) 
     float t = 0.f;
 #pragma unroll 8
     for (int r = 0; r < RPP; ++r) t += cs[(r * 2 + pl) * BN + ch];
-    if (n0 + ch < a.Ncols) a.partial[(MODE == 0 ? pl + 1 : pl) * plane + static_cast<int64_t>(n0 + ch) * nrows + mt] = t;
+    if (n0 + ch < a.Ncols)
+      a.partial[(MODE == 0 ? pl + 1 : pl) * plane +
+                (a.partial_rm ? static_cast<int64_t>(mt) * a.Ncols + n0 + ch : static_cast<int64_t>(n0 + ch) * nrows + mt)] = t;
   }
-  if (MODE == 0 && tid < BN && n0 + tid < a.Ncols) a.partial[static_cast<int64_t>(n0 + tid) * nrows + mt] = kshift;
+  if (MODE == 0 && tid < BN && n0 + tid < a.Ncols)
+    a.partial[a.partial_rm ? static_cast<int64_t>(mt) * a.Ncols + n0 + tid : static_cast<int64_t>(n0 + tid) * nrows + mt] = kshift;
 }
 
 // ------------------------------------------------------------ weight gradient
@@ -1338,6 +1342,7 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   const bool classes = a.mode == 1 && a.stride == 2;
   a.mtiles = static_cast<int>(classes ? 4 * tiles_per_class : ceil_div(a.M, BM));
   const int64_t grid = static_cast<int64_t>(a.mtiles) * a.ntn;
+  a.partial_rm = a.mode == 0 && a.partial != nullptr && bn_partials_row_major(a.mtiles);
   a.div_ntn = make_fastdiv(a.ntn);
   a.linear = a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0 && !a.pair && a.H == a.P && a.W == a.Q;
   for (int c = 0; c < 2; ++c) {

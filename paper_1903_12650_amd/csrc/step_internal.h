@@ -31,6 +31,16 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
                      hipStream_t s);
 // A BN+ReLU layer applied to a convolution's input on the fly (1x1, stride 1 convolutions only): its parameters
 // and saved statistics, float[Cin] each.
+// The forward BN sums that a convolution's output stage leaves (one row per row tile) are stored row-major,
+// partial[plane][tile row][C], when there are few tile rows: the BN apply pass then takes the statistics from them
+// itself, in every workgroup, and the finalize launch in front of it is gone.  Otherwise channel-major,
+// partial[plane][C][tile row], for the finalize kernel.  The writer and the reader both decide by this function.
+// Measured on the whole step at batch 40 (thresholds 40 / 64 / 128 rows against none: 4.664 / 4.674 / 4.700 against
+// 4.678 ms): with 31 tile rows (the 7x7 layers) the redundant sums cost less than the launch, with 123 (14x14) the
+// double-precision sums of every workgroup cost more.
+constexpr int kBnSelfFinalizeRows = 40;
+inline bool bn_partials_row_major(int nrows) { return nrows <= kBnSelfFinalizeRows; }
+
 struct BnIn {
   const float *gamma, *beta, *mean, *rstd;
 };
