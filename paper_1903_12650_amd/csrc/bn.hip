@@ -83,6 +83,23 @@ static BnGeom bn_apply_geom(int64_t m, int C, int dtype, int target) {
   return g;
 }
 
+// Geometry of an apply pass that finalizes by itself: column slices of 8 vectors (TY = 32 rows per pass), about
+// kBnSelfFinalizeGroups workgroups, every thread a multiple of 4 rows.
+constexpr int kBnSelfFinalizeGroups = 768;
+static void bn_self_finalize_geom(int64_t m, int C, int V, int* gy_out, int* rpb_out) {
+  int target = kBnSelfFinalizeGroups;
+#ifdef RN50_TUNING  // tuning builds only: RN50_BN_FIN_TARGET=workgroups
+  if (const char* e = getenv("RN50_BN_FIN_TARGET")) target = atoi(e) > 0 ? atoi(e) : target;
+#endif
+  const int TY = 32;
+  const int gy = static_cast<int>(ceil_div(C / V, 8));
+  const int64_t nblk_target = target / gy > 0 ? target / gy : 1;
+  int64_t rpt = ceil_div(m, TY * nblk_target);
+  rpt = ceil_div(rpt, kBnRows) * kBnRows;
+  *gy_out = gy;
+  *rpb_out = static_cast<int>(rpt) * TY;
+}
+
 // Tree-combine NV floats per thread over the TY rows of the workgroup; the
 // result lands in the threads of row 0.
 template <int NV>
@@ -201,11 +218,18 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
   const int c = wpc == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
   const int first = (wpc == 1 ? 0 : wave * 64) + lane, step = 64 * wpc;
   double s1 = 0.0, s2 = 0.0, k0 = 0.0;
-  if (c < C) {
-    // element (c, row) of a plane: channel-major c * nrows + row, or row-major row * C + c (the layout of layers
-    // with few tile rows, whose apply pass normally finalizes by itself)
-    const int64_t rs = row_major ? C : 1;
-    const float* pk = partial + (row_major ? static_cast<int64_t>(c) : static_cast<int64_t>(c) * nrows);
+  if (c < C && row_major) {
+    // the layout of layers with few tile rows, whose apply pass normally finalizes by itself: per tile row and
+    // channel the doubles (sum y, sum y^2); k0 stays 0
+    const double2* pd = reinterpret_cast<const double2*>(partial) + c;
+    for (int b = first; b < nrows; b += step) {
+      const double2 v = pd[static_cast<int64_t>(b) * C];
+      s1 += v.x;
+      s2 += v.y;
+    }
+  } else if (c < C) {
+    const int64_t rs = 1;
+    const float* pk = partial + static_cast<int64_t>(c) * nrows;
     const float* p1 = pk + static_cast<int64_t>(C) * nrows;
     const float* p2 = p1 + static_cast<int64_t>(C) * nrows;
     k0 = static_cast<double>(pk[0]);
@@ -248,17 +272,18 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
 }
 
 // What a pass that finalizes its own statistics gets on top of the apply pass's arguments (FIN kernels below):
-// the per-tile sums in ROW-major order, partial[plane][tile row][C], and where the statistics go.
+// the per-tile sums in ROW-major order (forward: double2 per tile row and channel, sums at shift 0; backward: float
+// planes partial[plane][tile row][C]) and where the results go (backward: mean_out = dbeta, rstd_out = dgamma).
 struct BnFinArgs {
   const float* partial;
-  int nrows, rpp;  // tile rows; pixel rows summed per tile row (the last may cover fewer)
+  int nrows, rpp;  // tile rows; (unused by the row-major layouts) pixel rows summed per tile row
   float eps, momentum;
   float *mean_out, *rstd_out, *running_mean, *running_var;
 };
 // Forward statistics of the CS channels from c0 on, by all 256 threads of a workgroup, into mean_s / rstd_s (LDS),
-// with the arithmetic of bn_finalize_kernel (every tile row's sums moved to the first row's shift, in double).
-// Thread (channel ch, part p) adds tile rows p, p + P, ... in order, the P parts are added in order: a fixed order,
-// the same in every workgroup that computes these channels.  Ends with a barrier.
+// from row-major sums: per tile row and channel the doubles (sum y, sum y^2) that the convolution's output stage
+// made of its shifted float sums.  Thread (channel ch, part p) adds tile rows p, p + P, ... in order, the P parts
+// are added in order: a fixed order, the same in every workgroup that computes these channels.  Ends with a barrier.
 template <int CS>
 __device__ __forceinline__ void finalize_slice_fwd(const BnFinArgs& f, int64_t m, int C, int c0, bool writer,
                                                    float* mean_s, float* rstd_s) {
@@ -266,27 +291,17 @@ __device__ __forceinline__ void finalize_slice_fwd(const BnFinArgs& f, int64_t m
   __shared__ double red[2][256];
   const int ch = threadIdx.x % CS, part = threadIdx.x / CS;
   const int c = min(c0 + ch, C - 1);
-  const int64_t plane = static_cast<int64_t>(f.nrows) * C;
-  const float* pk = f.partial + c;
-  const double k0 = static_cast<double>(pk[0]);
+  const double2* pk = reinterpret_cast<const double2*>(f.partial) + c;
   double s1 = 0.0, s2 = 0.0;
   for (int b = part; b < f.nrows; b += P * U) {
-    float vk[U], v1[U], v2[U];
+    double2 v[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t at = static_cast<int64_t>(min(b + u * P, f.nrows - 1)) * C;
-      vk[u] = pk[at];
-      v1[u] = pk[plane + at];
-      v2[u] = pk[2 * plane + at];
-    }
+    for (int u = 0; u < U; ++u) v[u] = pk[static_cast<int64_t>(min(b + u * P, f.nrows - 1)) * C];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (b + u * P < f.nrows) {
-        const int64_t left = m - static_cast<int64_t>(b + u * P) * f.rpp;
-        const double n = static_cast<double>(left < f.rpp ? left : f.rpp);
-        const double e = static_cast<double>(vk[u]) - k0, a1 = static_cast<double>(v1[u]);
-        s1 += a1 + n * e;
-        s2 += static_cast<double>(v2[u]) + e * (2.0 * a1 + n * e);
+        s1 += v[u].x;
+        s2 += v[u].y;
       }
     }
   }
@@ -300,10 +315,9 @@ __device__ __forceinline__ void finalize_slice_fwd(const BnFinArgs& f, int64_t m
       t1 += red[0][q * CS + ch];
       t2 += red[1][q * CS + ch];
     }
-    const double d = t1 / static_cast<double>(m);
-    double var = t2 / static_cast<double>(m) - d * d;
+    const double mean = t1 / static_cast<double>(m);
+    double var = t2 / static_cast<double>(m) - mean * mean;
     if (var < 0.0) var = 0.0;
-    const double mean = k0 + d;
     const float mf = static_cast<float>(mean), rf = static_cast<float>(1.0 / sqrt(var + static_cast<double>(f.eps)));
     mean_s[ch] = mf;
     rstd_s[ch] = rf;
@@ -578,32 +592,96 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
   dgamma[c] = static_cast<float>(s2);
 }
 
-template <typename T, bool DZ2, int ZK>
+// Backward sums of the CS channels from c0 on, from row-major float planes partial[plane][tile row][C]
+// (plane 0: sum g, plane 1: sum g * xhat), by all 256 threads, in double and in the fixed order of
+// finalize_slice_fwd; dbeta / dgamma land in db_s / dg_s (LDS).  Ends with a barrier.
+template <int CS>
+__device__ __forceinline__ void finalize_slice_bwd(const BnFinArgs& f, int C, int c0, bool writer, float* db_s,
+                                                   float* dg_s) {
+  constexpr int P = 256 / CS, U = 4;
+  __shared__ double red[2][256];
+  const int ch = threadIdx.x % CS, part = threadIdx.x / CS;
+  const int c = min(c0 + ch, C - 1);
+  const int64_t plane = static_cast<int64_t>(f.nrows) * C;
+  const float* p1 = f.partial + c;
+  double s1 = 0.0, s2 = 0.0;
+  for (int b = part; b < f.nrows; b += P * U) {
+    float v1[U], v2[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t at = static_cast<int64_t>(min(b + u * P, f.nrows - 1)) * C;
+      v1[u] = p1[at];
+      v2[u] = p1[plane + at];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (b + u * P < f.nrows) {
+        s1 += static_cast<double>(v1[u]);
+        s2 += static_cast<double>(v2[u]);
+      }
+    }
+  }
+  red[0][threadIdx.x] = s1;
+  red[1][threadIdx.x] = s2;
+  __syncthreads();
+  if (threadIdx.x < CS) {
+    double t1 = red[0][ch], t2 = red[1][ch];
+#pragma unroll
+    for (int q = 1; q < P; ++q) {
+      t1 += red[0][q * CS + ch];
+      t2 += red[1][q * CS + ch];
+    }
+    db_s[ch] = static_cast<float>(t1);
+    dg_s[ch] = static_cast<float>(t2);
+    if (writer && c0 + ch < C) {
+      f.mean_out[c] = static_cast<float>(t1);  // dbeta
+      f.rstd_out[c] = static_cast<float>(t2);  // dgamma
+    }
+  }
+  __syncthreads();
+}
+
+// FIN: as in bn_apply_kernel -- the pass adds up the row-major per-tile sums of its 8 vector columns itself
+// (tx_log2 = 3) and the first row block of every column slice stores dgamma / dbeta.
+template <typename T, bool DZ2, int ZK, bool FIN = false>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     const T* __restrict__ dz, const T* __restrict__ dz2, const T* __restrict__ x,
     const T* __restrict__ z, const uint8_t* __restrict__ zmask, const float* __restrict__ gamma,
     const float* __restrict__ beta,
     const float* __restrict__ mean, const float* __restrict__ rstd,
     const float* __restrict__ dgamma, const float* __restrict__ dbeta, T* __restrict__ dx,
-    T* __restrict__ dres, int64_t m, int C, int tx_log2, int rpb, int mode) {
+    T* __restrict__ dres, int64_t m, int C, int tx_log2, int rpb, int mode, const BnFinArgs fin) {
   constexpr int V = Elem<T>::VEC;
   const int TX = 1 << tx_log2, TY = 256 >> tx_log2;
   const int tcol = threadIdx.x & (TX - 1), trow = threadIdx.x >> tx_log2;
-  const int col = blockIdx.y * TX + tcol;
-  if (col >= C / V) return;
+  int col = blockIdx.y * TX + tcol;
+  __shared__ float db_s[FIN ? 8 * V : 1], dg_s[FIN ? 8 * V : 1];
+  if (!FIN && col >= C / V) return;
+  const bool live = col < C / V;  // (FIN: every thread takes part in the sums)
+  if (!live) col = C / V - 1;      // (its loads stay in range; it leaves before it stores anything)
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rpb;
   const int64_t r1 = min(r0 + rpb, m);
   int64_t r = r0 + trow;
   // the first rows are requested before the per-channel values, so both arrive in one round trip
   BwdRows<DZ2, ZK> b;
-  if (r < r1) load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
+  if (live && r < r1) load_bwd_rows<T, DZ2, ZK>(b, dz, dz2, x, z, zmask, r, r1, TY, C, col);
   const float inv_m = 1.0f / static_cast<float>(m);
   float scale[V], bias[V], rs[V], nmr[V], mg[V], mgx[V], cg[V], cb[V], cm[V];
   load_floats<V>(gamma + col * V, cg);
   load_floats<V>(mean + col * V, cm);
   load_floats<V>(rstd + col * V, rs);
-  load_floats<V>(dbeta + col * V, mg);
-  load_floats<V>(dgamma + col * V, mgx);
+  if constexpr (FIN) {
+    finalize_slice_bwd<8 * V>(fin, C, blockIdx.y * 8 * V, blockIdx.x == 0, db_s, dg_s);
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      mg[j] = db_s[tcol * V + j];
+      mgx[j] = dg_s[tcol * V + j];
+    }
+  } else {
+    load_floats<V>(dbeta + col * V, mg);
+    load_floats<V>(dgamma + col * V, mgx);
+  }
   if (beta) {
     load_floats<V>(beta + col * V, cb);
   } else {
@@ -670,13 +748,9 @@ static void launch_fwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             uint8_t* relu_mask, float* save_mean, float* save_rstd, float* rm, float* rv,
                             float momentum, const float* partial, int nrows, int rpp, bool row_major, hipStream_t s) {
   if (row_major && y) {
-    // few tile rows: the apply pass finalizes for itself.  Column slices of 8 vectors, about 768 workgroups.
-    const int V = d->dtype == RN50_BF16 ? 8 : 4, TY = 32;
-    const int gy = static_cast<int>(ceil_div(d->C / V, 8));
-    const int64_t nblk_target = 768 / gy > 0 ? 768 / gy : 1;
-    int64_t rpt = ceil_div(m, TY * nblk_target);
-    rpt = ceil_div(rpt, kBnRows) * kBnRows;
-    const int rpb = static_cast<int>(rpt) * TY;
+    // few tile rows: the apply pass finalizes for itself
+    int gy, rpb;
+    bn_self_finalize_geom(m, d->C, d->dtype == RN50_BF16 ? 8 : 4, &gy, &rpb);
     const BnFinArgs fin{partial, nrows, rpp, d->eps, momentum, save_mean, save_rstd, rm, rv};
     RN50_LAUNCH("bn_apply", (bn_apply_kernel<T, true>), dim3(static_cast<unsigned>(ceil_div(m, rpb)), gy), dim3(256), 0, s, static_cast<const T*>(x), gamma, beta, nullptr, nullptr, static_cast<const T*>(residual), static_cast<T*>(y), relu_mask, m, d->C, 3, rpb, d->mode, fin);
     return;
@@ -709,19 +783,32 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
                             const void* dz2, const void* x, const void* z, const uint8_t* zmask,
                             const float* gamma, const float* beta, const float* mean, const float* rstd,
                             void* dx, void* dres, float* dgamma, float* dbeta, const float* partial,
-                            int nrows, hipStream_t s) {
+                            int nrows, bool row_major, hipStream_t s) {
+  BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnBwdApplyGroups);
+  BnFinArgs fin{};
+  if (row_major) {
+    // few tile rows: the apply pass adds them up itself
+    ga.tx_log2 = 3;
+    bn_self_finalize_geom(m, d->C, ga.V, &ga.gy, &ga.rpb);
+    ga.nblk = static_cast<int>(ceil_div(m, ga.rpb));
+    fin = BnFinArgs{partial, nrows, 0, 0.f, 0.f, dbeta, dgamma, nullptr, nullptr};
+  } else {
 #ifdef RN50_TUNING
-  static const bool skip_fin = getenv("RN50_SKIP_BN_FINALIZE") != nullptr;
-  static const int skip_below = getenv("RN50_SKIP_BN_FINALIZE_ROWS") ? atoi(getenv("RN50_SKIP_BN_FINALIZE_ROWS")) : 1 << 30;
-  if (!skip_fin || nrows > skip_below)
+    static const bool skip_fin = getenv("RN50_SKIP_BN_FINALIZE") != nullptr;
+    static const int skip_below = getenv("RN50_SKIP_BN_FINALIZE_ROWS") ? atoi(getenv("RN50_SKIP_BN_FINALIZE_ROWS")) : 1 << 30;
+    if (!skip_fin || nrows > skip_below)
 #endif
-  RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
-  const BnGeom ga = bn_apply_geom(m, d->C, d->dtype, kBnBwdApplyGroups);
-#define RN50_BWD_APPLY(DZ2, ZK)                                                                                  \
-  RN50_LAUNCH("bn_bwd_apply", (bn_bwd_apply_kernel<T, DZ2, ZK>), dim3(ga.nblk, ga.gy), dim3(256), 0, s,            \
+    RN50_LAUNCH("bn_bwd_finalize", bn_bwd_finalize_kernel, dim3(finalize_grid(d->C, nrows)), dim3(256), 0, s, partial, nrows, d->C, finalize_wpc(nrows), dgamma, dbeta);
+  }
+#define RN50_BWD_APPLY_K(DZ2, ZK, FIN)                                                                             \
+  RN50_LAUNCH("bn_bwd_apply", (bn_bwd_apply_kernel<T, DZ2, ZK, FIN>), dim3(ga.nblk, ga.gy), dim3(256), 0, s,       \
               static_cast<const T*>(dz), static_cast<const T*>(dz2), static_cast<const T*>(x),                     \
               static_cast<const T*>(z), zmask, gamma, beta, mean, rstd, dgamma, dbeta, static_cast<T*>(dx),        \
-              static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode)
+              static_cast<T*>(dres), m, d->C, ga.tx_log2, ga.rpb, d->mode, fin)
+#define RN50_BWD_APPLY(DZ2, ZK)                                                  \
+  do {                                                                           \
+    if (row_major) RN50_BWD_APPLY_K(DZ2, ZK, true); else RN50_BWD_APPLY_K(DZ2, ZK, false); \
+  } while (0)
   const int zk = d->mode == 0 ? 0 : (zmask ? 2 : (z ? 1 : 0));
   if (dz2) {
     if (zk == 2) RN50_BWD_APPLY(true, 2); else if (zk == 1) RN50_BWD_APPLY(true, 1); else RN50_BWD_APPLY(true, 0);
@@ -729,6 +816,7 @@ static void launch_bwd_tail(const rn50_bn_desc* d, const BnGeom& g, int64_t m, c
     if (zk == 2) RN50_BWD_APPLY(false, 2); else if (zk == 1) RN50_BWD_APPLY(false, 1); else RN50_BWD_APPLY(false, 0);
   }
 #undef RN50_BWD_APPLY
+#undef RN50_BWD_APPLY_K
 }
 
 template <typename T>
@@ -749,7 +837,7 @@ static void launch_bwd(const rn50_bn_desc* d, const BnGeom& g, int64_t m, const 
   }
 #undef RN50_BWD_REDUCE
   launch_bwd_tail<T>(d, g, m, dz, dz2, x, z, zmask, gamma, beta, mean, rstd, dx, dres, dgamma, dbeta, partial,
-                     g.nblk, s);
+                     g.nblk, false, s);
 }
 
 // Entry points for the whole-step driver and the fused C-ABI calls: the sums come from the output stage
@@ -795,10 +883,10 @@ void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, 
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
     launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, relu_mask, gamma, beta, mean, rstd, dx, dres, dgamma,
-                              dbeta, partial, nrows, s);
+                              dbeta, partial, nrows, bn_partials_row_major(nrows), s);
   else
     launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, relu_mask, gamma, beta, mean, rstd, dx, dres, dgamma,
-                           dbeta, partial, nrows, s);
+                           dbeta, partial, nrows, bn_partials_row_major(nrows), s);
 }
 
 }  // namespace rn50

@@ -105,7 +105,10 @@ struct IgemmArgs {
   // in_lds: byte offset of the per-channel coefficient table behind the ring (host side: lds bytes without it).
   const float *in_gamma, *in_beta, *in_mean, *in_rstd;
   int in_lds;
-  int partial_rm;  // forward sums stored row-major, partial[plane][tile row][Ncols] (bn_partials_row_major)
+  // Sums stored row-major for a BN pass that finalizes by itself (bn_partials_row_major).  Forward: per tile row and
+  // channel the two doubles (sum y, sum y^2), the tile's shifted float sums moved to shift 0 here; data gradient:
+  // partial[plane][tile row][Ncols] in float.
+  int partial_rm;
 };
 
 // relu(bn(x)) of one 16-byte vector with the arithmetic of the stand-alone BN pass (bn_affine, one rounding to
@@ -737,6 +740,23 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) 
   __syncthreads();
   // partial[plane][channel][tile row]: the rows of one channel are contiguous for the finalize pass
   const int64_t nrows = a.mtiles, plane = static_cast<int64_t>(a.Ncols) * nrows;
+  if (MODE == 0 && a.partial_rm) {
+    // row-major, for an apply pass that finalizes by itself: one thread per column moves the tile's sums from the
+    // tile's shift k to shift 0, exactly enough in double (S1 + n k, S2 + 2 k S1 + n k^2), so that the readers only add
+    if (tid < BN && n0 + tid < a.Ncols) {
+      float t1 = 0.f, t2 = 0.f;
+#pragma unroll 8
+      for (int r = 0; r < RPP; ++r) {
+        t1 += cs[(r * 2 + 0) * BN + tid];
+        t2 += cs[(r * 2 + 1) * BN + tid];
+      }
+      const double k = static_cast<double>(kshift), n = static_cast<double>(min(BM, Mc - m0));
+      const double d1 = static_cast<double>(t1), d2 = static_cast<double>(t2);
+      double2* out2 = reinterpret_cast<double2*>(a.partial);
+      out2[static_cast<int64_t>(mt) * a.Ncols + n0 + tid] = make_double2(d1 + n * k, d2 + k * (2.0 * d1 + n * k));
+    }
+    return;
+  }
   if (tid < 2 * BN) {
     const int pl = tid / BN, ch = tid % BN;
     float t = 0.f;
@@ -746,8 +766,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(const IgemmArgs a) 
       a.partial[(MODE == 0 ? pl + 1 : pl) * plane +
                 (a.partial_rm ? static_cast<int64_t>(mt) * a.Ncols + n0 + ch : static_cast<int64_t>(n0 + ch) * nrows + mt)] = t;
   }
-  if (MODE == 0 && tid < BN && n0 + tid < a.Ncols)
-    a.partial[a.partial_rm ? static_cast<int64_t>(mt) * a.Ncols + n0 + tid : static_cast<int64_t>(n0 + tid) * nrows + mt] = kshift;
+  if (MODE == 0 && tid < BN && n0 + tid < a.Ncols) a.partial[static_cast<int64_t>(n0 + tid) * nrows + mt] = kshift;
 }
 
 // ------------------------------------------------------------ weight gradient
@@ -1342,7 +1361,7 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   const bool classes = a.mode == 1 && a.stride == 2;
   a.mtiles = static_cast<int>(classes ? 4 * tiles_per_class : ceil_div(a.M, BM));
   const int64_t grid = static_cast<int64_t>(a.mtiles) * a.ntn;
-  a.partial_rm = a.mode == 0 && a.partial != nullptr && bn_partials_row_major(a.mtiles);
+  a.partial_rm = a.partial != nullptr && bn_partials_row_major(a.mtiles);
   a.div_ntn = make_fastdiv(a.ntn);
   a.linear = a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0 && !a.pair && a.H == a.P && a.W == a.Q;
   for (int c = 0; c < 2; ++c) {
@@ -1982,9 +2001,10 @@ extern "C" int conv_wgrad(const rn50_conv_desc* d, const void* x, const void* dy
 // ---- fused batch-norm sums (the BN side is in bn.hip)
 extern "C" size_t conv_bn_sums_bytes(const rn50_conv_desc* d) {
   if (!d || check_conv(d, "conv_bn_sums_bytes")) return 0;
-  // one row per output tile of at least 64 pixels; three planes forward, two backward
+  // one row per output tile of at least 64 pixels; forward three float planes or, row-major, two doubles per
+  // channel and row; two planes backward
   const int P = out_dim(d->H, d->pad, d->R, d->stride), Q = out_dim(d->W, d->pad, d->S, d->stride);
-  const size_t fwd = static_cast<size_t>(ceil_div(static_cast<int64_t>(d->N) * P * Q, 64)) * 3 * d->Cout;
+  const size_t fwd = static_cast<size_t>(ceil_div(static_cast<int64_t>(d->N) * P * Q, 64)) * 4 * d->Cout;
   const size_t bwd = static_cast<size_t>(dgrad_partial_rows_bound(d)) * 2 * d->Cin;
   return align_up((fwd > bwd ? fwd : bwd) * sizeof(float), 256);
 }

@@ -197,10 +197,10 @@ extern "C" int resnet_plan_create(const rn50_step_config* cfg, rn50_plan** plan_
     if (u.conv.Cin != 3 && dgrad_wt_bytes(&u.conv) > max_wT) max_wT = dgrad_wt_bytes(&u.conv);
     if (wgrad_partial_bytes(&u.conv) > max_wg) max_wg = wgrad_partial_bytes(&u.conv);
     if (bn_relu_fwd_workspace_bytes(&u.bn) > max_bn) max_bn = bn_relu_fwd_workspace_bytes(&u.bn);
-    // sums fused into the convolutions: one row per output tile, at most ceil(M/64) rows of 3 planes
+    // sums fused into the convolutions: one row per output tile, at most ceil(M/64) rows of 16 bytes per channel
     const size_t fwd_rows = ceil_div(static_cast<int64_t>(N) * u.P * u.Q, 64);
     const size_t dgrad_rows = u.conv.Cin != 3 ? dgrad_partial_rows_bound(&u.conv) : 0;
-    max_bn = std::max(max_bn, align_up(fwd_rows * 3 * u.conv.Cout * sizeof(float), 256));
+    max_bn = std::max(max_bn, align_up(fwd_rows * 4 * u.conv.Cout * sizeof(float), 256));
     if (u.conv.Cin != 3) max_bn = std::max(max_bn, align_up(dgrad_rows * 2 * u.conv.Cin * sizeof(float), 256));
   }
   p->pool = bump(&top, static_cast<size_t>(N) * Hpool * Hpool * cfg->stem * es);

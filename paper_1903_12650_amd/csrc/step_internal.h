@@ -31,14 +31,16 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
                      hipStream_t s);
 // A BN+ReLU layer applied to a convolution's input on the fly (1x1, stride 1 convolutions only): its parameters
 // and saved statistics, float[Cin] each.
-// The forward BN sums that a convolution's output stage leaves (one row per row tile) are stored row-major,
-// partial[plane][tile row][C], when there are few tile rows: the BN apply pass then takes the statistics from them
-// itself, in every workgroup, and the finalize launch in front of it is gone.  Otherwise channel-major,
-// partial[plane][C][tile row], for the finalize kernel.  The writer and the reader both decide by this function.
-// Measured on the whole step at batch 40 (thresholds 40 / 64 / 128 rows against none: 4.664 / 4.674 / 4.700 against
-// 4.678 ms): with 31 tile rows (the 7x7 layers) the redundant sums cost less than the launch, with 123 (14x14) the
-// double-precision sums of every workgroup cost more.
-constexpr int kBnSelfFinalizeRows = 40;
+// The BN sums that a convolution's output stage leaves (one row per row tile) are stored ROW-major when there are
+// few tile rows: the BN apply pass (forward or backward) then adds them up itself, in every workgroup, for the
+// channels it applies, and the finalize launch in front of it -- about 4 us on the step's dependency chain whatever
+// it computes -- is gone.  Forward: per tile row and channel the doubles (sum y, sum y^2), moved from the tile's
+// shift to shift 0 by the writer so that the readers only add; backward: float planes [plane][tile row][C].
+// Otherwise channel-major float planes, partial[plane][C][tile row], for the finalize kernels.  The writer and the
+// reader both decide by this function.  Threshold from whole-step measurements at batch 40 (40 / 128 / 256 rows
+// against none: 4.613 / 4.577 / 4.666 against 4.649 ms): up to 123 tile rows (the 14x14 and 7x7 layers) the
+// redundant sums cost less than the launch; at 245 (28x28) every workgroup would read more sums than data.
+constexpr int kBnSelfFinalizeRows = 128;
 inline bool bn_partials_row_major(int nrows) { return nrows <= kBnSelfFinalizeRows; }
 
 struct BnIn {
