@@ -850,10 +850,10 @@ void bn_fwd_from_partials(const rn50_bn_desc* d, const void* x, const float* par
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
     launch_fwd_tail<uint16_t>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv,
-                              momentum, partial, nrows, rpp, bn_partials_row_major(nrows), s);
+                              momentum, partial, nrows, rpp, bn_partials_row_major(nrows, false), s);
   else
     launch_fwd_tail<float>(d, g, m, x, gamma, beta, residual, y, relu_mask, save_mean, save_rstd, rm, rv, momentum,
-                           partial, nrows, rpp, bn_partials_row_major(nrows), s);
+                           partial, nrows, rpp, bn_partials_row_major(nrows, false), s);
 }
 // Evaluation mode: 1/sqrt(running_var + eps) per channel, then the training pass's apply kernel with the
 // moving averages in place of the batch statistics.
@@ -883,10 +883,10 @@ void bn_bwd_from_partials(const rn50_bn_desc* d, const void* dz, const void* x, 
   const BnGeom g = bn_geom(m, d->C, d->dtype);
   if (d->dtype == RN50_BF16)
     launch_bwd_tail<uint16_t>(d, g, m, dz, nullptr, x, nullptr, relu_mask, gamma, beta, mean, rstd, dx, dres, dgamma,
-                              dbeta, partial, nrows, bn_partials_row_major(nrows), s);
+                              dbeta, partial, nrows, bn_partials_row_major(nrows, true), s);
   else
     launch_bwd_tail<float>(d, g, m, dz, nullptr, x, nullptr, relu_mask, gamma, beta, mean, rstd, dx, dres, dgamma,
-                           dbeta, partial, nrows, bn_partials_row_major(nrows), s);
+                           dbeta, partial, nrows, bn_partials_row_major(nrows, true), s);
 }
 
 }  // namespace rn50

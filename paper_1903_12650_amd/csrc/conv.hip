@@ -1361,7 +1361,7 @@ static void launch_igemm_cfg(IgemmArgs a, const char* tag, hipStream_t s) {
   const bool classes = a.mode == 1 && a.stride == 2;
   a.mtiles = static_cast<int>(classes ? 4 * tiles_per_class : ceil_div(a.M, BM));
   const int64_t grid = static_cast<int64_t>(a.mtiles) * a.ntn;
-  a.partial_rm = a.partial != nullptr && bn_partials_row_major(a.mtiles);
+  a.partial_rm = a.partial != nullptr && bn_partials_row_major(a.mtiles, a.mode == 1);
   a.div_ntn = make_fastdiv(a.ntn);
   a.linear = a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0 && !a.pair && a.H == a.P && a.W == a.Q;
   for (int c = 0; c < 2; ++c) {

@@ -39,9 +39,12 @@ void stem_fwd_padded(const rn50_conv_desc* d, const void* xp, const void* w, voi
 // Otherwise channel-major float planes, partial[plane][C][tile row], for the finalize kernels.  The writer and the
 // reader both decide by this function.  Threshold from whole-step measurements at batch 40 (40 / 128 / 256 rows
 // against none: 4.613 / 4.577 / 4.666 against 4.649 ms): up to 123 tile rows (the 14x14 and 7x7 layers) the
-// redundant sums cost less than the launch; at 245 (28x28) every workgroup would read more sums than data.
-constexpr int kBnSelfFinalizeRows = 128;
-inline bool bn_partials_row_major(int nrows) { return nrows <= kBnSelfFinalizeRows; }
+// redundant sums cost less than the launch; at 245 (28x28) every workgroup would read more sums than data (raising
+// the backward threshold alone to 256 / 512 rows: 4.78 -> 4.83 / 4.84 ms).
+constexpr int kBnSelfFinalizeRows = 128, kBnSelfFinalizeRowsBwd = 128;
+inline bool bn_partials_row_major(int nrows, bool backward) {
+  return nrows <= (backward ? kBnSelfFinalizeRowsBwd : kBnSelfFinalizeRows);
+}
 
 struct BnIn {
   const float *gamma, *beta, *mean, *rstd;
