@@ -220,7 +220,8 @@ int avgpool_bwd(int N, int HW, int C, int dtype, const void* dy, void* dx, void*
  * logits[n,k] = sum_c a[n,c]*W[k,c] + b[k].  a [N,Cin], W [K,Cin]: device dtype;
  * b, logits: device float; Cin a multiple of the 16-byte vector.  Backward:
  * da[n,c] = sum_k dlogits[n,k]*W[k,c] (dtype; dlogits is rounded to dtype for this product),
- * dW[k,c] = sum_n dlogits[n,k]*a[n,c], db[k] = sum_n dlogits[n,k] (float). */
+ * dW[k,c] = sum_n dlogits[n,k]*a[n,c], db[k] = sum_n dlogits[n,k] (float); with dW and db both
+ * NULL the parameter gradients are left out (da only). */
 int fc_fwd(int N, int Cin, int K, int dtype, const void* a, const void* W, const float* b,
            float* logits, void* stream);
 size_t fc_bwd_workspace_bytes(int N, int Cin, int K, int dtype);

@@ -652,13 +652,25 @@ extern "C" size_t fc_bwd_workspace_bytes(int N, int Cin, int K, int dtype) {
   return align_up(static_cast<size_t>(N) * K * es, 256) + align_up(static_cast<size_t>(K) * Cin * es, 256);
 }
 
+namespace rn50 {
+// The parameter gradients of the classifier: dW[k,c] = sum_n dl[n,k] * a[n,c] (float dl: the parameter gradient
+// keeps float accuracy) and db[k] = sum_n dl[n,k].  Nothing in the backward pass reads them.
+void fc_bwd_params(int N, int Cin, int K, int dtype, const void* a, const float* dlogits, float* dW, float* db,
+                   hipStream_t s) {
+  DISPATCH_T(dtype, {
+    small_gemm<float, T, float>(dlogits, 1, K, static_cast<const T*>(a), Cin, 1, nullptr, dW, K, Cin, N, s);
+  });
+  RN50_LAUNCH("fc_bwd_bias", colsum_kernel, dim3(ceil_div(K, 256)), dim3(256), 0, s, dlogits, db, N, K);
+}
+}  // namespace rn50
+
 extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const void* W,
                       const float* dlogits, void* da, float* dW, float* db, void* workspace,
                       size_t workspace_bytes, void* stream) {
   clear_error();
   if (int rc = check_dtype(dtype, "fc_bwd")) return rc;
   RN50_REQUIRE(N > 0 && Cin > 0 && K > 0, RN50_ERR_INVALID, "fc_bwd: non-positive size");
-  RN50_REQUIRE(a && W && dlogits && da && dW && db, RN50_ERR_INVALID, "fc_bwd: null pointer");
+  RN50_REQUIRE(a && W && dlogits && da && (dW != nullptr) == (db != nullptr), RN50_ERR_INVALID, "fc_bwd: null pointer");
   const size_t need = fc_bwd_workspace_bytes(N, Cin, K, dtype);
   RN50_REQUIRE(workspace_bytes >= need && (need == 0 || workspace), RN50_ERR_WORKSPACE,
                "fc_bwd: workspace %zu < %zu bytes", workspace_bytes, need);
@@ -686,12 +698,8 @@ extern "C" int fc_bwd(int N, int Cin, int K, int dtype, const void* a, const voi
                               static_cast<T*>(da), N, Cin, K, s);
     });
   }
-  DISPATCH_T(dtype, {
-    // dW[k,c] = sum_n dl[n,k] * a[n,c] (float dl: the parameter gradient keeps float accuracy)
-    small_gemm<float, T, float>(dlogits, 1, K, static_cast<const T*>(a), Cin, 1, nullptr, dW, K,
-                                Cin, N, s);
-  });
-  RN50_LAUNCH("fc_bwd_bias", colsum_kernel, dim3(ceil_div(K, 256)), dim3(256), 0, s, dlogits, db, N, K);
+  // (internal callers that run the parameter gradients elsewhere pass dW = db = null)
+  if (dW && db) fc_bwd_params(N, Cin, K, dtype, a, dlogits, dW, db, s);
   return launch_status("fc_bwd");
 }
 

@@ -102,12 +102,25 @@ __global__ __launch_bounds__(256) void lars_norms_kernel(const Args a) {
   const int64_t end = min(base + static_cast<int64_t>(kLarsChunk), T.n);
   const int64_t vend = base + ((end - base) & ~static_cast<int64_t>(3));
   float sw = 0.f, sg = 0.f;
-  for (int64_t i = base + threadIdx.x * 4; i < vend; i += 1024) {
-    const float4 w4 = *reinterpret_cast<const float4*>(T.w + i);
-    float g4[4];
-    load_g4<GBF16>(T.g, i, g4);
-    sw += (w4.x * w4.x + w4.y * w4.y) + (w4.z * w4.z + w4.w * w4.w);
-    sg += (g4[0] * g4[0] + g4[1] * g4[1]) + (g4[2] * g4[2] + g4[3] * g4[3]);
+  // all of a thread's vectors of the chunk are requested before the first is used (16 loads in flight per thread:
+  // the pass is a pure stream, and its rate is the bytes in flight); they are added in index order
+  constexpr int NV = kLarsChunk / 1024;
+  float4 w4[NV];
+  float g4[NV][4];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int64_t i = base + threadIdx.x * 4 + k * 1024;
+    if (i < vend) {
+      w4[k] = *reinterpret_cast<const float4*>(T.w + i);
+      load_g4<GBF16>(T.g, i, g4[k]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    if (base + threadIdx.x * 4 + k * 1024 < vend) {
+      sw += (w4[k].x * w4[k].x + w4[k].y * w4[k].y) + (w4[k].z * w4[k].z + w4[k].w * w4[k].w);
+      sg += (g4[k][0] * g4[k][0] + g4[k][1] * g4[k][1]) + (g4[k][2] * g4[k][2] + g4[k][3] * g4[k][3]);
+    }
   }
   for (int64_t i = vend + threadIdx.x; i < end; i += 256) {
     const float w = T.w[i], g = load_g1<GBF16>(T.g, i);

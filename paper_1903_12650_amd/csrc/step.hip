@@ -489,8 +489,12 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
                         F(plan->row_loss), F(plan->dlogits), s));
 
   // -------------------------------------------------------------- backward
+  // the classifier's parameter gradients, which only the update reads, run on the side stream
+  (void)hipEventRecord(plan->ev_fork, s);
+  (void)hipStreamWaitEvent(side, plan->ev_fork, 0);
+  fc_bwd_params(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, F(plan->dlogits), G(fcw), G(fcb), side);
   STEP_TRY(fc_bwd(cfg.N, plan->fc_in, cfg.classes, dt, ws + plan->avg, W(fcw), F(plan->dlogits), ws + plan->davg,
-                  G(fcw), G(fcb), ws + plan->fc_scratch, plan->fc_scratch_bytes, s));
+                  nullptr, nullptr, ws + plan->fc_scratch, plan->fc_scratch_bytes, s));
   (void)hipStreamWaitEvent(s, plan->ev_wt, 0);  // the transposed weights
   unsigned char* g[5];
   for (int i = 0; i < 5; ++i) g[i] = ws + plan->g[i];

@@ -95,6 +95,10 @@ void bn_infer_run(const rn50_bn_desc* d, const void* x, const float* gamma, cons
                   const float* running_mean, const float* running_var, const void* residual, void* y,
                   float* rstd_scratch, hipStream_t s);
 
+// head.hip: the classifier's parameter gradients alone (fc_bwd with dW = db = null leaves them out)
+void fc_bwd_params(int N, int Cin, int K, int dtype, const void* a, const float* dlogits, float* dW, float* db,
+                   hipStream_t s);
+
 // lars.hip
 struct LarsArenaSpec {
   int num = 0;
