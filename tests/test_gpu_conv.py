@@ -62,6 +62,10 @@ SMALL = [  # N,H,W,C,K,R,stride,pad : ragged tiles, tails, every stride/pad/filt
     (7, 4, 48, 64, 128, 3, 1, 1),    # wide, low images
     (2, 1, 56, 64, 64, 3, 1, 1),     # one-row images: every tap row but the middle one is padding
     (3, 8, 8, 128, 128, 3, 1, 1),    # one 64-pixel tile per image
+    (1, 1, 1, 8, 8, 3, 1, 1),        # a single pixel: eight of the nine taps are padding
+    (2, 2, 2, 16, 8, 3, 1, 1),       # 2x2 images: every pixel is a corner
+    (1, 3, 100, 8, 8, 3, 1, 1),      # too wide for the one-run kernels (run of 2W + 2 rows): the general path
+    (2, 3, 62, 8, 16, 3, 1, 1),      # the widest image the nine-tap weight gradient takes
 ]
 
 
