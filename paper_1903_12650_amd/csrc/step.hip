@@ -417,7 +417,12 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   // of the model weights, for one) and transposes the weights for the data gradients while the forward
   // pass runs: [Cout][R][S][Cin] -> [Cin][R][S][Cout], every convolution in one launch.
   STEP_TRY(ensure_side_stream(plan));
-  hipStream_t side = plan->side;
+#ifdef RN50_TUNING  // what-if measurement: the whole step on the caller's stream (no concurrency between its parts)
+  static const bool one_stream = getenv("RN50_ONE_STREAM") != nullptr;
+#else
+  constexpr bool one_stream = false;
+#endif
+  hipStream_t side = one_stream ? s : plan->side;
   (void)hipEventRecord(plan->ev_fork, s);
   (void)hipStreamWaitEvent(side, plan->ev_fork, 0);
   // the learning rate of this step (read by the update at the end, which waits for the side stream)
@@ -434,7 +439,7 @@ int run_step(const char* who, rn50_plan* plan, const void* images, const int32_t
   stem_pad_input(&u0.conv, images, ws + plan->xp, s);
   // Every convolution leaves the sums its batch norm needs, one row per output tile, in bn_ws.
   float* sums = static_cast<float*>(bn_ws);
-  hipStream_t branch = plan->branch;
+  hipStream_t branch = one_stream ? s : plan->branch;
   void* bn_ws2 = ws + plan->bn_scratch2;  // the projection branch's own BN scratch
   float* sums2 = static_cast<float*>(bn_ws2);
   // stats_only: the layer's output is not stored (its consumer applies it on the fly).
