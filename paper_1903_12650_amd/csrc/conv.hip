@@ -791,6 +791,7 @@ struct WgradArgs {
   // wgrad3x3_kernel: the padded pixel index space, Gpad = N * (H + 1) * (W + 1) positions
   int Gpad;
   FastDiv div_img, div_w1;  // by (H + 1) * (W + 1) and by W + 1
+  int whatif;  // tuning builds only: 1 = leave out the stores of the result, 2 = leave out the MFMAs (what-if timings)
 };
 
 template <typename T> struct WgradCfg;
@@ -970,6 +971,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
         read_frags(kk + AHEAD);
         __builtin_amdgcn_sched_barrier(0);
       }
+#ifdef RN50_TUNING
+      if (a.whatif == 2) {  // the fragments are still read; one add keeps them alive
+        acc[0][0][0] += fa[kk][0].f[0] + fb[kk][0].f[0];
+        continue;
+      }
+#endif
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -1012,6 +1019,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 
   // acc[i][j][v]: ko = i*32 + (v/4)*8 + (lane/32)*4 + v%4, c = j*32 + lane%32
   float* out = a.out + static_cast<int64_t>(split) * a.split_stride;
+#ifdef RN50_TUNING
+  if (a.whatif == 1 && acc[0][0][0] != 12345.678f) return;
+#endif
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -1556,6 +1566,10 @@ static void launch_wgrad(WgradArgs a, const WgradPlan& p, float* dw, float* part
   a.rows_per_split = p.rows_per_split;
   a.split_stride = static_cast<int64_t>(a.Cout) * a.Ktot;
   a.out = p.splits > 1 ? partial : dw;
+#ifdef RN50_TUNING
+  static const int whatif = getenv("RN50_WGRAD_WHATIF") ? atoi(getenv("RN50_WGRAD_WHATIF")) : 0;
+  a.whatif = whatif;
+#endif
   a.divQ = make_fastdiv(a.Q);
   a.divP = make_fastdiv(a.P);
   if (p.bmo == 128 && p.bc == 128) launch_wgrad_cfg<T, 128, 128>(a, p.splits, s);
