@@ -52,3 +52,24 @@ def assert_close(got, want, tol, name="", elementwise=None):
         ex = elementwise_excess(g, want)
         assert ex <= 1.0, f"{name}: an element is off by more than 2^-7*|want| + {ex:.2f} * 2^-7*rms(want)"
     return err
+
+
+def impose_relu_decisions(z_oracle, relu_bits, max_differing=8):
+    """The oracle's BN+ReLU output with the ReLU decisions of the GPU pass imposed on it.
+
+    relu_bits: the GPU forward pass's recorded decisions (one byte per 16-byte vector of its output, bit j = stored
+    output j is positive).  A pre-activation within float rounding of zero may land on either side of the ReLU, and one
+    differing decision moves a gradient by more than the float bar; both outcomes are valid.  So the decisions are
+    checked to differ from the oracle's only where the oracle's value is within rounding of zero (and only in a
+    handful of places), then the oracle's backward pass runs with the decisions of the pass under test: zero where
+    the GPU decided "off", the oracle's value (or the smallest positive number) where it decided "on"."""
+    z = np.asarray(z_oracle)
+    bits = host(relu_bits) if isinstance(relu_bits, torch.Tensor) else np.asarray(relu_bits)
+    V = z.size // bits.size
+    on = ((bits.reshape(-1, 1) >> np.arange(V, dtype=np.uint8)) & 1).astype(bool).reshape(z.shape)
+    differ = on != (z > 0)
+    n = int(differ.sum())
+    if n:
+        rms = float(np.sqrt(np.mean(np.square(z, dtype=np.float64)))) or 1.0
+        assert n <= max_differing and float(np.abs(z[differ]).max()) <= 1e-5 * rms, (n, float(np.abs(z[differ]).max()), rms)
+    return np.where(on, np.maximum(z, np.finfo(np.float32).tiny), 0).astype(z.dtype), n

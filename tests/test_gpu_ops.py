@@ -7,7 +7,7 @@ import torch
 import oracle as orc
 import synth
 from oracle import net
-from gpu_util import TOL, assert_close, dev, host, inputs
+from gpu_util import impose_relu_decisions, TOL, assert_close, dev, host, inputs
 
 pytestmark = pytest.mark.gpu
 SEED = synth.DEFAULT_SEED
@@ -50,14 +50,21 @@ def test_bn_fwd_bwd(rn, mode_name, shape, mode):
         dzsum = (dz + dz2) if use_dz2 else dz
         dx_o, dres_o, dg_o, db_o = orc.bn_relu_bwd(dzsum, x, z_o, gamma, mean_o, rstd_o, mode)
         zt = dev(z_o, bf) if (use_z or mode == 2) else None
-        dx, dres, dg, db = rn.bn_relu_bwd(dev(dz, bf), dev(x, bf), zt, dev(gamma), dev(mean_o), dev(rstd_o), mode,
+        mean_b, rstd_b = dev(mean_o), dev(rstd_o)
+        if zt is None and mode == 1:
+            # The ReLU decision is recomputed from x.  It is the forward pass's decision bit for bit when it is
+            # given that pass's statistics, so those decisions (recorded as bits) are imposed on the oracle's
+            # backward pass wherever a pre-activation within rounding of zero landed on the other side.
+            bits = rn.relu_mask_like(dev(x, bf))
+            _, mean_b, rstd_b = rn.bn_relu_fwd(dev(x, bf), dev(gamma), dev(beta), None, 1e-5, mode, relu_mask=bits)
+            z_imp, _ = impose_relu_decisions(z_o, bits)
+            dx_o, dres_o, dg_o, db_o = orc.bn_relu_bwd(dzsum, x, z_imp, gamma, mean_o, rstd_o, mode)
+        dx, dres, dg, db = rn.bn_relu_bwd(dev(dz, bf), dev(x, bf), zt, dev(gamma), mean_b, rstd_b, mode,
                                           beta=dev(beta), dz2=dev(dz2, bf) if use_dz2 else None)
         if m > 1:
-            # the recomputed mask may flip for values that round to zero: loosen slightly when z is not given
-            t2 = tol if zt is not None else max(tol, 2e-3)
-            assert_close(dx, dx_o, t2, "dx")
-            assert_close(dg, dg_o, t2, "dgamma")
-            assert_close(db, db_o, t2, "dbeta")
+            assert_close(dx, dx_o, tol, "dx")
+            assert_close(dg, dg_o, tol, "dgamma")
+            assert_close(db, db_o, tol, "dbeta")
             if mode == 2:
                 assert_close(dres, dres_o, tol, "dres")
 
